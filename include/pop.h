@@ -1,0 +1,134 @@
+/*
+ * pop.h -- C ABI of the POP (Partition-guided Online Pruning) pruned-FFN library for MI355X (gfx950).
+ *
+ * One layer = one SwiGLU FFN  y = W_down (silu(W_gate x) * (W_up x))  with hidden size d and
+ * intermediate size m.  "Channel" always means one of the m intermediate channels: row j of W_gate and
+ * W_up, column j of W_down (Sec. 3.1: an output channel of the first projections is one dimension of the
+ * intermediate representation, shared by the consecutive linear maps).
+ *
+ * Importance (Sec. 3.1 Eq. 1-2, Sec. 3.4 Eq. 3), read on the down projection and its input activations:
+ *     I_j = || W_down[:, j] ||_2 * sqrt( sum over tokens t of H[t][j]^2 ),   H = silu(X W_gate^T) * (X W_up^T).
+ * The same formula is used at prefill (all prompt tokens) and at a decode step (one token).
+ *
+ * Conventions for every entry point
+ *   - returns a status code (POP_OK == 0, negative on error); never throws, never exits.
+ *   - pointers marked "dev" are device (HBM) pointers, "host" are host pointers.  The caller owns every
+ *     buffer it passes; the library never frees or keeps them beyond the call, except that
+ *     pop_layer_create reads the three weight matrices once and keeps its own repacked copy
+ *     (device memory cost: one extra copy of the weights plus O(max_batch * m) scratch).
+ *   - argument errors are found on the host before anything is launched.  Device work is enqueued on
+ *     the given HIP stream (a hipStream_t passed as void*, NULL = the null stream) and is NOT
+ *     synchronised: the caller synchronises the stream before reading outputs.
+ *   - a layer handle may be used from one stream at a time.  Calls on one handle that overlap in time race.
+ *   - index lists are int32, ascending by channel; regions are one byte per channel.
+ *   - dtype of x, weights: the layer's wdtype (float32, or bf16 stored as 16-bit patterns).
+ *     bf16 layers need d % 8 == 0, float32 layers d % 4 == 0 (128-bit loads), else POP_EUNSUPPORTED.
+ *   - inputs must be finite; with non-finite inputs results are deterministic but unspecified.
+ */
+#ifndef POP_H
+#define POP_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pop_layer pop_layer_t; /* opaque, owned by the library */
+
+typedef enum { POP_F32 = 0, POP_BF16 = 1 } pop_dtype_t;
+
+enum {
+    POP_OK = 0,
+    POP_EINVAL = -1,       /* NULL pointer, negative size, bad enum */
+    POP_ESHAPE = -2,       /* sizes inconsistent with the layer or with each other */
+    POP_ENOMEM = -3,       /* device allocation failed */
+    POP_EHIP = -4,         /* a HIP call failed; text via pop_last_hip_error() */
+    POP_ESTATE = -5,       /* call order violated (e.g. decode before prefill) */
+    POP_EUNSUPPORTED = -6  /* valid request this build does not implement */
+};
+
+enum { POP_REGION_RETAINED = 0, POP_REGION_CANDIDATE = 1, POP_REGION_PRUNED = 2 };
+
+#define POP_MAX_BATCH 8 /* largest B of pop_decode_mask / largest token chunk processed per pass */
+
+int pop_version(void);
+const char *pop_strerror(int status);      /* static storage */
+const char *pop_last_hip_error(void);      /* text of the last failing HIP call on this thread */
+
+/* Host only.  Region sizes from fractions (Sec. 3.3: thresholds at quantile levels r-delta and r+delta,
+ * realised as exact rank counts):  n_ret = floor(f_ret*m + 1/2),  n_ret + n_cand = floor((f_ret+f_cand)*m + 1/2),
+ * n_prn = m - n_ret - n_cand.  With the paper's (r, delta): f_ret = 1-r-delta, f_cand = 2*delta. */
+int pop_region_counts(int m, double f_ret, double f_cand, int *n_ret, int *n_cand, int *n_prn);
+
+/* Host only.  Number of candidates to select per token so that the active channel count is
+ * floor((1-r)*m + 1/2) (Sec. 3.3 "Decoding Stage"), clamped to [0, n_cand]. */
+int pop_k_for_ratio(int m, double r, int n_ret, int n_cand, int *k);
+
+/* Create a layer.  w_gate, w_up: dev [m][d]; w_down: dev [d][m]; all of dtype wdtype, read once, on `stream`,
+ * and repacked channel-major (one contiguous gate+up row pair and one contiguous down column per channel).
+ * Also computes the data-free weight factor n_j = ||W_down[:,j]||_2 of Eq. 3.
+ * max_tokens: largest T of pop_prefill_partition; max_batch: largest B (1..POP_MAX_BATCH).
+ * The stream is synchronised before returning (the caller may free the source weights afterwards). */
+int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype,
+                     const void *w_gate, const void *w_up, const void *w_down,
+                     int max_tokens, int max_batch, void *stream);
+int pop_layer_destroy(pop_layer_t *layer);
+
+/* Prefill (Sec. 3.3 "Prefilling Stage"): H for all m channels and all T prompt tokens (x: dev [T][d]),
+ * I_j over the T tokens, then the three regions by rank in the order (score descending, channel ascending):
+ * the best n_ret channels are retained, the next n_cand are candidates, the rest are pruned.
+ * Outputs (dev, any may be NULL): scores [m] float32; region [m] (POP_REGION_*); ret_idx [n_ret];
+ * cand_idx [n_cand].  The partition is also kept inside the layer for the decode calls.
+ * Errors: T < 1 or T > max_tokens, n_ret/n_cand < 0 or n_ret + n_cand > m -> POP_ESHAPE. */
+int pop_prefill_partition(pop_layer_t *layer, const void *x, int T, int n_ret, int n_cand,
+                          float *scores, unsigned char *region, int *ret_idx, int *cand_idx, void *stream);
+
+/* Decode step, mask part (Sec. 3.3 "Decoding Stage", Sec. 3.4 two-step decoding).  x_t: dev [B][d].
+ * Pass 1 evaluates h_j = silu(g_j) * u_j for every retained and candidate channel, for each of the B
+ * sequences; candidates are re-scored, I_j(t) = n_j * |h_j|, and for sequence b the best k[b] (host array [B],
+ * 0 <= k[b] <= n_cand) are selected with the same tie rule as above.
+ * Outputs (dev, any may be NULL): cand_scores [B][n_cand] float32 in cand_idx order; mask [B][m], 1 = active
+ * (retained or selected); active_idx [B][n_ret + n_cand], row b holds the retained channels ascending followed
+ * by the selected ones ascending, n_active[b] = n_ret + k[b] entries valid; n_active [B].
+ * h and the masks stay cached in the layer for pop_pruned_ffn(mask = NULL).
+ * Errors: no partition yet -> POP_ESTATE; B < 1 or B > max_batch, k[b] out of range -> POP_ESHAPE. */
+int pop_decode_mask(pop_layer_t *layer, const void *x_t, int B, const int *k,
+                    float *cand_scores, unsigned char *mask, int *active_idx, int *n_active, void *stream);
+
+/* Pruned FFN output (Sec. 3.3: only retained and selected channels form the step's computation;
+ * Sec. 3.4 final computation).  y: dev [T][d] of dtype ydtype.
+ *   mask == NULL: finish the decode step started by the immediately preceding pop_decode_mask on this layer
+ *       (T must equal its B; x is not read again):  y_b = sum over active j of h_bj * W_down[:, j].
+ *   mask != NULL: stand-alone pruned FFN of x (dev [T][d]) under the given masks, dev [mask_rows][m],
+ *       mask_rows == 1 (shared by all tokens) or == T (one per token); any T >= 1.  Does not need a
+ *       partition.  An all-ones mask gives the dense FFN.
+ * Errors: mask == NULL without a preceding decode step -> POP_ESTATE; T mismatch, bad mask_rows -> POP_ESHAPE. */
+int pop_pruned_ffn(pop_layer_t *layer, const void *x, int T, const unsigned char *mask, int mask_rows,
+                   void *y, pop_dtype_t ydtype, void *stream);
+
+/* ---- pieces of the path exposed on their own (selection parity is defined on caller-supplied scores) ---- */
+
+/* Three regions from given scores (dev [m] float32), as in pop_prefill_partition.  Needs no layer. */
+int pop_partition_from_scores(const float *scores, int m, int n_ret, int n_cand,
+                              unsigned char *region, int *ret_idx, int *cand_idx, void *stream);
+
+/* Step selection from given candidate scores: cand_scores dev [n_cand] in cand_idx order, cand_idx dev [n_cand]
+ * ascending, region dev [m].  Outputs (dev, may be NULL): mask [m] (retained + selected), sel_idx [k] ascending. */
+int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_cand, int k,
+                         const unsigned char *region, int m, unsigned char *mask, int *sel_idx, void *stream);
+
+/* Column-wise importance reduction alone (Eq. 3): h dev [T][m] (float32 or bf16), nrm dev [m] float32,
+ * scores[j] = nrm[j] * sqrt(sum_t h[t][j]^2). */
+int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const float *nrm,
+                          float *scores, void *stream);
+
+/* Read-only views of layer state, for tests and callers that build on the partition.
+ * Copies are enqueued on `stream`; outputs dev, any may be NULL: nrm [m] float32 (n_j of Eq. 3),
+ * h [B][m] float32 of the last decode step (0 for pruned channels is NOT guaranteed: only retained and
+ * candidate entries are defined). */
+int pop_layer_get_norms(pop_layer_t *layer, float *nrm, void *stream);
+int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POP_H */

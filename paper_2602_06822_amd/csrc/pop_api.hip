@@ -1,0 +1,335 @@
+// C ABI of the POP pruned-FFN library: argument validation, layer state and kernel sequencing.
+// Every step of the path runs in the HIP kernels of the sibling files; nothing here computes on the host
+// except the integer region counts.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "pop_internal.h"
+
+using namespace pop;
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e, const char *what)
+{
+    snprintf(g_hip_err, sizeof g_hip_err, "%s: %s", what, hipGetErrorString(e));
+    return POP_EHIP;
+}
+
+#define POP_HIP(call)                                      \
+    do {                                                   \
+        hipError_t e__ = (call);                           \
+        if (e__ != hipSuccess) return hip_fail(e__, #call); \
+    } while (0)
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+}  // namespace
+
+struct pop_layer {
+    int d = 0, m = 0, esize = 0, is_bf16 = 0, max_tokens = 0, max_batch = 0;
+    void *w_gu = nullptr;  // [m][2][d]
+    void *w_dt = nullptr;  // [m][d]
+    float *nrm = nullptr;  // [m]
+    // partition
+    bool has_partition = false;
+    int n_ret = 0, n_cand = 0;
+    float *scores = nullptr;           // [m]
+    float *s2_part = nullptr;          // [tiles][m]
+    int tiles_cap = 0;
+    unsigned char *region = nullptr;   // [m]
+    int *ret_idx = nullptr;            // [m]
+    int *cand_idx = nullptr;           // [m]
+    int *rc_idx = nullptr;             // [m]: candidates then retained
+    // decode step
+    bool has_step = false;
+    int step_B = 0;
+    BatchK step_k = {};
+    float *h = nullptr;                // [max_batch][m]
+    float *cscore = nullptr;           // [max_batch][m]
+    unsigned char *mask = nullptr;     // [max_batch][m]
+    int *active_idx = nullptr;         // [max_batch][m]
+    int *n_active = nullptr;           // [max_batch]
+    int *ulist = nullptr;              // [m]
+    int *n_ulist = nullptr;            // [1]
+    float *partial = nullptr;          // [n_slabs][max_batch][d]
+    int n_slabs = 0;
+};
+
+extern "C" {
+
+int pop_version(void) { return 100; }
+
+const char *pop_strerror(int status)
+{
+    switch (status) {
+        case POP_OK: return "ok";
+        case POP_EINVAL: return "invalid argument";
+        case POP_ESHAPE: return "inconsistent sizes";
+        case POP_ENOMEM: return "out of device memory";
+        case POP_EHIP: return "HIP call failed";
+        case POP_ESTATE: return "call order violated";
+        case POP_EUNSUPPORTED: return "unsupported configuration";
+        default: return "unknown status";
+    }
+}
+
+const char *pop_last_hip_error(void) { return g_hip_err; }
+
+int pop_region_counts(int m, double f_ret, double f_cand, int *n_ret, int *n_cand, int *n_prn)
+{
+    if (!n_ret || !n_cand || !n_prn) return POP_EINVAL;
+    if (m <= 0 || !(f_ret >= 0.0) || !(f_cand >= 0.0) || !(f_ret + f_cand <= 1.0 + 1e-12)) return POP_EINVAL;
+    long long a = (long long)floor(f_ret * (double)m + 0.5);
+    long long b = (long long)floor((f_ret + f_cand) * (double)m + 0.5);
+    if (a > m) a = m;
+    if (b > m) b = m;
+    if (b < a) b = a;
+    *n_ret = (int)a;
+    *n_cand = (int)(b - a);
+    *n_prn = (int)(m - b);
+    return POP_OK;
+}
+
+int pop_k_for_ratio(int m, double r, int n_ret, int n_cand, int *k)
+{
+    if (!k) return POP_EINVAL;
+    if (m <= 0 || !(r >= 0.0) || !(r <= 1.0) || n_ret < 0 || n_cand < 0 || n_ret + n_cand > m) return POP_EINVAL;
+    long long a = (long long)floor((1.0 - r) * (double)m + 0.5);
+    long long kk = a - n_ret;
+    if (kk < 0) kk = 0;
+    if (kk > n_cand) kk = n_cand;
+    *k = (int)kk;
+    return POP_OK;
+}
+
+int pop_layer_destroy(pop_layer_t *L)
+{
+    if (!L) return POP_EINVAL;
+    void *ptrs[] = {L->w_gu,   L->w_dt, L->nrm,        L->scores,   L->s2_part, L->region, L->ret_idx, L->cand_idx,
+                    L->rc_idx, L->h,    L->cscore,     L->mask,     L->active_idx, L->n_active, L->ulist, L->n_ulist,
+                    L->partial};
+    for (void *p : ptrs)
+        if (p) (void)hipFree(p);
+    delete L;
+    return POP_OK;
+}
+
+int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const void *w_gate, const void *w_up,
+                     const void *w_down, int max_tokens, int max_batch, void *stream)
+{
+    if (!out) return POP_EINVAL;
+    *out = nullptr;
+    if (!w_gate || !w_up || !w_down) return POP_EINVAL;
+    if (wdtype != POP_F32 && wdtype != POP_BF16) return POP_EINVAL;
+    if (d <= 0 || m <= 0 || max_tokens < 1) return POP_ESHAPE;
+    if (max_batch < 1 || max_batch > POP_MAX_BATCH) return POP_ESHAPE;
+    const int is_bf16 = wdtype == POP_BF16, esize = is_bf16 ? 2 : 4;
+    if ((d * esize) % 16 != 0) return POP_EUNSUPPORTED;
+    if ((long long)m * 2 * d >= (1LL << 40)) return POP_EUNSUPPORTED;
+
+    int dev = 0, lds_max = 0;
+    POP_HIP(hipGetDevice(&dev));
+    POP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+    if ((long long)max_batch * d * esize > lds_max) return POP_EUNSUPPORTED;  // x_t is staged in LDS
+
+    pop_layer *L = new (std::nothrow) pop_layer;
+    if (!L) return POP_ENOMEM;
+    L->d = d;
+    L->m = m;
+    L->esize = esize;
+    L->is_bf16 = is_bf16;
+    L->max_tokens = max_tokens;
+    L->max_batch = max_batch;
+    L->tiles_cap = prefill_num_tiles(max_tokens, is_bf16);
+    L->n_slabs = down_num_slabs(d, is_bf16);
+
+    const size_t mm = (size_t)m, B = (size_t)max_batch;
+    struct Req { void **p; size_t bytes; };
+    Req reqs[] = {
+        {&L->w_gu, mm * 2 * d * esize},
+        {&L->w_dt, mm * d * esize},
+        {(void **)&L->nrm, mm * 4},
+        {(void **)&L->scores, mm * 4},
+        {(void **)&L->s2_part, (size_t)L->tiles_cap * mm * 4},
+        {(void **)&L->region, mm},
+        {(void **)&L->ret_idx, mm * 4},
+        {(void **)&L->cand_idx, mm * 4},
+        {(void **)&L->rc_idx, mm * 4},
+        {(void **)&L->h, B * mm * 4},
+        {(void **)&L->cscore, B * mm * 4},
+        {(void **)&L->mask, B * mm},
+        {(void **)&L->active_idx, B * mm * 4},
+        {(void **)&L->n_active, B * 4},
+        {(void **)&L->ulist, mm * 4},
+        {(void **)&L->n_ulist, 4},
+        {(void **)&L->partial, (size_t)L->n_slabs * B * d * 4},
+    };
+    for (const Req &r : reqs) {
+        hipError_t e = hipMalloc(r.p, r.bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            pop_layer_destroy(L);
+            return e == hipErrorOutOfMemory ? POP_ENOMEM : hip_fail(e, "hipMalloc");
+        }
+    }
+    hipStream_t s = as_stream(stream);
+    hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w_gu, L->w_dt, L->nrm, is_bf16, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) {
+        pop_layer_destroy(L);
+        return hip_fail(e, "layer repack");
+    }
+    *out = L;
+    return POP_OK;
+}
+
+int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n_cand, float *scores,
+                          unsigned char *region, int *ret_idx, int *cand_idx, void *stream)
+{
+    if (!L || !x) return POP_EINVAL;
+    if (T < 1 || T > L->max_tokens) return POP_ESHAPE;
+    if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
+    hipStream_t s = as_stream(stream);
+    const int m = L->m;
+    L->has_partition = false;
+    L->has_step = false;
+    POP_HIP(launch_prefill_gateup(L->w_gu, L->is_bf16, L->d, m, x, T, L->s2_part, s));
+    POP_HIP(launch_scores_from_partials(L->s2_part, prefill_num_tiles(T, L->is_bf16), m, L->nrm, L->scores, s));
+    POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s));
+    if (n_cand) POP_HIP(hipMemcpyAsync(L->rc_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
+    if (n_ret) POP_HIP(hipMemcpyAsync(L->rc_idx + n_cand, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
+    if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
+    if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    if (cand_idx && n_cand)
+        POP_HIP(hipMemcpyAsync(cand_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
+    L->n_ret = n_ret;
+    L->n_cand = n_cand;
+    L->has_partition = true;
+    return POP_OK;
+}
+
+int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float *cand_scores, unsigned char *mask,
+                    int *active_idx, int *n_active, void *stream)
+{
+    if (!L || !x_t || !k) return POP_EINVAL;
+    if (!L->has_partition) return POP_ESTATE;
+    if (B < 1 || B > L->max_batch) return POP_ESHAPE;
+    BatchK kk = {};
+    for (int b = 0; b < B; ++b) {
+        if (k[b] < 0 || k[b] > L->n_cand) return POP_ESHAPE;
+        kk.k[b] = k[b];
+    }
+    hipStream_t s = as_stream(stream);
+    const int m = L->m, n_ret = L->n_ret, n_cand = L->n_cand;
+    L->has_step = false;
+    POP_HIP(launch_gateup(L->w_gu, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
+                          L->cscore, m, n_cand, s));
+    POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, L->ret_idx, n_ret, L->region, m, B, kk, m, L->mask,
+                        L->active_idx, L->n_active, nullptr, s));
+    if (B > 1)
+        POP_HIP(launch_union(L->mask, m, B, L->ret_idx, n_ret, L->cand_idx, n_cand, L->ulist, L->n_ulist, s));
+    if (cand_scores && n_cand)
+        POP_HIP(hipMemcpy2DAsync(cand_scores, (size_t)n_cand * 4, L->cscore, (size_t)m * 4, (size_t)n_cand * 4, B,
+                                 hipMemcpyDeviceToDevice, s));
+    if (mask) POP_HIP(hipMemcpyAsync(mask, L->mask, (size_t)B * m, hipMemcpyDeviceToDevice, s));
+    if (active_idx && n_ret + n_cand)
+        POP_HIP(hipMemcpy2DAsync(active_idx, (size_t)(n_ret + n_cand) * 4, L->active_idx, (size_t)m * 4,
+                                 (size_t)(n_ret + n_cand) * 4, B, hipMemcpyDeviceToDevice, s));
+    if (n_active) POP_HIP(hipMemcpyAsync(n_active, L->n_active, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+    L->step_B = B;
+    L->step_k = kk;
+    L->has_step = true;
+    return POP_OK;
+}
+
+int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *mask, int mask_rows, void *y,
+                   pop_dtype_t ydtype, void *stream)
+{
+    if (!L || !y) return POP_EINVAL;
+    if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
+    hipStream_t s = as_stream(stream);
+    const int m = L->m, d = L->d, y_bf16 = ydtype == POP_BF16, ysize = y_bf16 ? 2 : 4;
+    if (!mask) {
+        if (!L->has_step) return POP_ESTATE;
+        if (T != L->step_B) return POP_ESHAPE;
+        if (T == 1)
+            POP_HIP(launch_down(L->w_dt, L->is_bf16, d, m, L->active_idx, nullptr, L->n_ret + L->step_k.k[0], L->h,
+                                nullptr, 0, 1, L->partial, L->n_slabs, y, y_bf16, s));
+        else
+            POP_HIP(launch_down(L->w_dt, L->is_bf16, d, m, L->ulist, L->n_ulist, 0, L->h, L->mask, m, T, L->partial,
+                                L->n_slabs, y, y_bf16, s));
+        return POP_OK;
+    }
+    if (!x) return POP_EINVAL;
+    if (T < 1) return POP_ESHAPE;
+    if (mask_rows != 1 && mask_rows != T) return POP_ESHAPE;
+    L->has_step = false;  // the step scratch is reused below
+    if (mask_rows == 1) POP_HIP(launch_mask_to_list(mask, 1, m, L->ulist, L->n_ulist, s));
+    for (int t0 = 0; t0 < T; t0 += L->max_batch) {
+        const int Bc = (T - t0 < L->max_batch) ? T - t0 : L->max_batch;
+        const unsigned char *mk = mask_rows == 1 ? nullptr : mask + (size_t)t0 * m;
+        if (mk) POP_HIP(launch_mask_to_list(mk, Bc, m, L->ulist, L->n_ulist, s));
+        const char *xc = (const char *)x + (size_t)t0 * d * L->esize;
+        POP_HIP(launch_gateup(L->w_gu, L->is_bf16, d, m, xc, Bc, L->ulist, m, L->n_ulist, L->h, nullptr, nullptr, 0, 0,
+                              s));
+        POP_HIP(launch_down(L->w_dt, L->is_bf16, d, m, L->ulist, L->n_ulist, 0, L->h, mk, m, Bc, L->partial, L->n_slabs,
+                            (char *)y + (size_t)t0 * d * ysize, y_bf16, s));
+    }
+    return POP_OK;
+}
+
+int pop_partition_from_scores(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
+                              int *cand_idx, void *stream)
+{
+    if (!scores) return POP_EINVAL;
+    if (m <= 0 || n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > m) return POP_ESHAPE;
+    POP_HIP(launch_partition(scores, m, n_ret, n_cand, region, ret_idx, cand_idx, as_stream(stream)));
+    return POP_OK;
+}
+
+int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_cand, int k, const unsigned char *region,
+                         int m, unsigned char *mask, int *sel_idx, void *stream)
+{
+    if (m <= 0 || n_cand < 0 || n_cand > m || k < 0 || k > n_cand) return POP_ESHAPE;
+    if (n_cand > 0 && (!cand_scores || !cand_idx)) return POP_EINVAL;
+    if (mask && !region) return POP_EINVAL;
+    BatchK kk = {};
+    kk.k[0] = k;
+    POP_HIP(launch_topk(cand_scores, n_cand, cand_idx, n_cand, nullptr, 0, region, m, 1, kk, 0, mask, nullptr, nullptr,
+                        sel_idx, as_stream(stream)));
+    return POP_OK;
+}
+
+int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const float *nrm, float *scores,
+                          void *stream)
+{
+    if (!h || !nrm || !scores) return POP_EINVAL;
+    if (hdtype != POP_F32 && hdtype != POP_BF16) return POP_EINVAL;
+    if (T < 1 || m < 1) return POP_ESHAPE;
+    POP_HIP(launch_importance_reduce(h, hdtype == POP_BF16, T, m, nrm, scores, as_stream(stream)));
+    return POP_OK;
+}
+
+int pop_layer_get_norms(pop_layer_t *L, float *nrm, void *stream)
+{
+    if (!L) return POP_EINVAL;
+    if (nrm) POP_HIP(hipMemcpyAsync(nrm, L->nrm, (size_t)L->m * 4, hipMemcpyDeviceToDevice, as_stream(stream)));
+    return POP_OK;
+}
+
+int pop_layer_get_hidden(pop_layer_t *L, float *h, int B, void *stream)
+{
+    if (!L) return POP_EINVAL;
+    if (B < 1 || B > L->max_batch) return POP_ESHAPE;
+    if (h) POP_HIP(hipMemcpyAsync(h, L->h, (size_t)B * L->m * 4, hipMemcpyDeviceToDevice, as_stream(stream)));
+    return POP_OK;
+}
+
+}  // extern "C"

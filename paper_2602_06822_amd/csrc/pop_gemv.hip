@@ -1,0 +1,322 @@
+// Decode-step GEMVs over gathered channel rows (Sec. 3.4 two-step decoding).  Both are HBM-bandwidth bound:
+// every weight byte of an active channel is read exactly once per step with 128-bit loads, one contiguous
+// row per channel thanks to the channel-major layout.
+//
+//   gateup: for each listed channel j and each of the B sequences,
+//           h[b][j] = silu(x_b . W_gate[j,:]) * (x_b . W_up[j,:]); the first n_score listed channels (the
+//           candidates) also get their step score I_j(t) = n_j * |h[b][j]| (Eq. 3 with a single token).
+//   down:   y[b][:] = sum over listed j of h[b][j] * W_down[:, j], optionally masked per sequence.
+//
+// A wave owns a whole row at a time (gateup) or a 64-vector column chunk of a slab of rows (down); lanes
+// stride the row in 16-byte vectors, so each wave-level load instruction fetches 1 KiB of contiguous HBM.
+#include "pop_internal.h"
+
+namespace pop {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// bf16 rows: products of two bf16 values are exact in float32, so dot products accumulate in float32
+// (v_dot2_f32_bf16).  float32 rows: dot products accumulate in float64 so that h keeps full float32
+// accuracy even when the sum cancels; the kernels stay HBM-bound either way.
+struct VecBF16 {
+    typedef uint4 vec_t;
+    typedef float acc_t;
+    static constexpr int kElems = 8;
+    static __device__ __forceinline__ vec_t zero() { return make_uint4(0, 0, 0, 0); }
+    static __device__ __forceinline__ float dot(const vec_t &w, const vec_t &x, float acc)
+    {
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x), __builtin_bit_cast(bf16x2_t, x.x), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y), __builtin_bit_cast(bf16x2_t, x.y), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z), __builtin_bit_cast(bf16x2_t, x.z), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w), __builtin_bit_cast(bf16x2_t, x.w), acc, false);
+        return acc;
+    }
+    static __device__ __forceinline__ void axpy(float a, const vec_t &w, float (&acc)[8])
+    {
+        acc[0] = fmaf(a, bf16_lo(w.x), acc[0]);
+        acc[1] = fmaf(a, bf16_hi(w.x), acc[1]);
+        acc[2] = fmaf(a, bf16_lo(w.y), acc[2]);
+        acc[3] = fmaf(a, bf16_hi(w.y), acc[3]);
+        acc[4] = fmaf(a, bf16_lo(w.z), acc[4]);
+        acc[5] = fmaf(a, bf16_hi(w.z), acc[5]);
+        acc[6] = fmaf(a, bf16_lo(w.w), acc[6]);
+        acc[7] = fmaf(a, bf16_hi(w.w), acc[7]);
+    }
+};
+
+struct VecF32 {
+    typedef float4 vec_t;
+    typedef double acc_t;
+    static constexpr int kElems = 4;
+    static __device__ __forceinline__ vec_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ double dot(const vec_t &w, const vec_t &x, double acc)
+    {
+        acc = fma((double)w.x, (double)x.x, acc);
+        acc = fma((double)w.y, (double)x.y, acc);
+        acc = fma((double)w.z, (double)x.z, acc);
+        acc = fma((double)w.w, (double)x.w, acc);
+        return acc;
+    }
+    static __device__ __forceinline__ void axpy(float a, const vec_t &w, float (&acc)[8])
+    {
+        acc[0] = fmaf(a, w.x, acc[0]);
+        acc[1] = fmaf(a, w.y, acc[1]);
+        acc[2] = fmaf(a, w.z, acc[2]);
+        acc[3] = fmaf(a, w.w, acc[3]);
+    }
+};
+
+// ---------------------------------------------------------------- gate/up GEMV
+constexpr int kGuUnroll = 4;  // 16-byte loads per matrix in flight per lane within one group
+
+template <class V, int B>
+__global__ __launch_bounds__(256) void gateup_kernel(const typename V::vec_t *__restrict__ w_gu, int nvec,
+                                                     const typename V::vec_t *__restrict__ x,
+                                                     const int *__restrict__ rows, int n_rows,
+                                                     const int *__restrict__ n_rows_dev, float *__restrict__ h, int m,
+                                                     const float *__restrict__ nrm, float *__restrict__ cscore,
+                                                     int cs_stride, int n_score)
+{
+    typedef typename V::vec_t vec_t;
+    extern __shared__ uint4 xs_raw[];
+    vec_t *xs = reinterpret_cast<vec_t *>(xs_raw);  // [B][nvec]
+    for (int i = threadIdx.x; i < B * nvec; i += blockDim.x) xs[i] = x[i];
+    __syncthreads();
+
+    const int n = n_rows_dev ? *n_rows_dev : n_rows;
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int n_waves = gridDim.x * (blockDim.x / kWave);
+    const int group = kWave * kGuUnroll;
+    const int nvec_full = nvec / group * group;
+
+    for (int p = blockIdx.x * (blockDim.x / kWave) + wave; p < n; p += n_waves) {
+        const int j = rows[p];
+        const vec_t *g = w_gu + (size_t)j * 2 * nvec;
+        const vec_t *u = g + nvec;
+        typename V::acc_t ag[B], au[B];
+#pragma unroll
+        for (int b = 0; b < B; ++b) ag[b] = au[b] = 0;
+
+        for (int c0 = 0; c0 < nvec_full; c0 += group) {
+            vec_t wg[kGuUnroll], wu[kGuUnroll];
+#pragma unroll
+            for (int q = 0; q < kGuUnroll; ++q) {
+                wg[q] = g[c0 + q * kWave + lane];
+                wu[q] = u[c0 + q * kWave + lane];
+            }
+#pragma unroll
+            for (int q = 0; q < kGuUnroll; ++q) {
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    vec_t xv = xs[b * nvec + c0 + q * kWave + lane];
+                    ag[b] = V::dot(wg[q], xv, ag[b]);
+                    au[b] = V::dot(wu[q], xv, au[b]);
+                }
+            }
+        }
+        for (int c = nvec_full + lane; c < nvec; c += kWave) {
+            vec_t wg = g[c], wu = u[c];
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                vec_t xv = xs[b * nvec + c];
+                ag[b] = V::dot(wg, xv, ag[b]);
+                au[b] = V::dot(wu, xv, au[b]);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            float gs = (float)wave_sum(ag[b]), us = (float)wave_sum(au[b]);
+            if (lane == 0) {
+                float hv = silu_mul(gs, us);
+                h[(size_t)b * m + j] = hv;
+                if (p < n_score) cscore[(size_t)b * cs_stride + p] = nrm[j] * fabsf(hv);
+            }
+        }
+    }
+}
+
+template <class V>
+static hipError_t gateup_dispatch(const void *w_gu, int nvec, const void *x, int B, const int *rows, int n_rows,
+                                  const int *n_rows_dev, float *h, int m, const float *nrm, float *cscore, int cs_stride,
+                                  int n_score, hipStream_t s)
+{
+    typedef typename V::vec_t vec_t;
+    if (n_rows <= 0) return hipSuccess;
+    int blocks = (n_rows + 3) / 4;
+    if (blocks > 1024) blocks = 1024;
+    size_t lds = (size_t)B * nvec * sizeof(vec_t);
+#define POP_GU(BB)                                                                                                  \
+    case BB:                                                                                                        \
+        if (lds > 48 * 1024) {                                                                                      \
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&gateup_kernel<V, BB>),               \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);               \
+            if (e != hipSuccess) return e;                                                                          \
+        }                                                                                                           \
+        hipLaunchKernelGGL((gateup_kernel<V, BB>), dim3(blocks), dim3(256), lds, s, (const vec_t *)w_gu, nvec,       \
+                           (const vec_t *)x, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score);       \
+        break;
+    switch (B) {
+        POP_GU(1) POP_GU(2) POP_GU(3) POP_GU(4) POP_GU(5) POP_GU(6) POP_GU(7) POP_GU(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef POP_GU
+    return hipGetLastError();
+}
+
+hipError_t launch_gateup(const void *w_gu, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
+                         const int *n_rows_dev, float *h, const float *nrm, float *cscore, int cs_stride, int n_score,
+                         hipStream_t s)
+{
+    if (is_bf16)
+        return gateup_dispatch<VecBF16>(w_gu, d / 8, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride,
+                                        n_score, s);
+    return gateup_dispatch<VecF32>(w_gu, d / 4, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score, s);
+}
+
+// ---------------------------------------------------------------- down projection
+// grid = (column chunks of 64 vectors, slabs).  The 4 waves of a workgroup split the slab's rows, keep
+// float32 accumulators for their 64-vector column chunk, and are combined through LDS in wave order; the
+// slab partials are then summed in slab order by down_reduce_kernel, so y does not depend on scheduling.
+constexpr int kDownUnroll = 8;
+
+template <class V, int B>
+__global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__restrict__ w_dt, int nvec,
+                                                   const int *__restrict__ list, int n_host,
+                                                   const int *__restrict__ n_dev, const float *__restrict__ h, int m,
+                                                   const unsigned char *__restrict__ mask, int mask_stride,
+                                                   float *__restrict__ partial, int d)
+{
+    typedef typename V::vec_t vec_t;
+    constexpr int E = V::kElems;
+    __shared__ float red[3][kWave * 8];
+    const int n = n_dev ? *n_dev : n_host;
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int n_slabs = gridDim.y, slab = blockIdx.y;
+    const int col = blockIdx.x * kWave + lane;  // vector column
+    const bool col_ok = col < nvec;
+    // rows of this wave: slab-major, then wave
+    const int per_slab = (n + n_slabs - 1) / n_slabs;
+    const int per_wave = (per_slab + 3) / 4;
+    const int r0 = min(n, slab * per_slab + wave * per_wave);
+    const int r1 = min(min(n, (slab + 1) * per_slab), r0 + per_wave);
+
+    float acc[B][8];
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
+
+    int i = r0;
+    for (; i + kDownUnroll <= r1; i += kDownUnroll) {
+        vec_t w[kDownUnroll];
+        int jj[kDownUnroll];
+#pragma unroll
+        for (int q = 0; q < kDownUnroll; ++q) {
+            jj[q] = list[i + q];
+            w[q] = col_ok ? w_dt[(size_t)jj[q] * nvec + col] : V::zero();
+        }
+#pragma unroll
+        for (int q = 0; q < kDownUnroll; ++q) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                float hv = h[(size_t)b * m + jj[q]];
+                if (mask && !mask[(size_t)b * mask_stride + jj[q]]) hv = 0.f;
+                V::axpy(hv, w[q], acc[b]);
+            }
+        }
+    }
+    for (; i < r1; ++i) {
+        int j = list[i];
+        vec_t w = col_ok ? w_dt[(size_t)j * nvec + col] : V::zero();
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            float hv = h[(size_t)b * m + j];
+            if (mask && !mask[(size_t)b * mask_stride + j]) hv = 0.f;
+            V::axpy(hv, w, acc[b]);
+        }
+    }
+
+    // combine the 4 waves in wave order, one sequence at a time
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        if (wave > 0) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) red[wave - 1][e * kWave + lane] = acc[b][e];
+        }
+        __syncthreads();
+        if (wave == 0 && col_ok) {
+            float *dst = partial + ((size_t)slab * B + b) * d + (size_t)col * E;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                float v = acc[b][e];
+                v += red[0][e * kWave + lane];
+                v += red[1][e * kWave + lane];
+                v += red[2][e * kWave + lane];
+                dst[e] = v;
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// y[b][o] = sum over slabs (in slab order) of partial[slab][b][o]; total = B*d outputs.
+__global__ __launch_bounds__(256) void down_reduce_kernel(const float *__restrict__ partial, int n_slabs, int total,
+                                                          void *__restrict__ y, int y_bf16)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    float acc = 0.f;
+    for (int s = 0; s < n_slabs; ++s) acc += partial[(size_t)s * total + i];
+    if (y_bf16)
+        ((uint16_t *)y)[i] = f32_to_bf16(acc);
+    else
+        ((float *)y)[i] = acc;
+}
+
+template <class V>
+static hipError_t down_dispatch(const void *w_dt, int nvec, int d, int m, const int *list, const int *n_dev, int n_host,
+                                const float *h, const unsigned char *mask, int mask_stride, int B, float *partial,
+                                int n_slabs, void *y, int y_bf16, hipStream_t s)
+{
+    typedef typename V::vec_t vec_t;
+    dim3 grid((nvec + kWave - 1) / kWave, n_slabs);
+#define POP_DN(BB)                                                                                                  \
+    case BB:                                                                                                        \
+        hipLaunchKernelGGL((down_kernel<V, BB>), grid, dim3(256), 0, s, (const vec_t *)w_dt, nvec, list, n_host,     \
+                           n_dev, h, m, mask, mask_stride, partial, d);                                              \
+        break;
+    switch (B) {
+        POP_DN(1) POP_DN(2) POP_DN(3) POP_DN(4) POP_DN(5) POP_DN(6) POP_DN(7) POP_DN(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef POP_DN
+    int total = B * d;
+    hipLaunchKernelGGL(down_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, s, partial, n_slabs, total, y,
+                       y_bf16);
+    return hipGetLastError();
+}
+
+int down_num_slabs(int d, int is_bf16)
+{
+    int nvec = d / (is_bf16 ? 8 : 4);
+    int chunks = (nvec + kWave - 1) / kWave;
+    int slabs = (512 + chunks - 1) / chunks;  // about 512 workgroups = 2048 waves
+    if (slabs < 1) slabs = 1;
+    if (slabs > 256) slabs = 256;
+    return slabs;
+}
+
+hipError_t launch_down(const void *w_dt, int is_bf16, int d, int m, const int *list, const int *n_dev, int n_host,
+                       const float *h, const unsigned char *mask, int mask_stride, int B, float *partial, int n_slabs,
+                       void *y, int y_bf16, hipStream_t s)
+{
+    if (is_bf16)
+        return down_dispatch<VecBF16>(w_dt, d / 8, d, m, list, n_dev, n_host, h, mask, mask_stride, B, partial, n_slabs,
+                                      y, y_bf16, s);
+    return down_dispatch<VecF32>(w_dt, d / 4, d, m, list, n_dev, n_host, h, mask, mask_stride, B, partial, n_slabs, y,
+                                 y_bf16, s);
+}
+
+}  // namespace pop

@@ -1,0 +1,91 @@
+// Internal declarations shared by the HIP translation units of the POP library.
+// Each .hip file defines its kernels and a host launcher; pop_api.hip holds the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pop.h"
+
+namespace pop {
+
+constexpr int kWave = 64;
+
+// Order-preserving key of a float32 score: larger score <=> larger key; -0.0 maps to the key of +0.0.
+__device__ __forceinline__ uint32_t score_key(float s)
+{
+    uint32_t b = __float_as_uint(s);
+    if (b == 0x80000000u) b = 0u;
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// round-to-nearest-even float32 -> bf16 bits (finite inputs)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
+
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+}
+
+struct BatchK {
+    int k[POP_MAX_BATCH];
+};
+
+// ---- setup (pop_setup.hip) ----
+// w_gu[j][0][:] = w_gate[j][:], w_gu[j][1][:] = w_up[j][:];  w_dt[j][o] = w_down[o][j];  nrm[j] = ||w_down[:,j]||.
+hipError_t launch_repack(const void *w_gate, const void *w_up, const void *w_down, int d, int m, int esize,
+                         void *w_gu, void *w_dt, float *nrm, int is_bf16, hipStream_t s);
+
+// ---- selection (pop_select.hip) ----
+// Regions by rank of scores[m]; outputs may be null.
+hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
+                            int *cand_idx, hipStream_t s);
+// Per sequence b (grid = B): select k.k[b] of n_cand candidates by cscore[b*cs_stride + i]; writes mask[b][m],
+// active_idx[b*act_stride + 0..n_ret+k), n_active[b], sel_idx (sequence 0 only), each if non-null.
+hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, int n_cand, const int *ret_idx,
+                       int n_ret, const unsigned char *region, int m, int B, BatchK k, int act_stride,
+                       unsigned char *mask, int *active_idx, int *n_active, int *sel_idx, hipStream_t s);
+// Union of B active sets for the batched down projection: list = ret_idx ++ {candidates selected by any b}.
+hipError_t launch_union(const unsigned char *mask, int m, int B, const int *ret_idx, int n_ret, const int *cand_idx,
+                        int n_cand, int *list, int *n_list, hipStream_t s);
+// mask rows -> ascending list of channels active in any row.
+hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s);
+
+// ---- decode GEMVs (pop_gemv.hip) ----
+// h[b][j] = silu(x_b . gate_j) * (x_b . up_j) for j in rows[0..n_rows); if cscore != null, rows [0, n_score)
+// also get cscore[b][pos] = nrm[j] * |h|.  n_rows_dev (optional) overrides n_rows with a device-side count.
+hipError_t launch_gateup(const void *w_gu, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
+                         const int *n_rows_dev, float *h, const float *nrm, float *cscore, int cs_stride, int n_score,
+                         hipStream_t s);
+// y[b][:] = sum_{i<n} hm(b, list[i]) * w_dt[list[i]][:], hm = h[b][j] (masked by mask[b][j] when mask != null).
+// Two stages: slab partials then a fixed-order reduction; y written as float32 or bf16.
+hipError_t launch_down(const void *w_dt, int is_bf16, int d, int m, const int *list, const int *n_dev, int n_host,
+                       const float *h, const unsigned char *mask, int mask_stride, int B, float *partial, int n_slabs,
+                       void *y, int y_bf16, hipStream_t s);
+int down_num_slabs(int d, int is_bf16);
+
+// ---- prefill (pop_prefill.hip) ----
+// s2_part[tile][j] = sum over the tile's tokens of H[t][j]^2, one row per token tile.
+int prefill_num_tiles(int T, int is_bf16);
+hipError_t launch_prefill_gateup(const void *w_gu, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
+                                 hipStream_t s);
+// scores[j] = nrm[j] * sqrt(sum_tile s2_part[tile][j])
+hipError_t launch_scores_from_partials(const float *s2_part, int n_tiles, int m, const float *nrm, float *scores,
+                                       hipStream_t s);
+// stand-alone column reduction of a materialised H[T][m]
+hipError_t launch_importance_reduce(const void *h, int is_bf16, int T, int m, const float *nrm, float *scores,
+                                    hipStream_t s);
+
+}  // namespace pop

@@ -1,0 +1,294 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars: partitions, masks and index lists byte-identical when both sides are given identical float32
+scores; scores within 1e-5 relative (prefill: purely relative; single-token decode quantities: purely relative
+for float32 layers, with a floor of 1e-2 * max for bf16 layers, see DECODE_FLOOR);
+FFN outputs within 1e-4 (float32 weights) / 2e-2 (bf16 weights) max-abs relative to max|y|.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_06822_amd import synth
+
+from gpu_util import GpuLayer, dev, host, max_abs_rel, score_rel_err
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16 = synth.F32, synth.BF16
+SCORE_TOL = 1e-5
+# Floor of the relative measure for single-token (decode) quantities, as a fraction of the largest value.
+# float32 layers accumulate dot products in float64, so h is accurate to a few ulp and the measure is purely
+# relative.  bf16 layers accumulate in float32: a dot product that cancels carries an absolute error of about
+# log2(d) * 2^-24 * sum|x_k w_k|, which is ~1e-7 of the largest h, so relative accuracy 1e-5 holds down to 1e-2 of it.
+DECODE_FLOOR = {0: 1e-9, 1: 1e-2}
+Y_TOL = {F32: 1e-4, BF16: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def pop():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2602_06822_amd import binding
+    return binding
+
+
+# ---------------------------------------------------------------- selection on given scores (bit-exact)
+
+SEL_CASES = [
+    # m, n_ret, n_cand
+    (1, 0, 1), (1, 1, 0), (1, 0, 0), (7, 3, 2), (64, 20, 30), (257, 77, 103), (1000, 0, 1000), (1000, 1000, 0),
+    (1376, 413, 550), (4097, 1, 4095), (11008, 6605, 1101), (11008, 0, 0), (14336, 8602, 1433), (30000, 12000, 9000),
+]
+
+
+@pytest.mark.parametrize("ties", ["none", "some", "all", "zeros"])
+def test_partition_from_scores_bit_exact(pop, oracle, ties):
+    for m, n_ret, n_cand in SEL_CASES:
+        s = synth.make_scores(m, f"gpu_part_{m}", ties)
+        region = torch.full((m,), 9, dtype=torch.uint8, device="cuda")
+        ret = torch.full((max(n_ret, 1),), -1, dtype=torch.int32, device="cuda")
+        cand = torch.full((max(n_cand, 1),), -1, dtype=torch.int32, device="cuda")
+        pop.pop_partition_from_scores(dev(s), m, n_ret, n_cand, region, ret, cand)
+        r0, ret0, cand0 = oracle.partition(s, n_ret, n_cand)
+        assert np.array_equal(host(region), r0), (m, n_ret, n_cand, ties)
+        assert np.array_equal(host(ret)[:n_ret], ret0), (m, n_ret, n_cand, ties)
+        assert np.array_equal(host(cand)[:n_cand], cand0), (m, n_ret, n_cand, ties)
+
+
+@pytest.mark.parametrize("ties", ["none", "some", "all", "zeros"])
+def test_topk_from_scores_bit_exact(pop, oracle, ties):
+    for m, n_ret, n_cand in SEL_CASES:
+        region, ret, cand = oracle.partition(synth.make_scores(m, f"gpu_topk_r_{m}", "some"), n_ret, n_cand)
+        cs = synth.make_scores(n_cand, f"gpu_topk_{m}", ties) if n_cand else np.zeros(0, np.float32)
+        for k in sorted({0, 1 if n_cand else 0, n_cand // 2, max(n_cand - 1, 0), n_cand}):
+            mask = torch.full((m,), 9, dtype=torch.uint8, device="cuda")
+            sel = torch.full((max(k, 1),), -1, dtype=torch.int32, device="cuda")
+            pop.pop_topk_from_scores(dev(cs) if n_cand else None, dev(cand) if n_cand else None, n_cand, k,
+                                     dev(region), m, mask, sel)
+            mask0, sel0, _ = oracle.select(region, cs, cand, k)
+            assert np.array_equal(host(mask), mask0), (m, n_ret, n_cand, k, ties)
+            assert np.array_equal(host(sel)[:k], sel0), (m, n_ret, n_cand, k, ties)
+
+
+# ---------------------------------------------------------------- whole path on small layers
+
+SMALL = [
+    # name, d, m, dtype, T, fractions, r
+    ("f32_ragged", 260, 333, F32, 70, (0.3, 0.4), 0.5),
+    ("bf16_ragged", 264, 333, BF16, 150, (0.3, 0.4), 0.5),
+    ("bf16_tiles", 512, 640, BF16, 300, (0.6, 0.1), 0.35),
+    ("f32_tiles", 512, 200, F32, 130, (0.45, 0.1), 0.5),
+    ("bf16_wide", 2056, 96, BF16, 9, (0.25, 0.5), 0.4),
+]
+
+
+def _check_prefill(oracle, G, L, x, n_ret, n_cand, score_tol=SCORE_TOL):
+    scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+    s_ref, region_ref, ret_ref, cand_ref = oracle.prefill(x, L.w_gate, L.w_up, L.w_down, L.cfg.dtype, n_ret, n_cand)
+    err = score_rel_err(scores, s_ref, eps=1e-6)
+    assert err <= score_tol, f"prefill score error {err:.3e}"
+    # identical scores -> identical partition, both ways
+    r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+    assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1)
+    return scores, region, ret, cand, s_ref
+
+
+def _check_decode(oracle, G, L, region, cand, x_t, ks, ydtype=None):
+    dtype = L.cfg.dtype
+    out = G.decode(x_t, ks, ydtype)
+    B = x_t.shape[0]
+    ks = [ks] * B if isinstance(ks, int) else ks
+    n_ret = int((region == 0).sum())
+    rc = region != 2
+    for b in range(B):
+        ref = oracle.decode(x_t[b], L.w_gate, L.w_up, L.w_down, dtype, region, cand, ks[b], want_y=False)
+        herr = score_rel_err(out["h"][b][rc], ref["h"][rc], eps=DECODE_FLOOR[dtype])
+        assert herr <= SCORE_TOL, f"h error {herr:.3e}"
+        cerr = score_rel_err(out["cscore"][b], ref["cscore"], eps=DECODE_FLOOR[dtype])
+        assert cerr <= SCORE_TOL, f"candidate score error {cerr:.3e}"
+        # the GPU's own float32 scores through the oracle's selector: byte-identical decisions
+        mask1, sel1, act1 = oracle.select(region, out["cscore"][b], cand, ks[b])
+        assert np.array_equal(out["mask"][b], mask1)
+        assert out["n_active"][b] == n_ret + ks[b]
+        assert np.array_equal(out["active_idx"][b][:n_ret + ks[b]], act1)
+        # FFN output under the same mask, oracle in double
+        y_ref = oracle.down(ref["h"].reshape(1, -1), L.w_down, dtype, mask1)[0]
+        yerr = max_abs_rel(out["y"][b], y_ref)
+        assert yerr <= Y_TOL[dtype], f"y error {yerr:.3e}"
+    return out
+
+
+@pytest.mark.parametrize("name,d,m,dtype,T,fr,r", SMALL)
+def test_small_layer_end_to_end(pop, oracle, name, d, m, dtype, T, fr, r):
+    L = synth.make_layer(synth.small_config(name, d, m, dtype, n_outlier=3, heavy_tail=dtype == BF16))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 5, "decode")
+    n_ret, n_cand, _ = pop.pop_region_counts(m, *fr)
+    assert (n_ret, n_cand) == oracle.region_counts(m, *fr)[:2]
+    k = pop.pop_k_for_ratio(m, r, n_ret, n_cand)
+    assert k == oracle.k_for_ratio(m, r, n_ret, n_cand)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=4) as G:
+        np.testing.assert_allclose(G.norms(), oracle.down_norms(L.w_down, dtype), rtol=2e-7)
+        scores, region, ret, cand, s_ref = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        # oracle scores rounded to float32 through the GPU selector
+        s32 = s_ref.astype(np.float32)
+        reg_t = torch.empty(m, dtype=torch.uint8, device="cuda")
+        pop.pop_partition_from_scores(dev(s32), m, n_ret, n_cand, reg_t, None, None)
+        assert np.array_equal(host(reg_t), oracle.partition(s32, n_ret, n_cand)[0])
+        for t in range(3):
+            _check_decode(oracle, G, L, region, cand, xt[t:t + 1], k)
+        # edge selections: nothing / everything selected
+        _check_decode(oracle, G, L, region, cand, xt[3:4], 0)
+        _check_decode(oracle, G, L, region, cand, xt[4:5], n_cand)
+        # batch with a different k per sequence
+        _check_decode(oracle, G, L, region, cand, xt[:4], [k, 0, n_cand, max(k - 1, 0)])
+        _check_decode(oracle, G, L, region, cand, xt[1:3], [k, k], ydtype=F32)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_degenerate_partitions(pop, oracle, dtype):
+    d, m, T = 128, 90, 20
+    L = synth.make_layer(synth.small_config("degenerate", d, m, dtype))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 2, "decode")
+    with GpuLayer(pop, L, max_tokens=T, max_batch=2) as G:
+        for n_ret, n_cand, k in ((0, m, 30), (m, 0, 0), (0, 0, 0), (10, 0, 0), (0, 17, 17), (89, 1, 1)):
+            scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+            _check_decode(oracle, G, L, region, cand, xt[:1], k)
+            _check_decode(oracle, G, L, region, cand, xt, [k, 0])
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_pruned_ffn_standalone(pop, oracle, dtype):
+    """Stand-alone masks: all ones (= dense FFN), a shared random mask, per-token masks, token chunks with a tail."""
+    d, m, T = 264 if dtype == BF16 else 260, 301, 19
+    L = synth.make_layer(synth.small_config("standalone", d, m, dtype))
+    x = synth.make_activations(L, T, "tokens")
+    g = synth.rng("standalone_masks", dtype)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=8) as G:
+        for mask in (np.ones(m, np.uint8), (g.random(m) < 0.4).astype(np.uint8), np.zeros(m, np.uint8),
+                     (g.random((T, m)) < 0.5).astype(np.uint8)):
+            for ydtype in (F32, dtype):
+                y = G.ffn(x, mask, ydtype)
+                y_ref = oracle.pruned_ffn(x, L.w_gate, L.w_up, L.w_down, dtype, mask)
+                if not y_ref.any():
+                    assert not y.any()
+                else:
+                    assert max_abs_rel(y, y_ref) <= (Y_TOL[dtype] if ydtype == BF16 else 1e-4)
+        # a stand-alone call invalidates the cached decode step
+        with pytest.raises(pop.PopError) as e:
+            y = torch.empty((1, d), dtype=torch.float32, device="cuda")
+            pop.pop_pruned_ffn(G.handle, None, 1, None, 0, y, F32)
+        assert e.value.status == pop.POP_ESTATE
+
+
+def test_importance_reduce_standalone(pop, oracle):
+    T, m = 77, 1000
+    g = synth.rng("impred")
+    H = g.standard_normal((T, m), dtype=np.float32)
+    nrm = np.abs(g.standard_normal(m, dtype=np.float32)) + np.float32(0.1)
+    ref = nrm.astype(np.float64) * np.sqrt((H.astype(np.float64) ** 2).sum(axis=0))
+    # the oracle's importance with a one-row "down projection" holding the norms reproduces nrm_j * ||H[:,j]||
+    ref2 = oracle.importance(nrm.reshape(1, m), F32, H.astype(np.float64))
+    np.testing.assert_allclose(ref, ref2, rtol=1e-13)
+    out = torch.empty(m, dtype=torch.float32, device="cuda")
+    pop.pop_importance_reduce(dev(H), F32, T, m, dev(nrm), out)
+    assert score_rel_err(host(out), ref2, eps=1e-9) <= SCORE_TOL
+    Hb = synth.f32_to_bf16_bits(H)
+    refb = oracle.importance(nrm.reshape(1, m), F32, synth.storage_to_f64(Hb, BF16))
+    pop.pop_importance_reduce(dev(Hb), BF16, T, m, dev(nrm), out)
+    assert score_rel_err(host(out), refb, eps=1e-9) <= SCORE_TOL
+
+
+def test_determinism_and_poisoned_scratch(pop, oracle):
+    """Two identical step sequences give bit-identical outputs, also after other work dirtied the scratch."""
+    d, m, T = 512, 700, 64
+    L = synth.make_layer(synth.small_config("determinism", d, m, BF16))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 4, "decode")
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 0.55, 0.1)
+    k = pop.pop_k_for_ratio(m, 0.4, n_ret, n_cand)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=4) as G:
+        a = G.prefill(x, n_ret, n_cand)
+        o1 = G.decode(xt, k)
+        # dirty the scratch with a different call pattern, then repeat
+        G.ffn(xt, (synth.rng("dirty").random((4, m)) < 0.9).astype(np.uint8))
+        G.prefill(synth.make_activations(L, T, "other_prompt"), n_ret // 2, n_cand)
+        b = G.prefill(x, n_ret, n_cand)
+        o2 = G.decode(xt, k)
+        for u, v in zip(a, b):
+            assert np.array_equal(u, v)
+        rc = a[1] != 2  # h is defined on retained and candidate channels only
+        for key in o1:
+            if key == "h":
+                assert np.array_equal(o1[key][:, rc], o2[key][:, rc]), key
+            else:
+                assert np.array_equal(o1[key], o2[key]), key
+
+
+def test_error_paths(pop):
+    d, m = 64, 40
+    L = synth.make_layer(synth.small_config("errors", d, m, F32))
+    E = pop.PopError
+
+    def status(fn, *a, **kw):
+        with pytest.raises(E) as e:
+            fn(*a, **kw)
+        return e.value.status
+
+    wg, wu, wd = dev(L.w_gate), dev(L.w_up), dev(L.w_down)
+    assert status(pop.pop_layer_create, d, m, 7, wg, wu, wd, 8, 1) == pop.POP_EINVAL
+    assert status(pop.pop_layer_create, d, m, F32, None, wu, wd, 8, 1) == pop.POP_EINVAL
+    assert status(pop.pop_layer_create, d, m, F32, wg, wu, wd, 8, 9) == pop.POP_ESHAPE
+    assert status(pop.pop_layer_create, d, m, F32, wg, wu, wd, 0, 1) == pop.POP_ESHAPE
+    assert status(pop.pop_layer_create, 62, m, F32, wg, wu, wd, 8, 1) == pop.POP_EUNSUPPORTED
+    assert status(pop.pop_layer_create, 68, m, BF16, wg, wu, wd, 8, 1) == pop.POP_EUNSUPPORTED
+    with GpuLayer(pop, L, max_tokens=8, max_batch=2) as G:
+        x = dev(synth.make_activations(L, 8, "p"))
+        y = torch.empty((2, d), dtype=torch.float32, device="cuda")
+        assert status(pop.pop_decode_mask, G.handle, x, 1, 1) == pop.POP_ESTATE
+        assert status(pop.pop_pruned_ffn, G.handle, None, 1, None, 0, y, F32) == pop.POP_ESTATE
+        assert status(pop.pop_prefill_partition, G.handle, x, 9, 10, 10) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_partition, G.handle, x, 0, 10, 10) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_partition, G.handle, x, 8, 30, 11) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_partition, G.handle, x, 8, -1, 11) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_partition, G.handle, None, 8, 10, 10) == pop.POP_EINVAL
+        pop.pop_prefill_partition(G.handle, x, 8, 10, 10)
+        assert status(pop.pop_decode_mask, G.handle, x, 3, 1) == pop.POP_ESHAPE
+        assert status(pop.pop_decode_mask, G.handle, x, 1, 11) == pop.POP_ESHAPE
+        assert status(pop.pop_decode_mask, G.handle, x, 2, [1, -1]) == pop.POP_ESHAPE
+        pop.pop_decode_mask(G.handle, x, 2, [3, 4])
+        assert status(pop.pop_pruned_ffn, G.handle, None, 1, None, 0, y, F32) == pop.POP_ESHAPE
+        assert status(pop.pop_pruned_ffn, G.handle, None, 2, None, 0, y, 5) == pop.POP_EINVAL
+        pop.pop_pruned_ffn(G.handle, None, 2, None, 0, y, F32)
+        mask = torch.ones((2, m), dtype=torch.uint8, device="cuda")
+        assert status(pop.pop_pruned_ffn, G.handle, x, 4, mask, 2, y, F32) == pop.POP_ESHAPE
+        assert status(pop.pop_pruned_ffn, G.handle, None, 2, mask, 2, y, F32) == pop.POP_EINVAL
+        torch.cuda.synchronize()
+    s = torch.zeros(10, dtype=torch.float32, device="cuda")
+    assert status(pop.pop_partition_from_scores, s, 10, 6, 5) == pop.POP_ESHAPE
+    assert status(pop.pop_partition_from_scores, None, 10, 6, 4) == pop.POP_EINVAL
+    assert status(pop.pop_topk_from_scores, s, None, 10, 3, None, 10) == pop.POP_EINVAL
+    assert status(pop.pop_topk_from_scores, s, s, 10, 11, None, 10) == pop.POP_ESHAPE
+
+
+# ---------------------------------------------------------------- benchmark configurations
+
+def test_config1_small_fp32(pop, oracle):
+    """d=512, m=1376, float32, prompt 64, regions .3/.4/.3, top-k keeps half the candidates, 16 decode steps."""
+    cfg = synth.CFG1
+    L = synth.make_layer(cfg)
+    x = synth.make_activations(L, 64, "prompt")
+    xt = synth.make_activations(L, 16, "decode")
+    n_ret, n_cand, n_prn = pop.pop_region_counts(cfg.m, 0.3, 0.4)
+    assert (n_ret, n_cand, n_prn) == (413, 550, 413)
+    k = n_cand // 2
+    with GpuLayer(pop, L, max_tokens=64, max_batch=1) as G:
+        scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        for t in range(16):
+            out = _check_decode(oracle, G, L, region, cand, xt[t:t + 1], k)
+            assert out["mask"].sum() == n_ret + k
+        # 0 % pruning reproduces the dense FFN
+        y = G.ffn(xt, np.ones(cfg.m, np.uint8))
+        dense = oracle.pruned_ffn(xt, L.w_gate, L.w_up, L.w_down, F32, np.ones(cfg.m, np.uint8))
+        assert max_abs_rel(y, dense) <= 1e-4
