@@ -1,0 +1,263 @@
+#!/usr/bin/env python3
+"""Benchmark of the POP pruned-FFN hot path on one MI355X.
+
+Workload (the Llama-2-7B-shaped configuration the metric is quoted on): bf16 SwiGLU FFN layers with
+d = 4096, m = 11008, synthetic N(0, 0.02^2) weights, Gaussian activations with 0.1 % heavy-tailed outlier
+channels; prompt of 512 tokens, then 128 decode steps at batch 1; channel sparsity r = 0.35 with a
+candidate band of 0.1 (regions 0.60 / 0.10 / 0.30), plus r = 0.20 and 0.50 as extra lines.
+
+A "step" is one request: prefill partition of the prompt (importance reduction + three-region partition)
+on each of `--layers` independent layers, then 128 decode tokens, each running decode-mask + pruned-FFN
+on every layer in turn.  Rotating over several independent layers (default 8, 1.5 GB of active weights
+per token) keeps the weights out of the 256 MB last-level cache between tokens, as in a real decoder
+where one layer's weights are touched once per token; `--layers 1` gives the cache-warm single-layer
+number, which is also reported as `warm_us_per_token`.
+
+The reported value is decode microseconds per token per layer, measured with events on the stream the
+kernels run on, inside the timed region; all inputs are resident in HBM before timing starts.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes as C
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+import torch  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0
+PROMPT, DECODE_STEPS = 512, 128
+F_CAND = 0.10
+
+
+def region_fractions(r: float):
+    """(f_ret, f_cand) for channel sparsity r with candidate band F_CAND centred on the pruning threshold."""
+    return 1.0 - r - F_CAND / 2, F_CAND
+
+
+def byte_model(d, n_ret, n_cand, k, esize=2):
+    """Algorithmic HBM bytes of one decode token on one layer (weights only dominate; vectors included)."""
+    n_rc, a = n_ret + n_cand, n_ret + k
+    gateup = 2 * n_rc * d * esize + d * esize + 4 * n_rc * 2 + 4 * n_rc
+    down = a * d * esize + 4 * a * 2 + 4 * d
+    active = 3 * a * d * esize
+    return dict(gateup=gateup, down=down, algorithmic=gateup + down, active=active)
+
+
+class BenchLayer:
+    def __init__(self, pop, synth, cfg, layer_id, r_list):
+        L = synth.make_layer(cfg, layer_id)
+        to_dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda()  # noqa: E731
+        self.pop = pop
+        self.d, self.m = cfg.d, cfg.m
+        wg, wu, wd = to_dev(L.w_gate), to_dev(L.w_up), to_dev(L.w_down)
+        self.handle = pop.pop_layer_create(cfg.d, cfg.m, pop.POP_BF16, wg, wu, wd, PROMPT, 1)
+        del wg, wu, wd
+        self.x_prompt = to_dev(synth.make_activations(L, PROMPT, "prompt", layer_id))
+        self.x_decode = to_dev(synth.make_activations(L, DECODE_STEPS, "decode", layer_id))
+        self.y = torch.empty(cfg.d, dtype=torch.int16, device="cuda")
+        self.host_layer = L
+
+    def close(self):
+        self.pop.pop_layer_destroy(self.handle)
+
+
+def run(args):
+    from paper_2602_06822_amd import binding as pop
+    from paper_2602_06822_amd import synth
+
+    torch.cuda.set_device(0)
+    cfg = synth.CFG2
+    lib = pop.raw()
+    stream = torch.cuda.current_stream()
+    sp = C.c_void_p(stream.cuda_stream)
+    layers = [BenchLayer(pop, synth, cfg, i, None) for i in range(args.layers)]
+    d, m = cfg.d, cfg.m
+    torch.cuda.synchronize()
+
+    def counts(r):
+        f_ret, f_cand = region_fractions(r)
+        n_ret, n_cand, _ = pop.pop_region_counts(m, f_ret, f_cand)
+        return n_ret, n_cand, pop.pop_k_for_ratio(m, r, n_ret, n_cand)
+
+    def make_calls(r):
+        n_ret, n_cand, k = counts(r)
+        karr = (C.c_int * 1)(k)
+        prefill, decode = [], []
+        for L in layers:
+            prefill.append((L.handle, C.c_void_p(L.x_prompt.data_ptr()), PROMPT, n_ret, n_cand, None, None, None,
+                            None, sp))
+            per_tok = []
+            for t in range(DECODE_STEPS):
+                xt = C.c_void_p(L.x_decode.data_ptr() + t * d * 2)
+                per_tok.append(((L.handle, xt, 1, karr, None, None, None, None, sp),
+                                (L.handle, None, 1, None, 0, C.c_void_p(L.y.data_ptr()), pop.POP_BF16, sp)))
+            decode.append(per_tok)
+        return prefill, decode
+
+    def check(rc):
+        if rc != 0:
+            raise pop.PopError(rc, "bench")
+
+    def one_request(calls, ev=None, probe=None):
+        prefill, decode = calls
+        if ev:
+            ev[0].record(stream)
+        for a in prefill:
+            check(lib.pop_prefill_partition(*a))
+        if ev:
+            ev[1].record(stream)
+        for t in range(DECODE_STEPS):
+            for li in range(len(layers)):
+                a_mask, a_ffn = decode[li][t]
+                if probe is not None and (t * len(layers) + li) % probe["every"] == 0:
+                    e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                    e0.record(stream)
+                    check(lib.pop_decode_mask(*a_mask))
+                    e1.record(stream)
+                    check(lib.pop_pruned_ffn(*a_ffn))
+                    e2.record(stream)
+                    probe["events"].append((e0, e1, e2))
+                else:
+                    check(lib.pop_decode_mask(*a_mask))
+                    check(lib.pop_pruned_ffn(*a_ffn))
+        if ev:
+            ev[2].record(stream)
+
+    def timed(r, steps, warmup, probe_every=None):
+        calls = make_calls(r)
+        for _ in range(warmup):
+            one_request(calls)
+        torch.cuda.synchronize()
+        evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        probe = dict(every=probe_every, events=[]) if probe_every else None
+        t0 = time.perf_counter()
+        for s in range(steps):
+            one_request(calls, evs[s], probe)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs)
+        decode_ms = sum(e[1].elapsed_time(e[2]) for e in evs)
+        n_tok_layers = steps * DECODE_STEPS * len(layers)
+        out = dict(wall_s=wall, ms_per_step=1e3 * wall / steps,
+                   decode_us_per_token=1e3 * decode_ms / n_tok_layers,
+                   prefill_us_per_layer=1e3 * prefill_ms / (steps * len(layers)))
+        if probe:
+            mk = [a.elapsed_time(b) * 1e3 for a, b, _ in probe["events"]]
+            dn = [b.elapsed_time(c) * 1e3 for _, b, c in probe["events"]]
+            out["probe_mask_us"] = float(np.mean(mk))
+            out["probe_ffn_us"] = float(np.mean(dn))
+            out["probe_n"] = len(mk)
+        return out
+
+    r_main = 0.35
+    main = timed(r_main, args.steps, args.warmup, probe_every=args.probe_every)
+    n_ret, n_cand, k = counts(r_main)
+    bm = byte_model(d, n_ret, n_cand, k)
+    us = main["decode_us_per_token"]
+
+    extra = {}
+    if not args.quick:
+        for r in (0.20, 0.50):
+            t = timed(r, max(1, args.steps // 2), 1)
+            nr, nc, kk = counts(r)
+            b = byte_model(d, nr, nc, kk)
+            extra[f"r={r:.2f}"] = dict(us_per_token=round(t["decode_us_per_token"], 3),
+                                       active_GBps=round(b["active"] / t["decode_us_per_token"] / 1e3, 1),
+                                       frac_of_peak_active=round(b["active"] / t["decode_us_per_token"] / 1e3 / HBM_PEAK_GBS, 4))
+    # cache-warm single-layer figure (same layer every token)
+    warm = None
+    if not args.quick and len(layers) > 1:
+        keep = layers
+        layers = layers[:1]
+        warm = timed(r_main, max(1, args.steps // 2), 1)["decode_us_per_token"]
+        layers = keep
+
+    gate_us = main.get("probe_mask_us")
+    roofline = None
+    if gate_us:
+        ach = bm["gateup"] / gate_us / 1e3  # GB/s
+        roofline = dict(bound="hbm", kernel="pop_decode_mask (gate/up GEMV + candidate re-score + top-k)",
+                        achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4),
+                        traffic=None, algorithmic_bytes_per_launch=bm["gateup"], avg_launch_us=round(gate_us, 3),
+                        down_kernel_us=round(main["probe_ffn_us"], 3),
+                        down_GBps=round(bm["down"] / main["probe_ffn_us"] / 1e3, 1))
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(synth, layers[0].host_layer, n_ret, n_cand, k, args.cpu_tokens)
+
+    for L in layers:
+        L.close()
+
+    result = {
+        "metric": "pruned-FFN decode us/token (per layer, Llama-2-7B shape, 1 GPU)",
+        "value": round(us, 3),
+        "unit": "us/token",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(main["ms_per_step"], 3),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "configs[1]: Llama-2-7B-shaped FFN layer, bf16, d=4096 m=11008, prompt 512 + 128 decode "
+                               "steps at batch 1, channel sparsity 0.35 (regions .60/.10/.30, k=550)",
+                   "layers_rotated": args.layers, "step": "prefill partition + 128 decode tokens on every layer",
+                   "n_ret": n_ret, "n_cand": n_cand, "k": k},
+        "tokens_per_s_per_layer": round(1e6 / us, 1),
+        "prefill_us_per_layer": round(main["prefill_us_per_layer"], 2),
+        "active_GBps": round(bm["active"] / us / 1e3, 1),
+        "algorithmic_GBps": round(bm["algorithmic"] / us / 1e3, 1),
+        "frac_of_peak_active_bytes": round(bm["active"] / us / 1e3 / HBM_PEAK_GBS, 4),
+        "warm_us_per_token": None if warm is None else round(warm, 3),
+        "other_sparsities": extra,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(result))
+
+
+def cpu_baseline(synth, L, n_ret, n_cand, k, n_tokens):
+    """The oracle's decode step (double precision, as it stands) timed on the host cores for a few tokens."""
+    from oracle import pop_oracle as oracle
+    oracle.build()
+    region, ret, cand = oracle.partition(synth.make_scores(L.cfg.m, "cpu_baseline_scores", "none"), n_ret, n_cand)
+    xt = synth.make_activations(L, n_tokens, "decode")
+    oracle.decode(xt[0], L.w_gate, L.w_up, L.w_down, L.cfg.dtype, region, cand, k)  # warm the pages
+    t0 = time.perf_counter()
+    for t in range(n_tokens):
+        oracle.decode(xt[t], L.w_gate, L.w_up, L.w_down, L.cfg.dtype, region, cand, k)
+    dt = time.perf_counter() - t0
+    return {"value": round(1e6 * dt / n_tokens, 1), "unit": "us/token", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{n_tokens} decode tokens of one layer (pass 1 over retained+candidate channels, re-score, "
+                      f"top-k, down projection), same shape and sparsity; prefill not included"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=8, help="independent layers rotated per token (cache-cold weights)")
+    ap.add_argument("--probe-every", type=int, default=8, help="bracket every n-th decode call pair with events")
+    ap.add_argument("--cpu-tokens", type=int, default=384)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--quick", action="store_true", help="main line only: skip other sparsities and the warm figure")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only; --gpus must be 1 (nothing here shards across GPUs)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    run(args)
+
+
+if __name__ == "__main__":
+    main()

@@ -43,7 +43,8 @@ enum {
     POP_ENOMEM = -3,       /* device allocation failed */
     POP_EHIP = -4,         /* a HIP call failed; text via pop_last_hip_error() */
     POP_ESTATE = -5,       /* call order violated (e.g. decode before prefill) */
-    POP_EUNSUPPORTED = -6  /* valid request this build does not implement */
+    POP_EUNSUPPORTED = -6, /* valid request this build does not implement */
+    POP_EDEVICE = -7       /* a kernel gave up a bounded wait; results of that step are invalid */
 };
 
 enum { POP_REGION_RETAINED = 0, POP_REGION_CANDIDATE = 1, POP_REGION_PRUNED = 2 };
@@ -126,6 +127,10 @@ int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const
  * h [B][m] float32 of the last decode step (0 for pruned channels is NOT guaranteed: only retained and
  * candidate entries are defined). */
 int pop_layer_get_norms(pop_layer_t *layer, float *nrm, void *stream);
+/* Synchronises `stream`, then reports whether any decode step on this layer since the last prefill hit the
+ * bound of an in-kernel wait (the fused decode kernel waits, with a bound, for its own selection stage):
+ * POP_OK, or POP_EDEVICE.  Every kernel exits either way; this call is how a caller finds out. */
+int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
 
 #ifdef __cplusplus

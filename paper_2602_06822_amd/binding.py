@@ -22,6 +22,7 @@ _lib = C.CDLL(LIB_PATH)
 
 POP_F32, POP_BF16 = 0, 1
 POP_OK, POP_EINVAL, POP_ESHAPE, POP_ENOMEM, POP_EHIP, POP_ESTATE, POP_EUNSUPPORTED = 0, -1, -2, -3, -4, -5, -6
+POP_EDEVICE = -7
 POP_REGION_RETAINED, POP_REGION_CANDIDATE, POP_REGION_PRUNED = 0, 1, 2
 POP_MAX_BATCH = 8
 
@@ -44,6 +45,7 @@ _SIGS = {
     "pop_importance_reduce": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "pop_layer_get_norms": (_i, [_vp, _vp, _vp]),
     "pop_layer_get_hidden": (_i, [_vp, _vp, _i, _vp]),
+    "pop_layer_sync_status": (_i, [_vp, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -165,6 +167,10 @@ def pop_layer_get_norms(layer, nrm, stream=None):
 
 def pop_layer_get_hidden(layer, h, B, stream=None):
     _check(_lib.pop_layer_get_hidden(layer, _ptr(h), B, _stream(stream)), "pop_layer_get_hidden")
+
+
+def pop_layer_sync_status(layer, stream=None):
+    _check(_lib.pop_layer_sync_status(layer, _stream(stream)), "pop_layer_sync_status")
 
 
 def raw():

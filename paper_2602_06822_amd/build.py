@@ -12,7 +12,8 @@ CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libpop_hip.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
-SOURCES = ["pop_api.hip", "pop_setup.hip", "pop_select.hip", "pop_gemv.hip", "pop_prefill.hip"]
+SOURCES = ["pop_api.hip", "pop_setup.hip", "pop_select.hip", "pop_gemv.hip", "pop_decode_fused.hip",
+           "pop_prefill.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -32,7 +33,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build_hip(jobs: int = 5) -> str:
+def build_hip(jobs: int = 6) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, SOURCES))

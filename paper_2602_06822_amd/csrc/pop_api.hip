@@ -3,6 +3,7 @@
 // except the integer region counts.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
@@ -33,9 +34,9 @@ inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s);
 
 struct pop_layer {
     int d = 0, m = 0, esize = 0, is_bf16 = 0, max_tokens = 0, max_batch = 0;
-    void *w_gu = nullptr;  // [m][2][d]
-    void *w_dt = nullptr;  // [m][d]
+    void *w = nullptr;     // [m][3][d]: gate row, up row, down column of each channel
     float *nrm = nullptr;  // [m]
+    int n_cu = 0, wg_target = 0;
     // partition
     bool has_partition = false;
     int n_ret = 0, n_cand = 0;
@@ -47,8 +48,13 @@ struct pop_layer {
     int *cand_idx = nullptr;           // [m]
     int *rc_idx = nullptr;             // [m]: candidates then retained
     // decode step
-    bool has_step = false;
+    bool has_step = false, step_fused = false, ulist_prefix_ok = false;
     int step_B = 0;
+    bool fused_ok = false;             // the fused kernel supports this partition
+    FusedPlan plan = {};
+    int epoch = 0;
+    int *sync = nullptr;               // [4]
+    int *deferred = nullptr;           // [fused_max_workgroups]
     BatchK step_k = {};
     float *h = nullptr;                // [max_batch][m]
     float *cscore = nullptr;           // [max_batch][m]
@@ -57,7 +63,7 @@ struct pop_layer {
     int *n_active = nullptr;           // [max_batch]
     int *ulist = nullptr;              // [m]
     int *n_ulist = nullptr;            // [1]
-    float *partial = nullptr;          // [n_slabs][max_batch][d]
+    float *partial = nullptr;          // max([n_slabs][max_batch][d], [fused workgroups][d])
     int n_slabs = 0;
 };
 
@@ -75,6 +81,7 @@ const char *pop_strerror(int status)
         case POP_EHIP: return "HIP call failed";
         case POP_ESTATE: return "call order violated";
         case POP_EUNSUPPORTED: return "unsupported configuration";
+        case POP_EDEVICE: return "a kernel gave up a bounded wait";
         default: return "unknown status";
     }
 }
@@ -111,9 +118,9 @@ int pop_k_for_ratio(int m, double r, int n_ret, int n_cand, int *k)
 int pop_layer_destroy(pop_layer_t *L)
 {
     if (!L) return POP_EINVAL;
-    void *ptrs[] = {L->w_gu,   L->w_dt, L->nrm,        L->scores,   L->s2_part, L->region, L->ret_idx, L->cand_idx,
-                    L->rc_idx, L->h,    L->cscore,     L->mask,     L->active_idx, L->n_active, L->ulist, L->n_ulist,
-                    L->partial};
+    void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
+                    L->h,      L->cscore, L->mask, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
+                    L->sync,   L->deferred};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -133,9 +140,10 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     if ((d * esize) % 16 != 0) return POP_EUNSUPPORTED;
     if ((long long)m * 2 * d >= (1LL << 40)) return POP_EUNSUPPORTED;
 
-    int dev = 0, lds_max = 0;
+    int dev = 0, lds_max = 0, n_cu = 0;
     POP_HIP(hipGetDevice(&dev));
     POP_HIP(hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+    POP_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     if ((long long)max_batch * d * esize > lds_max) return POP_EUNSUPPORTED;  // x_t is staged in LDS
 
     pop_layer *L = new (std::nothrow) pop_layer;
@@ -148,12 +156,18 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     L->max_batch = max_batch;
     L->tiles_cap = prefill_num_tiles(max_tokens, is_bf16);
     L->n_slabs = down_num_slabs(d, is_bf16);
+    L->n_cu = n_cu;
+    L->wg_target = n_cu;  // one workgroup per compute unit; POP_FUSED_WGS overrides (tuning)
+    if (const char *e = getenv("POP_FUSED_WGS")) {
+        int v = atoi(e);
+        if (v >= 2 && v <= fused_max_workgroups()) L->wg_target = v;
+    }
+    if (L->wg_target > fused_max_workgroups()) L->wg_target = fused_max_workgroups();
 
     const size_t mm = (size_t)m, B = (size_t)max_batch;
     struct Req { void **p; size_t bytes; };
     Req reqs[] = {
-        {&L->w_gu, mm * 2 * d * esize},
-        {&L->w_dt, mm * d * esize},
+        {&L->w, mm * 3 * d * esize},
         {(void **)&L->nrm, mm * 4},
         {(void **)&L->scores, mm * 4},
         {(void **)&L->s2_part, (size_t)L->tiles_cap * mm * 4},
@@ -168,7 +182,10 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         {(void **)&L->n_active, B * 4},
         {(void **)&L->ulist, mm * 4},
         {(void **)&L->n_ulist, 4},
-        {(void **)&L->partial, (size_t)L->n_slabs * B * d * 4},
+        {(void **)&L->partial, ((size_t)L->n_slabs * B > (size_t)fused_max_workgroups() ? (size_t)L->n_slabs * B
+                                                                                        : (size_t)fused_max_workgroups()) * d * 4},
+        {(void **)&L->sync, 16},
+        {(void **)&L->deferred, (size_t)fused_max_workgroups() * 4},
     };
     for (const Req &r : reqs) {
         hipError_t e = hipMalloc(r.p, r.bytes);
@@ -179,7 +196,9 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         }
     }
     hipStream_t s = as_stream(stream);
-    hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w_gu, L->w_dt, L->nrm, is_bf16, s);
+    hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w, L->nrm, is_bf16, s);
+    if (e == hipSuccess) e = launch_fill_int(L->sync, 4, 0, s);
+    if (e == hipSuccess) e = launch_fill_int(L->deferred, fused_max_workgroups(), 0, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         pop_layer_destroy(L);
@@ -199,11 +218,28 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
     const int m = L->m;
     L->has_partition = false;
     L->has_step = false;
-    POP_HIP(launch_prefill_gateup(L->w_gu, L->is_bf16, L->d, m, x, T, L->s2_part, s));
+    POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, s));
     POP_HIP(launch_scores_from_partials(L->s2_part, prefill_num_tiles(T, L->is_bf16), m, L->nrm, L->scores, s));
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s));
     if (n_cand) POP_HIP(hipMemcpyAsync(L->rc_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
     if (n_ret) POP_HIP(hipMemcpyAsync(L->rc_idx + n_cand, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    // partition-constant step state: retained bytes of every mask row, retained prefix of every active list
+    POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s));
+    if (n_ret) POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    L->ulist_prefix_ok = true;
+    // fused single-sequence step: launch shape for this partition, sized to be co-resident
+    L->fused_ok = fused_plan(L->d, L->is_bf16, n_ret, n_cand, L->wg_target, &L->plan);
+    if (L->fused_ok) {
+        int max_wg = 0;
+        POP_HIP(fused_resident_limit(L->is_bf16, L->plan, L->n_cu, &max_wg));
+        if (max_wg < 2) {
+            L->fused_ok = false;
+        } else if (L->plan.n_wg > max_wg) {
+            L->fused_ok = fused_plan(L->d, L->is_bf16, n_ret, n_cand, max_wg, &L->plan) && L->plan.n_wg <= max_wg;
+        }
+    }
+    POP_HIP(launch_fill_int(L->sync, 4, 0, s));
+    L->epoch = 0;
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
@@ -229,12 +265,47 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
     hipStream_t s = as_stream(stream);
     const int m = L->m, n_ret = L->n_ret, n_cand = L->n_cand;
     L->has_step = false;
-    POP_HIP(launch_gateup(L->w_gu, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
-                          L->cscore, m, n_cand, s));
-    POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, L->ret_idx, n_ret, L->region, m, B, kk, m, L->mask,
-                        L->active_idx, L->n_active, nullptr, s));
-    if (B > 1)
-        POP_HIP(launch_union(L->mask, m, B, L->ret_idx, n_ret, L->cand_idx, n_cand, L->ulist, L->n_ulist, s));
+    if (B == 1 && L->fused_ok) {
+        if ((long long)(L->epoch + 1) * (L->plan.n_wg - 1) > (1LL << 30)) {
+            POP_HIP(launch_fill_int(L->sync, 2, 0, s));
+            L->epoch = 0;
+        }
+        FusedParams p = {};
+        p.w = L->w;
+        p.x = x_t;
+        p.nvec = L->d / (L->is_bf16 ? 8 : 4);
+        p.d = L->d;
+        p.m = m;
+        p.ret_idx = L->ret_idx;
+        p.n_ret = n_ret;
+        p.cand_idx = L->cand_idx;
+        p.n_cand = n_cand;
+        p.k = kk.k[0];
+        p.nrm = L->nrm;
+        p.h = L->h;
+        p.cscore = L->cscore;
+        p.mask = L->mask;
+        p.active_idx = L->active_idx;
+        p.n_active = L->n_active;
+        p.partial = L->partial;
+        p.sync = L->sync;
+        p.deferred = L->deferred;
+        p.epoch = ++L->epoch;
+        POP_HIP(launch_decode_fused(L->plan, L->is_bf16, p, s));
+        L->step_fused = true;
+    } else {
+        POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
+                              L->cscore, m, n_cand, s));
+        POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx, L->n_active,
+                            nullptr, s));
+        if (B > 1) {
+            if (!L->ulist_prefix_ok && n_ret)
+                POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+            L->ulist_prefix_ok = true;
+            POP_HIP(launch_union(L->mask, m, B, n_ret, L->cand_idx, n_cand, L->ulist, L->n_ulist, s));
+        }
+        L->step_fused = false;
+    }
     if (cand_scores && n_cand)
         POP_HIP(hipMemcpy2DAsync(cand_scores, (size_t)n_cand * 4, L->cscore, (size_t)m * 4, (size_t)n_cand * 4, B,
                                  hipMemcpyDeviceToDevice, s));
@@ -259,11 +330,14 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
     if (!mask) {
         if (!L->has_step) return POP_ESTATE;
         if (T != L->step_B) return POP_ESHAPE;
-        if (T == 1)
-            POP_HIP(launch_down(L->w_dt, L->is_bf16, d, m, L->active_idx, nullptr, L->n_ret + L->step_k.k[0], L->h,
+        if (L->step_fused)
+            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->active_idx + L->n_ret,
+                                       L->step_k.k[0], L->h, L->w, m, L->is_bf16, y, y_bf16, s));
+        else if (T == 1)
+            POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->active_idx, nullptr, L->n_ret + L->step_k.k[0], L->h,
                                 nullptr, 0, 1, L->partial, L->n_slabs, y, y_bf16, s));
         else
-            POP_HIP(launch_down(L->w_dt, L->is_bf16, d, m, L->ulist, L->n_ulist, 0, L->h, L->mask, m, T, L->partial,
+            POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->ulist, L->n_ulist, 0, L->h, L->mask, m, T, L->partial,
                                 L->n_slabs, y, y_bf16, s));
         return POP_OK;
     }
@@ -271,15 +345,16 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
     if (T < 1) return POP_ESHAPE;
     if (mask_rows != 1 && mask_rows != T) return POP_ESHAPE;
     L->has_step = false;  // the step scratch is reused below
+    L->ulist_prefix_ok = false;
     if (mask_rows == 1) POP_HIP(launch_mask_to_list(mask, 1, m, L->ulist, L->n_ulist, s));
     for (int t0 = 0; t0 < T; t0 += L->max_batch) {
         const int Bc = (T - t0 < L->max_batch) ? T - t0 : L->max_batch;
         const unsigned char *mk = mask_rows == 1 ? nullptr : mask + (size_t)t0 * m;
         if (mk) POP_HIP(launch_mask_to_list(mk, Bc, m, L->ulist, L->n_ulist, s));
         const char *xc = (const char *)x + (size_t)t0 * d * L->esize;
-        POP_HIP(launch_gateup(L->w_gu, L->is_bf16, d, m, xc, Bc, L->ulist, m, L->n_ulist, L->h, nullptr, nullptr, 0, 0,
+        POP_HIP(launch_gateup(L->w, L->is_bf16, d, m, xc, Bc, L->ulist, m, L->n_ulist, L->h, nullptr, nullptr, 0, 0,
                               s));
-        POP_HIP(launch_down(L->w_dt, L->is_bf16, d, m, L->ulist, L->n_ulist, 0, L->h, mk, m, Bc, L->partial, L->n_slabs,
+        POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->ulist, L->n_ulist, 0, L->h, mk, m, Bc, L->partial, L->n_slabs,
                             (char *)y + (size_t)t0 * d * ysize, y_bf16, s));
     }
     return POP_OK;
@@ -302,8 +377,9 @@ int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_ca
     if (mask && !region) return POP_EINVAL;
     BatchK kk = {};
     kk.k[0] = k;
-    POP_HIP(launch_topk(cand_scores, n_cand, cand_idx, n_cand, nullptr, 0, region, m, 1, kk, 0, mask, nullptr, nullptr,
-                        sel_idx, as_stream(stream)));
+    if (mask) POP_HIP(launch_step_state_init(region, m, nullptr, 0, 1, 0, mask, nullptr, as_stream(stream)));
+    POP_HIP(launch_topk(cand_scores, n_cand, cand_idx, n_cand, 0, m, 1, kk, 0, mask, nullptr, nullptr, sel_idx,
+                        as_stream(stream)));
     return POP_OK;
 }
 
@@ -322,6 +398,15 @@ int pop_layer_get_norms(pop_layer_t *L, float *nrm, void *stream)
     if (!L) return POP_EINVAL;
     if (nrm) POP_HIP(hipMemcpyAsync(nrm, L->nrm, (size_t)L->m * 4, hipMemcpyDeviceToDevice, as_stream(stream)));
     return POP_OK;
+}
+
+int pop_layer_sync_status(pop_layer_t *L, void *stream)
+{
+    if (!L) return POP_EINVAL;
+    int flag = 0;
+    POP_HIP(hipMemcpyAsync(&flag, L->sync + 2, 4, hipMemcpyDeviceToHost, as_stream(stream)));
+    POP_HIP(hipStreamSynchronize(as_stream(stream)));
+    return flag ? POP_EDEVICE : POP_OK;
 }
 
 int pop_layer_get_hidden(pop_layer_t *L, float *h, int B, void *stream)

@@ -1,6 +1,7 @@
-// Decode-step GEMVs over gathered channel rows (Sec. 3.4 two-step decoding).  Both are HBM-bandwidth bound:
-// every weight byte of an active channel is read exactly once per step with 128-bit loads, one contiguous
-// row per channel thanks to the channel-major layout.
+// Decode-step GEMVs over gathered channel rows (Sec. 3.4 two-step decoding), batch-general form.  Both are
+// HBM-bandwidth bound: every weight byte of an active channel is read exactly once per step with 128-bit
+// loads, contiguous per channel thanks to the channel-major layout w[j] = [gate | up | down].  The single-
+// sequence decode step uses the fused kernel in pop_decode_fused.hip instead.
 //
 //   gateup: for each listed channel j and each of the B sequences,
 //           h[b][j] = silu(x_b . W_gate[j,:]) * (x_b . W_up[j,:]); the first n_score listed channels (the
@@ -9,68 +10,15 @@
 //
 // A wave owns a whole row at a time (gateup) or a 64-vector column chunk of a slab of rows (down); lanes
 // stride the row in 16-byte vectors, so each wave-level load instruction fetches 1 KiB of contiguous HBM.
-#include "pop_internal.h"
+#include "pop_vec.h"
 
 namespace pop {
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-
-// bf16 rows: products of two bf16 values are exact in float32, so dot products accumulate in float32
-// (v_dot2_f32_bf16).  float32 rows: dot products accumulate in float64 so that h keeps full float32
-// accuracy even when the sum cancels; the kernels stay HBM-bound either way.
-struct VecBF16 {
-    typedef uint4 vec_t;
-    typedef float acc_t;
-    static constexpr int kElems = 8;
-    static __device__ __forceinline__ vec_t zero() { return make_uint4(0, 0, 0, 0); }
-    static __device__ __forceinline__ float dot(const vec_t &w, const vec_t &x, float acc)
-    {
-        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x), __builtin_bit_cast(bf16x2_t, x.x), acc, false);
-        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y), __builtin_bit_cast(bf16x2_t, x.y), acc, false);
-        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z), __builtin_bit_cast(bf16x2_t, x.z), acc, false);
-        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w), __builtin_bit_cast(bf16x2_t, x.w), acc, false);
-        return acc;
-    }
-    static __device__ __forceinline__ void axpy(float a, const vec_t &w, float (&acc)[8])
-    {
-        acc[0] = fmaf(a, bf16_lo(w.x), acc[0]);
-        acc[1] = fmaf(a, bf16_hi(w.x), acc[1]);
-        acc[2] = fmaf(a, bf16_lo(w.y), acc[2]);
-        acc[3] = fmaf(a, bf16_hi(w.y), acc[3]);
-        acc[4] = fmaf(a, bf16_lo(w.z), acc[4]);
-        acc[5] = fmaf(a, bf16_hi(w.z), acc[5]);
-        acc[6] = fmaf(a, bf16_lo(w.w), acc[6]);
-        acc[7] = fmaf(a, bf16_hi(w.w), acc[7]);
-    }
-};
-
-struct VecF32 {
-    typedef float4 vec_t;
-    typedef double acc_t;
-    static constexpr int kElems = 4;
-    static __device__ __forceinline__ vec_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
-    static __device__ __forceinline__ double dot(const vec_t &w, const vec_t &x, double acc)
-    {
-        acc = fma((double)w.x, (double)x.x, acc);
-        acc = fma((double)w.y, (double)x.y, acc);
-        acc = fma((double)w.z, (double)x.z, acc);
-        acc = fma((double)w.w, (double)x.w, acc);
-        return acc;
-    }
-    static __device__ __forceinline__ void axpy(float a, const vec_t &w, float (&acc)[8])
-    {
-        acc[0] = fmaf(a, w.x, acc[0]);
-        acc[1] = fmaf(a, w.y, acc[1]);
-        acc[2] = fmaf(a, w.z, acc[2]);
-        acc[3] = fmaf(a, w.w, acc[3]);
-    }
-};
 
 // ---------------------------------------------------------------- gate/up GEMV
 constexpr int kGuUnroll = 4;  // 16-byte loads per matrix in flight per lane within one group
 
 template <class V, int B>
-__global__ __launch_bounds__(256) void gateup_kernel(const typename V::vec_t *__restrict__ w_gu, int nvec,
+__global__ __launch_bounds__(256) void gateup_kernel(const typename V::vec_t *__restrict__ w, int nvec,
                                                      const typename V::vec_t *__restrict__ x,
                                                      const int *__restrict__ rows, int n_rows,
                                                      const int *__restrict__ n_rows_dev, float *__restrict__ h, int m,
@@ -92,7 +40,7 @@ __global__ __launch_bounds__(256) void gateup_kernel(const typename V::vec_t *__
 
     for (int p = blockIdx.x * (blockDim.x / kWave) + wave; p < n; p += n_waves) {
         const int j = rows[p];
-        const vec_t *g = w_gu + (size_t)j * 2 * nvec;
+        const vec_t *g = w + (size_t)j * 3 * nvec;
         const vec_t *u = g + nvec;
         typename V::acc_t ag[B], au[B];
 #pragma unroll
@@ -137,7 +85,7 @@ __global__ __launch_bounds__(256) void gateup_kernel(const typename V::vec_t *__
 }
 
 template <class V>
-static hipError_t gateup_dispatch(const void *w_gu, int nvec, const void *x, int B, const int *rows, int n_rows,
+static hipError_t gateup_dispatch(const void *w, int nvec, const void *x, int B, const int *rows, int n_rows,
                                   const int *n_rows_dev, float *h, int m, const float *nrm, float *cscore, int cs_stride,
                                   int n_score, hipStream_t s)
 {
@@ -153,7 +101,7 @@ static hipError_t gateup_dispatch(const void *w_gu, int nvec, const void *x, int
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);               \
             if (e != hipSuccess) return e;                                                                          \
         }                                                                                                           \
-        hipLaunchKernelGGL((gateup_kernel<V, BB>), dim3(blocks), dim3(256), lds, s, (const vec_t *)w_gu, nvec,       \
+        hipLaunchKernelGGL((gateup_kernel<V, BB>), dim3(blocks), dim3(256), lds, s, (const vec_t *)w, nvec,          \
                            (const vec_t *)x, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score);       \
         break;
     switch (B) {
@@ -164,14 +112,14 @@ static hipError_t gateup_dispatch(const void *w_gu, int nvec, const void *x, int
     return hipGetLastError();
 }
 
-hipError_t launch_gateup(const void *w_gu, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
+hipError_t launch_gateup(const void *w, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
                          const int *n_rows_dev, float *h, const float *nrm, float *cscore, int cs_stride, int n_score,
                          hipStream_t s)
 {
     if (is_bf16)
-        return gateup_dispatch<VecBF16>(w_gu, d / 8, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride,
+        return gateup_dispatch<VecBF16>(w, d / 8, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride,
                                         n_score, s);
-    return gateup_dispatch<VecF32>(w_gu, d / 4, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score, s);
+    return gateup_dispatch<VecF32>(w, d / 4, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score, s);
 }
 
 // ---------------------------------------------------------------- down projection
@@ -181,7 +129,7 @@ hipError_t launch_gateup(const void *w_gu, int is_bf16, int d, int m, const void
 constexpr int kDownUnroll = 8;
 
 template <class V, int B>
-__global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__restrict__ w_dt, int nvec,
+__global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__restrict__ w, int nvec,
                                                    const int *__restrict__ list, int n_host,
                                                    const int *__restrict__ n_dev, const float *__restrict__ h, int m,
                                                    const unsigned char *__restrict__ mask, int mask_stride,
@@ -210,12 +158,12 @@ __global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__re
 
     int i = r0;
     for (; i + kDownUnroll <= r1; i += kDownUnroll) {
-        vec_t w[kDownUnroll];
+        vec_t wv[kDownUnroll];
         int jj[kDownUnroll];
 #pragma unroll
         for (int q = 0; q < kDownUnroll; ++q) {
             jj[q] = list[i + q];
-            w[q] = col_ok ? w_dt[(size_t)jj[q] * nvec + col] : V::zero();
+            wv[q] = col_ok ? w[((size_t)jj[q] * 3 + 2) * nvec + col] : V::zero();
         }
 #pragma unroll
         for (int q = 0; q < kDownUnroll; ++q) {
@@ -223,18 +171,18 @@ __global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__re
             for (int b = 0; b < B; ++b) {
                 float hv = h[(size_t)b * m + jj[q]];
                 if (mask && !mask[(size_t)b * mask_stride + jj[q]]) hv = 0.f;
-                V::axpy(hv, w[q], acc[b]);
+                V::axpy(hv, wv[q], acc[b]);
             }
         }
     }
     for (; i < r1; ++i) {
         int j = list[i];
-        vec_t w = col_ok ? w_dt[(size_t)j * nvec + col] : V::zero();
+        vec_t wv1 = col_ok ? w[((size_t)j * 3 + 2) * nvec + col] : V::zero();
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             float hv = h[(size_t)b * m + j];
             if (mask && !mask[(size_t)b * mask_stride + j]) hv = 0.f;
-            V::axpy(hv, w, acc[b]);
+            V::axpy(hv, wv1, acc[b]);
         }
     }
 
@@ -261,22 +209,41 @@ __global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__re
     }
 }
 
-// y[b][o] = sum over slabs (in slab order) of partial[slab][b][o]; total = B*d outputs.
+// y[b][o] = sum over slabs of partial[slab][b][o]; total = B*d outputs.  A workgroup owns 64 outputs; its 4
+// waves each sum a contiguous quarter of the slabs (independent loads, added in slab order) and are combined in
+// wave order, so the result does not depend on scheduling.
 __global__ __launch_bounds__(256) void down_reduce_kernel(const float *__restrict__ partial, int n_slabs, int total,
                                                           void *__restrict__ y, int y_bf16)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
+    __shared__ float part[4][kWave];
+    const int lane = threadIdx.x % kWave, q = threadIdx.x / kWave;
+    const int i = blockIdx.x * kWave + lane;
+    const int per = (n_slabs + 3) / 4, s0 = min(n_slabs, q * per), s1 = min(n_slabs, s0 + per);
     float acc = 0.f;
-    for (int s = 0; s < n_slabs; ++s) acc += partial[(size_t)s * total + i];
-    if (y_bf16)
-        ((uint16_t *)y)[i] = f32_to_bf16(acc);
-    else
-        ((float *)y)[i] = acc;
+    if (i < total) {
+        int s = s0;
+        for (; s + 8 <= s1; s += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(s + u) * total + i];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; s < s1; ++s) acc += partial[(size_t)s * total + i];
+    }
+    part[q][lane] = acc;
+    __syncthreads();
+    if (q == 0 && i < total) {
+        float v = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+        if (y_bf16)
+            ((uint16_t *)y)[i] = f32_to_bf16(v);
+        else
+            ((float *)y)[i] = v;
+    }
 }
 
 template <class V>
-static hipError_t down_dispatch(const void *w_dt, int nvec, int d, int m, const int *list, const int *n_dev, int n_host,
+static hipError_t down_dispatch(const void *w, int nvec, int d, int m, const int *list, const int *n_dev, int n_host,
                                 const float *h, const unsigned char *mask, int mask_stride, int B, float *partial,
                                 int n_slabs, void *y, int y_bf16, hipStream_t s)
 {
@@ -284,7 +251,7 @@ static hipError_t down_dispatch(const void *w_dt, int nvec, int d, int m, const 
     dim3 grid((nvec + kWave - 1) / kWave, n_slabs);
 #define POP_DN(BB)                                                                                                  \
     case BB:                                                                                                        \
-        hipLaunchKernelGGL((down_kernel<V, BB>), grid, dim3(256), 0, s, (const vec_t *)w_dt, nvec, list, n_host,     \
+        hipLaunchKernelGGL((down_kernel<V, BB>), grid, dim3(256), 0, s, (const vec_t *)w, nvec, list, n_host,        \
                            n_dev, h, m, mask, mask_stride, partial, d);                                              \
         break;
     switch (B) {
@@ -293,8 +260,8 @@ static hipError_t down_dispatch(const void *w_dt, int nvec, int d, int m, const 
     }
 #undef POP_DN
     int total = B * d;
-    hipLaunchKernelGGL(down_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, s, partial, n_slabs, total, y,
-                       y_bf16);
+    hipLaunchKernelGGL(down_reduce_kernel, dim3((total + kWave - 1) / kWave), dim3(256), 0, s, partial, n_slabs, total,
+                       y, y_bf16);
     return hipGetLastError();
 }
 
@@ -308,14 +275,14 @@ int down_num_slabs(int d, int is_bf16)
     return slabs;
 }
 
-hipError_t launch_down(const void *w_dt, int is_bf16, int d, int m, const int *list, const int *n_dev, int n_host,
+hipError_t launch_down(const void *w, int is_bf16, int d, int m, const int *list, const int *n_dev, int n_host,
                        const float *h, const unsigned char *mask, int mask_stride, int B, float *partial, int n_slabs,
                        void *y, int y_bf16, hipStream_t s)
 {
     if (is_bf16)
-        return down_dispatch<VecBF16>(w_dt, d / 8, d, m, list, n_dev, n_host, h, mask, mask_stride, B, partial, n_slabs,
+        return down_dispatch<VecBF16>(w, d / 8, d, m, list, n_dev, n_host, h, mask, mask_stride, B, partial, n_slabs,
                                       y, y_bf16, s);
-    return down_dispatch<VecF32>(w_dt, d / 4, d, m, list, n_dev, n_host, h, mask, mask_stride, B, partial, n_slabs, y,
+    return down_dispatch<VecF32>(w, d / 4, d, m, list, n_dev, n_host, h, mask, mask_stride, B, partial, n_slabs, y,
                                  y_bf16, s);
 }
 

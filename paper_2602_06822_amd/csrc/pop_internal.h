@@ -44,42 +44,84 @@ struct BatchK {
 };
 
 // ---- setup (pop_setup.hip) ----
-// w_gu[j][0][:] = w_gate[j][:], w_gu[j][1][:] = w_up[j][:];  w_dt[j][o] = w_down[o][j];  nrm[j] = ||w_down[:,j]||.
+// w[j][0][:] = w_gate[j][:], w[j][1][:] = w_up[j][:], w[j][2][o] = w_down[o][j];  nrm[j] = ||w_down[:,j]||.
 hipError_t launch_repack(const void *w_gate, const void *w_up, const void *w_down, int d, int m, int esize,
-                         void *w_gu, void *w_dt, float *nrm, int is_bf16, hipStream_t s);
+                         void *w, float *nrm, int is_bf16, hipStream_t s);
 
 // ---- selection (pop_select.hip) ----
 // Regions by rank of scores[m]; outputs may be null.
 hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
                             int *cand_idx, hipStream_t s);
-// Per sequence b (grid = B): select k.k[b] of n_cand candidates by cscore[b*cs_stride + i]; writes mask[b][m],
-// active_idx[b*act_stride + 0..n_ret+k), n_active[b], sel_idx (sequence 0 only), each if non-null.
-hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, int n_cand, const int *ret_idx,
-                       int n_ret, const unsigned char *region, int m, int B, BatchK k, int act_stride,
-                       unsigned char *mask, int *active_idx, int *n_active, int *sel_idx, hipStream_t s);
-// Union of B active sets for the batched down projection: list = ret_idx ++ {candidates selected by any b}.
-hipError_t launch_union(const unsigned char *mask, int m, int B, const int *ret_idx, int n_ret, const int *cand_idx,
-                        int n_cand, int *list, int *n_list, hipStream_t s);
+// Per sequence b (grid = B): select k.k[b] of n_cand candidates by cscore[b*cs_stride + i]; writes the candidate
+// bytes of mask[b][m], active_idx[b*act_stride + n_ret .. n_ret+k), n_active[b], sel_idx (sequence 0, only when
+// active_idx is null), each if non-null.
+hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, int n_cand, int n_ret, int m, int B,
+                       BatchK k, int act_stride, unsigned char *mask, int *active_idx, int *n_active, int *sel_idx,
+                       hipStream_t s);
+// Partition-constant step state: mask[b][j] = (region[j] == retained), active_idx[b][0..n_ret) = ret_idx.
+hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
+                                  int act_stride, unsigned char *mask, int *active_idx, hipStream_t s);
+// Union of B active sets for the batched down projection: list[n_ret..] = candidates selected by any b; the
+// prefix list[0..n_ret) = ret_idx is written by the caller once per partition.
+hipError_t launch_union(const unsigned char *mask, int m, int B, int n_ret, const int *cand_idx, int n_cand, int *list,
+                        int *n_list, hipStream_t s);
 // mask rows -> ascending list of channels active in any row.
 hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s);
 
 // ---- decode GEMVs (pop_gemv.hip) ----
 // h[b][j] = silu(x_b . gate_j) * (x_b . up_j) for j in rows[0..n_rows); if cscore != null, rows [0, n_score)
 // also get cscore[b][pos] = nrm[j] * |h|.  n_rows_dev (optional) overrides n_rows with a device-side count.
-hipError_t launch_gateup(const void *w_gu, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
+hipError_t launch_gateup(const void *w, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
                          const int *n_rows_dev, float *h, const float *nrm, float *cscore, int cs_stride, int n_score,
                          hipStream_t s);
-// y[b][:] = sum_{i<n} hm(b, list[i]) * w_dt[list[i]][:], hm = h[b][j] (masked by mask[b][j] when mask != null).
+// y[b][:] = sum_{i<n} hm(b, list[i]) * w[list[i]][2][:], hm = h[b][j] (masked by mask[b][j] when mask != null).
 // Two stages: slab partials then a fixed-order reduction; y written as float32 or bf16.
-hipError_t launch_down(const void *w_dt, int is_bf16, int d, int m, const int *list, const int *n_dev, int n_host,
+hipError_t launch_down(const void *w, int is_bf16, int d, int m, const int *list, const int *n_dev, int n_host,
                        const float *h, const unsigned char *mask, int mask_stride, int B, float *partial, int n_slabs,
                        void *y, int y_bf16, hipStream_t s);
 int down_num_slabs(int d, int is_bf16);
 
+// ---- fused single-sequence decode step (pop_decode_fused.hip) ----
+struct FusedParams {
+    const void *w;
+    const void *x;
+    int nvec, d, m;
+    const int *ret_idx;
+    int n_ret;
+    const int *cand_idx;
+    int n_cand, k;
+    const float *nrm;
+    float *h;                // [m]
+    float *cscore;           // [n_cand]
+    unsigned char *mask;     // [m]
+    int *active_idx;         // [>= n_ret + k]
+    int *n_active;           // [1]
+    float *partial;          // [n_wg][d]
+    int *sync;               // [0] phase-A counter (monotonic), [1] select-done epoch, [2] error flag
+    int *deferred;           // [n_wg]
+    int epoch;
+    int rows_per_wg, ncw, groups;
+};
+
+struct FusedPlan {
+    int n_wg, block, ncw, groups, cpw, rows_per_wg;
+    size_t lds;
+};
+
+int fused_max_workgroups();
+// Launch shape for (d, dtype, region sizes); false when the fused kernel does not support this d.
+bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl);
+// Largest grid of this shape that is co-resident on n_cu compute units.
+hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int *max_wg);
+hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p, hipStream_t s);
+hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sel, int k,
+                              const float *h, const void *w, int m, int is_bf16, void *y, int y_bf16, hipStream_t s);
+hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s);
+
 // ---- prefill (pop_prefill.hip) ----
 // s2_part[tile][j] = sum over the tile's tokens of H[t][j]^2, one row per token tile.
 int prefill_num_tiles(int T, int is_bf16);
-hipError_t launch_prefill_gateup(const void *w_gu, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
+hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
                                  hipStream_t s);
 // scores[j] = nrm[j] * sqrt(sum_tile s2_part[tile][j])
 hipError_t launch_scores_from_partials(const float *s2_part, int n_tiles, int m, const float *nrm, float *scores,

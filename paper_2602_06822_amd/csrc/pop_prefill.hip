@@ -3,7 +3,7 @@
 // tokens and samples).  H itself is never written to memory.
 //
 // bf16: MFMA 32x32x16 tiles.  A workgroup owns 128 tokens x 64 channels; its B operand is the channel-major
-// block w_gu[j] = [gate row | up row], so the gate and up accumulators of one (token, channel) pair sit in
+// block w[j] = [gate row | up row | down column], so the gate and up accumulators of one (token, channel) pair sit in
 // the same lane and register slot and silu(g)*u is formed without any exchange.  Each accumulator lane holds
 // 16 token rows of one channel column, so the token reduction is in-register adds, one cross-half shuffle
 // and a 2-wave LDS combine.  Token tiles write separate partial rows that are summed in tile order.
@@ -30,7 +30,7 @@ int prefill_num_tiles(int T, int is_bf16) { return is_bf16 ? (T + kPfBM - 1) / k
 // of one channel tile, which share the weight block) land on the same XCD and meet in its L2.
 __device__ __forceinline__ int xcd_logical_block(int bid, int per_xcd) { return (bid % 8) * per_xcd + bid / 8; }
 
-__global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__restrict__ w_gu,
+__global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ x, int T, int d, int m,
                                                            int n_ttiles, int n_tiles_total, int per_xcd,
                                                            float *__restrict__ s2_part)
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__res
             ra[p] = (k_ok && t < T) ? *reinterpret_cast<const uint4 *>(x + (size_t)t * d + k) : make_uint4(0, 0, 0, 0);
             // B rows 0..63: gate of channel c0+r; rows 64..127: up of channel c0+r-64
             const int ch = c0 + (r % kPfBC), which = r / kPfBC;
-            rb[p] = (k_ok && ch < m) ? *reinterpret_cast<const uint4 *>(w_gu + ((size_t)ch * 2 + which) * d + k)
+            rb[p] = (k_ok && ch < m) ? *reinterpret_cast<const uint4 *>(w + ((size_t)ch * 3 + which) * d + k)
                                      : make_uint4(0, 0, 0, 0);
         }
     };
@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__res
 }
 
 // float32: 64 tokens x 32 channels per workgroup; thread (tx = channel, ty = group of 8 tokens).
-__global__ __launch_bounds__(256) void prefill_f32_kernel(const float *__restrict__ w_gu, const float *__restrict__ x,
+__global__ __launch_bounds__(256) void prefill_f32_kernel(const float *__restrict__ w, const float *__restrict__ x,
                                                           int T, int d, int m, float *__restrict__ s2_part)
 {
     __shared__ float As[kPf32BM][kPf32BK + 1];
@@ -141,8 +141,8 @@ __global__ __launch_bounds__(256) void prefill_f32_kernel(const float *__restric
         for (int i = tid; i < kPf32BC * kPf32BK; i += 256) {
             int r = i / kPf32BK, k = i % kPf32BK;
             bool ok = c0 + r < m && k0 + k < d;
-            Bg[r][k] = ok ? w_gu[((size_t)(c0 + r) * 2) * d + k0 + k] : 0.f;
-            Bu[r][k] = ok ? w_gu[((size_t)(c0 + r) * 2 + 1) * d + k0 + k] : 0.f;
+            Bg[r][k] = ok ? w[((size_t)(c0 + r) * 3) * d + k0 + k] : 0.f;
+            Bu[r][k] = ok ? w[((size_t)(c0 + r) * 3 + 1) * d + k0 + k] : 0.f;
         }
         __syncthreads();
 #pragma unroll
@@ -173,17 +173,17 @@ __global__ __launch_bounds__(256) void prefill_f32_kernel(const float *__restric
     }
 }
 
-hipError_t launch_prefill_gateup(const void *w_gu, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
+hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
                                  hipStream_t s)
 {
     if (is_bf16) {
         int n_tt = (T + kPfBM - 1) / kPfBM, n_ct = (m + kPfBC - 1) / kPfBC;
         int total = n_tt * n_ct, per_xcd = (total + 7) / 8;
-        hipLaunchKernelGGL(prefill_bf16_kernel, dim3(per_xcd * 8), dim3(256), 0, s, (const uint16_t *)w_gu,
+        hipLaunchKernelGGL(prefill_bf16_kernel, dim3(per_xcd * 8), dim3(256), 0, s, (const uint16_t *)w,
                            (const uint16_t *)x, T, d, m, n_tt, total, per_xcd, s2_part);
     } else {
         dim3 grid((m + kPf32BC - 1) / kPf32BC, (T + kPf32BM - 1) / kPf32BM);
-        hipLaunchKernelGGL(prefill_f32_kernel, grid, dim3(256), 0, s, (const float *)w_gu, (const float *)x, T, d, m,
+        hipLaunchKernelGGL(prefill_f32_kernel, grid, dim3(256), 0, s, (const float *)w, (const float *)x, T, d, m,
                            s2_part);
     }
     return hipGetLastError();

@@ -5,106 +5,9 @@
 // index.  Scores are mapped to order-preserving 32-bit keys; an MSB-first radix select over four 8-bit digits
 // finds the key of the n-th best element, and a block scan in index order admits elements equal to that key
 // until the count is exact.  One workgroup handles one selection, so the result is deterministic.
-#include "pop_internal.h"
+#include "pop_select_dev.h"
 
 namespace pop {
-
-constexpr int kSelMaxWaves = 16;
-
-struct SelShared {
-    unsigned int hist[256];
-    int wave_tot[4][kSelMaxWaves];
-    int digit;
-    int remaining;
-};
-
-// Exclusive block scan of up to 4 integer streams at once (N streams).  Returns exclusive prefix in v[],
-// block totals in tot[].  All threads of the block must call.
-template <int N>
-__device__ void block_excl_scan(int (&v)[N], int (&tot)[N], SelShared &sh)
-{
-    int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave, nw = (blockDim.x + kWave - 1) / kWave;
-    int inc[N];
-#pragma unroll
-    for (int q = 0; q < N; ++q) {
-        int x = v[q];
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            int y = __shfl_up(x, off, kWave);
-            if (lane >= off) x += y;
-        }
-        inc[q] = x;
-        if (lane == kWave - 1) sh.wave_tot[q][wave] = x;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < N; ++q) {
-        int base = 0, total = 0;
-        for (int w = 0; w < nw; ++w) {
-            int t = sh.wave_tot[q][w];
-            if (w < wave) base += t;
-            total += t;
-        }
-        v[q] = base + inc[q] - v[q];
-        tot[q] = total;
-    }
-    __syncthreads();
-}
-
-// Key of the n_top-th best element among key(0..n), and how many elements equal to that key belong to the
-// top n_top (taken in index order).  n_top == 0 gives take_eq = 0 with kth = 0xffffffff.
-template <class KeyFn>
-__device__ void radix_threshold(KeyFn key, int n, int n_top, SelShared &sh, uint32_t &kth, int &take_eq)
-{
-    if (n_top <= 0) {
-        kth = 0xffffffffu;
-        take_eq = 0;
-        return;
-    }
-    uint32_t prefix = 0, known = 0;
-    int remaining = n_top;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        if (threadIdx.x < 256) sh.hist[threadIdx.x] = 0;
-        __syncthreads();
-        for (int i = threadIdx.x; i < n; i += blockDim.x) {
-            uint32_t k = key(i);
-            if ((k & known) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (threadIdx.x < kWave) {
-            // lane l owns the four digits 255-4l .. 252-4l, scanned from the largest digit down
-            int l = threadIdx.x;
-            int c[4], lane_tot = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                c[q] = (int)sh.hist[255 - (4 * l + q)];
-                lane_tot += c[q];
-            }
-            int x = lane_tot;
-#pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                int y = __shfl_up(x, off, kWave);
-                if (l >= off) x += y;
-            }
-            int before = x - lane_tot;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (before < remaining && remaining <= before + c[q]) {
-                    sh.digit = 255 - (4 * l + q);
-                    sh.remaining = remaining - before;
-                }
-                before += c[q];
-            }
-        }
-        __syncthreads();
-        prefix |= ((uint32_t)sh.digit) << shift;
-        known |= 255u << shift;
-        remaining = sh.remaining;
-        __syncthreads();
-    }
-    kth = prefix;
-    take_eq = remaining;
-}
 
 // ---------------------------------------------------------------- three-region partition
 __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict__ scores, int m, int n_ret, int n_cand,
@@ -168,80 +71,74 @@ hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, u
 }
 
 // ---------------------------------------------------------------- per-step candidate top-k
-// One workgroup per sequence b.  Writes mask[b][:], active_idx[b][:], n_active[b] (and sel_idx for b == 0).
+// One workgroup per sequence b.  Only candidate-dependent state is written: the candidate bytes of mask[b][:]
+// and the selected suffix of active_idx[b][:]; the retained / pruned bytes and the retained prefix are constant
+// for a partition (step_state_init_kernel).
 __global__ __launch_bounds__(1024) void topk_kernel(const float *__restrict__ cscore, int cs_stride,
-                                                    const int *__restrict__ cand_idx, int n_cand,
-                                                    const int *__restrict__ ret_idx, int n_ret,
-                                                    const unsigned char *__restrict__ region, int m, BatchK kk,
-                                                    int act_stride, unsigned char *__restrict__ mask,
+                                                    const int *__restrict__ cand_idx, int n_cand, int n_ret, int m,
+                                                    BatchK kk, int act_stride, unsigned char *__restrict__ mask,
                                                     int *__restrict__ active_idx, int *__restrict__ n_active,
                                                     int *__restrict__ sel_idx)
 {
     __shared__ SelShared sh;
-    int b = blockIdx.x;
-    int k = kk.k[b];
-    const float *cs = cscore + (size_t)b * cs_stride;
-    auto key = [&](int i) { return score_key(cs[i]); };
-    uint32_t kth;
-    int take;
-    radix_threshold(key, n_cand, k, sh, kth, take);
-
-    int E = (n_cand + blockDim.x - 1) / blockDim.x;
-    int lo = min(n_cand, (int)threadIdx.x * E), hi = min(n_cand, lo + E);
-    int cnt[1] = {0}, tot[1];
-    for (int i = lo; i < hi; ++i) cnt[0] += (key(i) == kth);
-    block_excl_scan<1>(cnt, tot, sh);
-    int eq0 = cnt[0];
-    int ns[1] = {0};
-    int eq = eq0;
-    for (int i = lo; i < hi; ++i) {
-        uint32_t kv = key(i);
-        bool sel = (kv > kth) || (kv == kth && eq < take);
-        eq += (kv == kth);
-        ns[0] += sel;
-    }
-    block_excl_scan<1>(ns, tot, sh);
-    int ps = ns[0];
-    eq = eq0;
+    const int b = blockIdx.x, k = kk.k[b];
     unsigned char *mk = mask ? mask + (size_t)b * m : nullptr;
-    int *act = active_idx ? active_idx + (size_t)b * act_stride : nullptr;
-    for (int i = lo; i < hi; ++i) {
-        uint32_t kv = key(i);
-        bool sel = (kv > kth) || (kv == kth && eq < take);
-        eq += (kv == kth);
-        int j = cand_idx[i];
-        if (mk) mk[j] = sel ? 1 : 0;
-        if (sel) {
-            if (act) act[n_ret + ps] = j;
-            if (sel_idx && b == 0) sel_idx[ps] = j;
-            ++ps;
-        }
-    }
-    // retained and pruned channels of the mask; retained prefix of the active list
-    if (mk)
-        for (int j = threadIdx.x; j < m; j += blockDim.x) {
-            unsigned char r = region[j];
-            if (r != POP_REGION_CANDIDATE) mk[j] = (r == POP_REGION_RETAINED) ? 1 : 0;
-        }
-    if (act)
-        for (int i = threadIdx.x; i < n_ret; i += blockDim.x) act[i] = ret_idx[i];
+    int *act = active_idx ? active_idx + (size_t)b * act_stride + n_ret : (b == 0 ? sel_idx : nullptr);
+    block_select_candidates(cscore + (size_t)b * cs_stride, cand_idx, n_cand, k, mk, act, sh);
     if (n_active && threadIdx.x == 0) n_active[b] = n_ret + k;
 }
 
-hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, int n_cand, const int *ret_idx,
-                       int n_ret, const unsigned char *region, int m, int B, BatchK k, int act_stride,
-                       unsigned char *mask, int *active_idx, int *n_active, int *sel_idx, hipStream_t s)
+hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, int n_cand, int n_ret, int m, int B,
+                       BatchK k, int act_stride, unsigned char *mask, int *active_idx, int *n_active, int *sel_idx,
+                       hipStream_t s)
 {
     int threads = n_cand <= 2048 ? 256 : 1024;
-    hipLaunchKernelGGL(topk_kernel, dim3(B), dim3(threads), 0, s, cscore, cs_stride, cand_idx, n_cand, ret_idx, n_ret,
-                       region, m, k, act_stride, mask, active_idx, n_active, sel_idx);
+    hipLaunchKernelGGL(topk_kernel, dim3(B), dim3(threads), 0, s, cscore, cs_stride, cand_idx, n_cand, n_ret, m, k,
+                       act_stride, mask, active_idx, n_active, sel_idx);
+    return hipGetLastError();
+}
+
+// Partition-constant part of the step state, for `rows` sequences: mask[b][j] = 1 for retained channels, 0 for
+// pruned and (until a step selects them) candidate channels; active_idx[b][0..n_ret) = ret_idx.
+__global__ __launch_bounds__(256) void step_state_init_kernel(const unsigned char *__restrict__ region, int m,
+                                                              const int *__restrict__ ret_idx, int n_ret, int rows,
+                                                              int act_stride, unsigned char *__restrict__ mask,
+                                                              int *__restrict__ active_idx)
+{
+    const int b = blockIdx.y;
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < m; j += gridDim.x * blockDim.x) {
+        if (mask) mask[(size_t)b * m + j] = region[j] == POP_REGION_RETAINED ? 1 : 0;
+        if (active_idx && j < n_ret) active_idx[(size_t)b * act_stride + j] = ret_idx[j];
+    }
+}
+
+hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
+                                  int act_stride, unsigned char *mask, int *active_idx, hipStream_t s)
+{
+    dim3 grid((m + 255) / 256, rows);
+    hipLaunchKernelGGL(step_state_init_kernel, grid, dim3(256), 0, s, region, m, ret_idx, n_ret, rows, act_stride, mask,
+                       active_idx);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void fill_int_kernel(int *__restrict__ p, int n, int value)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_int_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n, value);
     return hipGetLastError();
 }
 
 // ---------------------------------------------------------------- list compactions
-// list = ret_idx ++ { cand_idx[i] : mask[b][cand_idx[i]] for some b }, n_list = its length.
+// list[n_ret..] = { cand_idx[i] : mask[b][cand_idx[i]] for some b }, n_list = n_ret + their number.  The prefix
+// list[0..n_ret) = ret_idx is constant for a partition and is written by the caller when the partition is made.
 __global__ __launch_bounds__(1024) void union_kernel(const unsigned char *__restrict__ mask, int m, int B,
-                                                     const int *__restrict__ ret_idx, int n_ret,
+                                                     int n_ret,
                                                      const int *__restrict__ cand_idx, int n_cand,
                                                      int *__restrict__ list, int *__restrict__ n_list)
 {
@@ -263,16 +160,14 @@ __global__ __launch_bounds__(1024) void union_kernel(const unsigned char *__rest
         for (int b = 0; b < B; ++b) any |= mask[(size_t)b * m + j];
         if (any) list[p++] = j;
     }
-    for (int i = threadIdx.x; i < n_ret; i += blockDim.x) list[i] = ret_idx[i];
     if (threadIdx.x == 0) *n_list = n_ret + tot[0];
 }
 
-hipError_t launch_union(const unsigned char *mask, int m, int B, const int *ret_idx, int n_ret, const int *cand_idx,
-                        int n_cand, int *list, int *n_list, hipStream_t s)
+hipError_t launch_union(const unsigned char *mask, int m, int B, int n_ret, const int *cand_idx, int n_cand, int *list,
+                        int *n_list, hipStream_t s)
 {
     int threads = n_cand <= 2048 ? 256 : 1024;
-    hipLaunchKernelGGL(union_kernel, dim3(1), dim3(threads), 0, s, mask, m, B, ret_idx, n_ret, cand_idx, n_cand, list,
-                       n_list);
+    hipLaunchKernelGGL(union_kernel, dim3(1), dim3(threads), 0, s, mask, m, B, n_ret, cand_idx, n_cand, list, n_list);
     return hipGetLastError();
 }
 

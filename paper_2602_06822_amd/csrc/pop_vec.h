@@ -1,0 +1,94 @@
+// 16-byte vector traits for the weight rows: bf16 (8 elements) and float32 (4 elements).
+#pragma once
+#include "pop_internal.h"
+
+namespace pop {
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// bf16 rows: products of two bf16 values are exact in float32, so dot products accumulate in float32
+// (v_dot2_f32_bf16).  float32 rows: dot products accumulate in float64 so that h keeps full float32
+// accuracy even when the sum cancels; the kernels stay HBM-bound either way.
+struct VecBF16 {
+    typedef uint4 vec_t;
+    typedef float acc_t;
+    static constexpr int kElems = 8;
+    static __device__ __forceinline__ vec_t zero() { return make_uint4(0, 0, 0, 0); }
+    static __device__ __forceinline__ float dot(const vec_t &w, const vec_t &x, float acc)
+    {
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.x), __builtin_bit_cast(bf16x2_t, x.x), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.y), __builtin_bit_cast(bf16x2_t, x.y), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.z), __builtin_bit_cast(bf16x2_t, x.z), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, w.w), __builtin_bit_cast(bf16x2_t, x.w), acc, false);
+        return acc;
+    }
+    static __device__ __forceinline__ void axpy(float a, const vec_t &w, float (&acc)[8])
+    {
+        acc[0] = fmaf(a, bf16_lo(w.x), acc[0]);
+        acc[1] = fmaf(a, bf16_hi(w.x), acc[1]);
+        acc[2] = fmaf(a, bf16_lo(w.y), acc[2]);
+        acc[3] = fmaf(a, bf16_hi(w.y), acc[3]);
+        acc[4] = fmaf(a, bf16_lo(w.z), acc[4]);
+        acc[5] = fmaf(a, bf16_hi(w.z), acc[5]);
+        acc[6] = fmaf(a, bf16_lo(w.w), acc[6]);
+        acc[7] = fmaf(a, bf16_hi(w.w), acc[7]);
+    }
+};
+
+struct VecF32 {
+    typedef float4 vec_t;
+    typedef double acc_t;
+    static constexpr int kElems = 4;
+    static __device__ __forceinline__ vec_t zero() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+    static __device__ __forceinline__ double dot(const vec_t &w, const vec_t &x, double acc)
+    {
+        acc = fma((double)w.x, (double)x.x, acc);
+        acc = fma((double)w.y, (double)x.y, acc);
+        acc = fma((double)w.z, (double)x.z, acc);
+        acc = fma((double)w.w, (double)x.w, acc);
+        return acc;
+    }
+    static __device__ __forceinline__ void axpy(float a, const vec_t &w, float (&acc)[8])
+    {
+        acc[0] = fmaf(a, w.x, acc[0]);
+        acc[1] = fmaf(a, w.y, acc[1]);
+        acc[2] = fmaf(a, w.z, acc[2]);
+        acc[3] = fmaf(a, w.w, acc[3]);
+    }
+};
+
+// Dot products of one channel's gate and up rows with x (staged in LDS as vectors), lanes striding the row.
+// Returns per-lane partial sums; the caller reduces across the wave.
+template <class V, int U>
+__device__ __forceinline__ void row_dot_gate_up(const typename V::vec_t *__restrict__ g,
+                                                const typename V::vec_t *__restrict__ u,
+                                                const typename V::vec_t *xs, int nvec, int lane,
+                                                typename V::acc_t &ag, typename V::acc_t &au)
+{
+    typedef typename V::vec_t vec_t;
+    const int group = kWave * U;
+    const int nvec_full = nvec / group * group;
+    ag = 0;
+    au = 0;
+    for (int c0 = 0; c0 < nvec_full; c0 += group) {
+        vec_t wg[U], wu[U];
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            wg[q] = g[c0 + q * kWave + lane];
+            wu[q] = u[c0 + q * kWave + lane];
+        }
+#pragma unroll
+        for (int q = 0; q < U; ++q) {
+            vec_t xv = xs[c0 + q * kWave + lane];
+            ag = V::dot(wg[q], xv, ag);
+            au = V::dot(wu[q], xv, au);
+        }
+    }
+    for (int c = nvec_full + lane; c < nvec; c += kWave) {
+        vec_t wg = g[c], wu = u[c], xv = xs[c];
+        ag = V::dot(wg, xv, ag);
+        au = V::dot(wu, xv, au);
+    }
+}
+
+}  // namespace pop

@@ -80,6 +80,7 @@ class GpuLayer:
         y = torch.empty((B, d), dtype=torch.float32 if ydtype == synth.F32 else torch.int16, device="cuda")
         self.pop.pop_pruned_ffn(self.handle, None, B, None, 0, y, ydtype)
         yh = host(y).astype(np.float64) if ydtype == synth.F32 else bf16_out_to_f64(y)
+        self.pop.pop_layer_sync_status(self.handle)  # raises if an in-kernel bounded wait expired
         return dict(cscore=host(cs)[:, :n_cand], mask=host(mask), active_idx=host(act), n_active=host(na),
                     h=host(h), y=yh)
 
