@@ -12,7 +12,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpop_hip.so")
+LIB_PATH = os.environ.get("POP_HIP_LIB") or os.path.join(_HERE, "libpop_hip.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_06822_amd.build` "

@@ -30,6 +30,10 @@ int hip_fail(hipError_t e, const char *what)
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
 
+#ifdef POP_TRACE
+unsigned long long *g_trace = nullptr;  // profiling builds: device buffer the fused kernel stamps into
+#endif
+
 }  // namespace
 
 struct pop_layer {
@@ -268,6 +272,7 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
     if (B == 1 && L->fused_ok) {
         if ((long long)(L->epoch + 1) * (L->plan.n_wg - 1) > (1LL << 30)) {
             POP_HIP(launch_fill_int(L->sync, 2, 0, s));
+            POP_HIP(launch_fill_int(L->sync + 3, 1, 0, s));
             L->epoch = 0;
         }
         FusedParams p = {};
@@ -291,6 +296,9 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         p.sync = L->sync;
         p.deferred = L->deferred;
         p.epoch = ++L->epoch;
+#ifdef POP_TRACE
+        p.trace = g_trace;
+#endif
         POP_HIP(launch_decode_fused(L->plan, L->is_bf16, p, s));
         L->step_fused = true;
     } else {
@@ -331,8 +339,9 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
         if (!L->has_step) return POP_ESTATE;
         if (T != L->step_B) return POP_ESHAPE;
         if (L->step_fused)
-            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->active_idx + L->n_ret,
-                                       L->step_k.k[0], L->h, L->w, m, L->is_bf16, y, y_bf16, s));
+            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->sync, L->epoch,
+                                       L->active_idx + L->n_ret, L->step_k.k[0], L->h, L->w, m, L->is_bf16, y, y_bf16,
+                                       s));
         else if (T == 1)
             POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->active_idx, nullptr, L->n_ret + L->step_k.k[0], L->h,
                                 nullptr, 0, 1, L->partial, L->n_slabs, y, y_bf16, s));
@@ -399,6 +408,10 @@ int pop_layer_get_norms(pop_layer_t *L, float *nrm, void *stream)
     if (nrm) POP_HIP(hipMemcpyAsync(nrm, L->nrm, (size_t)L->m * 4, hipMemcpyDeviceToDevice, as_stream(stream)));
     return POP_OK;
 }
+
+#ifdef POP_TRACE
+void pop_trace_set_buffer(void *dev_ptr) { g_trace = (unsigned long long *)dev_ptr; }
+#endif
 
 int pop_layer_sync_status(pop_layer_t *L, void *stream)
 {

@@ -4,20 +4,24 @@
 // channels and down columns of the retained and selected channels, each channel's block w[j] = [gate|up|down]
 // being contiguous in memory.
 //
-//   phase A  every workgroup evaluates a share of the candidate channels: h_j = silu(g_j) u_j and the step
-//            score I_j(t) = n_j |h_j| (Eq. 3 with one token); results go to global memory.
+// Work unit: a "round" of kRB channels handled by one whole workgroup.  The workgroup's threads split the d
+// columns (thread t owns 16-byte vector column t), so a channel's gate, up and down rows are each read by one
+// coalesced sweep of the workgroup, x and the partial y live in registers (no LDS staging, no reduction of y
+// across waves), and the only exchange is the per-row gate/up dot product: wave partials go through LDS, one
+// barrier per round.  The next round's rows are loaded into a second register buffer before the current round
+// is reduced, so the barrier never drains the memory pipeline.
+//
+//   phase A  candidate rounds (gate+up only), dealt round-robin to all workgroups: h_j = silu(g_j) u_j and the
+//            step score I_j(t) = n_j |h_j| (Eq. 3 with one token) go to global memory.
 //   select   workgroup 0 owns no retained rows.  It waits until all workgroups have published their phase A
-//            results (bounded spin on a counter; the others never wait for anything before that point), then
-//            runs the top-k selection and publishes the selected list and a done flag.
-//   phase B  every other workgroup owns a contiguous block of retained channels: gate+up dot products, one wave
-//            per row, h kept in LDS (and stored for the caller).
-//   phase C  the same workgroup multiplies its block's down columns by those h values.  Waves own 64-vector
-//            column chunks, so the workgroup's partial y needs no reduction across waves (or a fixed-order one
-//            across row groups when d is small).
-//   phase D  down columns of the selected candidates, dealt round-robin to the workgroups, added into the same
-//            accumulators.  Needs the selection: a workgroup waits (bounded) for the done flag, which in
-//            practice was set long before.  If the bound is ever hit, the workgroup marks its share as
-//            deferred and the tail kernel adds it, so the result is correct and every wave still exits.
+//            results (bounded spin on a counter; nobody waits for anything before that point), then runs the
+//            top-k selection and publishes the selected list and a done flag.
+//   phase B  retained rounds, dealt round-robin to workgroups 1..: gate+up dot products -> h, then the down
+//            rows of the same round, already in registers, are multiplied by h into the partial y.
+//   phase D  down rows of the selected candidates, dealt the same way.  Needs the selection: the workgroup
+//            waits (bounded) for the done flag, which in practice was set long before.  If the bound is ever
+//            hit, the workgroup marks its share as deferred (and stamps the step's epoch into sync[3]) and
+//            the tail kernel adds it, so the result is correct and every wave still exits.
 //   tail     a second small kernel sums the per-workgroup partials in workgroup order (plus deferred shares)
 //            and writes y.
 //
@@ -28,65 +32,154 @@
 
 namespace pop {
 
-constexpr int kFusedGuUnroll = 8;    // 16-byte loads per matrix in flight per lane in the row dot products
-constexpr int kFusedDownUnroll = 8;  // down-column loads in flight per lane
+constexpr int kRB = 2;  // channels per round
 constexpr int kSpinLimit = 1 << 16;
+
+// Optional per-workgroup timestamps (100 MHz wall clock), compiled in only for profiling builds.
+#ifdef POP_TRACE
+#define POP_STAMP(slot)                                                                 \
+    do {                                                                                \
+        if (p.trace && threadIdx.x == 0) p.trace[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64(); \
+    } while (0)
+#else
+#define POP_STAMP(slot) \
+    do {                \
+    } while (0)
+#endif
 
 __device__ __forceinline__ bool spin_until(const int *addr, int target, bool ge)
 {
     for (int it = 0; it < kSpinLimit; ++it) {
         int v = __hip_atomic_load(addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (ge ? (v >= target) : (v == target)) return true;
-        __builtin_amdgcn_s_sleep(4);
+        __builtin_amdgcn_s_sleep(2);
     }
     return false;
 }
 
-template <class V, int CPW>
+template <class V, int PER>
+struct RoundBuf {
+    typename V::vec_t g[kRB][PER], u[kRB][PER], dn[kRB][PER];
+    int j[kRB];  // channel of each slot, -1 when the slot is empty
+};
+
+// Loads the rows of round `round_idx` of a list dealt round-robin to `n_sharers` workgroups (`me` = this one).
+template <class V, int PER, bool GU, bool DN>
+__device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const typename V::vec_t *__restrict__ w, int nvec,
+                                           const int *__restrict__ list, int n_list, int round_idx, int n_sharers,
+                                           int me, const int (&col)[PER], const bool (&ok)[PER])
+{
+#pragma unroll
+    for (int t = 0; t < kRB; ++t) {
+        const int r = (round_idx * n_sharers + me) * kRB + t;
+        const int j = r < n_list ? list[r] : -1;
+        rb.j[t] = j;
+        const typename V::vec_t *row = w + (size_t)(j < 0 ? 0 : j) * 3 * nvec;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const bool ld = ok[q] && j >= 0;
+            if (GU) {
+                rb.g[t][q] = ld ? row[col[q]] : V::zero();
+                rb.u[t][q] = ld ? row[nvec + col[q]] : V::zero();
+            }
+            if (DN) rb.dn[t][q] = ld ? row[2 * nvec + col[q]] : V::zero();
+        }
+    }
+}
+
+// Gate/up dot products of the round's rows with x: lane partials -> wave sums -> LDS -> totals in every thread.
+// One barrier; `part` is double-buffered by the caller (parity of the round).
+template <class V, int PER>
+__device__ __forceinline__ void round_hidden(const RoundBuf<V, PER> &rb, const typename V::vec_t (&xv)[PER],
+                                             typename V::acc_t (*part)[kSelMaxWaves], int wave, int lane, int nw,
+                                             float (&hv)[kRB])
+{
+    typedef typename V::acc_t acc_t;
+#pragma unroll
+    for (int t = 0; t < kRB; ++t) {
+        acc_t ag = 0, au = 0;
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            ag = V::dot(rb.g[t][q], xv[q], ag);
+            au = V::dot(rb.u[t][q], xv[q], au);
+        }
+        ag = wave_sum(ag);
+        au = wave_sum(au);
+        if (lane == 0) {
+            part[2 * t][wave] = ag;
+            part[2 * t + 1][wave] = au;
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < kRB; ++t) {
+        acc_t gs = 0, us = 0;
+        for (int wv = 0; wv < nw; ++wv) {
+            gs += part[2 * t][wv];
+            us += part[2 * t + 1][wv];
+        }
+        hv[t] = rb.j[t] >= 0 ? silu_mul((float)gs, (float)us) : 0.f;
+    }
+}
+
+template <class V, int PER>
 __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
 {
     typedef typename V::vec_t vec_t;
+    typedef typename V::acc_t acc_t;
     constexpr int E = V::kElems;
-    extern __shared__ uint4 smem_raw[];
     __shared__ SelShared sh;
     __shared__ int s_flag;
+    __shared__ acc_t part[2][2 * kRB][kSelMaxWaves];
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int nw = blockDim.x / kWave;
-    const int b = blockIdx.x, n_wg = gridDim.x;
+    const int b = blockIdx.x, n_wg = gridDim.x, n_workers = n_wg - 1, wb = b - 1;
     const int nvec = p.nvec;
     const vec_t *w = reinterpret_cast<const vec_t *>(p.w);
 
-    // dynamic LDS: x | h_s[rows_per_wg] | j_s[rows_per_wg] | red[(groups-1)][ncw*CPW*64*E]
-    vec_t *xs = reinterpret_cast<vec_t *>(smem_raw);
-    float *h_s = reinterpret_cast<float *>(xs + nvec);
-    int *j_s = reinterpret_cast<int *>(h_s + p.rows_per_wg);
-    float *red = reinterpret_cast<float *>(j_s + p.rows_per_wg);
+    POP_STAMP(0);
+    int col[PER];
+    bool ok[PER];
+    vec_t xv[PER];
+#pragma unroll
+    for (int q = 0; q < PER; ++q) {
+        col[q] = tid + q * blockDim.x;
+        ok[q] = col[q] < nvec;
+        xv[q] = ok[q] ? reinterpret_cast<const vec_t *>(p.x)[col[q]] : V::zero();
+    }
 
-    for (int i = tid; i < nvec; i += blockDim.x) xs[i] = reinterpret_cast<const vec_t *>(p.x)[i];
-    // retained rows of this workgroup (workgroup 0 has none)
-    const int r_lo = b == 0 ? 0 : min(p.n_ret, (b - 1) * p.rows_per_wg);
-    const int r_hi = b == 0 ? 0 : min(p.n_ret, r_lo + p.rows_per_wg);
-    const int n_rows = r_hi - r_lo;
-    for (int i = tid; i < n_rows; i += blockDim.x) j_s[i] = p.ret_idx[r_lo + i];
-    __syncthreads();
+    RoundBuf<V, PER> buf_a, buf_b;  // ping-pong: one is reduced while the other's loads are in flight
 
-    // ---- phase A: candidates c = b, b + n_wg, ...; wave takes every nw-th of them
-    for (int i = wave; b + i * n_wg < p.n_cand; i += nw) {
-        const int c = b + i * n_wg;
-        const int j = p.cand_idx[c];
-        const vec_t *g = w + (size_t)j * 3 * nvec;
-        typename V::acc_t ag, au;
-        row_dot_gate_up<V, kFusedGuUnroll>(g, g + nvec, xs, nvec, lane, ag, au);
-        float gs = (float)wave_sum(ag), us = (float)wave_sum(au);
-        if (lane == 0) {
-            float hv = silu_mul(gs, us);
-            p.h[j] = hv;
-            p.cscore[c] = p.nrm[j] * fabsf(hv);
+    // ---- phase A: candidate rounds, shared by all n_wg workgroups
+    {
+        const int my_rounds = (b * kRB < p.n_cand) ? (p.n_cand - b * kRB + n_wg * kRB - 1) / (n_wg * kRB) : 0;
+        auto finish = [&](const RoundBuf<V, PER> &rb, int i) {
+            float hv[kRB];
+            round_hidden<V, PER>(rb, xv, part[i & 1], wave, lane, nw, hv);
+            if (tid == 0) {
+#pragma unroll
+                for (int t = 0; t < kRB; ++t)
+                    if (rb.j[t] >= 0) {
+                        const int c = (i * n_wg + b) * kRB + t;
+                        p.h[rb.j[t]] = hv[t];
+                        p.cscore[c] = p.nrm[rb.j[t]] * fabsf(hv[t]);
+                    }
+            }
+        };
+        if (my_rounds > 0) load_round<V, PER, true, false>(buf_a, w, nvec, p.cand_idx, p.n_cand, 0, n_wg, b, col, ok);
+        for (int i = 0; i < my_rounds; i += 2) {
+            if (i + 1 < my_rounds)
+                load_round<V, PER, true, false>(buf_b, w, nvec, p.cand_idx, p.n_cand, i + 1, n_wg, b, col, ok);
+            finish(buf_a, i);
+            if (i + 2 < my_rounds)
+                load_round<V, PER, true, false>(buf_a, w, nvec, p.cand_idx, p.n_cand, i + 2, n_wg, b, col, ok);
+            if (i + 1 < my_rounds) finish(buf_b, i + 1);
         }
     }
     __syncthreads();
+    POP_STAMP(1);
     if (b != 0) {
         if (tid == 0) {
             __threadfence();
@@ -95,12 +188,13 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     } else {
         // ---- select (workgroup 0 only)
         if (tid == 0) {
-            bool ok = spin_until(&p.sync[0], p.epoch * (n_wg - 1), true);  // the counter only grows within a partition
-            if (!ok) p.sync[2] = 1;
+            bool ok_a = spin_until(&p.sync[0], p.epoch * n_workers, true);  // the counter only grows within a partition
+            if (!ok_a) p.sync[2] = 1;
             __threadfence();
-            s_flag = ok ? 1 : 0;
+            s_flag = ok_a ? 1 : 0;
         }
         __syncthreads();
+        POP_STAMP(2);
         if (s_flag) {
             block_select_candidates(p.cscore, p.cand_idx, p.n_cand, p.k, p.mask, p.active_idx + p.n_ret, sh);
             if (tid == 0 && p.n_active) *p.n_active = p.n_ret + p.k;
@@ -110,129 +204,92 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
                 __hip_atomic_store(&p.sync[1], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+        POP_STAMP(3);
         return;
     }
 
-    // ---- phase B: gate/up of the block's retained rows, one wave per row
-    for (int r = wave; r < n_rows; r += nw) {
-        const int j = j_s[r];
-        const vec_t *g = w + (size_t)j * 3 * nvec;
-        typename V::acc_t ag, au;
-        row_dot_gate_up<V, kFusedGuUnroll>(g, g + nvec, xs, nvec, lane, ag, au);
-        float gs = (float)wave_sum(ag), us = (float)wave_sum(au);
-        if (lane == 0) {
-            float hv = silu_mul(gs, us);
-            h_s[r] = hv;
-            p.h[j] = hv;
-        }
-    }
-    __syncthreads();
-
-    // ---- phase C: down columns of the block; wave = (row group grp, chunk-wave cw)
-    const int cw = wave % p.ncw, grp = wave / p.ncw;
-    const bool down_wave = grp < p.groups;
-    float acc[CPW][8];
+    float acc[PER][8];
 #pragma unroll
-    for (int q = 0; q < CPW; ++q)
+    for (int q = 0; q < PER; ++q)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
-    int col[CPW];
-    bool col_ok[CPW];
-#pragma unroll
-    for (int q = 0; q < CPW; ++q) {
-        col[q] = (cw + q * p.ncw) * kWave + lane;
-        col_ok[q] = down_wave && col[q] < nvec;
-    }
-    if (down_wave) {
-        int r = grp;
-        for (; r + (kFusedDownUnroll - 1) * p.groups < n_rows; r += kFusedDownUnroll * p.groups) {
-            vec_t wv[kFusedDownUnroll][CPW];
-            float hv[kFusedDownUnroll];
-#pragma unroll
-            for (int u = 0; u < kFusedDownUnroll; ++u) {
-                const int rr = r + u * p.groups;
-                const size_t base = ((size_t)j_s[rr] * 3 + 2) * nvec;
-                hv[u] = h_s[rr];
-#pragma unroll
-                for (int q = 0; q < CPW; ++q) wv[u][q] = col_ok[q] ? w[base + col[q]] : V::zero();
-            }
-#pragma unroll
-            for (int u = 0; u < kFusedDownUnroll; ++u)
-#pragma unroll
-                for (int q = 0; q < CPW; ++q) V::axpy(hv[u], wv[u][q], acc[q]);
-        }
-        for (; r < n_rows; r += p.groups) {
-            const size_t base = ((size_t)j_s[r] * 3 + 2) * nvec;
-            const float hv = h_s[r];
-#pragma unroll
-            for (int q = 0; q < CPW; ++q) {
-                vec_t wv = col_ok[q] ? w[base + col[q]] : V::zero();
-                V::axpy(hv, wv, acc[q]);
-            }
-        }
-    }
 
-    // ---- phase D: selected candidates i = (b-1), (b-1) + (n_wg-1), ...; needs the selection
+    // ---- phase B: retained rounds, shared by workgroups 1..n_wg-1
+    {
+        const int my_rounds =
+            (wb * kRB < p.n_ret) ? (p.n_ret - wb * kRB + n_workers * kRB - 1) / (n_workers * kRB) : 0;
+        auto finish = [&](const RoundBuf<V, PER> &rb, int i) {
+            float hv[kRB];
+            round_hidden<V, PER>(rb, xv, part[i & 1], wave, lane, nw, hv);
+            if (tid == 0) {
+#pragma unroll
+                for (int t = 0; t < kRB; ++t)
+                    if (rb.j[t] >= 0) p.h[rb.j[t]] = hv[t];
+            }
+#pragma unroll
+            for (int t = 0; t < kRB; ++t)
+#pragma unroll
+                for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
+        };
+        if (my_rounds > 0) load_round<V, PER, true, true>(buf_a, w, nvec, p.ret_idx, p.n_ret, 0, n_workers, wb, col, ok);
+        for (int i = 0; i < my_rounds; i += 2) {
+            if (i + 1 < my_rounds)
+                load_round<V, PER, true, true>(buf_b, w, nvec, p.ret_idx, p.n_ret, i + 1, n_workers, wb, col, ok);
+            finish(buf_a, i);
+            if (i + 2 < my_rounds)
+                load_round<V, PER, true, true>(buf_a, w, nvec, p.ret_idx, p.n_ret, i + 2, n_workers, wb, col, ok);
+            if (i + 1 < my_rounds) finish(buf_b, i + 1);
+        }
+    }
+    POP_STAMP(2);
+
+    // ---- phase D: selected candidates; needs the selection
+    POP_STAMP(3);
     if (tid == 0) {
-        bool ok = spin_until(&p.sync[1], p.epoch, false);
+        bool ok_d = spin_until(&p.sync[1], p.epoch, false);
         __threadfence();
-        s_flag = ok ? 1 : 0;
-        p.deferred[b] = ok ? 0 : 1;
-        if (!ok) p.sync[2] = 1;
+        s_flag = ok_d ? 1 : 0;
+        p.deferred[b] = ok_d ? 0 : 1;
+        if (!ok_d) {
+            p.sync[2] = 1;
+            __hip_atomic_store(&p.sync[3], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
     __syncthreads();
-    if (s_flag && down_wave) {
+    POP_STAMP(4);
+    if (s_flag) {
         const int *sel = p.active_idx + p.n_ret;
-        int n_mine = 0;  // index among this workgroup's selected rows, dealt to row groups
-        for (int i = b - 1; i < p.k; i += n_wg - 1, ++n_mine) {
-            if (n_mine % p.groups != grp) continue;
-            const int j = sel[i];
-            const float hv = p.h[j];
-            const size_t base = ((size_t)j * 3 + 2) * nvec;
+        const int my_rounds = (wb * kRB < p.k) ? (p.k - wb * kRB + n_workers * kRB - 1) / (n_workers * kRB) : 0;
+        for (int i = 0; i < my_rounds; ++i) {
+            load_round<V, PER, false, true>(buf_a, w, nvec, sel, p.k, i, n_workers, wb, col, ok);
 #pragma unroll
-            for (int q = 0; q < CPW; ++q) {
-                vec_t wv = col_ok[q] ? w[base + col[q]] : V::zero();
-                V::axpy(hv, wv, acc[q]);
+            for (int t = 0; t < kRB; ++t) {
+                const float hv = buf_a.j[t] >= 0 ? p.h[buf_a.j[t]] : 0.f;
+#pragma unroll
+                for (int q = 0; q < PER; ++q) V::axpy(hv, buf_a.dn[t][q], acc[q]);
             }
         }
     }
 
-    // ---- partial y of this workgroup: combine row groups in group order, then store
-    const int chunk_floats = kWave * E;  // floats per (chunk, wave)
-    if (p.groups > 1) {
-        if (down_wave && grp > 0) {
+    // ---- partial y of this workgroup
+    POP_STAMP(5);
+    float *dst = p.partial + (size_t)b * p.d;
 #pragma unroll
-            for (int q = 0; q < CPW; ++q)
+    for (int q = 0; q < PER; ++q)
+        if (ok[q]) {
 #pragma unroll
-                for (int e = 0; e < E; ++e)
-                    red[((size_t)(grp - 1) * p.ncw * CPW + cw * CPW + q) * chunk_floats + e * kWave + lane] = acc[q][e];
+            for (int e = 0; e < E; e += 4)
+                *reinterpret_cast<float4 *>(dst + (size_t)col[q] * E + e) =
+                    make_float4(acc[q][e], acc[q][e + 1], acc[q][e + 2], acc[q][e + 3]);
         }
-        __syncthreads();
-        if (down_wave && grp == 0) {
-            for (int g2 = 1; g2 < p.groups; ++g2)
-#pragma unroll
-                for (int q = 0; q < CPW; ++q)
-#pragma unroll
-                    for (int e = 0; e < E; ++e)
-                        acc[q][e] += red[((size_t)(g2 - 1) * p.ncw * CPW + cw * CPW + q) * chunk_floats + e * kWave + lane];
-        }
-    }
-    if (down_wave && grp == 0) {
-        float *dst = p.partial + (size_t)b * p.d;
-#pragma unroll
-        for (int q = 0; q < CPW; ++q)
-            if (col_ok[q]) {
-#pragma unroll
-                for (int e = 0; e < E; ++e) dst[(size_t)col[q] * E + e] = acc[q][e];
-            }
-    }
+    POP_STAMP(6);
 }
 
 // y[o] = sum over workgroups 1..n_wg-1 (in order) of partial[b][o], plus shares a workgroup deferred.
 // A workgroup owns 64 outputs; its 4 waves sum contiguous quarters of the partial rows and combine in wave order.
 __global__ __launch_bounds__(256) void decode_tail_kernel(const float *__restrict__ partial, int n_wg, int d,
-                                                          const int *__restrict__ deferred,
-                                                          const int *__restrict__ sel, int k,
+                                                          const int *__restrict__ deferred, const int *sync,
+                                                          int epoch, const int *__restrict__ sel, int k,
                                                           const float *__restrict__ h, const void *__restrict__ w,
                                                           int m, int is_bf16, void *__restrict__ y, int y_bf16)
 {
@@ -257,16 +314,21 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(const float *__restric
     __syncthreads();
     if (q == 0 && o < d) {
         float v = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
-        for (int b = 1; b < n_wg; ++b) {
+        const bool any_deferred = sync[3] == epoch;  // set only when some workgroup gave up waiting in this step
+        for (int b = 1; any_deferred && b < n_wg; ++b) {
             if (!deferred[b]) continue;
-            for (int i = b - 1; i < k; i += n_wg - 1) {
-                const int j = sel[i];
-                if (j < 0 || j >= m) continue;  // selection never ran: the step is flagged invalid, stay in bounds
-                const size_t idx = ((size_t)j * 3 + 2) * d + o;
-                const float wv = is_bf16 ? __uint_as_float(((uint32_t)((const uint16_t *)w)[idx]) << 16)
-                                         : ((const float *)w)[idx];
-                v = fmaf(h[j], wv, v);
-            }
+            // the workgroup's phase D share: rows (i * n_workers + b - 1) * kRB + t, as in the fused kernel
+            for (int i = 0; (i * (n_wg - 1) + b - 1) * kRB < k; ++i)
+                for (int t = 0; t < kRB; ++t) {
+                    const int r = (i * (n_wg - 1) + b - 1) * kRB + t;
+                    if (r >= k) break;
+                    const int j = sel[r];
+                    if (j < 0 || j >= m) continue;  // selection never ran: the step is flagged invalid, stay in bounds
+                    const size_t idx = ((size_t)j * 3 + 2) * d + o;
+                    const float wv = is_bf16 ? __uint_as_float(((uint32_t)((const uint16_t *)w)[idx]) << 16)
+                                             : ((const float *)w)[idx];
+                    v = fmaf(h[j], wv, v);
+                }
         }
         if (y_bf16)
             ((uint16_t *)y)[o] = f32_to_bf16(v);
@@ -276,50 +338,36 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(const float *__restric
 }
 
 // ---------------------------------------------------------------- host side
-template <class V, int CPW>
+template <class V, int PER>
 static hipError_t fused_launch(const FusedPlan &pl, FusedParams &p, hipStream_t s)
 {
-    if (pl.lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&decode_fused_kernel<V, CPW>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)pl.lds);
-        if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL((decode_fused_kernel<V, CPW>), dim3(pl.n_wg), dim3(pl.block), pl.lds, s, p);
+    hipLaunchKernelGGL((decode_fused_kernel<V, PER>), dim3(pl.n_wg), dim3(pl.block), 0, s, p);
     return hipGetLastError();
 }
 
-template <class V, int CPW>
-static hipError_t fused_occupancy(int block, size_t lds, int *blocks_per_cu)
+template <class V, int PER>
+static hipError_t fused_occupancy(int block, int *blocks_per_cu)
 {
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_fused_kernel<V, CPW>, block, lds);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_fused_kernel<V, PER>, block, 0);
 }
 
-int fused_max_workgroups() { return 512; }
+int fused_max_workgroups() { return 1024; }
 
 // Chooses the launch shape; returns false when this d is not supported by the fused kernel.
 bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl)
 {
     const int E = is_bf16 ? 8 : 4, nvec = d / E;
-    const int n_cc = (nvec + kWave - 1) / kWave;
-    int cpw = 1;
-    if (n_cc > 16) cpw = 2;
-    const int ncw = (n_cc + cpw - 1) / cpw;
-    if (ncw > 16) return false;
-    int groups = ncw >= 8 ? 1 : 8 / ncw;
-    if (groups < 1) groups = 1;
-    pl->ncw = ncw;
-    pl->groups = groups;
-    pl->cpw = cpw;
-    pl->block = ncw * groups * kWave;
-    int workers = (n_ret + 7) / 8;  // at least ~8 retained rows per workgroup
-    const int by_cand = (n_cand + 3) / 4;
+    int per = 1;
+    if (nvec > 1024) per = 2;
+    if (nvec > 2048) return false;
+    pl->per = per;
+    pl->block = ((nvec + per * kWave - 1) / (per * kWave)) * kWave;
+    int workers = (n_ret + kRB - 1) / kRB;
+    const int by_cand = (n_cand + kRB - 1) / kRB;
     if (by_cand > workers) workers = by_cand;
     if (workers < 1) workers = 1;
     if (workers > wg_target - 1) workers = wg_target - 1;
     pl->n_wg = workers + 1;
-    pl->rows_per_wg = n_ret > 0 ? (n_ret + workers - 1) / workers : 1;
-    pl->lds = (size_t)nvec * 16 + (size_t)pl->rows_per_wg * 8 +
-              (size_t)(groups > 1 ? (groups - 1) : 0) * ncw * cpw * kWave * E * 4;
     return true;
 }
 
@@ -328,11 +376,9 @@ hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int 
     int per_cu = 0;
     hipError_t e;
     if (is_bf16)
-        e = pl.cpw == 1 ? fused_occupancy<VecBF16, 1>(pl.block, pl.lds, &per_cu)
-                        : fused_occupancy<VecBF16, 2>(pl.block, pl.lds, &per_cu);
+        e = pl.per == 1 ? fused_occupancy<VecBF16, 1>(pl.block, &per_cu) : fused_occupancy<VecBF16, 2>(pl.block, &per_cu);
     else
-        e = pl.cpw == 1 ? fused_occupancy<VecF32, 1>(pl.block, pl.lds, &per_cu)
-                        : fused_occupancy<VecF32, 2>(pl.block, pl.lds, &per_cu);
+        e = pl.per == 1 ? fused_occupancy<VecF32, 1>(pl.block, &per_cu) : fused_occupancy<VecF32, 2>(pl.block, &per_cu);
     if (e != hipSuccess) return e;
     *max_wg = per_cu * n_cu;
     return hipSuccess;
@@ -340,19 +386,16 @@ hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int 
 
 hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p, hipStream_t s)
 {
-    p.rows_per_wg = pl.rows_per_wg;
-    p.ncw = pl.ncw;
-    p.groups = pl.groups;
-    if (is_bf16)
-        return pl.cpw == 1 ? fused_launch<VecBF16, 1>(pl, p, s) : fused_launch<VecBF16, 2>(pl, p, s);
-    return pl.cpw == 1 ? fused_launch<VecF32, 1>(pl, p, s) : fused_launch<VecF32, 2>(pl, p, s);
+    if (is_bf16) return pl.per == 1 ? fused_launch<VecBF16, 1>(pl, p, s) : fused_launch<VecBF16, 2>(pl, p, s);
+    return pl.per == 1 ? fused_launch<VecF32, 1>(pl, p, s) : fused_launch<VecF32, 2>(pl, p, s);
 }
 
-hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sel, int k,
-                              const float *h, const void *w, int m, int is_bf16, void *y, int y_bf16, hipStream_t s)
+hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync, int epoch,
+                              const int *sel, int k, const float *h, const void *w, int m, int is_bf16, void *y,
+                              int y_bf16, hipStream_t s)
 {
     hipLaunchKernelGGL(decode_tail_kernel, dim3((d + kWave - 1) / kWave), dim3(256), 0, s, partial, n_wg, d, deferred,
-                       sel, k, h, w, m, is_bf16, y, y_bf16);
+                       sync, epoch, sel, k, h, w, m, is_bf16, y, y_bf16);
     return hipGetLastError();
 }
 
