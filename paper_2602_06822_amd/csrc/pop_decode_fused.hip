@@ -27,6 +27,8 @@
 //
 // Waiting is safe because the launch is sized to be co-resident (host checks the occupancy) and both waits
 // are bounded; nothing spins without an exit.
+#include <type_traits>
+
 #include "pop_select_dev.h"
 #include "pop_vec.h"
 
@@ -57,22 +59,23 @@ __device__ __forceinline__ bool spin_until(const int *addr, int target, bool ge)
     return false;
 }
 
+constexpr int kKeepRounds = 64;              // rounds whose indices / results are staged in LDS at a time
+constexpr int kKeep = kKeepRounds * kRB;
+
 template <class V, int PER>
 struct RoundBuf {
     typename V::vec_t g[kRB][PER], u[kRB][PER], dn[kRB][PER];
     int j[kRB];  // channel of each slot, -1 when the slot is empty
 };
 
-// Loads the rows of round `round_idx` of a list dealt round-robin to `n_sharers` workgroups (`me` = this one).
+// Loads the rows of one round; js points at the round's kRB staged channel indices (LDS), -1 = empty slot.
 template <class V, int PER, bool GU, bool DN>
 __device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const typename V::vec_t *__restrict__ w, int nvec,
-                                           const int *__restrict__ list, int n_list, int round_idx, int n_sharers,
-                                           int me, const int (&col)[PER], const bool (&ok)[PER])
+                                           const int *js, const int (&col)[PER], const bool (&ok)[PER])
 {
 #pragma unroll
     for (int t = 0; t < kRB; ++t) {
-        const int r = (round_idx * n_sharers + me) * kRB + t;
-        const int j = r < n_list ? list[r] : -1;
+        const int j = js[t];
         rb.j[t] = j;
         const typename V::vec_t *row = w + (size_t)(j < 0 ? 0 : j) * 3 * nvec;
 #pragma unroll
@@ -87,14 +90,37 @@ __device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const typename 
     }
 }
 
+// Sum over the 16 lanes of each DPP row, result in every lane of the row (4 cross-lane adds, no LDS).
+__device__ __forceinline__ float dpp_row_sum(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xf, 0xf, true));   // quad_perm 1,0,3,2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xf, 0xf, true));   // quad_perm 2,3,0,1
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xf, 0xf, true));  // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xf, 0xf, true));  // row_mirror
+    return v;
+}
+
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+__device__ __forceinline__ float wave_total(float v)
+{
+    const float r = dpp_row_sum(v);
+    return (lane_value(r, 0) + lane_value(r, 16)) + (lane_value(r, 32) + lane_value(r, 48));
+}
+__device__ __forceinline__ double wave_total(double v) { return wave_sum(v); }
+
 // Gate/up dot products of the round's rows with x: lane partials -> wave sums -> LDS -> totals in every thread.
-// One barrier; `part` is double-buffered by the caller (parity of the round).
+// One barrier; `part` ([2*kRB][16], entries of absent waves stay zero) is double-buffered by the caller.
 template <class V, int PER>
 __device__ __forceinline__ void round_hidden(const RoundBuf<V, PER> &rb, const typename V::vec_t (&xv)[PER],
                                              typename V::acc_t (*part)[kSelMaxWaves], int wave, int lane, int nw,
                                              float (&hv)[kRB])
 {
     typedef typename V::acc_t acc_t;
+    static_assert(2 * kRB * kSelMaxWaves == kWave, "one LDS word per lane in the cross-wave step");
 #pragma unroll
     for (int t = 0; t < kRB; ++t) {
         acc_t ag = 0, au = 0;
@@ -103,22 +129,32 @@ __device__ __forceinline__ void round_hidden(const RoundBuf<V, PER> &rb, const t
             ag = V::dot(rb.g[t][q], xv[q], ag);
             au = V::dot(rb.u[t][q], xv[q], au);
         }
-        ag = wave_sum(ag);
-        au = wave_sum(au);
+        ag = wave_total(ag);
+        au = wave_total(au);
         if (lane == 0) {
             part[2 * t][wave] = ag;
             part[2 * t + 1][wave] = au;
         }
     }
     __syncthreads();
+    if constexpr (sizeof(acc_t) == 4) {
+        // lane l holds value l/16 of wave l%16; a DPP row sum adds the waves in a fixed tree order
+        const float tot = dpp_row_sum((&part[0][0])[lane]);
 #pragma unroll
-    for (int t = 0; t < kRB; ++t) {
-        acc_t gs = 0, us = 0;
-        for (int wv = 0; wv < nw; ++wv) {
-            gs += part[2 * t][wv];
-            us += part[2 * t + 1][wv];
+        for (int t = 0; t < kRB; ++t) {
+            const float gs = lane_value(tot, 32 * t), us = lane_value(tot, 32 * t + 16);
+            hv[t] = rb.j[t] >= 0 ? silu_mul(gs, us) : 0.f;
         }
-        hv[t] = rb.j[t] >= 0 ? silu_mul((float)gs, (float)us) : 0.f;
+    } else {
+#pragma unroll
+        for (int t = 0; t < kRB; ++t) {
+            acc_t gs = 0, us = 0;
+            for (int wv = 0; wv < nw; ++wv) {
+                gs += part[2 * t][wv];
+                us += part[2 * t + 1][wv];
+            }
+            hv[t] = rb.j[t] >= 0 ? silu_mul((float)gs, (float)us) : 0.f;
+        }
     }
 }
 
@@ -131,6 +167,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     __shared__ SelShared sh;
     __shared__ int s_flag;
     __shared__ acc_t part[2][2 * kRB][kSelMaxWaves];
+    __shared__ int j_s[kKeep];    // channel indices of the staged rounds
+    __shared__ float h_s[kKeep];  // their hidden activations, flushed to global memory outside the streaming loop
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -149,34 +187,60 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
         ok[q] = col[q] < nvec;
         xv[q] = ok[q] ? reinterpret_cast<const vec_t *>(p.x)[col[q]] : V::zero();
     }
+    for (int i = tid; i < 2 * 2 * kRB * kSelMaxWaves; i += blockDim.x) (&part[0][0][0])[i] = 0;
 
     RoundBuf<V, PER> buf_a, buf_b;  // ping-pong: one is reduced while the other's loads are in flight
+
+    // Streams `my_rounds` rounds of a list dealt round-robin (round i of sharer `me` = rows (i*n_sh + me)*kRB + t).
+    // No global stores happen inside the streaming loop (a store would make the next wait drain every load in
+    // flight, prefetched ones included): h is staged in LDS and flushed per chunk of kKeepRounds rounds.
+    auto stream_phase = [&](auto with_down, const int *list, int n_list, int n_sh, int me, int my_rounds, auto consume,
+                            auto flush) {
+        constexpr bool DN = decltype(with_down)::value;
+        for (int base = 0; base < my_rounds; base += kKeepRounds) {
+            const int nr = min(kKeepRounds, my_rounds - base);
+            for (int e = tid; e < nr * kRB; e += blockDim.x) {
+                const int r = ((base + e / kRB) * n_sh + me) * kRB + e % kRB;
+                j_s[e] = r < n_list ? list[r] : -1;
+            }
+            __syncthreads();
+            load_round<V, PER, true, DN>(buf_a, w, nvec, j_s, col, ok);
+            for (int i = 0; i < nr; i += 2) {
+                if (i + 1 < nr) load_round<V, PER, true, DN>(buf_b, w, nvec, j_s + (i + 1) * kRB, col, ok);
+                {
+                    float hv[kRB];
+                    round_hidden<V, PER>(buf_a, xv, part[0], wave, lane, nw, hv);
+                    if (tid == 0)
+#pragma unroll
+                        for (int t = 0; t < kRB; ++t) h_s[i * kRB + t] = hv[t];
+                    consume(buf_a, hv);
+                }
+                if (i + 2 < nr) load_round<V, PER, true, DN>(buf_a, w, nvec, j_s + (i + 2) * kRB, col, ok);
+                if (i + 1 < nr) {
+                    float hv[kRB];
+                    round_hidden<V, PER>(buf_b, xv, part[1], wave, lane, nw, hv);
+                    if (tid == 0)
+#pragma unroll
+                        for (int t = 0; t < kRB; ++t) h_s[(i + 1) * kRB + t] = hv[t];
+                    consume(buf_b, hv);
+                }
+            }
+            __syncthreads();
+            for (int e = tid; e < nr * kRB; e += blockDim.x)
+                if (j_s[e] >= 0) flush(j_s[e], h_s[e], ((base + e / kRB) * n_sh + me) * kRB + e % kRB);
+            __syncthreads();
+        }
+    };
 
     // ---- phase A: candidate rounds, shared by all n_wg workgroups
     {
         const int my_rounds = (b * kRB < p.n_cand) ? (p.n_cand - b * kRB + n_wg * kRB - 1) / (n_wg * kRB) : 0;
-        auto finish = [&](const RoundBuf<V, PER> &rb, int i) {
-            float hv[kRB];
-            round_hidden<V, PER>(rb, xv, part[i & 1], wave, lane, nw, hv);
-            if (tid == 0) {
-#pragma unroll
-                for (int t = 0; t < kRB; ++t)
-                    if (rb.j[t] >= 0) {
-                        const int c = (i * n_wg + b) * kRB + t;
-                        p.h[rb.j[t]] = hv[t];
-                        p.cscore[c] = p.nrm[rb.j[t]] * fabsf(hv[t]);
-                    }
-            }
-        };
-        if (my_rounds > 0) load_round<V, PER, true, false>(buf_a, w, nvec, p.cand_idx, p.n_cand, 0, n_wg, b, col, ok);
-        for (int i = 0; i < my_rounds; i += 2) {
-            if (i + 1 < my_rounds)
-                load_round<V, PER, true, false>(buf_b, w, nvec, p.cand_idx, p.n_cand, i + 1, n_wg, b, col, ok);
-            finish(buf_a, i);
-            if (i + 2 < my_rounds)
-                load_round<V, PER, true, false>(buf_a, w, nvec, p.cand_idx, p.n_cand, i + 2, n_wg, b, col, ok);
-            if (i + 1 < my_rounds) finish(buf_b, i + 1);
-        }
+        stream_phase(
+            std::false_type{}, p.cand_idx, p.n_cand, n_wg, b, my_rounds, [&](const RoundBuf<V, PER> &, const float(&)[kRB]) {},
+            [&](int j, float hv, int c) {
+                p.h[j] = hv;
+                p.cscore[c] = p.nrm[j] * fabsf(hv);
+            });
     }
     __syncthreads();
     POP_STAMP(1);
@@ -218,28 +282,15 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     {
         const int my_rounds =
             (wb * kRB < p.n_ret) ? (p.n_ret - wb * kRB + n_workers * kRB - 1) / (n_workers * kRB) : 0;
-        auto finish = [&](const RoundBuf<V, PER> &rb, int i) {
-            float hv[kRB];
-            round_hidden<V, PER>(rb, xv, part[i & 1], wave, lane, nw, hv);
-            if (tid == 0) {
+        stream_phase(
+            std::true_type{}, p.ret_idx, p.n_ret, n_workers, wb, my_rounds,
+            [&](const RoundBuf<V, PER> &rb, const float(&hv)[kRB]) {
 #pragma unroll
                 for (int t = 0; t < kRB; ++t)
-                    if (rb.j[t] >= 0) p.h[rb.j[t]] = hv[t];
-            }
 #pragma unroll
-            for (int t = 0; t < kRB; ++t)
-#pragma unroll
-                for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
-        };
-        if (my_rounds > 0) load_round<V, PER, true, true>(buf_a, w, nvec, p.ret_idx, p.n_ret, 0, n_workers, wb, col, ok);
-        for (int i = 0; i < my_rounds; i += 2) {
-            if (i + 1 < my_rounds)
-                load_round<V, PER, true, true>(buf_b, w, nvec, p.ret_idx, p.n_ret, i + 1, n_workers, wb, col, ok);
-            finish(buf_a, i);
-            if (i + 2 < my_rounds)
-                load_round<V, PER, true, true>(buf_a, w, nvec, p.ret_idx, p.n_ret, i + 2, n_workers, wb, col, ok);
-            if (i + 1 < my_rounds) finish(buf_b, i + 1);
-        }
+                    for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
+            },
+            [&](int j, float hv, int) { p.h[j] = hv; });
     }
     POP_STAMP(2);
 
@@ -260,14 +311,23 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     if (s_flag) {
         const int *sel = p.active_idx + p.n_ret;
         const int my_rounds = (wb * kRB < p.k) ? (p.k - wb * kRB + n_workers * kRB - 1) / (n_workers * kRB) : 0;
-        for (int i = 0; i < my_rounds; ++i) {
-            load_round<V, PER, false, true>(buf_a, w, nvec, sel, p.k, i, n_workers, wb, col, ok);
-#pragma unroll
-            for (int t = 0; t < kRB; ++t) {
-                const float hv = buf_a.j[t] >= 0 ? p.h[buf_a.j[t]] : 0.f;
-#pragma unroll
-                for (int q = 0; q < PER; ++q) V::axpy(hv, buf_a.dn[t][q], acc[q]);
+        for (int base = 0; base < my_rounds; base += kKeepRounds) {
+            const int nr = min(kKeepRounds, my_rounds - base);
+            for (int e = tid; e < nr * kRB; e += blockDim.x) {
+                const int r = ((base + e / kRB) * n_workers + wb) * kRB + e % kRB;
+                const int j = r < p.k ? sel[r] : -1;
+                j_s[e] = j;
+                h_s[e] = j >= 0 ? p.h[j] : 0.f;
             }
+            __syncthreads();
+            for (int i = 0; i < nr; ++i) {
+                load_round<V, PER, false, true>(buf_a, w, nvec, j_s + i * kRB, col, ok);
+#pragma unroll
+                for (int t = 0; t < kRB; ++t)
+#pragma unroll
+                    for (int q = 0; q < PER; ++q) V::axpy(h_s[i * kRB + t], buf_a.dn[t][q], acc[q]);
+            }
+            __syncthreads();
         }
     }
 
