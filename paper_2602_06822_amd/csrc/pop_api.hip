@@ -56,8 +56,7 @@ struct pop_layer {
     int step_B = 0;
     bool fused_ok = false;             // the fused kernel supports this partition
     FusedPlan plan = {};
-    int epoch = 0;
-    int *sync = nullptr;               // [4]
+    int *sync = nullptr;               // [8]
     int *deferred = nullptr;           // [fused_max_workgroups]
     BatchK step_k = {};
     float *h = nullptr;                // [max_batch][m]
@@ -188,7 +187,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         {(void **)&L->n_ulist, 4},
         {(void **)&L->partial, ((size_t)L->n_slabs * B > (size_t)fused_max_workgroups() ? (size_t)L->n_slabs * B
                                                                                         : (size_t)fused_max_workgroups()) * d * 4},
-        {(void **)&L->sync, 16},
+        {(void **)&L->sync, 32},
         {(void **)&L->deferred, (size_t)fused_max_workgroups() * 4},
     };
     for (const Req &r : reqs) {
@@ -201,7 +200,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     }
     hipStream_t s = as_stream(stream);
     hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w, L->nrm, is_bf16, s);
-    if (e == hipSuccess) e = launch_fill_int(L->sync, 4, 0, s);
+    if (e == hipSuccess) e = launch_fill_int(L->sync, 8, 0, s);
     if (e == hipSuccess) e = launch_fill_int(L->deferred, fused_max_workgroups(), 0, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
@@ -242,8 +241,7 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
             L->fused_ok = fused_plan(L->d, L->is_bf16, n_ret, n_cand, max_wg, &L->plan) && L->plan.n_wg <= max_wg;
         }
     }
-    POP_HIP(launch_fill_int(L->sync, 4, 0, s));
-    L->epoch = 0;
+    POP_HIP(launch_fill_int(L->sync, 8, 0, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
@@ -270,11 +268,6 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
     const int m = L->m, n_ret = L->n_ret, n_cand = L->n_cand;
     L->has_step = false;
     if (B == 1 && L->fused_ok) {
-        if ((long long)(L->epoch + 1) * (L->plan.n_wg - 1) > (1LL << 30)) {
-            POP_HIP(launch_fill_int(L->sync, 2, 0, s));
-            POP_HIP(launch_fill_int(L->sync + 3, 1, 0, s));
-            L->epoch = 0;
-        }
         FusedParams p = {};
         p.w = L->w;
         p.x = x_t;
@@ -295,7 +288,6 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         p.partial = L->partial;
         p.sync = L->sync;
         p.deferred = L->deferred;
-        p.epoch = ++L->epoch;
 #ifdef POP_TRACE
         p.trace = g_trace;
 #endif
@@ -339,8 +331,7 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
         if (!L->has_step) return POP_ESTATE;
         if (T != L->step_B) return POP_ESHAPE;
         if (L->step_fused)
-            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->sync, L->epoch,
-                                       L->active_idx + L->n_ret, L->step_k.k[0], L->h, L->w, m, L->is_bf16, y, y_bf16,
+            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->sync, L->active_idx + L->n_ret, L->step_k.k[0], L->h, L->w, m, L->is_bf16, y, y_bf16,
                                        s));
         else if (T == 1)
             POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->active_idx, nullptr, L->n_ret + L->step_k.k[0], L->h,

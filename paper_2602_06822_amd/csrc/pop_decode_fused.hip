@@ -20,7 +20,7 @@
 //            rows of the same round, already in registers, are multiplied by h into the partial y.
 //   phase D  down rows of the selected candidates, dealt the same way.  Needs the selection: the workgroup
 //            waits (bounded) for the done flag, which in practice was set long before.  If the bound is ever
-//            hit, the workgroup marks its share as deferred (and stamps the step's epoch into sync[3]) and
+//            hit, the workgroup marks its share as deferred (and raises sync[3]) and
 //            the tail kernel adds it, so the result is correct and every wave still exits.
 //   tail     a second small kernel sums the per-workgroup partials in workgroup order (plus deferred shares)
 //            and writes y.
@@ -49,11 +49,12 @@ constexpr int kSpinLimit = 1 << 16;
     } while (0)
 #endif
 
-__device__ __forceinline__ bool spin_until(const int *addr, int target, bool ge)
+// Bounded wait until *addr >= target.
+__device__ __forceinline__ bool spin_until(const int *addr, int target)
 {
     for (int it = 0; it < kSpinLimit; ++it) {
         int v = __hip_atomic_load(addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (ge ? (v >= target) : (v == target)) return true;
+        if (v >= target) return true;
         __builtin_amdgcn_s_sleep(2);
     }
     return false;
@@ -178,6 +179,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     const vec_t *w = reinterpret_cast<const vec_t *>(p.w);
 
     POP_STAMP(0);
+    if (b == 0 && tid == 0) p.sync[3] = 0;  // "some workgroup deferred its phase D share" flag of this step
     int col[PER];
     bool ok[PER];
     vec_t xv[PER];
@@ -252,8 +254,9 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     } else {
         // ---- select (workgroup 0 only)
         if (tid == 0) {
-            bool ok_a = spin_until(&p.sync[0], p.epoch * n_workers, true);  // the counter only grows within a partition
+            bool ok_a = spin_until(&p.sync[0], n_workers);
             if (!ok_a) p.sync[2] = 1;
+            __hip_atomic_store(&p.sync[0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // all arrivals are in
             __threadfence();
             s_flag = ok_a ? 1 : 0;
         }
@@ -265,7 +268,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
             __syncthreads();
             if (tid == 0) {
                 __threadfence();
-                __hip_atomic_store(&p.sync[1], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&p.sync[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         POP_STAMP(3);
@@ -297,13 +300,18 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     // ---- phase D: selected candidates; needs the selection
     POP_STAMP(3);
     if (tid == 0) {
-        bool ok_d = spin_until(&p.sync[1], p.epoch, false);
+        bool ok_d = spin_until(&p.sync[1], 1);
         __threadfence();
         s_flag = ok_d ? 1 : 0;
         p.deferred[b] = ok_d ? 0 : 1;
         if (!ok_d) {
             p.sync[2] = 1;
-            __hip_atomic_store(&p.sync[3], p.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&p.sync[3], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        // the last workgroup past this point rearms the flags for the next launch
+        if (atomicAdd(&p.sync[4], 1) == n_workers - 1) {
+            __hip_atomic_store(&p.sync[4], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&p.sync[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
     __syncthreads();
@@ -349,7 +357,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
 // A workgroup owns 64 outputs; its 4 waves sum contiguous quarters of the partial rows and combine in wave order.
 __global__ __launch_bounds__(256) void decode_tail_kernel(const float *__restrict__ partial, int n_wg, int d,
                                                           const int *__restrict__ deferred, const int *sync,
-                                                          int epoch, const int *__restrict__ sel, int k,
+                                                          const int *__restrict__ sel, int k,
                                                           const float *__restrict__ h, const void *__restrict__ w,
                                                           int m, int is_bf16, void *__restrict__ y, int y_bf16)
 {
@@ -374,7 +382,7 @@ __global__ __launch_bounds__(256) void decode_tail_kernel(const float *__restric
     __syncthreads();
     if (q == 0 && o < d) {
         float v = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
-        const bool any_deferred = sync[3] == epoch;  // set only when some workgroup gave up waiting in this step
+        const bool any_deferred = sync[3] != 0;  // set only when some workgroup gave up waiting in this step
         for (int b = 1; any_deferred && b < n_wg; ++b) {
             if (!deferred[b]) continue;
             // the workgroup's phase D share: rows (i * n_workers + b - 1) * kRB + t, as in the fused kernel
@@ -450,12 +458,12 @@ hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p,
     return pl.per == 1 ? fused_launch<VecF32, 1>(pl, p, s) : fused_launch<VecF32, 2>(pl, p, s);
 }
 
-hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync, int epoch,
+hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync,
                               const int *sel, int k, const float *h, const void *w, int m, int is_bf16, void *y,
                               int y_bf16, hipStream_t s)
 {
     hipLaunchKernelGGL(decode_tail_kernel, dim3((d + kWave - 1) / kWave), dim3(256), 0, s, partial, n_wg, d, deferred,
-                       sync, epoch, sel, k, h, w, m, is_bf16, y, y_bf16);
+                       sync, sel, k, h, w, m, is_bf16, y, y_bf16);
     return hipGetLastError();
 }
 
