@@ -58,6 +58,7 @@ struct pop_layer {
     FusedPlan plan = {};
     int *sync = nullptr;               // [8]
     int *deferred = nullptr;           // [fused_max_workgroups]
+    int *selbits = nullptr;            // [fused_max_workgroups]
     BatchK step_k = {};
     float *h = nullptr;                // [max_batch][m]
     float *cscore = nullptr;           // [max_batch][m]
@@ -123,7 +124,7 @@ int pop_layer_destroy(pop_layer_t *L)
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
                     L->h,      L->cscore, L->mask, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
-                    L->sync,   L->deferred};
+                    L->sync,   L->deferred, L->selbits};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -189,6 +190,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
                                                                                         : (size_t)fused_max_workgroups()) * d * 4},
         {(void **)&L->sync, 32},
         {(void **)&L->deferred, (size_t)fused_max_workgroups() * 4},
+        {(void **)&L->selbits, (size_t)fused_max_workgroups() * 4},
     };
     for (const Req &r : reqs) {
         hipError_t e = hipMalloc(r.p, r.bytes);
@@ -202,6 +204,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w, L->nrm, is_bf16, s);
     if (e == hipSuccess) e = launch_fill_int(L->sync, 8, 0, s);
     if (e == hipSuccess) e = launch_fill_int(L->deferred, fused_max_workgroups(), 0, s);
+    if (e == hipSuccess) e = launch_fill_int(L->selbits, fused_max_workgroups(), 0, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         pop_layer_destroy(L);
@@ -242,6 +245,7 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
         }
     }
     POP_HIP(launch_fill_int(L->sync, 8, 0, s));
+    POP_HIP(launch_fill_int(L->selbits, fused_max_workgroups(), 0, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
@@ -288,6 +292,7 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         p.partial = L->partial;
         p.sync = L->sync;
         p.deferred = L->deferred;
+        p.selbits = L->selbits;
 #ifdef POP_TRACE
         p.trace = g_trace;
 #endif
@@ -331,8 +336,8 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
         if (!L->has_step) return POP_ESTATE;
         if (T != L->step_B) return POP_ESHAPE;
         if (L->step_fused)
-            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->sync, L->active_idx + L->n_ret, L->step_k.k[0], L->h, L->w, m, L->is_bf16, y, y_bf16,
-                                       s));
+            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->sync, L->selbits, L->cand_idx,
+                                       L->n_cand, L->h, L->w, m, L->is_bf16, y, y_bf16, s));
         else if (T == 1)
             POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->active_idx, nullptr, L->n_ret + L->step_k.k[0], L->h,
                                 nullptr, 0, 1, L->partial, L->n_slabs, y, y_bf16, s));

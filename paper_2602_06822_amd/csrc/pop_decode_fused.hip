@@ -14,14 +14,15 @@
 //   phase A  candidate rounds (gate+up only), dealt round-robin to all workgroups: h_j = silu(g_j) u_j and the
 //            step score I_j(t) = n_j |h_j| (Eq. 3 with one token) go to global memory.
 //   select   workgroup 0 owns no retained rows.  It waits until all workgroups have published their phase A
-//            results (bounded spin on a counter; nobody waits for anything before that point), then runs the
-//            top-k selection and publishes the selected list and a done flag.
+//            results (bounded spin on a counter; nobody waits for anything before that point), runs the top-k
+//            selection and hands every workgroup one word: a valid bit plus one bit per candidate slot of that
+//            workgroup that was selected.  Mask and active list for the caller are written afterwards.
 //   phase B  retained rounds, dealt round-robin to workgroups 1..: gate+up dot products -> h, then the down
 //            rows of the same round, already in registers, are multiplied by h into the partial y.
-//   phase D  down rows of the selected candidates, dealt the same way.  Needs the selection: the workgroup
-//            waits (bounded) for the done flag, which in practice was set long before.  If the bound is ever
-//            hit, the workgroup marks its share as deferred (and raises sync[3]) and
-//            the tail kernel adds it, so the result is correct and every wave still exits.
+//   phase D  down rows of the workgroup's own selected candidates (their h is still in LDS).  The workgroup's
+//            word is polled during phase B without ever stalling it; if it has not arrived by the end of
+//            phase B the workgroup waits, bounded.  If the bound is ever hit, the workgroup marks its share as
+//            deferred (and raises sync[3]) and the tail kernel adds it, so every wave still exits.
 //   tail     a second small kernel sums the per-workgroup partials in workgroup order (plus deferred shares)
 //            and writes y.
 //
@@ -60,8 +61,8 @@ __device__ __forceinline__ bool spin_until(const int *addr, int target)
     return false;
 }
 
-constexpr int kKeepRounds = 64;              // rounds whose indices / results are staged in LDS at a time
-constexpr int kKeep = kKeepRounds * kRB;
+constexpr int kMaxRounds = 64;  // rounds per phase per workgroup (the host plan guarantees it)
+constexpr int kKeep = kMaxRounds * kRB;
 
 template <class V, int PER>
 struct RoundBuf {
@@ -159,6 +160,18 @@ __device__ __forceinline__ void round_hidden(const RoundBuf<V, PER> &rb, const t
     }
 }
 
+__device__ __forceinline__ int coherent_load(const int *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(int *p, int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+constexpr int kBitsValid = 1 << 31;                  // set in selbits[b] once the selection of this step is known
+constexpr int kMaxCandRounds = 30 / kRB;             // candidate slots of a workgroup must fit the other 31 bits
+
 template <class V, int PER>
 __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
 {
@@ -166,10 +179,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     typedef typename V::acc_t acc_t;
     constexpr int E = V::kElems;
     __shared__ SelShared sh;
-    __shared__ int s_flag;
+    __shared__ int s_flag, s_bits[2];
     __shared__ acc_t part[2][2 * kRB][kSelMaxWaves];
-    __shared__ int j_s[kKeep];    // channel indices of the staged rounds
-    __shared__ float h_s[kKeep];  // their hidden activations, flushed to global memory outside the streaming loop
+    __shared__ int j_a[kKeep], j_b[kKeep], j_d[kKeep];  // staged channel indices of this workgroup's rounds
+    __shared__ float h_a[kKeep], h_b[kKeep];            // their hidden activations
+    __shared__ int wg_bits[1024];                       // selector only: selected candidate slots per workgroup
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -191,89 +205,54 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     }
     for (int i = tid; i < 2 * 2 * kRB * kSelMaxWaves; i += blockDim.x) (&part[0][0][0])[i] = 0;
 
+    // rounds of this workgroup: round i of a list dealt to n_sh sharers = rows (i*n_sh + me)*kRB + t
+    auto rounds_of = [](int n_list, int n_sh, int me) {
+        return (me >= 0 && me * kRB < n_list) ? (n_list - me * kRB + n_sh * kRB - 1) / (n_sh * kRB) : 0;
+    };
+    const int n_a = rounds_of(p.n_cand, n_wg, b);
+    const int n_a2 = (n_a + 1) & ~1;  // padded to even with an empty round (simplifies the ping-pong)
+    const int n_b = rounds_of(p.n_ret, n_workers, wb);
+    for (int e = tid; e < n_a2 * kRB; e += blockDim.x) {
+        const int r = ((e / kRB) * n_wg + b) * kRB + e % kRB;
+        j_a[e] = (e / kRB < n_a && r < p.n_cand) ? p.cand_idx[r] : -1;
+    }
+    for (int e = tid; e < n_b * kRB; e += blockDim.x) {
+        const int r = ((e / kRB) * n_workers + wb) * kRB + e % kRB;
+        j_b[e] = r < p.n_ret ? p.ret_idx[r] : -1;
+    }
+    __syncthreads();
+
     RoundBuf<V, PER> buf_a, buf_b;  // ping-pong: one is reduced while the other's loads are in flight
 
-    // Streams `my_rounds` rounds of a list dealt round-robin (round i of sharer `me` = rows (i*n_sh + me)*kRB + t).
-    // No global stores happen inside the streaming loop (a store would make the next wait drain every load in
-    // flight, prefetched ones included): h is staged in LDS and flushed per chunk of kKeepRounds rounds.
-    auto stream_phase = [&](auto with_down, const int *list, int n_list, int n_sh, int me, int my_rounds, auto consume,
-                            auto flush) {
-        constexpr bool DN = decltype(with_down)::value;
-        for (int base = 0; base < my_rounds; base += kKeepRounds) {
-            const int nr = min(kKeepRounds, my_rounds - base);
-            for (int e = tid; e < nr * kRB; e += blockDim.x) {
-                const int r = ((base + e / kRB) * n_sh + me) * kRB + e % kRB;
-                j_s[e] = r < n_list ? list[r] : -1;
-            }
-            __syncthreads();
-            load_round<V, PER, true, DN>(buf_a, w, nvec, j_s, col, ok);
-            for (int i = 0; i < nr; i += 2) {
-                if (i + 1 < nr) load_round<V, PER, true, DN>(buf_b, w, nvec, j_s + (i + 1) * kRB, col, ok);
-                {
-                    float hv[kRB];
-                    round_hidden<V, PER>(buf_a, xv, part[0], wave, lane, nw, hv);
-                    if (tid == 0)
-#pragma unroll
-                        for (int t = 0; t < kRB; ++t) h_s[i * kRB + t] = hv[t];
-                    consume(buf_a, hv);
-                }
-                if (i + 2 < nr) load_round<V, PER, true, DN>(buf_a, w, nvec, j_s + (i + 2) * kRB, col, ok);
-                if (i + 1 < nr) {
-                    float hv[kRB];
-                    round_hidden<V, PER>(buf_b, xv, part[1], wave, lane, nw, hv);
-                    if (tid == 0)
-#pragma unroll
-                        for (int t = 0; t < kRB; ++t) h_s[(i + 1) * kRB + t] = hv[t];
-                    consume(buf_b, hv);
-                }
-            }
-            __syncthreads();
-            for (int e = tid; e < nr * kRB; e += blockDim.x)
-                if (j_s[e] >= 0) flush(j_s[e], h_s[e], ((base + e / kRB) * n_sh + me) * kRB + e % kRB);
-            __syncthreads();
-        }
-    };
+    // No global store happens inside the streaming loops: a store would make the next wait drain every load
+    // in flight, prefetched ones included.  Hidden activations are staged in LDS and written out later.
 
-    // ---- phase A: candidate rounds, shared by all n_wg workgroups
-    {
-        const int my_rounds = (b * kRB < p.n_cand) ? (p.n_cand - b * kRB + n_wg * kRB - 1) / (n_wg * kRB) : 0;
-        stream_phase(
-            std::false_type{}, p.cand_idx, p.n_cand, n_wg, b, my_rounds, [&](const RoundBuf<V, PER> &, const float(&)[kRB]) {},
-            [&](int j, float hv, int c) {
-                p.h[j] = hv;
-                p.cscore[c] = p.nrm[j] * fabsf(hv);
-            });
+    // ---- phase A: this workgroup's candidate rounds (gate+up only)
+    auto finish_a = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves]) {
+        float hv[kRB];
+        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv);
+        if (tid == 0)
+#pragma unroll
+            for (int t = 0; t < kRB; ++t) h_a[i * kRB + t] = hv[t];
+    };
+    if (n_a2 > 0) load_round<V, PER, true, false>(buf_a, w, nvec, j_a, col, ok);
+    for (int i = 0; i < n_a2; i += 2) {
+        load_round<V, PER, true, false>(buf_b, w, nvec, j_a + (i + 1) * kRB, col, ok);
+        finish_a(buf_a, i, part[0]);
+        if (i + 2 < n_a2) load_round<V, PER, true, false>(buf_a, w, nvec, j_a + (i + 2) * kRB, col, ok);
+        finish_a(buf_b, i + 1, part[1]);
+    }
+    __syncthreads();
+    for (int e = tid; e < n_a * kRB; e += blockDim.x) {
+        const int j = j_a[e];
+        if (j >= 0) {
+            const float hv = h_a[e];
+            p.h[j] = hv;
+            p.cscore[((e / kRB) * n_wg + b) * kRB + e % kRB] = p.nrm[j] * fabsf(hv);
+        }
     }
     __syncthreads();
     POP_STAMP(1);
-    if (b != 0) {
-        if (tid == 0) {
-            __threadfence();
-            atomicAdd(&p.sync[0], 1);
-        }
-    } else {
-        // ---- select (workgroup 0 only)
-        if (tid == 0) {
-            bool ok_a = spin_until(&p.sync[0], n_workers);
-            if (!ok_a) p.sync[2] = 1;
-            __hip_atomic_store(&p.sync[0], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // all arrivals are in
-            __threadfence();
-            s_flag = ok_a ? 1 : 0;
-        }
-        __syncthreads();
-        POP_STAMP(2);
-        if (s_flag) {
-            block_select_candidates(p.cscore, p.cand_idx, p.n_cand, p.k, p.mask, p.active_idx + p.n_ret, sh);
-            if (tid == 0 && p.n_active) *p.n_active = p.n_ret + p.k;
-            __syncthreads();
-            if (tid == 0) {
-                __threadfence();
-                __hip_atomic_store(&p.sync[1], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        POP_STAMP(3);
-        return;
-    }
 
     float acc[PER][8];
 #pragma unroll
@@ -281,122 +260,189 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
 
-    // ---- phase B: retained rounds, shared by workgroups 1..n_wg-1
-    {
-        const int my_rounds =
-            (wb * kRB < p.n_ret) ? (p.n_ret - wb * kRB + n_workers * kRB - 1) / (n_workers * kRB) : 0;
-        stream_phase(
-            std::true_type{}, p.ret_idx, p.n_ret, n_workers, wb, my_rounds,
-            [&](const RoundBuf<V, PER> &rb, const float(&hv)[kRB]) {
+    // Phase D of a workgroup: the down rows of those of its own candidates (slots of phase A, h still in LDS)
+    // that the selection kept; `bits` has one bit per slot.
+    auto phase_d = [&](int bits) {
+        for (int e = tid; e < n_a2 * kRB; e += blockDim.x) j_d[e] = ((bits >> e) & 1) ? j_a[e] : -1;
+        __syncthreads();
+        for (int i = 0; i < n_a2; i += 2) {
+            load_round<V, PER, false, true>(buf_a, w, nvec, j_d + i * kRB, col, ok);
+            load_round<V, PER, false, true>(buf_b, w, nvec, j_d + (i + 1) * kRB, col, ok);
 #pragma unroll
-                for (int t = 0; t < kRB; ++t)
+            for (int t = 0; t < kRB; ++t)
 #pragma unroll
-                    for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
-            },
-            [&](int j, float hv, int) { p.h[j] = hv; });
+                for (int q = 0; q < PER; ++q) {
+                    V::axpy(h_a[i * kRB + t], buf_a.dn[t][q], acc[q]);
+                    V::axpy(h_a[(i + 1) * kRB + t], buf_b.dn[t][q], acc[q]);
+                }
+        }
+    };
+    auto store_partial = [&]() {
+        float *dst = p.partial + (size_t)b * p.d;
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+            if (ok[q]) {
+#pragma unroll
+                for (int e = 0; e < E; e += 4)
+                    *reinterpret_cast<float4 *>(dst + (size_t)col[q] * E + e) =
+                        make_float4(acc[q][e], acc[q][e + 1], acc[q][e + 2], acc[q][e + 3]);
+            }
+    };
+
+    if (b == 0) {
+        // ---- select (workgroup 0 only): wait for every other workgroup's phase A, then top-k
+        if (tid == 0) {
+            bool ok_a = spin_until(&p.sync[0], n_workers);
+            if (!ok_a) p.sync[2] = 1;
+            coherent_store(&p.sync[0], 0);  // all arrivals are in
+            __threadfence();
+            s_flag = ok_a ? 1 : 0;
+        }
+        for (int i = tid; i < n_wg; i += blockDim.x) wg_bits[i] = 0;
+        __syncthreads();
+        POP_STAMP(2);
+        if (s_flag) {
+            block_select_candidates(
+                p.cscore, p.cand_idx, p.n_cand, p.k, p.mask, p.active_idx + p.n_ret, sh,
+                [&](int c) {  // candidate c was handled by workgroup (c/kRB) % n_wg in its round (c/kRB) / n_wg
+                    const int rd = c / kRB;
+                    atomicOr(&wg_bits[rd % n_wg], 1 << ((rd / n_wg) * kRB + c % kRB));
+                },
+                [&]() {  // publish the per-workgroup slot masks first: they are all the other workgroups wait for
+                    __syncthreads();
+                    for (int i = 1 + tid; i < n_wg; i += blockDim.x) coherent_store(&p.selbits[i], wg_bits[i] | kBitsValid);
+                });
+            if (tid == 0 && p.n_active) *p.n_active = p.n_ret + p.k;
+            POP_STAMP(3);
+            phase_d(wg_bits[0]);
+        }
+        store_partial();
+        return;
+    }
+
+    if (tid == 0) {
+        __threadfence();
+        atomicAdd(&p.sync[0], 1);
+    }
+
+    // ---- phase B: retained rounds (gate+up -> h, then the round's down rows).  Thread 0 polls this workgroup's
+    // word of selbits along the way; a value is looked at two rounds after its load was issued, when it has
+    // certainly arrived, so polling never stalls the stream.
+    int pv0 = 0, pv1 = 0, my_bits = 0, hk = 0;
+    auto finish_b = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves]) {
+        if (tid == 0) {
+            s_bits[hk & 1] = pv1;  // loaded two rounds ago
+            pv1 = pv0;
+            pv0 = my_bits ? 0 : coherent_load(&p.selbits[b]);
+        }
+        float hv[kRB];
+        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv);
+        // read after the round's barrier: every thread sees the same value; the slot is rewritten two rounds later
+        if (!my_bits && (s_bits[hk & 1] & kBitsValid)) my_bits = s_bits[hk & 1];
+        ++hk;
+        if (tid == 0)
+#pragma unroll
+            for (int t = 0; t < kRB; ++t) h_b[i * kRB + t] = hv[t];
+#pragma unroll
+        for (int t = 0; t < kRB; ++t)
+#pragma unroll
+            for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
+    };
+    if (n_b > 0) load_round<V, PER, true, true>(buf_a, w, nvec, j_b, col, ok);
+    for (int i = 0; i < n_b; i += 2) {
+        if (i + 1 < n_b) load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok);
+        finish_b(buf_a, i, part[0]);
+        if (i + 1 < n_b) {
+            if (i + 2 < n_b) load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok);
+            finish_b(buf_b, i + 1, part[1]);
+        }
     }
     POP_STAMP(2);
 
-    // ---- phase D: selected candidates; needs the selection
+    // ---- phase D: needs the selection; normally my_bits arrived during phase B, else wait (bounded)
+    int bits_final = my_bits;
+    if (!my_bits) {
+        if (tid == 0) {
+            int v = pv1 < 0 ? pv1 : pv0;  // values still in the polling pipeline
+            for (int it = 0; v >= 0 && it < kSpinLimit; ++it) {
+                v = coherent_load(&p.selbits[b]);
+                if (v >= 0) __builtin_amdgcn_s_sleep(2);
+            }
+            s_flag = v;
+        }
+        __syncthreads();
+        bits_final = s_flag;
+    }
+    const bool d_ok = bits_final < 0;  // kBitsValid is the sign bit
     POP_STAMP(3);
-    if (tid == 0) {
-        bool ok_d = spin_until(&p.sync[1], 1);
-        __threadfence();
-        s_flag = ok_d ? 1 : 0;
-        p.deferred[b] = ok_d ? 0 : 1;
-        if (!ok_d) {
-            p.sync[2] = 1;
-            __hip_atomic_store(&p.sync[3], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-        // the last workgroup past this point rearms the flags for the next launch
-        if (atomicAdd(&p.sync[4], 1) == n_workers - 1) {
-            __hip_atomic_store(&p.sync[4], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&p.sync[1], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-    __syncthreads();
+    if (d_ok) phase_d(bits_final);
     POP_STAMP(4);
-    if (s_flag) {
-        const int *sel = p.active_idx + p.n_ret;
-        const int my_rounds = (wb * kRB < p.k) ? (p.k - wb * kRB + n_workers * kRB - 1) / (n_workers * kRB) : 0;
-        for (int base = 0; base < my_rounds; base += kKeepRounds) {
-            const int nr = min(kKeepRounds, my_rounds - base);
-            for (int e = tid; e < nr * kRB; e += blockDim.x) {
-                const int r = ((base + e / kRB) * n_workers + wb) * kRB + e % kRB;
-                const int j = r < p.k ? sel[r] : -1;
-                j_s[e] = j;
-                h_s[e] = j >= 0 ? p.h[j] : 0.f;
-            }
-            __syncthreads();
-            for (int i = 0; i < nr; ++i) {
-                load_round<V, PER, false, true>(buf_a, w, nvec, j_s + i * kRB, col, ok);
-#pragma unroll
-                for (int t = 0; t < kRB; ++t)
-#pragma unroll
-                    for (int q = 0; q < PER; ++q) V::axpy(h_s[i * kRB + t], buf_a.dn[t][q], acc[q]);
-            }
-            __syncthreads();
+    store_partial();
+    if (tid == 0) {
+        p.deferred[b] = d_ok ? 0 : 1;
+        if (d_ok) {
+            coherent_store(&p.selbits[b], 0);  // rearmed for the next launch
+        } else {
+            p.sync[2] = 1;
+            coherent_store(&p.sync[3], 1);
         }
     }
-
-    // ---- partial y of this workgroup
-    POP_STAMP(5);
-    float *dst = p.partial + (size_t)b * p.d;
-#pragma unroll
-    for (int q = 0; q < PER; ++q)
-        if (ok[q]) {
-#pragma unroll
-            for (int e = 0; e < E; e += 4)
-                *reinterpret_cast<float4 *>(dst + (size_t)col[q] * E + e) =
-                    make_float4(acc[q][e], acc[q][e + 1], acc[q][e + 2], acc[q][e + 3]);
-        }
+    for (int e = tid; e < n_b * kRB; e += blockDim.x)
+        if (j_b[e] >= 0) p.h[j_b[e]] = h_b[e];
     POP_STAMP(6);
 }
 
-// y[o] = sum over workgroups 1..n_wg-1 (in order) of partial[b][o], plus shares a workgroup deferred.
-// A workgroup owns 64 outputs; its 4 waves sum contiguous quarters of the partial rows and combine in wave order.
-__global__ __launch_bounds__(256) void decode_tail_kernel(const float *__restrict__ partial, int n_wg, int d,
-                                                          const int *__restrict__ deferred, const int *sync,
-                                                          const int *__restrict__ sel, int k,
-                                                          const float *__restrict__ h, const void *__restrict__ w,
-                                                          int m, int is_bf16, void *__restrict__ y, int y_bf16)
+// y[o] = sum over workgroups (in order) of partial[b][o], plus shares a workgroup deferred.  A workgroup owns 64
+// outputs; its 16 waves each sum a contiguous sixteenth of the partial rows (independent loads, fixed order)
+// and wave 0 combines them in wave order, so y does not depend on scheduling.
+constexpr int kTailWaves = 16;
+__global__ __launch_bounds__(1024) void decode_tail_kernel(const float *__restrict__ partial, int n_wg, int d,
+                                                           const int *__restrict__ deferred, const int *sync,
+                                                           const int *__restrict__ selbits,
+                                                           const int *__restrict__ cand_idx, int n_cand,
+                                                           const float *__restrict__ h, const void *__restrict__ w,
+                                                           int m, int is_bf16, void *__restrict__ y, int y_bf16)
 {
-    __shared__ float part[4][kWave];
+    __shared__ float part[kTailWaves][kWave];
     const int lane = threadIdx.x % kWave, q = threadIdx.x / kWave;
     const int o = blockIdx.x * kWave + lane;
-    const int n = n_wg - 1, per = (n + 3) / 4;
-    const int s0 = 1 + min(n, q * per), s1 = 1 + min(n, q * per + per);
+    const int per = (n_wg + kTailWaves - 1) / kTailWaves;
+    const int s0 = min(n_wg, q * per), s1 = min(n_wg, q * per + per);
     float acc = 0.f;
     if (o < d) {
         int s = s0;
-        for (; s + 8 <= s1; s += 8) {
-            float v[8];
+        for (; s + 16 <= s1; s += 16) {
+            float v[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(s + u) * d + o];
+            for (int u = 0; u < 16; ++u) v[u] = partial[(size_t)(s + u) * d + o];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
+            for (int u = 0; u < 16; ++u) acc += v[u];
         }
         for (; s < s1; ++s) acc += partial[(size_t)s * d + o];
     }
     part[q][lane] = acc;
     __syncthreads();
     if (q == 0 && o < d) {
-        float v = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
+        float v = 0.f;
+#pragma unroll
+        for (int u = 0; u < kTailWaves; ++u) v += part[u][lane];
         const bool any_deferred = sync[3] != 0;  // set only when some workgroup gave up waiting in this step
         for (int b = 1; any_deferred && b < n_wg; ++b) {
             if (!deferred[b]) continue;
-            // the workgroup's phase D share: rows (i * n_workers + b - 1) * kRB + t, as in the fused kernel
-            for (int i = 0; (i * (n_wg - 1) + b - 1) * kRB < k; ++i)
-                for (int t = 0; t < kRB; ++t) {
-                    const int r = (i * (n_wg - 1) + b - 1) * kRB + t;
-                    if (r >= k) break;
-                    const int j = sel[r];
-                    if (j < 0 || j >= m) continue;  // selection never ran: the step is flagged invalid, stay in bounds
-                    const size_t idx = ((size_t)j * 3 + 2) * d + o;
-                    const float wv = is_bf16 ? __uint_as_float(((uint32_t)((const uint16_t *)w)[idx]) << 16)
-                                             : ((const float *)w)[idx];
-                    v = fmaf(h[j], wv, v);
-                }
+            // the workgroup's phase D share: its own candidate slots that the selection kept
+            const int bits = selbits[b];
+            if (bits >= 0) continue;  // the selection never ran: the step is flagged invalid
+            for (int e = 0; e < 31; ++e) {
+                if (!((bits >> e) & 1)) continue;
+                const int c = ((e / kRB) * n_wg + b) * kRB + e % kRB;
+                if (c >= n_cand) continue;
+                const int j = cand_idx[c];
+                if (j < 0 || j >= m) continue;
+                const size_t idx = ((size_t)j * 3 + 2) * d + o;
+                const float wv = is_bf16 ? __uint_as_float(((uint32_t)((const uint16_t *)w)[idx]) << 16)
+                                         : ((const float *)w)[idx];
+                v = fmaf(h[j], wv, v);
+            }
         }
         if (y_bf16)
             ((uint16_t *)y)[o] = f32_to_bf16(v);
@@ -436,6 +482,9 @@ bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedP
     if (workers < 1) workers = 1;
     if (workers > wg_target - 1) workers = wg_target - 1;
     pl->n_wg = workers + 1;
+    // the kernel stages at most kMaxRounds rounds per phase (the last candidate round may be padding)
+    if ((n_ret + workers * kRB - 1) / (workers * kRB) > kMaxRounds) return false;
+    if ((n_cand + (workers + 1) * kRB - 1) / ((workers + 1) * kRB) + 1 > kMaxCandRounds) return false;
     return true;
 }
 
@@ -459,11 +508,11 @@ hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p,
 }
 
 hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync,
-                              const int *sel, int k, const float *h, const void *w, int m, int is_bf16, void *y,
-                              int y_bf16, hipStream_t s)
+                              const int *selbits, const int *cand_idx, int n_cand, const float *h, const void *w,
+                              int m, int is_bf16, void *y, int y_bf16, hipStream_t s)
 {
-    hipLaunchKernelGGL(decode_tail_kernel, dim3((d + kWave - 1) / kWave), dim3(256), 0, s, partial, n_wg, d, deferred,
-                       sync, sel, k, h, w, m, is_bf16, y, y_bf16);
+    hipLaunchKernelGGL(decode_tail_kernel, dim3((d + kWave - 1) / kWave), dim3(kTailWaves * kWave), 0, s, partial, n_wg, d, deferred,
+                       sync, selbits, cand_idx, n_cand, h, w, m, is_bf16, y, y_bf16);
     return hipGetLastError();
 }
 

@@ -97,9 +97,10 @@ struct FusedParams {
     int *active_idx;         // [>= n_ret + k]
     int *n_active;           // [1]
     float *partial;          // [n_wg][d]
-    int *sync;               // [0] phase-A arrivals, [1] selection done, [2] sticky error flag, [3] some workgroup
-                             // deferred its phase D share in this step, [4] workgroups past the phase D wait.
-                             // [0], [1], [4] are back at zero when the kernel ends, so a launch can be replayed.
+    int *sync;               // [0] phase-A arrivals, [2] sticky error flag, [3] some workgroup deferred its
+                             // phase D share in this step.  [0] is back at zero when the kernel ends.
+    int *selbits;            // [n_wg] per-workgroup selection word (valid bit + selected candidate slots);
+                             // each workgroup clears its own word after use, so a launch can be replayed
     unsigned long long *trace;  // profiling builds only: 8 timestamps per workgroup, else null
     int *deferred;           // [n_wg]
 };
@@ -114,8 +115,8 @@ bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedP
 hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int *max_wg);
 hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p, hipStream_t s);
 hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync,
-                              const int *sel, int k, const float *h, const void *w, int m, int is_bf16, void *y,
-                              int y_bf16, hipStream_t s);
+                              const int *selbits, const int *cand_idx, int n_cand, const float *h, const void *w,
+                              int m, int is_bf16, void *y, int y_bf16, hipStream_t s);
 hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s);
 
 // ---- prefill (pop_prefill.hip) ----

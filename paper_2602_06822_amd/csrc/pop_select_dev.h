@@ -111,13 +111,23 @@ __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, Sel
     take_eq = remaining;
 }
 
+struct SelectNoHook {
+    __device__ __forceinline__ void operator()(int) const {}
+    __device__ __forceinline__ void operator()() const {}
+};
+
 // Select the best k of n_cand candidates (cs[i] is the score of channel cand_idx[i], cand_idx ascending).
 // Writes, each if non-null: mk[cand_idx[i]] = selected (candidate bytes only; the bytes of retained and pruned
 // channels are constant for a partition and written when the partition is made), act_sel[0..k) = selected
-// channels ascending.  All threads of the block must call.
+// channels ascending.  on_selected(i) is called for every selected position before any of those global writes,
+// then after_selected() by every thread (it may contain barriers): callers that only need the positions get
+// them without waiting for the index loads.  All threads of the block must call.
+template <class OnSelected = SelectNoHook, class AfterSelected = SelectNoHook>
 __device__ __forceinline__ void block_select_candidates(const float *__restrict__ cs, const int *__restrict__ cand_idx,
                                                         int n_cand, int k, unsigned char *__restrict__ mk,
-                                                        int *__restrict__ act_sel, SelShared &sh)
+                                                        int *__restrict__ act_sel, SelShared &sh,
+                                                        OnSelected on_selected = OnSelected(),
+                                                        AfterSelected after_selected = AfterSelected())
 {
     const bool in_lds = n_cand <= kSelLdsKeys;
     if (in_lds) {
@@ -138,6 +148,15 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
         cnt[1] += (kv > kth);
     }
     block_excl_scan<2>(cnt, tot, sh);
+    {
+        int eq = cnt[0];
+        for (int i = lo; i < hi; ++i) {
+            uint32_t kv = key(i);
+            if ((kv > kth) || (kv == kth && eq < take)) on_selected(i);
+            eq += (kv == kth);
+        }
+    }
+    after_selected();
     // position of a selected element = (# greater before it) + (# admitted equal before it)
     int eq = cnt[0], gt = cnt[1];
     for (int i = lo; i < hi; ++i) {

@@ -145,6 +145,27 @@ def test_small_layer_end_to_end(pop, oracle, name, d, m, dtype, T, fr, r):
         _check_decode(oracle, G, L, region, cand, xt[1:3], [k, k], ydtype=F32)
 
 
+@pytest.mark.parametrize("dtype,wgs", [(BF16, 6), (F32, 6), (BF16, 4), (BF16, 40)])
+def test_fused_step_many_rounds_per_workgroup(pop, oracle, monkeypatch, dtype, wgs):
+    """Few workgroups => many rounds each: exercises the ping-pong stream, the phase D preparation that rides
+    along with the retained rounds, and (with 4 workgroups) the multi-round candidate phase."""
+    monkeypatch.setenv("POP_FUSED_WGS", str(wgs))
+    d, m, T = 512, 1024, 40
+    L = synth.make_layer(synth.small_config(f"many_rounds_{wgs}", d, m, dtype, n_outlier=2, heavy_tail=dtype == BF16))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 6, "decode")
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 0.25 if wgs == 4 else 0.6, 0.1)
+    k = n_cand // 2
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        outs = [_check_decode(oracle, G, L, region, cand, xt[t:t + 1], kk)
+                for t, kk in enumerate([k, k, 0, n_cand, 1, k])]
+        # the same step again gives the same bits (the in-kernel flags were rearmed correctly)
+        again = G.decode(xt[5:6], k)
+        for key in ("mask", "active_idx", "y", "cscore"):
+            assert np.array_equal(outs[5][key], again[key]), key
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_degenerate_partitions(pop, oracle, dtype):
     d, m, T = 128, 90, 20
