@@ -190,7 +190,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
                                                                                         : (size_t)fused_max_workgroups()) * d * 4},
         {(void **)&L->sync, 32},
         {(void **)&L->deferred, (size_t)fused_max_workgroups() * 4},
-        {(void **)&L->selbits, (size_t)fused_max_workgroups() * 4},
+        {(void **)&L->selbits, (size_t)fused_selbits_ints() * 4},
     };
     for (const Req &r : reqs) {
         hipError_t e = hipMalloc(r.p, r.bytes);
@@ -204,7 +204,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w, L->nrm, is_bf16, s);
     if (e == hipSuccess) e = launch_fill_int(L->sync, 8, 0, s);
     if (e == hipSuccess) e = launch_fill_int(L->deferred, fused_max_workgroups(), 0, s);
-    if (e == hipSuccess) e = launch_fill_int(L->selbits, fused_max_workgroups(), 0, s);
+    if (e == hipSuccess) e = launch_fill_int(L->selbits, fused_selbits_ints(), 0, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         pop_layer_destroy(L);
@@ -245,7 +245,7 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
         }
     }
     POP_HIP(launch_fill_int(L->sync, 8, 0, s));
-    POP_HIP(launch_fill_int(L->selbits, fused_max_workgroups(), 0, s));
+    POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));

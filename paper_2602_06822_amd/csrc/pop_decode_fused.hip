@@ -71,9 +71,13 @@ struct RoundBuf {
 };
 
 // Loads the rows of one round; js points at the round's kRB staged channel indices (LDS), -1 = empty slot.
+// Every load is issued unconditionally (an empty slot or an out-of-range column reads the 16 bytes at `dummy`,
+// one cached transaction per wave): with no branch around a load the compiler knows exactly how many loads are
+// in flight and can wait for the older buffer alone instead of draining the prefetched one as well.
 template <class V, int PER, bool GU, bool DN>
 __device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const typename V::vec_t *__restrict__ w, int nvec,
-                                           const int *js, const int (&col)[PER], const bool (&ok)[PER])
+                                           const int *js, const int (&col)[PER], const bool (&ok)[PER],
+                                           const typename V::vec_t *__restrict__ dummy)
 {
 #pragma unroll
     for (int t = 0; t < kRB; ++t) {
@@ -84,10 +88,10 @@ __device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const typename 
         for (int q = 0; q < PER; ++q) {
             const bool ld = ok[q] && j >= 0;
             if (GU) {
-                rb.g[t][q] = ld ? row[col[q]] : V::zero();
-                rb.u[t][q] = ld ? row[nvec + col[q]] : V::zero();
+                rb.g[t][q] = *(ld ? row + col[q] : dummy);
+                rb.u[t][q] = *(ld ? row + nvec + col[q] : dummy);
             }
-            if (DN) rb.dn[t][q] = ld ? row[2 * nvec + col[q]] : V::zero();
+            if (DN) rb.dn[t][q] = *(ld ? row + 2 * nvec + col[q] : dummy);
         }
     }
 }
@@ -169,6 +173,7 @@ __device__ __forceinline__ void coherent_store(int *p, int v)
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+constexpr int kBitsStride = 1024;                   // ints between the selection words of two workgroups
 constexpr int kBitsValid = 1 << 31;                  // set in selbits[b] once the selection of this step is known
 constexpr int kMaxCandRounds = 30 / kRB;             // candidate slots of a workgroup must fit the other 31 bits
 
@@ -181,8 +186,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     __shared__ SelShared sh;
     __shared__ int s_flag, s_bits[2];
     __shared__ acc_t part[2][2 * kRB][kSelMaxWaves];
-    __shared__ int j_a[kKeep], j_b[kKeep], j_d[kKeep];  // staged channel indices of this workgroup's rounds
-    __shared__ float h_a[kKeep], h_b[kKeep];            // their hidden activations
+    __shared__ int j_a[kKeep + 2 * kRB], j_b[kKeep + 2 * kRB], j_d[kKeep + 2 * kRB];  // staged channel indices
+    __shared__ float h_a[kKeep + 2 * kRB], h_b[kKeep + 2 * kRB];                      // their hidden activations
     __shared__ int wg_bits[1024];                       // selector only: selected candidate slots per workgroup
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -212,14 +217,17 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     const int n_a = rounds_of(p.n_cand, n_wg, b);
     const int n_a2 = (n_a + 1) & ~1;  // padded to even with an empty round (simplifies the ping-pong)
     const int n_b = rounds_of(p.n_ret, n_workers, wb);
-    for (int e = tid; e < n_a2 * kRB; e += blockDim.x) {
+    // staged with empty rounds (-1) behind the real ones, so the streaming loops can prefetch unconditionally
+    const int n_b2 = (n_b + 1) & ~1;
+    for (int e = tid; e < (n_a2 + 1) * kRB; e += blockDim.x) {
         const int r = ((e / kRB) * n_wg + b) * kRB + e % kRB;
         j_a[e] = (e / kRB < n_a && r < p.n_cand) ? p.cand_idx[r] : -1;
     }
-    for (int e = tid; e < n_b * kRB; e += blockDim.x) {
+    for (int e = tid; e < (n_b2 + 1) * kRB; e += blockDim.x) {
         const int r = ((e / kRB) * n_workers + wb) * kRB + e % kRB;
-        j_b[e] = r < p.n_ret ? p.ret_idx[r] : -1;
+        j_b[e] = (e / kRB < n_b && r < p.n_ret) ? p.ret_idx[r] : -1;
     }
+    const vec_t *dummy = reinterpret_cast<const vec_t *>(p.x);
     __syncthreads();
 
     RoundBuf<V, PER> buf_a, buf_b;  // ping-pong: one is reduced while the other's loads are in flight
@@ -235,11 +243,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
 #pragma unroll
             for (int t = 0; t < kRB; ++t) h_a[i * kRB + t] = hv[t];
     };
-    if (n_a2 > 0) load_round<V, PER, true, false>(buf_a, w, nvec, j_a, col, ok);
+    if (n_a2 > 0) load_round<V, PER, true, false>(buf_a, w, nvec, j_a, col, ok, dummy);
     for (int i = 0; i < n_a2; i += 2) {
-        load_round<V, PER, true, false>(buf_b, w, nvec, j_a + (i + 1) * kRB, col, ok);
+        load_round<V, PER, true, false>(buf_b, w, nvec, j_a + (i + 1) * kRB, col, ok, dummy);
         finish_a(buf_a, i, part[0]);
-        if (i + 2 < n_a2) load_round<V, PER, true, false>(buf_a, w, nvec, j_a + (i + 2) * kRB, col, ok);
+        load_round<V, PER, true, false>(buf_a, w, nvec, j_a + (i + 2) * kRB, col, ok, dummy);  // maybe an empty round
         finish_a(buf_b, i + 1, part[1]);
     }
     __syncthreads();
@@ -266,14 +274,15 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
         for (int e = tid; e < n_a2 * kRB; e += blockDim.x) j_d[e] = ((bits >> e) & 1) ? j_a[e] : -1;
         __syncthreads();
         for (int i = 0; i < n_a2; i += 2) {
-            load_round<V, PER, false, true>(buf_a, w, nvec, j_d + i * kRB, col, ok);
-            load_round<V, PER, false, true>(buf_b, w, nvec, j_d + (i + 1) * kRB, col, ok);
+            load_round<V, PER, false, true>(buf_a, w, nvec, j_d + i * kRB, col, ok, dummy);
+            load_round<V, PER, false, true>(buf_b, w, nvec, j_d + (i + 1) * kRB, col, ok, dummy);
 #pragma unroll
             for (int t = 0; t < kRB; ++t)
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
-                    V::axpy(h_a[i * kRB + t], buf_a.dn[t][q], acc[q]);
-                    V::axpy(h_a[(i + 1) * kRB + t], buf_b.dn[t][q], acc[q]);
+                    // an unselected slot read the dummy vector: its weight is zero
+                    V::axpy(buf_a.j[t] >= 0 ? h_a[i * kRB + t] : 0.f, buf_a.dn[t][q], acc[q]);
+                    V::axpy(buf_b.j[t] >= 0 ? h_a[(i + 1) * kRB + t] : 0.f, buf_b.dn[t][q], acc[q]);
                 }
         }
     };
@@ -310,7 +319,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
                 },
                 [&]() {  // publish the per-workgroup slot masks first: they are all the other workgroups wait for
                     __syncthreads();
-                    for (int i = 1 + tid; i < n_wg; i += blockDim.x) coherent_store(&p.selbits[i], wg_bits[i] | kBitsValid);
+                    for (int i = 1 + tid; i < n_wg; i += blockDim.x) coherent_store(&p.selbits[(size_t)i * kBitsStride], wg_bits[i] | kBitsValid);
                 });
             if (tid == 0 && p.n_active) *p.n_active = p.n_ret + p.k;
             POP_STAMP(3);
@@ -329,12 +338,13 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     // word of selbits along the way; a value is looked at two rounds after its load was issued, when it has
     // certainly arrived, so polling never stalls the stream.
     int pv0 = 0, pv1 = 0, my_bits = 0, hk = 0;
-    auto finish_b = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves]) {
-        if (tid == 0) {
-            s_bits[hk & 1] = pv1;  // loaded two rounds ago
-            pv1 = pv0;
-            pv0 = my_bits ? 0 : coherent_load(&p.selbits[b]);
-        }
+    auto finish_b = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves], auto poll_tag) {
+        constexpr bool poll = decltype(poll_tag)::value;
+        if (tid == 0) s_bits[hk & 1] = pv1;  // loaded two rounds ago or earlier
+        pv1 = pv0;
+        // every thread, no branch around the load; one poll per pair of rounds, each workgroup's word in its own
+        // 4 KiB so that the polls of all workgroups do not queue up at one memory channel
+        if (poll) pv0 = coherent_load(&p.selbits[(size_t)b * kBitsStride]);
         float hv[kRB];
         round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv);
         // read after the round's barrier: every thread sees the same value; the slot is rewritten two rounds later
@@ -348,14 +358,12 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
 #pragma unroll
             for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
     };
-    if (n_b > 0) load_round<V, PER, true, true>(buf_a, w, nvec, j_b, col, ok);
-    for (int i = 0; i < n_b; i += 2) {
-        if (i + 1 < n_b) load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok);
-        finish_b(buf_a, i, part[0]);
-        if (i + 1 < n_b) {
-            if (i + 2 < n_b) load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok);
-            finish_b(buf_b, i + 1, part[1]);
-        }
+    if (n_b2 > 0) load_round<V, PER, true, true>(buf_a, w, nvec, j_b, col, ok, dummy);
+    for (int i = 0; i < n_b2; i += 2) {
+        load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok, dummy);
+        finish_b(buf_a, i, part[0], std::true_type{});
+        load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok, dummy);  // maybe an empty round
+        finish_b(buf_b, i + 1, part[1], std::false_type{});
     }
     POP_STAMP(2);
 
@@ -365,7 +373,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
         if (tid == 0) {
             int v = pv1 < 0 ? pv1 : pv0;  // values still in the polling pipeline
             for (int it = 0; v >= 0 && it < kSpinLimit; ++it) {
-                v = coherent_load(&p.selbits[b]);
+                v = coherent_load(&p.selbits[(size_t)b * kBitsStride]);
                 if (v >= 0) __builtin_amdgcn_s_sleep(2);
             }
             s_flag = v;
@@ -381,7 +389,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     if (tid == 0) {
         p.deferred[b] = d_ok ? 0 : 1;
         if (d_ok) {
-            coherent_store(&p.selbits[b], 0);  // rearmed for the next launch
+            coherent_store(&p.selbits[(size_t)b * kBitsStride], 0);  // rearmed for the next launch
         } else {
             p.sync[2] = 1;
             coherent_store(&p.sync[3], 1);
@@ -430,7 +438,7 @@ __global__ __launch_bounds__(1024) void decode_tail_kernel(const float *__restri
         for (int b = 1; any_deferred && b < n_wg; ++b) {
             if (!deferred[b]) continue;
             // the workgroup's phase D share: its own candidate slots that the selection kept
-            const int bits = selbits[b];
+            const int bits = selbits[(size_t)b * kBitsStride];
             if (bits >= 0) continue;  // the selection never ran: the step is flagged invalid
             for (int e = 0; e < 31; ++e) {
                 if (!((bits >> e) & 1)) continue;
@@ -466,6 +474,7 @@ static hipError_t fused_occupancy(int block, int *blocks_per_cu)
 }
 
 int fused_max_workgroups() { return 1024; }
+int fused_selbits_ints() { return 1024 * kBitsStride; }
 
 // Chooses the launch shape; returns false when this d is not supported by the fused kernel.
 bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl)
