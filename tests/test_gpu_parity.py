@@ -313,3 +313,50 @@ def test_config1_small_fp32(pop, oracle):
         y = G.ffn(xt, np.ones(cfg.m, np.uint8))
         dense = oracle.pruned_ffn(xt, L.w_gate, L.w_up, L.w_down, F32, np.ones(cfg.m, np.uint8))
         assert max_abs_rel(y, dense) <= 1e-4
+
+
+# ---------------------------------------------------------------- full-size shapes, sampled against the oracle
+
+def _full_size_case(pop, oracle, cfg, T, r, batches, n_sample=192, f_cand=0.10):
+    """Layer of a benchmark shape at full size, in the launch configuration bench.py uses.  Prefill scores are
+    checked on a sample of channels (the oracle computes them one by one), the partition on all channels (GPU
+    scores through the oracle's selector), decode steps completely (one token of the oracle is cheap)."""
+    L = synth.make_layer(cfg, layer_id=0)
+    dtype, m = cfg.dtype, cfg.m
+    x = synth.make_activations(L, T, "prompt")
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 1.0 - r - f_cand / 2, f_cand)
+    k = pop.pop_k_for_ratio(m, r, n_ret, n_cand)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=max(batches)) as G:
+        scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+        sample = np.sort(synth.rng("full_size_sample", cfg.name).choice(m, size=n_sample, replace=False)).astype(np.int32)
+        H = oracle.hidden(x, L.w_gate, L.w_up, dtype, chan=sample)
+        s_ref = oracle.importance(L.w_down, dtype, H, chan=sample)[sample]
+        err = score_rel_err(scores[sample], s_ref, eps=1e-6)
+        assert err <= SCORE_TOL, f"prefill score error {err:.3e}"
+        r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+        assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1)
+        for B in batches:
+            xt = synth.make_activations(L, B, f"decode_b{B}")
+            ks = [k] * B if B == 1 else [max(0, min(n_cand, k + 7 * b - 11)) for b in range(B)]
+            _check_decode(oracle, G, L, region, cand, xt, ks)
+
+
+def test_config2_llama7b_layer_full_size(pop, oracle):
+    """Llama-2-7B-shaped layer, bf16, prompt 512, B = 1, sparsity .20 / .35 / .50 (fused decode kernel)."""
+    for r in (0.35, 0.20, 0.50):
+        _full_size_case(pop, oracle, synth.CFG2, 512, r, [1], n_sample=128)
+
+
+def test_config3_long_prompt_full_size(pop, oracle):
+    """Same shape with the 2048-token prompt of the 32-layer stack configuration (one layer of it)."""
+    _full_size_case(pop, oracle, synth.CFG3, 2048, 0.35, [1], n_sample=48)
+
+
+def test_config4_llama13b_layer_batched_full_size(pop, oracle):
+    """Llama-2-13B-shaped layer, bf16, prompt 1024, decode at B = 1, 4, 8 with per-sequence masks."""
+    _full_size_case(pop, oracle, synth.CFG4, 1024, 0.50, [1, 4, 8], n_sample=64)
+
+
+def test_config5_mixtral_expert_full_size(pop, oracle):
+    """One Mixtral-shaped expert (d 4096, m 14336), bf16, a ragged share of the prompt tokens, sparsity .35."""
+    _full_size_case(pop, oracle, synth.CFG5, 300, 0.35, [1], n_sample=128)
