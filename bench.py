@@ -180,17 +180,28 @@ def run(args):
         warm = timed(r_main, max(1, args.steps // 2), 1)["decode_us_per_token"]
         layers = keep
 
-    gate_us = main.get("probe_mask_us")
+    fused_us = main.get("probe_mask_us")
     roofline = None
-    if gate_us:
-        ach = bm["gateup"] / gate_us / 1e3  # GB/s
-        roofline = dict(bound="hbm", kernel="pop_decode_mask (gate/up GEMV + candidate re-score + top-k)",
+    if fused_us:
+        # dominant kernel: the fused decode kernel behind pop_decode_mask (B = 1).  It streams every weight byte of
+        # the step (gate+up rows of retained and candidate channels, down columns of retained and selected ones);
+        # pop_pruned_ffn only reduces the per-workgroup partial sums.
+        ach = bm["algorithmic"] / fused_us / 1e3  # GB/s
+        roofline = dict(bound="hbm", kernel="decode_fused_kernel (pop_decode_mask, B=1)",
                         achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s", frac=round(ach / HBM_PEAK_GBS, 4),
-                        traffic=None, algorithmic_bytes_per_launch=bm["gateup"], avg_launch_us=round(gate_us, 3),
-                        down_kernel_us=round(main["probe_ffn_us"], 3),
-                        down_GBps=round(bm["down"] / main["probe_ffn_us"] / 1e3, 1))
+                        traffic=measured_traffic(), algorithmic_bytes_per_launch=bm["algorithmic"],
+                        avg_launch_us=round(fused_us, 3), tail_kernel_us=round(main["probe_ffn_us"], 3),
+                        note="event-bracketed durations include the launch gap of each call")
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(synth, layers[0].host_layer, n_ret, n_cand, k, args.cpu_tokens)
+
+    if args.pmc_calibration:
+        # a plain device-to-device copy of known size, for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters
+        a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
+        bb = torch.empty_like(a)
+        for _ in range(3):
+            bb.copy_(a)
+        torch.cuda.synchronize()
 
     for L in layers:
         L.close()
@@ -225,6 +236,18 @@ def run(args):
     print(json.dumps(result))
 
 
+def measured_traffic():
+    """HBM bytes per launch of the fused kernel from the committed rocprofv3 counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", "decode_fused_cfg2_r35_hbm_traffic.txt")
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return int(float(ln.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(synth, L, n_ret, n_cand, k, n_tokens):
     """The oracle's decode step (double precision, as it stands) timed on the host cores for a few tokens."""
     from oracle import pop_oracle as oracle
@@ -250,6 +273,7 @@ def main():
     ap.add_argument("--probe-every", type=int, default=8, help="bracket every n-th decode call pair with events")
     ap.add_argument("--cpu-tokens", type=int, default=384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true", help="also run three 256 MiB device copies")
     ap.add_argument("--quick", action="store_true", help="main line only: skip other sparsities and the warm figure")
     args = ap.parse_args()
     if args.gpus != 1:
