@@ -36,6 +36,10 @@
 namespace pop {
 
 constexpr int kRB = 2;  // channels per round
+#ifndef POP_PREFETCH_EARLY
+#define POP_PREFETCH_EARLY 0
+#endif
+constexpr bool kPrefetchEarly = POP_PREFETCH_EARLY != 0;
 constexpr int kSpinLimit = 1 << 16;
 
 // Optional per-workgroup timestamps (100 MHz wall clock), compiled in only for profiling builds.
@@ -120,26 +124,35 @@ __device__ __forceinline__ double wave_total(double v) { return wave_sum(v); }
 
 // Gate/up dot products of the round's rows with x: lane partials -> wave sums -> LDS -> totals in every thread.
 // One barrier; `part` ([2*kRB][16], entries of absent waves stay zero) is double-buffered by the caller.
-template <class V, int PER>
+// `after_dots` runs once the round's gate/up data has been consumed: the place to issue the next loads when the
+// memory pipeline should hold about one round at a time (see kPrefetchEarly).
+template <class V, int PER, class AfterDots>
 __device__ __forceinline__ void round_hidden(const RoundBuf<V, PER> &rb, const typename V::vec_t (&xv)[PER],
                                              typename V::acc_t (*part)[kSelMaxWaves], int wave, int lane, int nw,
-                                             float (&hv)[kRB])
+                                             float (&hv)[kRB], AfterDots after_dots)
 {
     typedef typename V::acc_t acc_t;
     static_assert(2 * kRB * kSelMaxWaves == kWave, "one LDS word per lane in the cross-wave step");
+    acc_t ag[kRB], au[kRB];
 #pragma unroll
     for (int t = 0; t < kRB; ++t) {
-        acc_t ag = 0, au = 0;
+        ag[t] = 0;
+        au[t] = 0;
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
-            ag = V::dot(rb.g[t][q], xv[q], ag);
-            au = V::dot(rb.u[t][q], xv[q], au);
+            ag[t] = V::dot(rb.g[t][q], xv[q], ag[t]);
+            au[t] = V::dot(rb.u[t][q], xv[q], au[t]);
         }
-        ag = wave_total(ag);
-        au = wave_total(au);
+    }
+    asm volatile("" ::: "memory");  // keep the loads below behind the uses above
+    after_dots();
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int t = 0; t < kRB; ++t) {
+        const acc_t gt = wave_total(ag[t]), ut = wave_total(au[t]);
         if (lane == 0) {
-            part[2 * t][wave] = ag;
-            part[2 * t + 1][wave] = au;
+            part[2 * t][wave] = gt;
+            part[2 * t + 1][wave] = ut;
         }
     }
     __syncthreads();
@@ -169,6 +182,10 @@ __device__ __forceinline__ int coherent_load(const int *p)
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ void coherent_store(int *p, int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -238,7 +255,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     // ---- phase A: this workgroup's candidate rounds (gate+up only)
     auto finish_a = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves]) {
         float hv[kRB];
-        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv);
+        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv, [] {});
         if (tid == 0)
 #pragma unroll
             for (int t = 0; t < kRB; ++t) h_a[i * kRB + t] = hv[t];
@@ -254,11 +271,15 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     for (int e = tid; e < n_a * kRB; e += blockDim.x) {
         const int j = j_a[e];
         if (j >= 0) {
+            // write-through stores: visible device-wide once acknowledged, so the hand-over below needs no
+            // cache write-back (a full release fence also invalidates this XCD's L2 under the other workgroups'
+            // streams; with one per workgroup that stalled the start of phase B for microseconds)
             const float hv = h_a[e];
-            p.h[j] = hv;
-            p.cscore[((e / kRB) * n_wg + b) * kRB + e % kRB] = p.nrm[j] * fabsf(hv);
+            coherent_store(&p.h[j], hv);
+            coherent_store(&p.cscore[((e / kRB) * n_wg + b) * kRB + e % kRB], p.nrm[j] * fabsf(hv));
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's stores are acknowledged
     __syncthreads();
     POP_STAMP(1);
 
@@ -329,24 +350,22 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
         return;
     }
 
-    if (tid == 0) {
-        __threadfence();
-        atomicAdd(&p.sync[0], 1);
-    }
+    if (tid == 0) atomicAdd(&p.sync[0], 1);  // every wave's results were acknowledged before the barrier above
 
     // ---- phase B: retained rounds (gate+up -> h, then the round's down rows).  Thread 0 polls this workgroup's
     // word of selbits along the way; a value is looked at two rounds after its load was issued, when it has
     // certainly arrived, so polling never stalls the stream.
-    int pv0 = 0, pv1 = 0, my_bits = 0, hk = 0;
-    auto finish_b = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves], auto poll_tag) {
+    int pv0 = 0, pv1 = 0, pv2 = 0, my_bits = 0, hk = 0;
+    auto finish_b = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves], auto poll_tag, auto late_load) {
         constexpr bool poll = decltype(poll_tag)::value;
-        if (tid == 0) s_bits[hk & 1] = pv1;  // loaded two rounds ago or earlier
+        if (tid == 0) s_bits[hk & 1] = pv2;  // loaded at least two full rounds ago: certainly arrived, never a stall
+        pv2 = pv1;
         pv1 = pv0;
         // every thread, no branch around the load; one poll per pair of rounds, each workgroup's word in its own
         // 4 KiB so that the polls of all workgroups do not queue up at one memory channel
         if (poll) pv0 = coherent_load(&p.selbits[(size_t)b * kBitsStride]);
         float hv[kRB];
-        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv);
+        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv, late_load);
         // read after the round's barrier: every thread sees the same value; the slot is rewritten two rounds later
         if (!my_bits && (s_bits[hk & 1] & kBitsValid)) my_bits = s_bits[hk & 1];
         ++hk;
@@ -358,12 +377,25 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
 #pragma unroll
             for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
     };
+    // kPrefetchEarly: the next round's loads go out before the current round's data is waited for (two rounds in
+    // flight).  Otherwise they go out right after the current round's data has been consumed (about one round in
+    // flight, the reduction and the barrier still overlap the load latency): measured faster on MI355X, whose
+    // memory system loses throughput when the request queues get deeper.
     if (n_b2 > 0) load_round<V, PER, true, true>(buf_a, w, nvec, j_b, col, ok, dummy);
     for (int i = 0; i < n_b2; i += 2) {
-        load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok, dummy);
-        finish_b(buf_a, i, part[0], std::true_type{});
-        load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok, dummy);  // maybe an empty round
-        finish_b(buf_b, i + 1, part[1], std::false_type{});
+        if (i == 4) POP_STAMP(5);
+        if (i == 8) POP_STAMP(7);
+        if (kPrefetchEarly) {
+            load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok, dummy);
+            finish_b(buf_a, i, part[0], std::true_type{}, [] {});
+            load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok, dummy);
+            finish_b(buf_b, i + 1, part[1], std::false_type{}, [] {});
+        } else {
+            finish_b(buf_a, i, part[0], std::true_type{},
+                     [&] { load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok, dummy); });
+            finish_b(buf_b, i + 1, part[1], std::false_type{},
+                     [&] { load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok, dummy); });
+        }
     }
     POP_STAMP(2);
 
@@ -371,7 +403,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     int bits_final = my_bits;
     if (!my_bits) {
         if (tid == 0) {
-            int v = pv1 < 0 ? pv1 : pv0;  // values still in the polling pipeline
+            int v = pv2 < 0 ? pv2 : (pv1 < 0 ? pv1 : pv0);  // values still in the polling pipeline
             for (int it = 0; v >= 0 && it < kSpinLimit; ++it) {
                 v = coherent_load(&p.selbits[(size_t)b * kBitsStride]);
                 if (v >= 0) __builtin_amdgcn_s_sleep(2);
