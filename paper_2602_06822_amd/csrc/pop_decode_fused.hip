@@ -325,14 +325,13 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
             bool ok_a = spin_until(&p.sync[0], n_workers);
             if (!ok_a) p.sync[2] = 1;
             coherent_store(&p.sync[0], 0);  // all arrivals are in
-            __threadfence();
             s_flag = ok_a ? 1 : 0;
         }
         for (int i = tid; i < n_wg; i += blockDim.x) wg_bits[i] = 0;
         __syncthreads();
         POP_STAMP(2);
         if (s_flag) {
-            block_select_candidates(
+            block_select_candidates<true>(
                 p.cscore, p.cand_idx, p.n_cand, p.k, p.mask, p.active_idx + p.n_ret, sh,
                 [&](int c) {  // candidate c was handled by workgroup (c/kRB) % n_wg in its round (c/kRB) / n_wg
                     const int rd = c / kRB;

@@ -122,19 +122,24 @@ struct SelectNoHook {
 // channels ascending.  on_selected(i) is called for every selected position before any of those global writes,
 // then after_selected() by every thread (it may contain barriers): callers that only need the positions get
 // them without waiting for the index loads.  All threads of the block must call.
-template <class OnSelected = SelectNoHook, class AfterSelected = SelectNoHook>
+// kCoherentScores: the scores were just written by other workgroups of the same kernel with write-through stores;
+// read them with device-coherent loads (no cache invalidation needed).
+template <bool kCoherentScores = false, class OnSelected = SelectNoHook, class AfterSelected = SelectNoHook>
 __device__ __forceinline__ void block_select_candidates(const float *__restrict__ cs, const int *__restrict__ cand_idx,
                                                         int n_cand, int k, unsigned char *__restrict__ mk,
                                                         int *__restrict__ act_sel, SelShared &sh,
                                                         OnSelected on_selected = OnSelected(),
                                                         AfterSelected after_selected = AfterSelected())
 {
+    auto score = [&](int i) -> float {
+        return kCoherentScores ? __hip_atomic_load(&cs[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : cs[i];
+    };
     const bool in_lds = n_cand <= kSelLdsKeys;
     if (in_lds) {
-        for (int i = threadIdx.x; i < n_cand; i += blockDim.x) sh.keys[i] = score_key(cs[i]);
+        for (int i = threadIdx.x; i < n_cand; i += blockDim.x) sh.keys[i] = score_key(score(i));
         __syncthreads();
     }
-    auto key = [&](int i) -> uint32_t { return in_lds ? sh.keys[i] : score_key(cs[i]); };
+    auto key = [&](int i) -> uint32_t { return in_lds ? sh.keys[i] : score_key(score(i)); };
     uint32_t kth;
     int take;
     radix_threshold(key, n_cand, k, sh, kth, take);
