@@ -279,7 +279,16 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
             coherent_store(&p.cscore[((e / kRB) * n_wg + b) * kRB + e % kRB], p.nrm[j] * fabsf(hv));
         }
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's stores are acknowledged
+    // Phase B's first round goes out now, behind the stores, so its latency overlaps the hand-over; the wait
+    // below leaves exactly those loads outstanding (the counter retires in order), i.e. the stores are acknowledged.
+    asm volatile("" ::: "memory");
+    load_round<V, PER, true, true>(buf_a, w, nvec, j_b, col, ok, dummy);
+    asm volatile("" ::: "memory");
+    static_assert(kRB * 3 * PER == 6 || kRB * 3 * PER == 12, "literal in the wait below");
+    if (PER == 1)
+        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+    else
+        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
     __syncthreads();
     POP_STAMP(1);
 
@@ -380,8 +389,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     // flight).  Otherwise they go out right after the current round's data has been consumed (about one round in
     // flight, the reduction and the barrier still overlap the load latency): measured faster on MI355X, whose
     // memory system loses throughput when the request queues get deeper.
-    if (n_b2 > 0) load_round<V, PER, true, true>(buf_a, w, nvec, j_b, col, ok, dummy);
-    for (int i = 0; i < n_b2; i += 2) {
+    for (int i = 0; i < n_b2; i += 2) {  // buf_a already holds round 0 (loaded during the hand-over)
         if (i == 4) POP_STAMP(5);
         if (i == 8) POP_STAMP(7);
         if (kPrefetchEarly) {
