@@ -132,6 +132,10 @@ int pop_layer_get_norms(pop_layer_t *layer, float *nrm, void *stream);
  * POP_OK, or POP_EDEVICE.  Every kernel exits either way; this call is how a caller finds out. */
 int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
+/* Host only.  Which implementation the last successful pop_decode_mask on this layer used: 0 = none yet,
+ * 1 = the fused single-sequence kernel, 2 = the batch-general kernels.  If workgroups != NULL it receives the
+ * fused kernel's grid size for the current partition (0 when the fused kernel does not apply). */
+int pop_layer_step_kind(pop_layer_t *layer, int *workgroups);
 
 #ifdef __cplusplus
 }

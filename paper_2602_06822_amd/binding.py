@@ -46,6 +46,7 @@ _SIGS = {
     "pop_layer_get_norms": (_i, [_vp, _vp, _vp]),
     "pop_layer_get_hidden": (_i, [_vp, _vp, _i, _vp]),
     "pop_layer_sync_status": (_i, [_vp, _vp]),
+    "pop_layer_step_kind": (_i, [_vp, _ip]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -171,6 +172,15 @@ def pop_layer_get_hidden(layer, h, B, stream=None):
 
 def pop_layer_sync_status(layer, stream=None):
     _check(_lib.pop_layer_sync_status(layer, _stream(stream)), "pop_layer_sync_status")
+
+
+def pop_layer_step_kind(layer):
+    """(kind, workgroups): kind 0 none, 1 fused kernel, 2 batch-general kernels."""
+    wg = C.c_int()
+    kind = _lib.pop_layer_step_kind(layer, C.byref(wg))
+    if kind < 0:
+        raise PopError(kind, "pop_layer_step_kind")
+    return kind, wg.value
 
 
 def raw():

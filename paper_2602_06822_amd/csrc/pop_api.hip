@@ -71,6 +71,26 @@ struct pop_layer {
     int n_slabs = 0;
 };
 
+namespace {
+
+// Launch shape of the fused single-sequence step for the layer's current region sizes, sized to be co-resident.
+int plan_fused_step(pop_layer *L)
+{
+    L->fused_ok = fused_plan(L->d, L->is_bf16, L->n_ret, L->n_cand, L->wg_target, &L->plan);
+    if (L->fused_ok) {
+        int max_wg = 0;
+        POP_HIP(fused_resident_limit(L->is_bf16, L->plan, L->n_cu, &max_wg));
+        if (max_wg < 2) {
+            L->fused_ok = false;
+        } else if (L->plan.n_wg > max_wg) {
+            L->fused_ok = fused_plan(L->d, L->is_bf16, L->n_ret, L->n_cand, max_wg, &L->plan) && L->plan.n_wg <= max_wg;
+        }
+    }
+    return POP_OK;
+}
+
+}  // namespace
+
 extern "C" {
 
 int pop_version(void) { return 100; }
@@ -233,17 +253,9 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
     POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s));
     if (n_ret) POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
     L->ulist_prefix_ok = true;
-    // fused single-sequence step: launch shape for this partition, sized to be co-resident
-    L->fused_ok = fused_plan(L->d, L->is_bf16, n_ret, n_cand, L->wg_target, &L->plan);
-    if (L->fused_ok) {
-        int max_wg = 0;
-        POP_HIP(fused_resident_limit(L->is_bf16, L->plan, L->n_cu, &max_wg));
-        if (max_wg < 2) {
-            L->fused_ok = false;
-        } else if (L->plan.n_wg > max_wg) {
-            L->fused_ok = fused_plan(L->d, L->is_bf16, n_ret, n_cand, max_wg, &L->plan) && L->plan.n_wg <= max_wg;
-        }
-    }
+    L->n_ret = n_ret;
+    L->n_cand = n_cand;
+    { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
     POP_HIP(launch_fill_int(L->sync, 8, 0, s));
     POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
@@ -416,6 +428,13 @@ int pop_layer_sync_status(pop_layer_t *L, void *stream)
     POP_HIP(hipMemcpyAsync(&flag, L->sync + 2, 4, hipMemcpyDeviceToHost, as_stream(stream)));
     POP_HIP(hipStreamSynchronize(as_stream(stream)));
     return flag ? POP_EDEVICE : POP_OK;
+}
+
+int pop_layer_step_kind(pop_layer_t *L, int *workgroups)
+{
+    if (!L) return POP_EINVAL;
+    if (workgroups) *workgroups = (L->has_partition && L->fused_ok) ? L->plan.n_wg : 0;
+    return !L->has_step ? 0 : (L->step_fused ? 1 : 2);
 }
 
 int pop_layer_get_hidden(pop_layer_t *L, float *h, int B, void *stream)

@@ -150,7 +150,7 @@ def test_fused_step_many_rounds_per_workgroup(pop, oracle, monkeypatch, dtype, w
     """Few workgroups => many rounds each: exercises the ping-pong stream, the phase D preparation that rides
     along with the retained rounds, and (with 4 workgroups) the multi-round candidate phase."""
     monkeypatch.setenv("POP_FUSED_WGS", str(wgs))
-    d, m, T = 512, 1024, 40
+    d, m, T = 512, 768, 40
     L = synth.make_layer(synth.small_config(f"many_rounds_{wgs}", d, m, dtype, n_outlier=2, heavy_tail=dtype == BF16))
     x = synth.make_activations(L, T, "prompt")
     xt = synth.make_activations(L, 6, "decode")
@@ -160,10 +160,14 @@ def test_fused_step_many_rounds_per_workgroup(pop, oracle, monkeypatch, dtype, w
         scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
         outs = [_check_decode(oracle, G, L, region, cand, xt[t:t + 1], kk)
                 for t, kk in enumerate([k, k, 0, n_cand, 1, k])]
-        # the same step again gives the same bits (the in-kernel flags were rearmed correctly)
-        again = G.decode(xt[5:6], k)
-        for key in ("mask", "active_idx", "y", "cscore"):
-            assert np.array_equal(outs[5][key], again[key]), key
+        assert pop.pop_layer_step_kind(G.handle) == (1, wgs)  # the fused kernel ran, with the forced grid
+        # the same step again gives the same bits (the in-kernel flags were rearmed correctly; the assignment
+        # of channels to workgroups is fixed, so the summation order of y is too)
+        first = outs[5]
+        for _ in range(3):
+            again = G.decode(xt[5:6], k)
+            for key in ("mask", "active_idx", "y", "cscore"):
+                assert np.array_equal(first[key], again[key]), key
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
@@ -245,6 +249,14 @@ def test_determinism_and_poisoned_scratch(pop, oracle):
                 assert np.array_equal(o1[key][:, rc], o2[key][:, rc]), key
             else:
                 assert np.array_equal(o1[key], o2[key]), key
+        # single-sequence steps (fused kernel): bit-identical y as well
+        s1 = G.decode(xt[:1], k)
+        G.ffn(xt, (synth.rng("dirty2").random((4, m)) < 0.5).astype(np.uint8))
+        G.prefill(x, n_ret, n_cand)
+        s2 = G.decode(xt[:1], k)
+        for key in s1:
+            sel = (slice(None), rc) if key == "h" else slice(None)
+            assert np.array_equal(s1[key][sel], s2[key][sel]), key
 
 
 def test_error_paths(pop):
