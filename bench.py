@@ -97,8 +97,10 @@ def run(args):
             per_tok = []
             for t in range(DECODE_STEPS):
                 xt = C.c_void_p(L.x_decode.data_ptr() + t * d * 2)
+                yp = C.c_void_p(L.y.data_ptr())
                 per_tok.append(((L.handle, xt, 1, karr, None, None, None, None, sp),
-                                (L.handle, None, 1, None, 0, C.c_void_p(L.y.data_ptr()), pop.POP_BF16, sp)))
+                                (L.handle, None, 1, None, 0, yp, pop.POP_BF16, sp),
+                                (L.handle, xt, 1, karr, yp, pop.POP_BF16, None, None, None, None, sp)))
             decode.append(per_tok)
         return prefill, decode
 
@@ -106,7 +108,7 @@ def run(args):
         if rc != 0:
             raise pop.PopError(rc, "bench")
 
-    def one_request(calls, ev=None, probe=None):
+    def one_request(calls, ev=None, probe=None, single=False):
         prefill, decode = calls
         if ev:
             ev[0].record(stream)
@@ -116,8 +118,11 @@ def run(args):
             ev[1].record(stream)
         for t in range(DECODE_STEPS):
             for li in range(len(layers)):
-                a_mask, a_ffn = decode[li][t]
-                if probe is not None and (t * len(layers) + li) % probe["every"] == 0:
+                a_mask, a_ffn, a_step = decode[li][t]
+                if single:
+                    # the whole step as one kernel launch (pop_decode_step in its single-launch form)
+                    check(lib.pop_decode_step(*a_step))
+                elif probe is not None and (t * len(layers) + li) % probe["every"] == 0:
                     e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                     e0.record(stream)
                     check(lib.pop_decode_mask(*a_mask))
@@ -131,16 +136,16 @@ def run(args):
         if ev:
             ev[2].record(stream)
 
-    def timed(r, steps, warmup, probe_every=None):
+    def timed(r, steps, warmup, probe_every=None, single=False):
         calls = make_calls(r)
         for _ in range(warmup):
-            one_request(calls)
+            one_request(calls, single=single)
         torch.cuda.synchronize()
         evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
         probe = dict(every=probe_every, events=[]) if probe_every else None
         t0 = time.perf_counter()
         for s in range(steps):
-            one_request(calls, evs[s], probe)
+            one_request(calls, evs[s], probe, single)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs)
@@ -179,6 +184,12 @@ def run(args):
         layers = layers[:1]
         warm = timed(r_main, max(1, args.steps // 2), 1)["decode_us_per_token"]
         layers = keep
+    # the same step as a single kernel launch that also sums the partial outputs, for comparison
+    single = None
+    if not args.quick:
+        for L in layers:
+            pop.pop_layer_set_single_launch(L.handle, True)
+        single = timed(r_main, max(1, args.steps // 2), 1, single=True)["decode_us_per_token"]
 
     fused_us = main.get("probe_mask_us")
     roofline = None
@@ -230,6 +241,7 @@ def run(args):
         "frac_of_peak_active_bytes": round(bm["active"] / us / 1e3 / HBM_PEAK_GBS, 4),
         "warm_us_per_token": None if warm is None else round(warm, 3),
         "other_sparsities": extra,
+        "single_launch_step_us_per_token": None if single is None else round(single, 3),
         "roofline": roofline,
         "cpu_baseline": cpu,
     }

@@ -106,6 +106,22 @@ int pop_decode_mask(pop_layer_t *layer, const void *x_t, int B, const int *k,
 int pop_pruned_ffn(pop_layer_t *layer, const void *x, int T, const unsigned char *mask, int mask_rows,
                    void *y, pop_dtype_t ydtype, void *stream);
 
+/* Whole decode step in one call (Sec. 3.3 "Decoding Stage", Sec. 3.4: pass 1 over retained and candidate
+ * channels, candidate re-scoring, per-token selection, then the output over retained and selected channels):
+ * the same results as pop_decode_mask followed by pop_pruned_ffn(mask = NULL), with y: dev [B][d] of dtype ydtype
+ * and the other outputs as in pop_decode_mask (each may be NULL).
+ * By default it issues exactly those two calls' launches.  With pop_layer_set_single_launch(layer, 1) (or the
+ * environment variable POP_SINGLE_LAUNCH=1 at layer creation) a B == 1 step is a single kernel launch, whose
+ * workgroups wait for each other at the end and then sum their partial outputs themselves; it keeps no host-side
+ * state per launch, so a captured launch can be replayed.  That wait is bounded: if it (or the wait for the
+ * selection) expires, y is not written and pop_layer_sync_status reports POP_EDEVICE; repeat the step in the
+ * default form, which never depends on such a wait for its result.  The single launch sums y in another (also
+ * fixed) order, so the two forms agree to float32 rounding, not bit for bit.  Measured on MI355X the two forms
+ * take the same time to within 3 %.
+ * Errors: as pop_decode_mask; y == NULL or bad ydtype -> POP_EINVAL. */
+int pop_decode_step(pop_layer_t *layer, const void *x_t, int B, const int *k, void *y, pop_dtype_t ydtype,
+                    float *cand_scores, unsigned char *mask, int *active_idx, int *n_active, void *stream);
+
 /* ---- pieces of the path exposed on their own (selection parity is defined on caller-supplied scores) ---- */
 
 /* Three regions from given scores (dev [m] float32), as in pop_prefill_partition.  Needs no layer. */
@@ -132,6 +148,8 @@ int pop_layer_get_norms(pop_layer_t *layer, float *nrm, void *stream);
  * POP_OK, or POP_EDEVICE.  Every kernel exits either way; this call is how a caller finds out. */
 int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
+/* Host only.  See pop_decode_step. */
+int pop_layer_set_single_launch(pop_layer_t *layer, int on);
 /* Host only.  Which implementation the last successful pop_decode_mask on this layer used: 0 = none yet,
  * 1 = the fused single-sequence kernel, 2 = the batch-general kernels.  If workgroups != NULL it receives the
  * fused kernel's grid size for the current partition (0 when the fused kernel does not apply). */

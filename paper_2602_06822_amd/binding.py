@@ -39,6 +39,7 @@ _SIGS = {
     "pop_layer_destroy": (_i, [_vp]),
     "pop_prefill_partition": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "pop_decode_mask": (_i, [_vp, _vp, _i, _ip, _vp, _vp, _vp, _vp, _vp]),
+    "pop_decode_step": (_i, [_vp, _vp, _i, _ip, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
     "pop_pruned_ffn": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _vp]),
     "pop_partition_from_scores": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
     "pop_topk_from_scores": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp]),
@@ -47,6 +48,7 @@ _SIGS = {
     "pop_layer_get_hidden": (_i, [_vp, _vp, _i, _vp]),
     "pop_layer_sync_status": (_i, [_vp, _vp]),
     "pop_layer_step_kind": (_i, [_vp, _ip]),
+    "pop_layer_set_single_launch": (_i, [_vp, _i]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -142,6 +144,12 @@ def pop_decode_mask(layer, x_t, B, k, cand_scores=None, mask=None, active_idx=No
                                 _ptr(active_idx), _ptr(n_active), _stream(stream)), "pop_decode_mask")
 
 
+def pop_decode_step(layer, x_t, B, k, y, ydtype, cand_scores=None, mask=None, active_idx=None, n_active=None,
+                    stream=None):
+    _check(_lib.pop_decode_step(layer, _ptr(x_t), B, _k_array(k, B), _ptr(y), ydtype, _ptr(cand_scores), _ptr(mask),
+                                _ptr(active_idx), _ptr(n_active), _stream(stream)), "pop_decode_step")
+
+
 def pop_pruned_ffn(layer, x, T, mask, mask_rows, y, ydtype, stream=None):
     _check(_lib.pop_pruned_ffn(layer, _ptr(x), T, _ptr(mask), mask_rows, _ptr(y), ydtype, _stream(stream)),
            "pop_pruned_ffn")
@@ -172,6 +180,10 @@ def pop_layer_get_hidden(layer, h, B, stream=None):
 
 def pop_layer_sync_status(layer, stream=None):
     _check(_lib.pop_layer_sync_status(layer, _stream(stream)), "pop_layer_sync_status")
+
+
+def pop_layer_set_single_launch(layer, on: bool):
+    _check(_lib.pop_layer_set_single_launch(layer, 1 if on else 0), "pop_layer_set_single_launch")
 
 
 def pop_layer_step_kind(layer):

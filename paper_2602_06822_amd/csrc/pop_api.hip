@@ -41,6 +41,7 @@ struct pop_layer {
     void *w = nullptr;     // [m][3][d]: gate row, up row, down column of each channel
     float *nrm = nullptr;  // [m]
     int n_cu = 0, wg_target = 0;
+    bool single_launch = false;  // pop_decode_step at B = 1: sum the partial outputs inside the fused kernel
     // partition
     bool has_partition = false;
     int n_ret = 0, n_cand = 0;
@@ -87,6 +88,52 @@ int plan_fused_step(pop_layer *L)
         }
     }
     return POP_OK;
+}
+
+// Copies the step's selection results from the layer's state to the caller's buffers (each may be null).
+int copy_step_outputs(pop_layer *L, int B, float *cand_scores, unsigned char *mask, int *active_idx, int *n_active,
+                      hipStream_t s)
+{
+    const int m = L->m, n_ret = L->n_ret, n_cand = L->n_cand;
+    if (cand_scores && n_cand)
+        POP_HIP(hipMemcpy2DAsync(cand_scores, (size_t)n_cand * 4, L->cscore, (size_t)m * 4, (size_t)n_cand * 4, B,
+                                 hipMemcpyDeviceToDevice, s));
+    if (mask) POP_HIP(hipMemcpyAsync(mask, L->mask, (size_t)B * m, hipMemcpyDeviceToDevice, s));
+    if (active_idx && n_ret + n_cand)
+        POP_HIP(hipMemcpy2DAsync(active_idx, (size_t)(n_ret + n_cand) * 4, L->active_idx, (size_t)m * 4,
+                                 (size_t)(n_ret + n_cand) * 4, B, hipMemcpyDeviceToDevice, s));
+    if (n_active) POP_HIP(hipMemcpyAsync(n_active, L->n_active, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+    return POP_OK;
+}
+
+// Arguments of the fused single-sequence kernel for the layer's current partition.
+FusedParams fused_params(pop_layer *L, const void *x_t, int k)
+{
+    FusedParams p = {};
+    p.w = L->w;
+    p.x = x_t;
+    p.nvec = L->d / (L->is_bf16 ? 8 : 4);
+    p.d = L->d;
+    p.m = L->m;
+    p.ret_idx = L->ret_idx;
+    p.n_ret = L->n_ret;
+    p.cand_idx = L->cand_idx;
+    p.n_cand = L->n_cand;
+    p.k = k;
+    p.nrm = L->nrm;
+    p.h = L->h;
+    p.cscore = L->cscore;
+    p.mask = L->mask;
+    p.active_idx = L->active_idx;
+    p.n_active = L->n_active;
+    p.partial = L->partial;
+    p.sync = L->sync;
+    p.deferred = L->deferred;
+    p.selbits = L->selbits;
+#ifdef POP_TRACE
+    p.trace = g_trace;
+#endif
+    return p;
 }
 
 }  // namespace
@@ -187,6 +234,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         if (v >= 2 && v <= fused_max_workgroups()) L->wg_target = v;
     }
     if (L->wg_target > fused_max_workgroups()) L->wg_target = fused_max_workgroups();
+    if (const char *e = getenv("POP_SINGLE_LAUNCH")) L->single_launch = atoi(e) != 0;
 
     const size_t mm = (size_t)m, B = (size_t)max_batch;
     struct Req { void **p; size_t bytes; };
@@ -284,30 +332,7 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
     const int m = L->m, n_ret = L->n_ret, n_cand = L->n_cand;
     L->has_step = false;
     if (B == 1 && L->fused_ok) {
-        FusedParams p = {};
-        p.w = L->w;
-        p.x = x_t;
-        p.nvec = L->d / (L->is_bf16 ? 8 : 4);
-        p.d = L->d;
-        p.m = m;
-        p.ret_idx = L->ret_idx;
-        p.n_ret = n_ret;
-        p.cand_idx = L->cand_idx;
-        p.n_cand = n_cand;
-        p.k = kk.k[0];
-        p.nrm = L->nrm;
-        p.h = L->h;
-        p.cscore = L->cscore;
-        p.mask = L->mask;
-        p.active_idx = L->active_idx;
-        p.n_active = L->n_active;
-        p.partial = L->partial;
-        p.sync = L->sync;
-        p.deferred = L->deferred;
-        p.selbits = L->selbits;
-#ifdef POP_TRACE
-        p.trace = g_trace;
-#endif
+        FusedParams p = fused_params(L, x_t, kk.k[0]);
         POP_HIP(launch_decode_fused(L->plan, L->is_bf16, p, s));
         L->step_fused = true;
     } else {
@@ -323,16 +348,38 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         }
         L->step_fused = false;
     }
-    if (cand_scores && n_cand)
-        POP_HIP(hipMemcpy2DAsync(cand_scores, (size_t)n_cand * 4, L->cscore, (size_t)m * 4, (size_t)n_cand * 4, B,
-                                 hipMemcpyDeviceToDevice, s));
-    if (mask) POP_HIP(hipMemcpyAsync(mask, L->mask, (size_t)B * m, hipMemcpyDeviceToDevice, s));
-    if (active_idx && n_ret + n_cand)
-        POP_HIP(hipMemcpy2DAsync(active_idx, (size_t)(n_ret + n_cand) * 4, L->active_idx, (size_t)m * 4,
-                                 (size_t)(n_ret + n_cand) * 4, B, hipMemcpyDeviceToDevice, s));
-    if (n_active) POP_HIP(hipMemcpyAsync(n_active, L->n_active, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+    { int rc = copy_step_outputs(L, B, cand_scores, mask, active_idx, n_active, s); if (rc != POP_OK) return rc; }
     L->step_B = B;
     L->step_k = kk;
+    L->has_step = true;
+    return POP_OK;
+}
+
+int pop_decode_step(pop_layer_t *L, const void *x_t, int B, const int *k, void *y, pop_dtype_t ydtype,
+                    float *cand_scores, unsigned char *mask, int *active_idx, int *n_active, void *stream)
+{
+    if (!L || !x_t || !k || !y) return POP_EINVAL;
+    if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
+    if (!L->has_partition) return POP_ESTATE;
+    if (B < 1 || B > L->max_batch) return POP_ESHAPE;
+    for (int b = 0; b < B; ++b)
+        if (k[b] < 0 || k[b] > L->n_cand) return POP_ESHAPE;
+    if (!(B == 1 && L->fused_ok && L->single_launch)) {
+        int rc = pop_decode_mask(L, x_t, B, k, cand_scores, mask, active_idx, n_active, stream);
+        if (rc != POP_OK) return rc;
+        return pop_pruned_ffn(L, nullptr, B, nullptr, 0, y, ydtype, stream);
+    }
+    hipStream_t s = as_stream(stream);
+    L->has_step = false;
+    FusedParams p = fused_params(L, x_t, k[0]);
+    p.y = y;
+    p.y_bf16 = ydtype == POP_BF16;
+    POP_HIP(launch_decode_fused(L->plan, L->is_bf16, p, s));
+    L->step_fused = true;
+    { int rc = copy_step_outputs(L, B, cand_scores, mask, active_idx, n_active, s); if (rc != POP_OK) return rc; }
+    L->step_B = 1;
+    L->step_k = BatchK{};
+    L->step_k.k[0] = k[0];
     L->has_step = true;
     return POP_OK;
 }
@@ -428,6 +475,13 @@ int pop_layer_sync_status(pop_layer_t *L, void *stream)
     POP_HIP(hipMemcpyAsync(&flag, L->sync + 2, 4, hipMemcpyDeviceToHost, as_stream(stream)));
     POP_HIP(hipStreamSynchronize(as_stream(stream)));
     return flag ? POP_EDEVICE : POP_OK;
+}
+
+int pop_layer_set_single_launch(pop_layer_t *L, int on)
+{
+    if (!L) return POP_EINVAL;
+    L->single_launch = on != 0;
+    return POP_OK;
 }
 
 int pop_layer_step_kind(pop_layer_t *L, int *workgroups)

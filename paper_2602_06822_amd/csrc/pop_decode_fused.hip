@@ -189,8 +189,18 @@ __device__ __forceinline__ void coherent_store(float *p, float v)
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// 16-byte write-through store (device scope), p 16-byte aligned.  Not tracked by the compiler's wait counting:
+// follow with an explicit wait before relying on it.
+__device__ __forceinline__ void coherent_store4(float *p, float4 v)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 t = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(t) : "memory");
+}
+constexpr int kStage = 4096;  // floats of a partial output row staged in LDS at a time
 
 constexpr int kBitsStride = 1024;                   // ints between the selection words of two workgroups
+constexpr int kGoWord = 64;                          // offset of a workgroup's end-of-step "go" word from its selection word
 constexpr int kBitsValid = 1 << 31;                  // set in selbits[b] once the selection of this step is known
 constexpr int kMaxCandRounds = 30 / kRB;             // candidate slots of a workgroup must fit the other 31 bits
 
@@ -205,6 +215,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     __shared__ acc_t part[2][2 * kRB][kSelMaxWaves];
     __shared__ int j_a[kKeep + 2 * kRB], j_b[kKeep + 2 * kRB], j_d[kKeep + 2 * kRB];  // staged channel indices
     __shared__ float h_a[kKeep + 2 * kRB], h_b[kKeep + 2 * kRB];                      // their hidden activations
+    __shared__ __attribute__((aligned(16))) float y_stage[kStage];  // single-launch step: partial row on its way out
     __shared__ int wg_bits[1024];                       // selector only: selected candidate slots per workgroup
 
     const int tid = threadIdx.x, lane = tid % kWave;
@@ -215,7 +226,11 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     const vec_t *w = reinterpret_cast<const vec_t *>(p.w);
 
     POP_STAMP(0);
-    if (b == 0 && tid == 0) p.sync[3] = 0;  // "some workgroup deferred its phase D share" flag of this step
+    // end-of-step "go" word of this workgroup: all go words hold the same value between launches, and change once,
+    // together, when the last workgroup of a single-launch step has delivered its partial output row
+    int *const go = p.selbits + (size_t)b * kBitsStride + kGoWord;
+    const int go_before = p.y ? coherent_load(go) : 0;
+    if (b == 0 && tid == 0) coherent_store(&p.sync[3], 0);  // "some workgroup deferred its phase D share" flag of this step
     int col[PER];
     bool ok[PER];
     vec_t xv[PER];
@@ -316,8 +331,28 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
                 }
         }
     };
-    auto store_partial = [&]() {
+    auto store_partial = [&]() __attribute__((always_inline)) {
         float *dst = p.partial + (size_t)b * p.d;
+        if (p.y) {
+            // single-launch step: other workgroups read these rows in this launch, so write them through; staged
+            // in LDS first so that each store instruction covers whole contiguous lines (a write-through store of
+            // a few bytes per lane is one memory transaction per lane)
+            for (int c0 = 0; c0 < p.d; c0 += kStage) {
+#pragma unroll
+                for (int q = 0; q < PER; ++q) {
+                    const int o = col[q] * E - c0;
+                    if (ok[q] && o >= 0 && o < kStage)
+#pragma unroll
+                        for (int e = 0; e < E; ++e) y_stage[o + e] = acc[q][e];
+                }
+                __syncthreads();
+                const int n = min(kStage, p.d - c0);
+                for (int v = tid * 4; v < n; v += blockDim.x * 4)
+                    coherent_store4(dst + c0 + v, *reinterpret_cast<const float4 *>(&y_stage[v]));
+                __syncthreads();
+            }
+            return;
+        }
 #pragma unroll
         for (int q = 0; q < PER; ++q)
             if (ok[q]) {
@@ -326,6 +361,75 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
                     *reinterpret_cast<float4 *>(dst + (size_t)col[q] * E + e) =
                         make_float4(acc[q][e], acc[q][e + 1], acc[q][e + 2], acc[q][e + 3]);
             }
+    };
+    // Single-launch step: once every workgroup's partial row is acknowledged device-wide (write-through stores,
+    // counter wait, barrier, then one arrival per workgroup), each workgroup sums a slice of the d outputs over
+    // all rows in a fixed order: 16 lanes take 16 adjacent outputs, the block's blockDim/16 lane groups take the
+    // rows round robin, then a fixed tree over the groups.  The wait is bounded like the others; if it expires
+    // the sticky error flag is raised and y is left unwritten.
+    auto final_reduce = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        // Arrival counter + one "go" word per workgroup (each in its own 4 KiB, next to its selection word): the
+        // last workgroup to arrive rewinds the counter and changes all the go words, and every workgroup polls
+        // only its own.  Hundreds of workgroups polling the one counter would queue up at a single memory
+        // channel, in front of the last arrivals.  Nothing here depends on host-side state, so a captured launch
+        // can be replayed.
+        if (tid == 0) s_flag = atomicAdd(&p.sync[6], 1) == n_wg - 1 ? 1 : 0;
+        __syncthreads();
+        if (s_flag) {
+            if (tid == 0) coherent_store(&p.sync[6], 0);
+            for (int i = tid; i < n_wg; i += blockDim.x)
+                coherent_store(p.selbits + (size_t)i * kBitsStride + kGoWord, go_before + 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            bool all_in = false;
+            for (int it = 0; !all_in && it < kSpinLimit; ++it) {
+                all_in = coherent_load(go) != go_before;
+                if (!all_in) __builtin_amdgcn_s_sleep(2);
+            }
+            if (!all_in) p.sync[2] = 1;
+            s_flag = all_in ? 1 : 0;
+        }
+        __syncthreads();
+        POP_STAMP(5);
+        if (!s_flag) return;
+        const bool whole = coherent_load(&p.sync[3]) == 0;  // some workgroup gave up waiting for the selection: y would miss its share
+        float *red = reinterpret_cast<float *>(&sh.hist[0]);  // [waves][16]
+        const int cpw = (p.d + n_wg - 1) / n_wg;
+        const int c_lo = min(p.d, b * cpw), c_hi = min(p.d, c_lo + cpw);
+        const int cc = tid % 16, g = tid / 16, ng = blockDim.x / 16;
+        for (int c0 = c_lo; c0 < c_hi; c0 += 16) {
+            const int c = c0 + cc;
+            const bool in = c < c_hi;
+            const float *src = p.partial + (in ? c : c_lo);
+            float s = 0.f;
+            int r = g;
+            for (; r + 15 * ng < n_wg; r += 16 * ng) {  // all of a 256-row grid in one batch of independent loads
+                float v[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u)
+                    v[u] = __hip_atomic_load(src + (size_t)(r + u * ng) * p.d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int u = 0; u < 16; ++u) s += v[u];
+            }
+            for (; r < n_wg; r += ng)
+                s += __hip_atomic_load(src + (size_t)r * p.d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            s += __shfl_xor(s, 16, kWave);
+            s += __shfl_xor(s, 32, kWave);
+            if (lane < 16) red[wave * 16 + lane] = s;
+            __syncthreads();
+            if (tid < 16 && in && whole) {
+                float v = 0.f;
+                for (int wv = 0; wv < nw; ++wv) v += red[wv * 16 + tid];
+                if (p.y_bf16)
+                    reinterpret_cast<uint16_t *>(p.y)[c] = f32_to_bf16(v);
+                else
+                    reinterpret_cast<float *>(p.y)[c] = v;
+            }
+            __syncthreads();
+        }
     };
 
     if (b == 0) {
@@ -355,6 +459,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
             phase_d(wg_bits[0]);
         }
         store_partial();
+        if (p.y) final_reduce();
         return;
     }
 
@@ -436,6 +541,7 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     }
     for (int e = tid; e < n_b * kRB; e += blockDim.x)
         if (j_b[e] >= 0) p.h[j_b[e]] = h_b[e];
+    if (p.y) final_reduce();
     POP_STAMP(6);
 }
 

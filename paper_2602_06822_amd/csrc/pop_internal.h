@@ -98,11 +98,16 @@ struct FusedParams {
     int *n_active;           // [1]
     float *partial;          // [n_wg][d]
     int *sync;               // [0] phase-A arrivals, [2] sticky error flag, [3] some workgroup deferred its
-                             // phase D share in this step.  [0] is back at zero when the kernel ends.
+                             // phase D share in this step, [6] end-of-step arrivals (single-launch step only).
+                             // [0] is back at zero when the kernel ends.
     int *selbits;            // [n_wg] per-workgroup selection word (valid bit + selected candidate slots);
                              // each workgroup clears its own word after use, so a launch can be replayed
     unsigned long long *trace;  // profiling builds only: 8 timestamps per workgroup, else null
     int *deferred;           // [n_wg]
+    // single-launch step: when y is non-null the kernel also sums the partial rows itself, behind a grid-wide
+    // arrival counter (sync[6], back at zero when the kernel ends)
+    void *y;                 // [d] float32 or bf16, or null: the partial rows are summed by decode_tail_kernel
+    int y_bf16;
 };
 
 struct FusedPlan {

@@ -63,8 +63,10 @@ class GpuLayer:
         self.n_ret, self.n_cand = n_ret, n_cand
         return host(scores), host(region), host(ret)[:n_ret], host(cand)[:n_cand]
 
-    def decode(self, x_t: np.ndarray, k, ydtype=None):
-        """x_t: [B][d] storage.  Returns dict of host arrays (cscore, mask, active_idx, n_active, h, y)."""
+    def decode(self, x_t: np.ndarray, k, ydtype=None, one_call=False):
+        """x_t: [B][d] storage.  Returns dict of host arrays (cscore, mask, active_idx, n_active, h, y).
+        one_call: use pop_decode_step instead of pop_decode_mask + pop_pruned_ffn (True: its default form;
+        "single_launch": its single-launch form)."""
         B = x_t.shape[0]
         ks = [k] * B if isinstance(k, int) else list(k)
         n_ret, n_cand, m, d = self.n_ret, self.n_cand, self.m, self.d
@@ -72,13 +74,18 @@ class GpuLayer:
         mask = torch.empty((B, m), dtype=torch.uint8, device="cuda")
         act = torch.full((B, max(n_ret + n_cand, 1)), -1, dtype=torch.int32, device="cuda")
         na = torch.empty(B, dtype=torch.int32, device="cuda")
-        self.pop.pop_decode_mask(self.handle, dev(x_t), B, ks, cs if n_cand else None, mask,
-                                 act if n_ret + n_cand else None, na)
+        ydtype = self.dtype if ydtype is None else ydtype
+        y = torch.full((B, d), 12345, dtype=torch.float32 if ydtype == synth.F32 else torch.int16, device="cuda")
+        if one_call:
+            self.pop.pop_layer_set_single_launch(self.handle, one_call == "single_launch")
+            self.pop.pop_decode_step(self.handle, dev(x_t), B, ks, y, ydtype, cs if n_cand else None, mask,
+                                     act if n_ret + n_cand else None, na)
+        else:
+            self.pop.pop_decode_mask(self.handle, dev(x_t), B, ks, cs if n_cand else None, mask,
+                                     act if n_ret + n_cand else None, na)
+            self.pop.pop_pruned_ffn(self.handle, None, B, None, 0, y, ydtype)
         h = torch.empty((B, m), dtype=torch.float32, device="cuda")
         self.pop.pop_layer_get_hidden(self.handle, h, B)
-        ydtype = self.dtype if ydtype is None else ydtype
-        y = torch.empty((B, d), dtype=torch.float32 if ydtype == synth.F32 else torch.int16, device="cuda")
-        self.pop.pop_pruned_ffn(self.handle, None, B, None, 0, y, ydtype)
         yh = host(y).astype(np.float64) if ydtype == synth.F32 else bf16_out_to_f64(y)
         self.pop.pop_layer_sync_status(self.handle)  # raises if an in-kernel bounded wait expired
         return dict(cscore=host(cs)[:, :n_cand], mask=host(mask), active_idx=host(act), n_active=host(na),

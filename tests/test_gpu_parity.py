@@ -115,6 +115,23 @@ def _check_decode(oracle, G, L, region, cand, x_t, ks, ydtype=None):
         y_ref = oracle.down(ref["h"].reshape(1, -1), L.w_down, dtype, mask1)[0]
         yerr = max_abs_rel(out["y"][b], y_ref)
         assert yerr <= Y_TOL[dtype], f"y error {yerr:.3e}"
+    # the whole step in one call: same selection, scores and h bit for bit.  Its default form issues the same
+    # launches (y bit for bit); the single-launch form sums y in another (fixed) order
+    for form in (True, "single_launch"):
+        one = G.decode(x_t, ks, ydtype, one_call=form)
+        for key in ("mask", "active_idx", "n_active", "cscore"):
+            assert np.array_equal(one[key], out[key]), (form, key)
+        assert np.array_equal(one["h"][:, rc], out["h"][:, rc]), form
+        if form is True:
+            assert np.array_equal(one["y"], out["y"])
+            continue
+        again = G.decode(x_t, ks, ydtype, one_call=form)
+        assert np.array_equal(one["y"], again["y"]), "single-launch y is not reproducible"
+        for b in range(B):
+            ref_scale = float(np.max(np.abs(out["y"][b]))) or 1.0
+            ystep = float(np.max(np.abs(one["y"][b] - out["y"][b]))) / ref_scale
+            lim = 1e-5 if (G.dtype if ydtype is None else ydtype) == F32 else 1e-2
+            assert ystep <= lim, f"single-launch y differs from two-call y by {ystep:.3e}"
     return out
 
 
@@ -223,6 +240,46 @@ def test_importance_reduce_standalone(pop, oracle):
     refb = oracle.importance(nrm.reshape(1, m), F32, synth.storage_to_f64(Hb, BF16))
     pop.pop_importance_reduce(dev(Hb), BF16, T, m, dev(nrm), out)
     assert score_rel_err(host(out), refb, eps=1e-9) <= SCORE_TOL
+
+
+def test_single_launch_step_replays_from_a_graph(pop):
+    """The single-launch step keeps no per-launch state on the host: a captured launch is replayed several times,
+    with eager steps in between, and every replay must reproduce the eager result bit for bit."""
+    d, m, T = 512, 1024, 32
+    L = synth.make_layer(synth.small_config("graph_replay", d, m, BF16, n_outlier=2, heavy_tail=True))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 3, "decode")
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 0.55, 0.1)
+    k = n_cand // 2
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        G.prefill(x, n_ret, n_cand)
+        pop.pop_layer_set_single_launch(G.handle, True)
+        side = torch.cuda.Stream()
+        xs = [dev(xt[i:i + 1]) for i in range(3)]
+        y_eager = [torch.zeros(d, dtype=torch.int16, device="cuda") for _ in range(3)]
+        y_graph = torch.zeros(d, dtype=torch.int16, device="cuda")
+        with torch.cuda.stream(side):
+            for i in range(3):
+                pop.pop_decode_step(G.handle, xs[i], 1, [k], y_eager[i], BF16, stream=side)
+            side.synchronize()
+            assert pop.pop_layer_step_kind(G.handle)[0] == 1
+            x_in = xs[0].clone()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                pop.pop_decode_step(G.handle, x_in, 1, [k], y_graph, BF16, stream=torch.cuda.current_stream())
+            for rep in range(6):
+                i = rep % 3
+                x_in.copy_(xs[i])
+                y_graph.fill_(777)
+                g.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(y_graph, y_eager[i]), f"replay {rep}"
+                # the program's own eager work between replays
+                y_tmp = torch.zeros(d, dtype=torch.int16, device="cuda")
+                pop.pop_decode_step(G.handle, xs[(i + 1) % 3], 1, [k], y_tmp, BF16, stream=torch.cuda.current_stream())
+                torch.cuda.synchronize()
+                assert torch.equal(y_tmp, y_eager[(i + 1) % 3])
+            pop.pop_layer_sync_status(G.handle)
 
 
 def test_determinism_and_poisoned_scratch(pop, oracle):
