@@ -4,43 +4,53 @@
 // channels and down columns of the retained and selected channels, each channel's block w[j] = [gate|up|down]
 // being contiguous in memory.
 //
-// Work unit: a "round" of kRB channels handled by one whole workgroup.  The workgroup's threads split the d
-// columns (thread t owns 16-byte vector column t), so a channel's gate, up and down rows are each read by one
-// coalesced sweep of the workgroup, x and the partial y live in registers (no LDS staging, no reduction of y
-// across waves), and the only exchange is the per-row gate/up dot product: wave partials go through LDS, one
-// barrier per round.  The next round's rows are loaded into a second register buffer before the current round
-// is reduced, so the barrier never drains the memory pipeline.
+// Work unit: a "round" handled by one whole workgroup.  The workgroup's threads split the d columns (thread t owns
+// 16-byte vector column t), so a channel's gate, up and down rows are each read by one coalesced sweep of the
+// workgroup, x and the partial y live in registers (no LDS staging, no reduction of y across waves), and the only
+// exchange is the per-row gate/up dot product: wave partials go through LDS, one barrier per round.  The next
+// round's rows are requested as soon as the current round's data has been consumed, so the reduction and the
+// barrier overlap the memory latency.
 //
-//   phase A  candidate rounds (gate+up only), dealt round-robin to all workgroups: h_j = silu(g_j) u_j and the
-//            step score I_j(t) = n_j |h_j| (Eq. 3 with one token) go to global memory.
-//   select   workgroup 0 owns no retained rows.  It waits until all workgroups have published their phase A
+// A round carries kRB retained channels (gate, up and down rows: h_j = silu(g_j) u_j, then y += h_j * down_j) and
+// kXL extra rows that ride along:
+//   - first the workgroup's share of the candidate channels, two per round (gate+up only): h_j and the step score
+//     I_j(t) = n_j |h_j| (Eq. 3 with one token) are published to global memory with write-through stores;
+//   - later, once the selection is known, the down rows of those of its own candidates that were selected.
+// Candidates are dealt round-robin to all workgroups.  Retained rounds are dealt round-robin for the first
+// n_static rounds of every worker; the rest form a shared pool that workers draw from with an atomic ticket counter
+// (requested four rounds ahead, so the counter's latency is never waited for), which evens out the finishing
+// times of workgroups whose memory requests happened to be served more slowly.  With an empty pool the schedule,
+// and with it the summation order of y, is fixed (bit-reproducible output).
+//
+//   select   workgroup 0 owns no retained rows.  It waits until all workgroups have published their candidate
 //            results (bounded spin on a counter; nobody waits for anything before that point), runs the top-k
 //            selection and hands every workgroup one word: a valid bit plus one bit per candidate slot of that
 //            workgroup that was selected.  Mask and active list for the caller are written afterwards.
-//   phase B  retained rounds, dealt round-robin to workgroups 1..: gate+up dot products -> h, then the down
-//            rows of the same round, already in registers, are multiplied by h into the partial y.
-//   phase D  down rows of the workgroup's own selected candidates (their h is still in LDS).  The workgroup's
-//            word is polled during phase B without ever stalling it; if it has not arrived by the end of
-//            phase B the workgroup waits, bounded.  If the bound is ever hit, the workgroup marks its share as
-//            deferred (and raises sync[3]) and the tail kernel adds it, so every wave still exits.
+//   poll     a worker looks at its word once per round without ever stalling on it (thread 0 passes the value
+//            loaded in the previous round to the others through LDS, at the round's barrier); if the word has not
+//            arrived when the retained rounds are done the workgroup waits, bounded.  If the bound is ever hit,
+//            the workgroup marks its share as deferred (and raises sync[3]) and the tail kernel adds it, so every
+//            wave still exits.
 //   tail     a second small kernel sums the per-workgroup partials in workgroup order (plus deferred shares)
-//            and writes y.
+//            and writes y; or, in the single-launch form, the workgroups do it themselves behind a bounded barrier.
 //
-// Waiting is safe because the launch is sized to be co-resident (host checks the occupancy) and both waits
-// are bounded; nothing spins without an exit.
-#include <type_traits>
+// Waiting is safe because the launch is sized to be co-resident (host checks the occupancy) and every wait is
+// bounded; nothing spins without an exit.
+#include <limits.h>
+#include <stdlib.h>
 
 #include "pop_select_dev.h"
 #include "pop_vec.h"
 
 namespace pop {
 
-constexpr int kRB = 2;  // channels per round
-#ifndef POP_PREFETCH_EARLY
-#define POP_PREFETCH_EARLY 0
-#endif
-constexpr bool kPrefetchEarly = POP_PREFETCH_EARLY != 0;
+constexpr int kRB = 2;           // retained channels per round
+constexpr int kXL = 4;           // extra rows per round: 2 candidates x (gate, up), or 4 selected down rows
 constexpr int kSpinLimit = 1 << 16;
+constexpr int kMaxStatic = 64;   // statically dealt rounds per workgroup (staged in LDS)
+constexpr int kKeep = 64;        // rounds whose hidden activations are staged in LDS between flushes
+constexpr int kMaxASlots = 30;   // candidate slots per workgroup: they must fit the selection word next to the valid bit
+constexpr int kNoTicket = INT_MAX;
 
 // Optional per-workgroup timestamps (100 MHz wall clock), compiled in only for profiling builds.
 #ifdef POP_TRACE
@@ -65,39 +75,61 @@ __device__ __forceinline__ bool spin_until(const int *addr, int target)
     return false;
 }
 
-constexpr int kMaxRounds = 64;  // rounds per phase per workgroup (the host plan guarantees it)
-constexpr int kKeep = kMaxRounds * kRB;
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
 template <class V, int PER>
 struct RoundBuf {
-    typename V::vec_t g[kRB][PER], u[kRB][PER], dn[kRB][PER];
-    int j[kRB];  // channel of each slot, -1 when the slot is empty
+    typename V::vec_t g[kRB][PER], u[kRB][PER], dn[kRB][PER], xl[kXL][PER];
 };
 
-// Loads the rows of one round; js points at the round's kRB staged channel indices (LDS), -1 = empty slot.
-// Every load is issued unconditionally (an empty slot or an out-of-range column reads the 16 bytes at `dummy`,
-// one cached transaction per wave): with no branch around a load the compiler knows exactly how many loads are
-// in flight and can wait for the older buffer alone instead of draining the prefetched one as well.
-template <class V, int PER, bool GU, bool DN>
-__device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const typename V::vec_t *__restrict__ w, int nvec,
-                                           const int *js, const int (&col)[PER], const bool (&ok)[PER],
-                                           const typename V::vec_t *__restrict__ dummy)
+// What a round holds; the same in every thread of the workgroup (kept in scalar registers).
+struct RoundDesc {
+    int jb[kRB];    // retained channels, -1 = empty slot
+    int xrow[kXL];  // the extra rows, as row numbers of w viewed as [3 m][d] (-1 = none): gate and up rows of two
+                    // candidates (xkind 1) or down rows of up to four selected candidates (xkind 2)
+    int xmeta;      // bits 0-1 xkind, bit 2 "this round completes the workgroup's candidates",
+                    // bits 8+5a .. 12+5a the candidate slot in this workgroup of extra item a
+    uint32_t boff[kRB], xoff[kXL];  // where those rows start in w, in 16-byte vectors (0 for an empty slot):
+                                    // worked out with the descriptor, a round before the rows are requested
+    bool work;      // the round holds anything at all
+    __device__ __forceinline__ int xkind() const { return xmeta & 3; }
+    __device__ __forceinline__ bool last_a() const { return (xmeta & 4) != 0; }
+    __device__ __forceinline__ int xslot(int a) const { return (xmeta >> (8 + 5 * a)) & 31; }
+};
+
+// Requests the rows of one round: the extra rows first (only in rounds that have any: a request for a dummy
+// vector still occupies the cache's return path for a full wave), then the retained channels' rows, always and in
+// the same order, with no branch around them (an empty slot or an out-of-range column reads the first 16 bytes of
+// w): the compiler then knows how many requests are younger than the rows it needs and waits for no others.
+// The down rows come last: they are needed last.  Addresses are w + 16 * (32-bit vector index).
+template <class V, int PER>
+__device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const RoundDesc &ds,
+                                           const typename V::vec_t *__restrict__ w, int nvec, const int (&col)[PER],
+                                           const bool (&ok)[PER])
 {
+    if (ds.xmeta != 0) {
 #pragma unroll
-    for (int t = 0; t < kRB; ++t) {
-        const int j = js[t];
-        rb.j[t] = j;
-        const typename V::vec_t *row = w + (size_t)(j < 0 ? 0 : j) * 3 * nvec;
+        for (int a = 0; a < kXL; ++a)
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                const uint32_t idx = (ok[q] && ds.xrow[a] >= 0) ? ds.xoff[a] + (uint32_t)col[q] : 0u;
+                rb.xl[a][q] = w[idx];
+            }
+    }
+    uint32_t idx[kRB][PER];
+#pragma unroll
+    for (int t = 0; t < kRB; ++t)
 #pragma unroll
         for (int q = 0; q < PER; ++q) {
-            const bool ld = ok[q] && j >= 0;
-            if (GU) {
-                rb.g[t][q] = *(ld ? row + col[q] : dummy);
-                rb.u[t][q] = *(ld ? row + nvec + col[q] : dummy);
-            }
-            if (DN) rb.dn[t][q] = *(ld ? row + 2 * nvec + col[q] : dummy);
+            const bool ld = ok[q] && ds.jb[t] >= 0;
+            idx[t][q] = ld ? ds.boff[t] + (uint32_t)col[q] : 0u;
+            rb.g[t][q] = w[idx[t][q]];
+            rb.u[t][q] = w[ld ? idx[t][q] + (uint32_t)nvec : 0u];
         }
-    }
+#pragma unroll
+    for (int t = 0; t < kRB; ++t)
+#pragma unroll
+        for (int q = 0; q < PER; ++q) rb.dn[t][q] = w[(ok[q] && ds.jb[t] >= 0) ? idx[t][q] + 2u * (uint32_t)nvec : 0u];
 }
 
 // Sum over the 16 lanes of each DPP row, result in every lane of the row (4 cross-lane adds, no LDS).
@@ -122,61 +154,6 @@ __device__ __forceinline__ float wave_total(float v)
 }
 __device__ __forceinline__ double wave_total(double v) { return wave_sum(v); }
 
-// Gate/up dot products of the round's rows with x: lane partials -> wave sums -> LDS -> totals in every thread.
-// One barrier; `part` ([2*kRB][16], entries of absent waves stay zero) is double-buffered by the caller.
-// `after_dots` runs once the round's gate/up data has been consumed: the place to issue the next loads when the
-// memory pipeline should hold about one round at a time (see kPrefetchEarly).
-template <class V, int PER, class AfterDots>
-__device__ __forceinline__ void round_hidden(const RoundBuf<V, PER> &rb, const typename V::vec_t (&xv)[PER],
-                                             typename V::acc_t (*part)[kSelMaxWaves], int wave, int lane, int nw,
-                                             float (&hv)[kRB], AfterDots after_dots)
-{
-    typedef typename V::acc_t acc_t;
-    static_assert(2 * kRB * kSelMaxWaves == kWave, "one LDS word per lane in the cross-wave step");
-    acc_t ag[kRB], au[kRB];
-#pragma unroll
-    for (int t = 0; t < kRB; ++t) {
-        ag[t] = 0;
-        au[t] = 0;
-#pragma unroll
-        for (int q = 0; q < PER; ++q) {
-            ag[t] = V::dot(rb.g[t][q], xv[q], ag[t]);
-            au[t] = V::dot(rb.u[t][q], xv[q], au[t]);
-        }
-    }
-    asm volatile("" ::: "memory");  // keep the loads below behind the uses above
-    after_dots();
-    asm volatile("" ::: "memory");
-#pragma unroll
-    for (int t = 0; t < kRB; ++t) {
-        const acc_t gt = wave_total(ag[t]), ut = wave_total(au[t]);
-        if (lane == 0) {
-            part[2 * t][wave] = gt;
-            part[2 * t + 1][wave] = ut;
-        }
-    }
-    __syncthreads();
-    if constexpr (sizeof(acc_t) == 4) {
-        // lane l holds value l/16 of wave l%16; a DPP row sum adds the waves in a fixed tree order
-        const float tot = dpp_row_sum((&part[0][0])[lane]);
-#pragma unroll
-        for (int t = 0; t < kRB; ++t) {
-            const float gs = lane_value(tot, 32 * t), us = lane_value(tot, 32 * t + 16);
-            hv[t] = rb.j[t] >= 0 ? silu_mul(gs, us) : 0.f;
-        }
-    } else {
-#pragma unroll
-        for (int t = 0; t < kRB; ++t) {
-            acc_t gs = 0, us = 0;
-            for (int wv = 0; wv < nw; ++wv) {
-                gs += part[2 * t][wv];
-                us += part[2 * t + 1][wv];
-            }
-            hv[t] = rb.j[t] >= 0 ? silu_mul((float)gs, (float)us) : 0.f;
-        }
-    }
-}
-
 __device__ __forceinline__ int coherent_load(const int *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -199,24 +176,41 @@ __device__ __forceinline__ void coherent_store4(float *p, float4 v)
 }
 constexpr int kStage = 4096;  // floats of a partial output row staged in LDS at a time
 
-constexpr int kBitsStride = 1024;                   // ints between the selection words of two workgroups
-constexpr int kGoWord = 64;                          // offset of a workgroup's end-of-step "go" word from its selection word
-constexpr int kBitsValid = 1 << 31;                  // set in selbits[b] once the selection of this step is known
-constexpr int kMaxCandRounds = 30 / kRB;             // candidate slots of a workgroup must fit the other 31 bits
+constexpr int kBitsStride = 1024;    // ints between the selection words of two workgroups
+constexpr int kGoWord = 64;          // offset of a workgroup's end-of-step "go" word from its selection word
+constexpr int kBitsValid = 1 << 31;  // set in a selection word once the selection of this step is known
+constexpr int kSyncDone = 1024;      // sync[kSyncDone]: workers that have stopped drawing tickets
+constexpr int kSyncPool = 2048;      // sync[kSyncPool + 1024 g]: ticket counter of pool group g
+constexpr int kPoolGroups = 8;       // The pool of retained rounds is split into groups, each with its own counter
+                                     // and its own share of the workers: requests to one address are served one
+                                     // after the other by the memory side, a few hundred per round would take
+                                     // longer than the round.
+constexpr int kScratchWord = 128;    // offset from a workgroup's selection word of a word it may scribble on
+// Number of pool groups for a number of workers: every group must have at least one worker.
+__host__ __device__ inline int fused_pool_groups(int n_workers)
+{
+    const int octets = (n_workers + 7) / 8;
+    return octets < kPoolGroups ? (octets < 1 ? 1 : octets) : kPoolGroups;
+}
 
-template <class V, int PER>
-__global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
+template <class V, int PER, int MAXB>
+__global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 {
     typedef typename V::vec_t vec_t;
     typedef typename V::acc_t acc_t;
     constexpr int E = V::kElems;
+    extern __shared__ int pool_j[];  // retained channels of the shared pool, round by round (-1 = empty slot)
     __shared__ SelShared sh;
-    __shared__ int s_flag, s_bits[2];
-    __shared__ acc_t part[2][2 * kRB][kSelMaxWaves];
-    __shared__ int j_a[kKeep + 2 * kRB], j_b[kKeep + 2 * kRB], j_d[kKeep + 2 * kRB];  // staged channel indices
-    __shared__ float h_a[kKeep + 2 * kRB], h_b[kKeep + 2 * kRB];                      // their hidden activations
+    __shared__ int s_flag;
+    __shared__ int mb_ticket[4], mb_bits[2];  // thread 0 -> everyone, handed over at the round's barrier
+    __shared__ acc_t part[2][2 * kRB + kXL][kSelMaxWaves];
+    __shared__ int j_s[(kMaxStatic + 1) * kRB];                     // statically dealt retained channels
+    __shared__ int j_a[32];                                         // this workgroup's candidates, by slot
+    __shared__ float h_a[32];                                       // their hidden activations
+    __shared__ int j_st[kKeep * kRB];                               // retained channels processed since the last flush
+    __shared__ float h_st[kKeep * kRB];                             // and their hidden activations
     __shared__ __attribute__((aligned(16))) float y_stage[kStage];  // single-launch step: partial row on its way out
-    __shared__ int wg_bits[1024];                       // selector only: selected candidate slots per workgroup
+    __shared__ int wg_bits[1024];                                   // selector only: selected candidate slots per workgroup
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
@@ -224,13 +218,14 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     const int b = blockIdx.x, n_wg = gridDim.x, n_workers = n_wg - 1, wb = b - 1;
     const int nvec = p.nvec;
     const vec_t *w = reinterpret_cast<const vec_t *>(p.w);
+    int *const my_word = p.selbits + (size_t)b * kBitsStride;
 
     POP_STAMP(0);
     // end-of-step "go" word of this workgroup: all go words hold the same value between launches, and change once,
     // together, when the last workgroup of a single-launch step has delivered its partial output row
-    int *const go = p.selbits + (size_t)b * kBitsStride + kGoWord;
+    int *const go = my_word + kGoWord;
     const int go_before = p.y ? coherent_load(go) : 0;
-    if (b == 0 && tid == 0) coherent_store(&p.sync[3], 0);  // "some workgroup deferred its phase D share" flag of this step
+    if (b == 0 && tid == 0) coherent_store(&p.sync[3], 0);  // "some workgroup deferred its share" flag of this step
     int col[PER];
     bool ok[PER];
     vec_t xv[PER];
@@ -240,97 +235,353 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
         ok[q] = col[q] < nvec;
         xv[q] = ok[q] ? reinterpret_cast<const vec_t *>(p.x)[col[q]] : V::zero();
     }
-    for (int i = tid; i < 2 * 2 * kRB * kSelMaxWaves; i += blockDim.x) (&part[0][0][0])[i] = 0;
+    for (int i = tid; i < 2 * (2 * kRB + kXL) * kSelMaxWaves; i += blockDim.x) (&part[0][0][0])[i] = 0;
 
-    // rounds of this workgroup: round i of a list dealt to n_sh sharers = rows (i*n_sh + me)*kRB + t
-    auto rounds_of = [](int n_list, int n_sh, int me) {
-        return (me >= 0 && me * kRB < n_list) ? (n_list - me * kRB + n_sh * kRB - 1) / (n_sh * kRB) : 0;
-    };
-    const int n_a = rounds_of(p.n_cand, n_wg, b);
-    const int n_a2 = (n_a + 1) & ~1;  // padded to even with an empty round (simplifies the ping-pong)
-    const int n_b = rounds_of(p.n_ret, n_workers, wb);
-    // staged with empty rounds (-1) behind the real ones, so the streaming loops can prefetch unconditionally
-    const int n_b2 = (n_b + 1) & ~1;
-    for (int e = tid; e < (n_a2 + 1) * kRB; e += blockDim.x) {
-        const int r = ((e / kRB) * n_wg + b) * kRB + e % kRB;
-        j_a[e] = (e / kRB < n_a && r < p.n_cand) ? p.cand_idx[r] : -1;
-    }
-    for (int e = tid; e < (n_b2 + 1) * kRB; e += blockDim.x) {
+    // ---- this workgroup's share
+    // candidates: slot s of workgroup b is candidate s * n_wg + b
+    const int n_aslots = b < p.n_cand ? (p.n_cand - b + n_wg - 1) / n_wg : 0;
+    // retained: static round i of worker wb covers ret_idx[(i * n_workers + wb) * kRB ..], below static_end;
+    // pool round t covers ret_idx[static_end + t * kRB ..]
+    // of this worker's pool group (eight consecutive workers, one per XCD, go to the same group, so that every
+    // group has workers on every XCD): rounds [group * per_group, ..) of the pool
+    const int n_static = wb >= 0 ? p.n_static : 0;
+    const int n_groups = fused_pool_groups(n_workers);
+    const int group = wb >= 0 ? (wb / 8) % n_groups : 0;
+    const int per_group = (p.pool_rounds + n_groups - 1) / n_groups;
+    const int pool_first = group * per_group;
+    const int pool_rounds = wb >= 0 ? max(0, min(per_group, p.pool_rounds - pool_first)) : 0;
+    const int static_end = p.pool_rounds > 0 ? p.n_static * n_workers * kRB : p.n_ret;
+    int *const pool_ctr = &p.sync[kSyncPool + group * 1024];
+    if (tid < 32) j_a[tid] = tid < n_aslots ? p.cand_idx[tid * n_wg + b] : -1;
+    for (int e = tid; e < (n_static + 1) * kRB; e += blockDim.x) {
         const int r = ((e / kRB) * n_workers + wb) * kRB + e % kRB;
-        j_b[e] = (e / kRB < n_b && r < p.n_ret) ? p.ret_idx[r] : -1;
+        j_s[e] = (e / kRB < n_static && r < static_end) ? p.ret_idx[r] : -1;
     }
-    const vec_t *dummy = reinterpret_cast<const vec_t *>(p.x);
+    for (int e = tid; e < pool_rounds * kRB; e += blockDim.x) {
+        const int r = static_end + pool_first * kRB + e;
+        pool_j[e] = r < p.n_ret ? p.ret_idx[r] : -1;
+    }
+    if (tid < 4) mb_ticket[tid] = kNoTicket;
+    if (tid < 2) mb_bits[tid] = 0;
     __syncthreads();
 
-    RoundBuf<V, PER> buf_a, buf_b;  // ping-pong: one is reduced while the other's loads are in flight
-
-    // No global store happens inside the streaming loops: a store would make the next wait drain every load
-    // in flight, prefetched ones included.  Hidden activations are staged in LDS and written out later.
-
-    // ---- phase A: this workgroup's candidate rounds (gate+up only)
-    auto finish_a = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves]) {
-        float hv[kRB];
-        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv, [] {});
-        if (tid == 0)
-#pragma unroll
-            for (int t = 0; t < kRB; ++t) h_a[i * kRB + t] = hv[t];
-    };
-    if (n_a2 > 0) load_round<V, PER, true, false>(buf_a, w, nvec, j_a, col, ok, dummy);
-    for (int i = 0; i < n_a2; i += 2) {
-        load_round<V, PER, true, false>(buf_b, w, nvec, j_a + (i + 1) * kRB, col, ok, dummy);
-        finish_a(buf_a, i, part[0]);
-        load_round<V, PER, true, false>(buf_a, w, nvec, j_a + (i + 2) * kRB, col, ok, dummy);  // maybe an empty round
-        finish_a(buf_b, i + 1, part[1]);
-    }
-    __syncthreads();
-    for (int e = tid; e < n_a * kRB; e += blockDim.x) {
-        const int j = j_a[e];
-        if (j >= 0) {
-            // write-through stores: visible device-wide once acknowledged, so the hand-over below needs no
-            // cache write-back (a full release fence also invalidates this XCD's L2 under the other workgroups'
-            // streams; with one per workgroup that stalled the start of phase B for microseconds)
-            const float hv = h_a[e];
-            coherent_store(&p.h[j], hv);
-            coherent_store(&p.cscore[((e / kRB) * n_wg + b) * kRB + e % kRB], p.nrm[j] * fabsf(hv));
-        }
-    }
-    // Phase B's first round goes out now, behind the stores, so its latency overlaps the hand-over; the wait
-    // below leaves exactly those loads outstanding (the counter retires in order), i.e. the stores are acknowledged.
-    asm volatile("" ::: "memory");
-    load_round<V, PER, true, true>(buf_a, w, nvec, j_b, col, ok, dummy);
-    asm volatile("" ::: "memory");
-    static_assert(kRB * 3 * PER == 6 || kRB * 3 * PER == 12, "literal in the wait below");
-    if (PER == 1)
-        asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-    else
-        asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-    __syncthreads();
-    POP_STAMP(1);
-
-    float acc[PER][8];
+    // partial y of the retained channels, and of the selected candidates: kept apart and added at the end, so that
+    // the summation order does not depend on the round in which the selection happened to arrive
+    float acc[PER][8], acc_sel[PER][8];
 #pragma unroll
     for (int q = 0; q < PER; ++q)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[q][e] = 0.f;
+        for (int e = 0; e < 8; ++e) acc[q][e] = acc_sel[q][e] = 0.f;
 
-    // Phase D of a workgroup: the down rows of those of its own candidates (slots of phase A, h still in LDS)
-    // that the selection kept; `bits` has one bit per slot.
-    auto phase_d = [&](int bits) {
-        for (int e = tid; e < n_a2 * kRB; e += blockDim.x) j_d[e] = ((bits >> e) & 1) ? j_a[e] : -1;
+    // ---- round state, identical in every thread
+    int ia = 0;                 // next candidate slot to evaluate
+    int rem_d = 0;              // selected slots whose down rows are still to be added (valid once bits_known)
+    bool bits_known = false;    // the selection word of this step has been seen
+    bool pool_end = pool_rounds == 0;
+    int n_st = 0;               // rounds staged in j_st / h_st
+    int a_pub = n_aslots == 0 ? -2 : -1;  // round after which the candidate results were stored (-1: not yet)
+    bool arrived = false;       // the arrival has been signalled to the selector
+    // thread 0 only: results of the ticket request and of the poll issued in the previous round
+    int tk_ret = kNoTicket, poll_ret = 0;
+    bool tk_wanted = false, claim_more = pool_rounds > 0;
+
+    // Descriptor of round r.  Called once per round, in order; a pool round's ticket was requested four rounds
+    // earlier and handed over through LDS one round before this call.
+    auto make_desc = [&](RoundDesc &ds, int r) {
+        bool work = false;
+#pragma unroll
+        for (int t = 0; t < kRB; ++t) ds.jb[t] = -1;
+        if (r < n_static) {
+#pragma unroll
+            for (int t = 0; t < kRB; ++t) ds.jb[t] = uniform(j_s[r * kRB + t]);
+            work = ds.jb[0] >= 0;
+        } else if (!pool_end) {
+            const int tk = uniform(mb_ticket[r & 3]);
+            if (tk < pool_rounds) {
+#pragma unroll
+                for (int t = 0; t < kRB; ++t) ds.jb[t] = uniform(pool_j[tk * kRB + t]);
+                work = true;
+            } else {
+                pool_end = true;  // the counter only grows: every later ticket is beyond the pool too
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < kRB; ++t) ds.boff[t] = (uint32_t)max(ds.jb[t], 0) * 3u * (uint32_t)nvec;
+        ds.xmeta = 0;
+#pragma unroll
+        for (int a = 0; a < kXL; ++a) ds.xrow[a] = -1;
+        if (ia < n_aslots) {
+            ds.xmeta = 1;
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+                if (ia + a < n_aslots) {
+                    const int j = uniform(j_a[ia + a]);
+                    ds.xmeta |= (ia + a) << (8 + 5 * a);
+                    ds.xrow[2 * a] = j * 3;
+                    ds.xrow[2 * a + 1] = j * 3 + 1;
+                }
+            ia += 2;
+            if (ia >= n_aslots) ds.xmeta |= 4;
+            work = true;
+        } else if (bits_known && rem_d && work) {
+            // selected rows ride along with retained rounds only: on their own they would cost a full trip to
+            // memory per round, while the drain after the loop requests them all at once
+            ds.xmeta = 2;
+#pragma unroll
+            for (int a = 0; a < kXL; ++a)
+                if (rem_d) {
+                    const int sl = __builtin_ctz(rem_d);
+                    rem_d &= rem_d - 1;
+                    ds.xmeta |= sl << (8 + 5 * a);
+                    ds.xrow[a] = uniform(j_a[sl]) * 3 + 2;
+                }
+            work = true;
+        }
+#pragma unroll
+        for (int a = 0; a < kXL; ++a) ds.xoff[a] = (uint32_t)max(ds.xrow[a], 0) * (uint32_t)nvec;
+        ds.work = work;
+    };
+
+    // all threads write the staged hidden activations of the retained channels out (between barriers)
+    auto flush_hidden = [&]() {
         __syncthreads();
-        for (int i = 0; i < n_a2; i += 2) {
-            load_round<V, PER, false, true>(buf_a, w, nvec, j_d + i * kRB, col, ok, dummy);
-            load_round<V, PER, false, true>(buf_b, w, nvec, j_d + (i + 1) * kRB, col, ok, dummy);
+        for (int e = tid; e < n_st * kRB; e += blockDim.x)
+            if (j_st[e] >= 0) p.h[j_st[e]] = h_st[e];
+        __syncthreads();
+        n_st = 0;
+    };
+
+    // One round: reduce the rows in `cur` (round i, descriptor dc).  Right after their gate/up data has been
+    // consumed the rows of round i + 1 are requested into `nxt` (descriptor dn1, prepared a round earlier, so that
+    // nothing stands between the arrival of one round and the request for the next); the descriptor of round i + 2
+    // is prepared into dn2 while that request is in flight.
+    auto step = [&](RoundBuf<V, PER> &cur, const RoundDesc &dc, RoundBuf<V, PER> &nxt, const RoundDesc &dn1,
+                    RoundDesc &dn2, int i, float nrm_mine) {
+        const int par = i & 1;
+        const int xkind = dc.xkind();
+        acc_t ag[kRB], au[kRB], ax[kXL];
+#pragma unroll
+        for (int t = 0; t < kRB; ++t) {
+            ag[t] = 0;
+            au[t] = 0;
+#pragma unroll
+            for (int q = 0; q < PER; ++q) {
+                ag[t] = V::dot(cur.g[t][q], xv[q], ag[t]);
+                au[t] = V::dot(cur.u[t][q], xv[q], au[t]);
+            }
+        }
+        if (xkind == 1) {
+#pragma unroll
+            for (int a = 0; a < kXL; ++a) {
+                ax[a] = 0;
+#pragma unroll
+                for (int q = 0; q < PER; ++q) ax[a] = V::dot(cur.xl[a][q], xv[q], ax[a]);
+            }
+        }
+        asm volatile("" ::: "memory");  // everything below stays behind the uses of this round's gate/up rows
+        // Candidate results stored in the previous round: the explicit wait below finds them acknowledged.
+        if (!arrived && a_pub != -1 && i >= a_pub + 1) {
+            if (wave == 0) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // only requests of the previous round are outstanding here
+                if (tid == 0 && b != 0) atomicAdd(&p.sync[0], 1);
+            }
+            arrived = true;
+            POP_STAMP(1);
+        }
+        load_round<V, PER>(nxt, dn1, w, nvec, col, ok);  // an empty round requests the dummy vector only
+        asm volatile("" ::: "memory");
+        if (tid == 0) {
+            // What thread 0 requested in the previous round (ticket for round i + 3, poll) arrived with this
+            // round's rows: hand it to the others at this round's barrier.
+            const int tk = tk_wanted ? tk_ret : kNoTicket;
+            mb_ticket[(i + 3) & 3] = tk;
+            mb_bits[par] = poll_ret;
+#ifdef POP_TRACE
+            if ((poll_ret & kBitsValid) && p.trace && p.trace[(size_t)blockIdx.x * 8 + 5] == 0) POP_STAMP(5);
+#endif
+            if (tk_wanted && tk >= pool_rounds) claim_more = false;
+            // Poll of the selection word (zero until the selector has written it), ticket for round i + 4.  Both
+            // are issued unconditionally, straight into the registers they are read from a round later: an
+            // unwanted ticket request adds zero to a word of this workgroup's own and its result is ignored.
+#ifndef POP_NO_POLL
+            poll_ret = coherent_load(my_word);
+#endif
+            tk_wanted = claim_more && i + 4 >= n_static;
+            if (p.pool_rounds > 0)
+                tk_ret = __hip_atomic_fetch_add(tk_wanted ? pool_ctr : my_word + kScratchWord, tk_wanted ? 1 : 0,
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        asm volatile("" ::: "memory");
+        // descriptor of round i + 2, from what thread 0 handed over at the previous barrier
+        if (!bits_known && i >= 1) {
+            const int v = uniform(mb_bits[par ^ 1]);
+            if (v & kBitsValid) {
+                bits_known = true;
+                rem_d = v & ~kBitsValid;
+                POP_STAMP(7);
+            }
+        }
+        make_desc(dn2, i + 2);
+
+        // wave partials -> LDS -> totals in every thread (one barrier)
+#pragma unroll
+        for (int t = 0; t < kRB; ++t) {
+            const acc_t gt = wave_total(ag[t]), ut = wave_total(au[t]);
+            if (lane == 0) {
+                part[par][2 * t][wave] = gt;
+                part[par][2 * t + 1][wave] = ut;
+            }
+        }
+        if (xkind == 1) {
+#pragma unroll
+            for (int a = 0; a < kXL; ++a) {
+                const acc_t xt = wave_total(ax[a]);
+                if (lane == 0) part[par][2 * kRB + a][wave] = xt;
+            }
+        }
+        __syncthreads();
+        float hv[kRB], hx[2] = {0.f, 0.f};
+        if constexpr (sizeof(acc_t) == 4) {
+            static_assert(2 * kRB * kSelMaxWaves == kWave && kXL * kSelMaxWaves == kWave, "one LDS word per lane");
+            // lane l holds value l/16 of wave l%16; a DPP row sum adds the waves in a fixed tree order
+            const float tot = dpp_row_sum((&part[par][0][0])[lane]);
 #pragma unroll
             for (int t = 0; t < kRB; ++t)
+                hv[t] = dc.jb[t] >= 0 ? silu_mul(lane_value(tot, 32 * t), lane_value(tot, 32 * t + 16)) : 0.f;
+            if (xkind == 1) {
+                const float tx = dpp_row_sum((&part[par][2 * kRB][0])[lane]);
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+                    hx[a] = dc.xrow[2 * a] >= 0 ? silu_mul(lane_value(tx, 32 * a), lane_value(tx, 32 * a + 16)) : 0.f;
+            }
+        } else {
+            auto total = [&](int v) {
+                acc_t sum = 0;
+                for (int wv = 0; wv < nw; ++wv) sum += part[par][v][wv];
+                return (float)sum;
+            };
+#pragma unroll
+            for (int t = 0; t < kRB; ++t) hv[t] = dc.jb[t] >= 0 ? silu_mul(total(2 * t), total(2 * t + 1)) : 0.f;
+            if (xkind == 1) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+                    hx[a] = dc.xrow[2 * a] >= 0 ? silu_mul(total(2 * kRB + 2 * a), total(2 * kRB + 2 * a + 1)) : 0.f;
+            }
+        }
+        if (tid == 0) {
+            if (dc.jb[0] >= 0) {
+#pragma unroll
+                for (int t = 0; t < kRB; ++t) {
+                    j_st[n_st * kRB + t] = dc.jb[t];
+                    h_st[n_st * kRB + t] = hv[t];
+                }
+            }
+            if (xkind == 1) {
+#pragma unroll
+                for (int a = 0; a < 2; ++a)
+                    if (dc.xrow[2 * a] >= 0) h_a[dc.xslot(a)] = hx[a];
+            }
+        }
+        if (dc.jb[0] >= 0) ++n_st;
+#pragma unroll
+        for (int t = 0; t < kRB; ++t)
+#pragma unroll
+            for (int q = 0; q < PER; ++q) V::axpy(hv[t], cur.dn[t][q], acc[q]);
+        if (xkind == 2) {
+#pragma unroll
+            for (int a = 0; a < kXL; ++a) {
+                // an empty slot read the dummy vector: its weight is zero
+                const float hd = dc.xrow[a] >= 0 ? h_a[dc.xslot(a)] : 0.f;
+#pragma unroll
+                for (int q = 0; q < PER; ++q) V::axpy(hd, cur.xl[a][q], acc_sel[q]);
+            }
+        }
+        if (dc.last_a()) {
+            // Publish this workgroup's candidate results: write-through stores, visible device-wide once
+            // acknowledged, so the hand-over needs no cache write-back.  h_a was written by thread 0 of this same
+            // wave, and a wave's LDS operations execute in order.
+            if (wave == 0 && lane < n_aslots) {
+                const int j = j_a[lane];
+                const float hvv = h_a[lane];
+                coherent_store(&p.h[j], hvv);
+                coherent_store(&p.cscore[lane * n_wg + b], nrm_mine * fabsf(hvv));
+            }
+            a_pub = i;
+        }
+        if (n_st == kKeep) flush_hidden();
+    };
+
+    RoundBuf<V, PER> buf_a, buf_b;  // ping-pong: one is reduced while the other's loads are in flight
+    RoundDesc d0, d1, d2;           // descriptors of the round being reduced, the one in flight, the one after
+    make_desc(d0, 0);
+    load_round<V, PER>(buf_a, d0, w, nvec, col, ok);
+    // weight factor n_j of this lane's candidate slot (wave 0), requested behind the first round's rows
+    const float nrm_mine = p.nrm[max(j_a[tid < 32 ? tid : 0], 0)];
+    asm volatile("" ::"v"(nrm_mine));  // waited for here, once, next to the first round's rows
+    make_desc(d1, 1);
+    int i = 0;
+    // a round without work can still be followed by one with work (selected rows, once the selection is known)
+    while (d0.work || d1.work) {
+        step(buf_a, d0, buf_b, d1, d2, i, nrm_mine);
+        ++i;
+        d0 = d1;
+        d1 = d2;
+        if (!(d0.work || d1.work)) break;
+        step(buf_b, d0, buf_a, d1, d2, i, nrm_mine);
+        ++i;
+        d0 = d1;
+        d1 = d2;
+    }
+    POP_STAMP(2);
+    if (!arrived) {
+        // fewer than two rounds followed the last candidate round
+        if (wave == 0) {
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (tid == 0 && b != 0) atomicAdd(&p.sync[0], 1);
+        }
+        arrived = true;
+        POP_STAMP(1);
+    }
+
+    // Adds the down rows of the selected slots in rem_d (this workgroup's own candidates; h still in LDS).
+    auto drain_selected = [&]() {
+        while (rem_d) {
+            // eight rows per trip to memory (both round buffers are free by now)
+            int sl[2 * kXL];
+            uint32_t off[2 * kXL];
+#pragma unroll
+            for (int a = 0; a < 2 * kXL; ++a) {
+                sl[a] = -1;
+                off[a] = 0;
+                if (rem_d) {
+                    sl[a] = __builtin_ctz(rem_d);
+                    rem_d &= rem_d - 1;
+                    off[a] = ((uint32_t)uniform(j_a[sl[a]]) * 3u + 2u) * (uint32_t)nvec;
+                }
+            }
+#pragma unroll
+            for (int a = 0; a < 2 * kXL; ++a)
 #pragma unroll
                 for (int q = 0; q < PER; ++q) {
-                    // an unselected slot read the dummy vector: its weight is zero
-                    V::axpy(buf_a.j[t] >= 0 ? h_a[i * kRB + t] : 0.f, buf_a.dn[t][q], acc[q]);
-                    V::axpy(buf_b.j[t] >= 0 ? h_a[(i + 1) * kRB + t] : 0.f, buf_b.dn[t][q], acc[q]);
+                    const vec_t v = w[(ok[q] && sl[a] >= 0) ? off[a] + (uint32_t)col[q] : 0u];
+                    if (a < kXL)
+                        buf_a.xl[a][q] = v;
+                    else
+                        buf_b.xl[a - kXL][q] = v;
                 }
+#pragma unroll
+            for (int a = 0; a < 2 * kXL; ++a) {
+                const float hd = sl[a] >= 0 ? h_a[sl[a]] : 0.f;  // an empty slot read a dummy vector: weight zero
+#pragma unroll
+                for (int q = 0; q < PER; ++q) V::axpy(hd, a < kXL ? buf_a.xl[a][q] : buf_b.xl[a - kXL][q], acc_sel[q]);
+            }
         }
+#pragma unroll
+        for (int q = 0; q < PER; ++q)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[q][e] += acc_sel[q][e];
     };
+
     auto store_partial = [&]() __attribute__((always_inline)) {
         float *dst = p.partial + (size_t)b * p.d;
         if (p.y) {
@@ -379,8 +630,8 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
         __syncthreads();
         if (s_flag) {
             if (tid == 0) coherent_store(&p.sync[6], 0);
-            for (int i = tid; i < n_wg; i += blockDim.x)
-                coherent_store(p.selbits + (size_t)i * kBitsStride + kGoWord, go_before + 1);
+            for (int q = tid; q < n_wg; q += blockDim.x)
+                coherent_store(p.selbits + (size_t)q * kBitsStride + kGoWord, go_before + 1);
         }
         __syncthreads();
         if (tid == 0) {
@@ -433,114 +684,88 @@ __global__ __launch_bounds__(1024) void decode_fused_kernel(FusedParams p)
     };
 
     if (b == 0) {
-        // ---- select (workgroup 0 only): wait for every other workgroup's phase A, then top-k
+        // ---- select (workgroup 0 only): wait for every other workgroup's candidate results, then top-k
         if (tid == 0) {
             bool ok_a = spin_until(&p.sync[0], n_workers);
             if (!ok_a) p.sync[2] = 1;
             coherent_store(&p.sync[0], 0);  // all arrivals are in
             s_flag = ok_a ? 1 : 0;
         }
-        for (int i = tid; i < n_wg; i += blockDim.x) wg_bits[i] = 0;
+        for (int q = tid; q < n_wg; q += blockDim.x) wg_bits[q] = 0;
         __syncthreads();
-        POP_STAMP(2);
+        POP_STAMP(3);
         if (s_flag) {
             block_select_candidates<true>(
                 p.cscore, p.cand_idx, p.n_cand, p.k, p.mask, p.active_idx + p.n_ret, sh,
-                [&](int c) {  // candidate c was handled by workgroup (c/kRB) % n_wg in its round (c/kRB) / n_wg
-                    const int rd = c / kRB;
-                    atomicOr(&wg_bits[rd % n_wg], 1 << ((rd / n_wg) * kRB + c % kRB));
-                },
+                [&](int c) { atomicOr(&wg_bits[c % n_wg], 1 << (c / n_wg)); },  // candidate c is slot c / n_wg of workgroup c % n_wg
                 [&]() {  // publish the per-workgroup slot masks first: they are all the other workgroups wait for
                     __syncthreads();
-                    for (int i = 1 + tid; i < n_wg; i += blockDim.x) coherent_store(&p.selbits[(size_t)i * kBitsStride], wg_bits[i] | kBitsValid);
-                });
+                    for (int q = 1 + tid; q < n_wg && q < p.n_cand; q += blockDim.x)
+                        coherent_store(&p.selbits[(size_t)q * kBitsStride], wg_bits[q] | kBitsValid);
+                }
+#ifdef POP_TRACE
+                , p.trace ? p.trace + 1023 * 8 : nullptr
+#endif
+                );
             if (tid == 0 && p.n_active) *p.n_active = p.n_ret + p.k;
-            POP_STAMP(3);
-            phase_d(wg_bits[0]);
+            POP_STAMP(4);
+            bits_known = true;
+            rem_d = wg_bits[0];
+            drain_selected();
         }
         store_partial();
         if (p.y) final_reduce();
+        POP_STAMP(6);
         return;
     }
 
-    if (tid == 0) atomicAdd(&p.sync[0], 1);  // every wave's results were acknowledged before the barrier above
-
-    // ---- phase B: retained rounds (gate+up -> h, then the round's down rows).  Thread 0 polls this workgroup's
-    // word of selbits along the way; a value is looked at two rounds after its load was issued, when it has
-    // certainly arrived, so polling never stalls the stream.
-    int pv0 = 0, pv1 = 0, pv2 = 0, my_bits = 0, hk = 0;
-    auto finish_b = [&](const RoundBuf<V, PER> &rb, int i, acc_t(*pt)[kSelMaxWaves], auto poll_tag, auto late_load) {
-        constexpr bool poll = decltype(poll_tag)::value;
-        if (tid == 0) s_bits[hk & 1] = pv2;  // loaded at least two full rounds ago: certainly arrived, never a stall
-        pv2 = pv1;
-        pv1 = pv0;
-        // every thread, no branch around the load; one poll per pair of rounds, each workgroup's word in its own
-        // 4 KiB so that the polls of all workgroups do not queue up at one memory channel
-        if (poll) pv0 = coherent_load(&p.selbits[(size_t)b * kBitsStride]);
-        float hv[kRB];
-        round_hidden<V, PER>(rb, xv, pt, wave, lane, nw, hv, late_load);
-        // read after the round's barrier: every thread sees the same value; the slot is rewritten two rounds later
-        if (!my_bits && (s_bits[hk & 1] & kBitsValid)) my_bits = s_bits[hk & 1];
-        ++hk;
-        if (tid == 0)
-#pragma unroll
-            for (int t = 0; t < kRB; ++t) h_b[i * kRB + t] = hv[t];
-#pragma unroll
-        for (int t = 0; t < kRB; ++t)
-#pragma unroll
-            for (int q = 0; q < PER; ++q) V::axpy(hv[t], rb.dn[t][q], acc[q]);
-    };
-    // kPrefetchEarly: the next round's loads go out before the current round's data is waited for (two rounds in
-    // flight).  Otherwise they go out right after the current round's data has been consumed (about one round in
-    // flight, the reduction and the barrier still overlap the load latency): measured faster on MI355X, whose
-    // memory system loses throughput when the request queues get deeper.
-    for (int i = 0; i < n_b2; i += 2) {  // buf_a already holds round 0 (loaded during the hand-over)
-        if (i == 4) POP_STAMP(5);
-        if (i == 8) POP_STAMP(7);
-        if (kPrefetchEarly) {
-            load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok, dummy);
-            finish_b(buf_a, i, part[0], std::true_type{}, [] {});
-            load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok, dummy);
-            finish_b(buf_b, i + 1, part[1], std::false_type{}, [] {});
-        } else {
-            finish_b(buf_a, i, part[0], std::true_type{},
-                     [&] { load_round<V, PER, true, true>(buf_b, w, nvec, j_b + (i + 1) * kRB, col, ok, dummy); });
-            finish_b(buf_b, i + 1, part[1], std::false_type{},
-                     [&] { load_round<V, PER, true, true>(buf_a, w, nvec, j_b + (i + 2) * kRB, col, ok, dummy); });
-        }
-    }
-    POP_STAMP(2);
-
-    // ---- phase D: needs the selection; normally my_bits arrived during phase B, else wait (bounded)
-    int bits_final = my_bits;
-    if (!my_bits) {
-        if (tid == 0) {
-            int v = pv2 < 0 ? pv2 : (pv1 < 0 ? pv1 : pv0);  // values still in the polling pipeline
-            for (int it = 0; v >= 0 && it < kSpinLimit; ++it) {
-                v = coherent_load(&p.selbits[(size_t)b * kBitsStride]);
-                if (v >= 0) __builtin_amdgcn_s_sleep(2);
+    // ---- selected candidates of this worker that did not ride along with the retained rounds
+    bool d_ok = true;
+    if (n_aslots > 0) {
+        if (!bits_known) {
+            // normally the word arrived during the retained rounds; else wait (bounded)
+            if (tid == 0) {
+                int v = 0;
+                for (int it = 0; v >= 0 && it < kSpinLimit; ++it) {
+                    v = coherent_load(my_word);
+                    if (v >= 0) __builtin_amdgcn_s_sleep(2);
+                }
+                s_flag = v;
             }
-            s_flag = v;
+            __syncthreads();
+            const int v = s_flag;
+            d_ok = v < 0;  // kBitsValid is the sign bit
+            if (d_ok) {
+                bits_known = true;
+                rem_d = v & ~kBitsValid;
+            }
         }
-        __syncthreads();
-        bits_final = s_flag;
+        POP_STAMP(3);
+        if (d_ok) drain_selected();
     }
-    const bool d_ok = bits_final < 0;  // kBitsValid is the sign bit
-    POP_STAMP(3);
-    if (d_ok) phase_d(bits_final);
     POP_STAMP(4);
     store_partial();
     if (tid == 0) {
         p.deferred[b] = d_ok ? 0 : 1;
         if (d_ok) {
-            coherent_store(&p.selbits[(size_t)b * kBitsStride], 0);  // rearmed for the next launch
+            if (n_aslots > 0) coherent_store(my_word, 0);  // rearmed for the next launch
         } else {
             p.sync[2] = 1;
             coherent_store(&p.sync[3], 1);
         }
+        if (p.pool_rounds > 0) {
+            // every ticket request of this workgroup has returned; the last worker to get here rewinds the
+            // counters for the next launch
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (atomicAdd(&p.sync[kSyncDone], 1) == n_workers - 1) {
+                for (int g = 0; g < kPoolGroups; ++g) coherent_store(&p.sync[kSyncPool + g * 1024], 0);
+                coherent_store(&p.sync[kSyncDone], 0);
+            }
+        }
     }
-    for (int e = tid; e < n_b * kRB; e += blockDim.x)
-        if (j_b[e] >= 0) p.h[j_b[e]] = h_b[e];
+    __syncthreads();
+    for (int e = tid; e < n_st * kRB; e += blockDim.x)
+        if (j_st[e] >= 0) p.h[j_st[e]] = h_st[e];
     if (p.y) final_reduce();
     POP_STAMP(6);
 }
@@ -582,12 +807,12 @@ __global__ __launch_bounds__(1024) void decode_tail_kernel(const float *__restri
         const bool any_deferred = sync[3] != 0;  // set only when some workgroup gave up waiting in this step
         for (int b = 1; any_deferred && b < n_wg; ++b) {
             if (!deferred[b]) continue;
-            // the workgroup's phase D share: its own candidate slots that the selection kept
+            // the workgroup's deferred share: its own candidate slots that the selection kept
             const int bits = selbits[(size_t)b * kBitsStride];
             if (bits >= 0) continue;  // the selection never ran: the step is flagged invalid
-            for (int e = 0; e < 31; ++e) {
+            for (int e = 0; e < kMaxASlots; ++e) {
                 if (!((bits >> e) & 1)) continue;
-                const int c = ((e / kRB) * n_wg + b) * kRB + e % kRB;
+                const int c = e * n_wg + b;
                 if (c >= n_cand) continue;
                 const int j = cand_idx[c];
                 if (j < 0 || j >= m) continue;
@@ -605,51 +830,132 @@ __global__ __launch_bounds__(1024) void decode_tail_kernel(const float *__restri
 }
 
 // ---------------------------------------------------------------- host side
-template <class V, int PER>
+// The kernel is built for two workgroup size limits: up to 512 threads (twice the registers per thread, enough for
+// two vector columns per thread without spilling) and up to 1024.
+template <class V, int PER, int MAXB>
 static hipError_t fused_launch(const FusedPlan &pl, FusedParams &p, hipStream_t s)
 {
-    hipLaunchKernelGGL((decode_fused_kernel<V, PER>), dim3(pl.n_wg), dim3(pl.block), 0, s, p);
+    hipLaunchKernelGGL((decode_fused_kernel<V, PER, MAXB>), dim3(pl.n_wg), dim3(pl.block), pl.lds_dynamic, s, p);
     return hipGetLastError();
 }
 
-template <class V, int PER>
-static hipError_t fused_occupancy(int block, int *blocks_per_cu)
+template <class V, int PER, int MAXB>
+static hipError_t fused_kernel_info(int block, size_t lds_dynamic, int *blocks_per_cu, size_t *lds_static)
 {
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_fused_kernel<V, PER>, block, 0);
+    const void *fn = reinterpret_cast<const void *>(&decode_fused_kernel<V, PER, MAXB>);
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, fn);
+    if (e != hipSuccess) return e;
+    if (lds_static) *lds_static = attr.sharedSizeBytes;
+    if (!blocks_per_cu) return hipSuccess;
+    if (lds_dynamic > 0) {
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_dynamic);
+        if (e != hipSuccess) return e;
+    }
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_fused_kernel<V, PER, MAXB>, block,
+                                                        lds_dynamic);
+}
+
+// Calls fn.template operator()<V, PER, MAXB>() for the plan's variant.
+template <class Fn>
+static hipError_t fused_dispatch(int is_bf16, int per, int block, Fn fn)
+{
+    const bool small = block <= 512;
+    if (is_bf16) {
+        if (per == 1) return small ? fn.template operator()<VecBF16, 1, 512>() : fn.template operator()<VecBF16, 1, 1024>();
+        return small ? fn.template operator()<VecBF16, 2, 512>() : fn.template operator()<VecBF16, 2, 1024>();
+    }
+    if (per == 1) return small ? fn.template operator()<VecF32, 1, 512>() : fn.template operator()<VecF32, 1, 1024>();
+    return small ? fn.template operator()<VecF32, 2, 512>() : fn.template operator()<VecF32, 2, 1024>();
+}
+
+struct FusedInfoFn {
+    int block;
+    size_t lds_dynamic;
+    int *blocks_per_cu;
+    size_t *lds_static;
+    template <class V, int PER, int MAXB>
+    hipError_t operator()() const
+    {
+        return fused_kernel_info<V, PER, MAXB>(block, lds_dynamic, blocks_per_cu, lds_static);
+    }
+};
+struct FusedLaunchFn {
+    const FusedPlan &pl;
+    FusedParams &p;
+    hipStream_t s;
+    template <class V, int PER, int MAXB>
+    hipError_t operator()() const
+    {
+        return fused_launch<V, PER, MAXB>(pl, p, s);
+    }
+};
+
+static hipError_t fused_info(int is_bf16, int per, int block, size_t lds_dynamic, int *blocks_per_cu, size_t *lds_static)
+{
+    return fused_dispatch(is_bf16, per, block, FusedInfoFn{block, lds_dynamic, blocks_per_cu, lds_static});
 }
 
 int fused_max_workgroups() { return 1024; }
 int fused_selbits_ints() { return 1024 * kBitsStride; }
+int fused_sync_ints() { return (2 + kPoolGroups) * 1024; }
 
-// Chooses the launch shape; returns false when this d is not supported by the fused kernel.
-bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl)
+// Chooses the launch shape and the split of the retained rounds into a statically dealt part and a shared pool
+// (static_pct = 100: no pool); false when the fused kernel does not support this shape.
+bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, int static_pct, size_t lds_limit,
+                FusedPlan *pl, hipError_t *err)
 {
+    *err = hipSuccess;
     const int E = is_bf16 ? 8 : 4, nvec = d / E;
-    int per = 1;
-    if (nvec > 1024) per = 2;
+    // one vector column per thread up to 512 threads, then two (a workgroup of up to 512 threads has twice the
+    // registers per thread); POP_FUSED_PER=1 keeps one column per thread up to 1024 threads (tuning)
+    int per = nvec > 512 ? 2 : 1;
+    if (nvec <= 1024 && nvec >= 128)
+        if (const char *e = getenv("POP_FUSED_PER")) per = atoi(e) == 1 ? 1 : 2;
     if (nvec > 2048) return false;
     pl->per = per;
     pl->block = ((nvec + per * kWave - 1) / (per * kWave)) * kWave;
-    int workers = (n_ret + kRB - 1) / kRB;
-    const int by_cand = (n_cand + kRB - 1) / kRB;
-    if (by_cand > workers) workers = by_cand;
+    const int rounds_total = (n_ret + kRB - 1) / kRB;
+    int workers = rounds_total;
+    if ((n_cand + 1) / 2 > workers) workers = (n_cand + 1) / 2;
     if (workers < 1) workers = 1;
     if (workers > wg_target - 1) workers = wg_target - 1;
     pl->n_wg = workers + 1;
-    // the kernel stages at most kMaxRounds rounds per phase (the last candidate round may be padding)
-    if ((n_ret + workers * kRB - 1) / (workers * kRB) > kMaxRounds) return false;
-    if ((n_cand + (workers + 1) * kRB - 1) / ((workers + 1) * kRB) + 1 > kMaxCandRounds) return false;
+    if ((n_cand + pl->n_wg - 1) / pl->n_wg > kMaxASlots) return false;
+    size_t lds_static = 0;
+    *err = fused_info(is_bf16, per, pl->block, 0, nullptr, &lds_static);
+    if (*err != hipSuccess) return false;
+    const int per_worker = rounds_total / workers;  // every worker can get this many static rounds
+    int n_static = (rounds_total + workers - 1) / workers, pool_rounds = 0;
+    if (static_pct < 100 && per_worker >= 5) {
+        n_static = per_worker * (static_pct < 0 ? 0 : static_pct) / 100;
+        if (n_static < 4) n_static = 4;  // tickets are requested four rounds ahead
+        if (n_static > kMaxStatic) n_static = kMaxStatic;
+        // the pool's channel list lives in LDS
+        // a workgroup keeps the channel list of its pool group in LDS
+        const int n_groups = fused_pool_groups(workers);
+        auto group_bytes = [&](int ns) {
+            return (size_t)((rounds_total - ns * workers + n_groups - 1) / n_groups) * kRB * 4;
+        };
+        while (n_static < per_worker && lds_static + group_bytes(n_static) > lds_limit) ++n_static;
+        pool_rounds = rounds_total - n_static * workers;
+        if (pool_rounds <= 0 || lds_static + group_bytes(n_static) > lds_limit) {
+            n_static = (rounds_total + workers - 1) / workers;
+            pool_rounds = 0;
+        }
+    }
+    if (n_static > kMaxStatic) return false;
+    pl->n_static = n_static;
+    pl->pool_rounds = pool_rounds;
+    const int n_groups_final = fused_pool_groups(workers);
+    pl->lds_dynamic = (size_t)((pool_rounds + n_groups_final - 1) / n_groups_final) * kRB * 4;
     return true;
 }
 
 hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int *max_wg)
 {
     int per_cu = 0;
-    hipError_t e;
-    if (is_bf16)
-        e = pl.per == 1 ? fused_occupancy<VecBF16, 1>(pl.block, &per_cu) : fused_occupancy<VecBF16, 2>(pl.block, &per_cu);
-    else
-        e = pl.per == 1 ? fused_occupancy<VecF32, 1>(pl.block, &per_cu) : fused_occupancy<VecF32, 2>(pl.block, &per_cu);
+    hipError_t e = fused_info(is_bf16, pl.per, pl.block, pl.lds_dynamic, &per_cu, nullptr);
     if (e != hipSuccess) return e;
     *max_wg = per_cu * n_cu;
     return hipSuccess;
@@ -657,8 +963,9 @@ hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int 
 
 hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p, hipStream_t s)
 {
-    if (is_bf16) return pl.per == 1 ? fused_launch<VecBF16, 1>(pl, p, s) : fused_launch<VecBF16, 2>(pl, p, s);
-    return pl.per == 1 ? fused_launch<VecF32, 1>(pl, p, s) : fused_launch<VecF32, 2>(pl, p, s);
+    p.n_static = pl.n_static;
+    p.pool_rounds = pl.pool_rounds;
+    return fused_dispatch(is_bf16, pl.per, pl.block, FusedLaunchFn{pl, p, s});
 }
 
 hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync,

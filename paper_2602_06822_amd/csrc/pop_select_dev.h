@@ -13,12 +13,27 @@ constexpr int kSelMaxWaves = 16;
 constexpr int kSelLdsKeys = 4096;  // candidate keys staged in LDS when they fit (16 KiB)
 
 struct SelShared {
-    unsigned int hist[256];
+    unsigned int hist[3][256];  // digit histograms of three consecutive radix passes (see radix_threshold)
     int wave_tot[4][kSelMaxWaves];
     int digit;
     int remaining;
     uint32_t keys[kSelLdsKeys];
 };
+
+// Inclusive prefix sum over the 64 lanes of a wave with DPP moves (register-to-register: a few cycles per step,
+// where a shuffle through the LDS crossbar costs a full LDS round trip per step).
+__device__ __forceinline__ int wave_incl_scan(int v)
+{
+    // within each row of 16 lanes: shifts by 1, 2, 4, 8 (lanes without a source keep 0)
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+    // across rows: last lane of row 0 -> row 1, of row 2 -> row 3; then last lane of row 1 -> rows 2 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31
+    return v;
+}
 
 // Exclusive block scan of N integer streams at once.  Returns the exclusive prefix in v[], block totals in
 // tot[].  All threads of the block must call.
@@ -29,32 +44,47 @@ __device__ __forceinline__ void block_excl_scan(int (&v)[N], int (&tot)[N], SelS
     int inc[N];
 #pragma unroll
     for (int q = 0; q < N; ++q) {
-        int x = v[q];
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-            int y = __shfl_up(x, off, kWave);
-            if (lane >= off) x += y;
-        }
-        inc[q] = x;
-        if (lane == kWave - 1) sh.wave_tot[q][wave] = x;
+        inc[q] = wave_incl_scan(v[q]);
+        if (lane == kWave - 1) sh.wave_tot[q][wave] = inc[q];
     }
     __syncthreads();
 #pragma unroll
     for (int q = 0; q < N; ++q) {
-        int base = 0, total = 0;
-        for (int w = 0; w < nw; ++w) {
-            int t = sh.wave_tot[q][w];
-            if (w < wave) base += t;
-            total += t;
-        }
+        // lane l < nw reads the total of wave l; a second in-wave scan gives every wave's base
+        const int t = lane < nw ? sh.wave_tot[q][lane] : 0;
+        const int ts = wave_incl_scan(t);
+        const int base = wave > 0 ? __builtin_amdgcn_readlane(ts, wave - 1) : 0;
+        const int total = __builtin_amdgcn_readlane(ts, kWave - 1);
         v[q] = base + inc[q] - v[q];
         tot[q] = total;
     }
     __syncthreads();
 }
 
+// hist[d] += 1 for every lane with valid set, d < 256.  Lanes of a wave that hold the same digit as its first
+// valid lane are counted by that lane, and again for the rest as long as such a group covers a quarter of the wave;
+// whatever is left adds on its own.  Scores of one layer share their exponent bits, so without this the leading
+// digit of every key would hit one LDS word, one lane at a time; for well-spread digits the loop ends after one try.
+__device__ __forceinline__ void wave_hist_add(unsigned int *hist, uint32_t d, bool valid)
+{
+    unsigned long long todo = __ballot(valid);
+    const int lane = threadIdx.x % kWave;
+#pragma unroll 1
+    for (int it = 0; it < 4 && todo; ++it) {
+        const int leader = __builtin_ctzll(todo);
+        const uint32_t d0 = (uint32_t)__builtin_amdgcn_readlane((int)d, leader);
+        const unsigned long long same = __ballot(valid && d == d0) & todo;
+        const int n_same = __popcll(same);
+        if (lane == leader) atomicAdd(&hist[d0], (unsigned int)n_same);
+        todo &= ~same;
+        if (n_same < kWave / 4) break;
+    }
+    if ((todo >> lane) & 1ull) atomicAdd(&hist[d], 1u);
+}
+
 // Key of the n_top-th best element among key(0..n), and how many elements equal to that key belong to the
 // top n_top (taken in index order).  n_top == 0 gives take_eq = 0 with kth = 0xffffffff.
+// MSB-first radix select over 8-bit digits, starting below the bits that all keys have in common.
 template <class KeyFn>
 __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, SelShared &sh, uint32_t &kth,
                                                 int &take_eq)
@@ -64,49 +94,74 @@ __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, Sel
         take_eq = 0;
         return;
     }
-    uint32_t prefix = 0, known = 0;
-    int remaining = n_top;
-    for (int shift = 24; shift >= 0; shift -= 8) {
-        if (threadIdx.x < 256) sh.hist[threadIdx.x] = 0;
-        if (blockDim.x < 256)
-            for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) sh.hist[i] = 0;
+    // bits in which any two keys differ: OR over all keys of (key ^ key(0))
+    unsigned int *scratch = &sh.hist[2][0];
+    if (threadIdx.x == 0) scratch[0] = 0;
+    if (threadIdx.x < 256) sh.hist[0][threadIdx.x] = 0;
+    if (blockDim.x < 256)
+        for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) sh.hist[0][i] = 0;
+    __syncthreads();
+    const uint32_t k0 = key(0);
+    uint32_t diff = 0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) diff |= key(i) ^ k0;
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0xB1, 0xf, 0xf, true);   // quad_perm 1,0,3,2
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x4E, 0xf, 0xf, true);   // quad_perm 2,3,0,1
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x141, 0xf, 0xf, true);  // row_half_mirror
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x140, 0xf, 0xf, true);  // row_mirror
+    if (threadIdx.x % 16 == 0 && diff) atomicOr(&scratch[0], diff);  // one lane per row of 16
+    __syncthreads();
+    diff = scratch[0];
+    if (diff == 0) {  // all keys equal
         __syncthreads();
-        for (int i = threadIdx.x; i < n; i += blockDim.x) {
-            uint32_t k = key(i);
-            if ((k & known) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
-        }
-        __syncthreads();
-        if (threadIdx.x < kWave) {
-            // lane l owns the four digits 255-4l .. 252-4l, scanned from the largest digit down
-            int l = threadIdx.x;
-            int c[4], lane_tot = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                c[q] = (int)sh.hist[255 - (4 * l + q)];
-                lane_tot += c[q];
-            }
-            int x = lane_tot;
-#pragma unroll
-            for (int off = 1; off < kWave; off <<= 1) {
-                int y = __shfl_up(x, off, kWave);
-                if (l >= off) x += y;
-            }
-            int before = x - lane_tot;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (before < remaining && remaining <= before + c[q]) {
-                    sh.digit = 255 - (4 * l + q);
-                    sh.remaining = remaining - before;
-                }
-                before += c[q];
-            }
-        }
-        __syncthreads();
-        prefix |= ((uint32_t)sh.digit) << shift;
-        known |= 255u << shift;
-        remaining = sh.remaining;
-        __syncthreads();
+        kth = k0;
+        take_eq = n_top;
+        return;
     }
+    const int top_bit = 31 - __builtin_clz(diff);          // highest bit in which keys differ
+    const int n_pass = top_bit / 8 + 1;                     // digits below and including that bit
+    uint32_t known = top_bit == 31 ? 0u : ~((2u << top_bit) - 1u);  // the common leading bits
+    uint32_t prefix = k0 & known;
+    int remaining = n_top;
+    const int lane = threadIdx.x % kWave;
+    // Pass p counts into hist[p % 3], and clears hist[(p + 1) % 3] for the next pass: that one was last read in
+    // pass p - 2, which every wave had finished before any wave could pass the barrier of pass p - 1.  Every wave
+    // then finds the digit for itself, so a pass has a single barrier.
+    int pass = 0;
+    for (int shift = (n_pass - 1) * 8; shift >= 0; shift -= 8, ++pass) {
+        unsigned int *hist = sh.hist[pass % 3], *next = sh.hist[(pass + 1) % 3];
+        if (threadIdx.x < 256) next[threadIdx.x] = 0;
+        if (blockDim.x < 256)
+            for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) next[i] = 0;
+        const int n_round = (n + blockDim.x - 1) / blockDim.x * blockDim.x;  // whole waves take part in the ballots
+        for (int i = threadIdx.x; i < n_round; i += blockDim.x) {
+            const uint32_t k = i < n ? key(i) : 0u;
+            wave_hist_add(hist, (k >> shift) & 255u, i < n && (k & known) == prefix);
+        }
+        __syncthreads();
+        // lane l owns the four digits 255-4l .. 252-4l, scanned from the largest digit down
+        int c[4], lane_tot = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            c[q] = (int)hist[255 - (4 * lane + q)];
+            lane_tot += c[q];
+        }
+        int before = wave_incl_scan(lane_tot) - lane_tot;
+        int digit = -1, rem_new = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (before < remaining && remaining <= before + c[q]) {
+                digit = 255 - (4 * lane + q);
+                rem_new = remaining - before;
+            }
+            before += c[q];
+        }
+        const int owner = __builtin_ctzll(__ballot(digit >= 0));  // exactly one lane holds the digit
+        digit = __builtin_amdgcn_readlane(digit, owner);
+        remaining = __builtin_amdgcn_readlane(rem_new, owner);
+        prefix |= ((uint32_t)digit) << shift;
+        known |= 255u << shift;
+    }
+    __syncthreads();  // the caller may reuse the histograms
     kth = prefix;
     take_eq = remaining;
 }
@@ -129,20 +184,38 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
                                                         int n_cand, int k, unsigned char *__restrict__ mk,
                                                         int *__restrict__ act_sel, SelShared &sh,
                                                         OnSelected on_selected = OnSelected(),
-                                                        AfterSelected after_selected = AfterSelected())
+                                                        AfterSelected after_selected = AfterSelected(),
+                                                        unsigned long long *tr = nullptr)
 {
+#define SEL_STAMP(k) do { if (tr && threadIdx.x == 0) tr[k] = wall_clock64(); } while (0)
+    SEL_STAMP(0);
     auto score = [&](int i) -> float {
         return kCoherentScores ? __hip_atomic_load(&cs[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : cs[i];
     };
     const bool in_lds = n_cand <= kSelLdsKeys;
     if (in_lds) {
-        for (int i = threadIdx.x; i < n_cand; i += blockDim.x) sh.keys[i] = score_key(score(i));
+        // eight independent loads in flight per thread: under a streaming load a trip to memory takes microseconds
+        for (int base = 0; base < n_cand; base += 8 * blockDim.x) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = base + u * blockDim.x + threadIdx.x;
+                v[u] = score(i < n_cand ? i : 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = base + u * blockDim.x + threadIdx.x;
+                if (i < n_cand) sh.keys[i] = score_key(v[u]);
+            }
+        }
         __syncthreads();
     }
     auto key = [&](int i) -> uint32_t { return in_lds ? sh.keys[i] : score_key(score(i)); };
     uint32_t kth;
     int take;
+    SEL_STAMP(1);
     radix_threshold(key, n_cand, k, sh, kth, take);
+    SEL_STAMP(2);
 
     const int E = (n_cand + blockDim.x - 1) / blockDim.x;
     const int lo = min(n_cand, (int)threadIdx.x * E), hi = min(n_cand, lo + E);
@@ -153,6 +226,7 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
         cnt[1] += (kv > kth);
     }
     block_excl_scan<2>(cnt, tot, sh);
+    SEL_STAMP(3);
     {
         int eq = cnt[0];
         for (int i = lo; i < hi; ++i) {
@@ -161,7 +235,9 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
             eq += (kv == kth);
         }
     }
+    SEL_STAMP(4);
     after_selected();
+    SEL_STAMP(5);
     // position of a selected element = (# greater before it) + (# admitted equal before it)
     int eq = cnt[0], gt = cnt[1];
     for (int i = lo; i < hi; ++i) {
