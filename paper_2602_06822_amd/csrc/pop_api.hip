@@ -308,8 +308,8 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
     const int m = L->m;
     L->has_partition = false;
     L->has_step = false;
-    POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, s));
-    POP_HIP(launch_scores_from_partials(L->s2_part, prefill_num_tiles(T, L->is_bf16), m, L->nrm, L->scores, s));
+    POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s));
+    POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16), m, L->nrm, L->scores, s));
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s));
     if (n_cand) POP_HIP(hipMemcpyAsync(L->rc_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
     if (n_ret) POP_HIP(hipMemcpyAsync(L->rc_idx + n_cand, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));

@@ -10,12 +10,34 @@
 namespace pop {
 
 // ---------------------------------------------------------------- three-region partition
+// The keys are staged in LDS once (eight independent loads in flight per thread), so the radix passes and the
+// index-ordered passes never go back to memory; beyond kPartLdsKeys channels they are read from global memory.
+constexpr int kPartLdsKeys = 24576;  // 96 KiB of keys
+
 __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict__ scores, int m, int n_ret, int n_cand,
                                                          unsigned char *__restrict__ region, int *__restrict__ ret_idx,
                                                          int *__restrict__ cand_idx)
 {
     __shared__ SelShared sh;
-    auto key = [&](int i) { return score_key(scores[i]); };
+    extern __shared__ uint32_t part_keys[];  // [m] when m <= kPartLdsKeys
+    const bool in_lds = m <= kPartLdsKeys;
+    if (in_lds) {
+        for (int base = 0; base < m; base += 8 * blockDim.x) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = base + u * blockDim.x + threadIdx.x;
+                v[u] = scores[i < m ? i : 0];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = base + u * blockDim.x + threadIdx.x;
+                if (i < m) part_keys[i] = score_key(v[u]);
+            }
+        }
+        __syncthreads();
+    }
+    auto key = [&](int i) { return in_lds ? part_keys[i] : score_key(scores[i]); };
     uint32_t kth_a, kth_b;
     int take_a, take_b;
     radix_threshold(key, m, n_ret, sh, kth_a, take_a);
@@ -23,7 +45,7 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
 
     // index-ordered pass: thread t owns channels [t*E, (t+1)*E)
     int E = (m + blockDim.x - 1) / blockDim.x;
-    int lo = threadIdx.x * E, hi = min(m, lo + E);
+    int lo = min(m, (int)threadIdx.x * E), hi = min(m, lo + E);
     int cnt[2] = {0, 0}, tot[2];
     for (int j = lo; j < hi; ++j) {
         uint32_t k = key(j);
@@ -66,7 +88,13 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
 hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
                             int *cand_idx, hipStream_t s)
 {
-    hipLaunchKernelGGL(partition_kernel, dim3(1), dim3(1024), 0, s, scores, m, n_ret, n_cand, region, ret_idx, cand_idx);
+    const size_t lds = m <= kPartLdsKeys ? (size_t)m * 4 : 0;
+    if (lds > 32 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&partition_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(partition_kernel, dim3(1), dim3(1024), lds, s, scores, m, n_ret, n_cand, region, ret_idx, cand_idx);
     return hipGetLastError();
 }
 
