@@ -66,6 +66,7 @@ struct pop_layer {
     float *h = nullptr;                // [max_batch][m]
     float *cscore = nullptr;           // [max_batch][m]
     unsigned char *mask = nullptr;     // [max_batch][m]
+    unsigned char *selflag = nullptr;  // [m][POP_MAX_BATCH]: per-sequence selection by candidate position (B > 1)
     int *active_idx = nullptr;         // [max_batch][m]
     int *n_active = nullptr;           // [max_batch]
     int *ulist = nullptr;              // [m]
@@ -201,7 +202,7 @@ int pop_layer_destroy(pop_layer_t *L)
 {
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
-                    L->h,      L->cscore, L->mask, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
+                    L->h,      L->cscore, L->mask, L->selflag, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
                     L->sync,   L->deferred, L->selbits};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
@@ -266,6 +267,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         {(void **)&L->h, B * mm * 4},
         {(void **)&L->cscore, B * mm * 4},
         {(void **)&L->mask, B * mm},
+        {(void **)&L->selflag, (size_t)POP_MAX_BATCH * mm},
         {(void **)&L->active_idx, B * mm * 4},
         {(void **)&L->n_active, B * 4},
         {(void **)&L->ulist, mm * 4},
@@ -353,15 +355,15 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         L->step_fused = true;
     } else {
         POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
-                              L->cscore, m, n_cand, s));
-        POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx, L->n_active,
-                            nullptr, s));
+                              L->cscore, m, n_cand, L->n_cu, s));
         if (B > 1) {
             if (!L->ulist_prefix_ok && n_ret)
                 POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
             L->ulist_prefix_ok = true;
-            POP_HIP(launch_union(L->mask, m, B, n_ret, L->cand_idx, n_cand, L->ulist, L->n_ulist, s));
         }
+        // B > 1: the kernel also builds the union of the B selections for the batched down projection
+        POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx, L->n_active,
+                            nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist, s));
         L->step_fused = false;
     }
     { int rc = copy_step_outputs(L, B, cand_scores, mask, active_idx, n_active, s); if (rc != POP_OK) return rc; }
@@ -433,7 +435,7 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
         if (mk) POP_HIP(launch_mask_to_list(mk, Bc, m, L->ulist, L->n_ulist, s));
         const char *xc = (const char *)x + (size_t)t0 * d * L->esize;
         POP_HIP(launch_gateup(L->w, L->is_bf16, d, m, xc, Bc, L->ulist, m, L->n_ulist, L->h, nullptr, nullptr, 0, 0,
-                              s));
+                              L->n_cu, s));
         POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->ulist, L->n_ulist, 0, L->h, mk, m, Bc, L->partial, L->n_slabs,
                             (char *)y + (size_t)t0 * d * ysize, y_bf16, s));
     }
@@ -459,7 +461,7 @@ int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_ca
     kk.k[0] = k;
     if (mask) POP_HIP(launch_step_state_init(region, m, nullptr, 0, 1, 0, mask, nullptr, as_stream(stream)));
     POP_HIP(launch_topk(cand_scores, n_cand, cand_idx, n_cand, 0, m, 1, kk, 0, mask, nullptr, nullptr, sel_idx,
-                        as_stream(stream)));
+                        nullptr, nullptr, nullptr, nullptr, as_stream(stream)));
     return POP_OK;
 }
 

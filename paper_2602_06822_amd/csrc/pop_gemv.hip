@@ -15,10 +15,10 @@
 namespace pop {
 
 // ---------------------------------------------------------------- gate/up GEMV
-constexpr int kGuUnroll = 4;  // 16-byte loads per matrix in flight per lane within one group
+constexpr int kGuUnroll = 8;  // 16-byte loads per matrix in flight per lane within one group
 
 template <class V, int B>
-__global__ __launch_bounds__(256) void gateup_kernel(const typename V::vec_t *__restrict__ w, int nvec,
+__global__ __launch_bounds__(1024) void gateup_kernel(const typename V::vec_t *__restrict__ w, int nvec,
                                                      const typename V::vec_t *__restrict__ x,
                                                      const int *__restrict__ rows, int n_rows,
                                                      const int *__restrict__ n_rows_dev, float *__restrict__ h, int m,
@@ -87,13 +87,18 @@ __global__ __launch_bounds__(256) void gateup_kernel(const typename V::vec_t *__
 template <class V>
 static hipError_t gateup_dispatch(const void *w, int nvec, const void *x, int B, const int *rows, int n_rows,
                                   const int *n_rows_dev, float *h, int m, const float *nrm, float *cscore, int cs_stride,
-                                  int n_score, hipStream_t s)
+                                  int n_score, int n_cu, hipStream_t s)
 {
     typedef typename V::vec_t vec_t;
     if (n_rows <= 0) return hipSuccess;
-    int blocks = (n_rows + 3) / 4;
-    if (blocks > 1024) blocks = 1024;
+    // x is staged in LDS by every workgroup: with several sequences it fills most of it, so one large workgroup
+    // per compute unit (16 waves sharing the copy) takes the place of many small ones
     size_t lds = (size_t)B * nvec * sizeof(vec_t);
+    const int threads = lds > 16 * 1024 ? 1024 : 256;
+    const int wpb = threads / kWave;
+    int blocks = (n_rows + wpb - 1) / wpb;
+    const int cap = threads == 1024 ? n_cu : 1024;
+    if (blocks > cap) blocks = cap;
 #define POP_GU(BB)                                                                                                  \
     case BB:                                                                                                        \
         if (lds > 48 * 1024) {                                                                                      \
@@ -101,7 +106,7 @@ static hipError_t gateup_dispatch(const void *w, int nvec, const void *x, int B,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);               \
             if (e != hipSuccess) return e;                                                                          \
         }                                                                                                           \
-        hipLaunchKernelGGL((gateup_kernel<V, BB>), dim3(blocks), dim3(256), lds, s, (const vec_t *)w, nvec,          \
+        hipLaunchKernelGGL((gateup_kernel<V, BB>), dim3(blocks), dim3(threads), lds, s, (const vec_t *)w, nvec,          \
                            (const vec_t *)x, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score);       \
         break;
     switch (B) {
@@ -114,19 +119,24 @@ static hipError_t gateup_dispatch(const void *w, int nvec, const void *x, int B,
 
 hipError_t launch_gateup(const void *w, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
                          const int *n_rows_dev, float *h, const float *nrm, float *cscore, int cs_stride, int n_score,
-                         hipStream_t s)
+                         int n_cu, hipStream_t s)
 {
     if (is_bf16)
         return gateup_dispatch<VecBF16>(w, d / 8, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride,
-                                        n_score, s);
-    return gateup_dispatch<VecF32>(w, d / 4, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score, s);
+                                        n_score, n_cu, s);
+    return gateup_dispatch<VecF32>(w, d / 4, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score,
+                                   n_cu, s);
 }
 
 // ---------------------------------------------------------------- down projection
-// grid = (column chunks of 64 vectors, slabs).  The 4 waves of a workgroup split the slab's rows, keep
-// float32 accumulators for their 64-vector column chunk, and are combined through LDS in wave order; the
-// slab partials are then summed in slab order by down_reduce_kernel, so y does not depend on scheduling.
+// grid = (column chunks of 64 vectors, slabs).  A workgroup first stages its slab's channel list and the B
+// sequences' hidden activations of those channels (zeroed where a sequence's mask excludes the channel) in LDS,
+// with independent loads, so that the streaming loop touches global memory for weight rows only.  The 4 waves
+// then split the slab's rows, keep float32 accumulators for their 64-vector column chunk, and are combined
+// through LDS in wave order; the slab partials are then summed in slab order by down_reduce_kernel, so y does
+// not depend on scheduling.
 constexpr int kDownUnroll = 8;
+constexpr int kDownSlabRows = 256;  // rows of a slab staged at a time
 
 template <class V, int B>
 __global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__restrict__ w, int nvec,
@@ -138,17 +148,16 @@ __global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__re
     typedef typename V::vec_t vec_t;
     constexpr int E = V::kElems;
     __shared__ float red[3][kWave * 8];
+    __shared__ int js[kDownSlabRows];
+    __shared__ float hs[B][kDownSlabRows];
     const int n = n_dev ? *n_dev : n_host;
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int n_slabs = gridDim.y, slab = blockIdx.y;
     const int col = blockIdx.x * kWave + lane;  // vector column
     const bool col_ok = col < nvec;
-    // rows of this wave: slab-major, then wave
     const int per_slab = (n + n_slabs - 1) / n_slabs;
-    const int per_wave = (per_slab + 3) / 4;
-    const int r0 = min(n, slab * per_slab + wave * per_wave);
-    const int r1 = min(min(n, (slab + 1) * per_slab), r0 + per_wave);
+    const int s0 = min(n, slab * per_slab), s1 = min(n, s0 + per_slab);
 
     float acc[B][8];
 #pragma unroll
@@ -156,39 +165,48 @@ __global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__re
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[b][e] = 0.f;
 
-    int i = r0;
-    for (; i + kDownUnroll <= r1; i += kDownUnroll) {
-        vec_t wv[kDownUnroll];
-        int jj[kDownUnroll];
-#pragma unroll
-        for (int q = 0; q < kDownUnroll; ++q) {
-            jj[q] = list[i + q];
-            wv[q] = col_ok ? w[((size_t)jj[q] * 3 + 2) * nvec + col] : V::zero();
-        }
-#pragma unroll
-        for (int q = 0; q < kDownUnroll; ++q) {
+    for (int c0 = s0; c0 < s1; c0 += kDownSlabRows) {
+        const int nc = min(kDownSlabRows, s1 - c0);
+        __syncthreads();  // the previous chunk's readers are done
+        for (int i = threadIdx.x; i < nc; i += blockDim.x) {
+            const int j = list[c0 + i];
+            js[i] = j;
+            float hv[B];
+            unsigned char mk[B];
 #pragma unroll
             for (int b = 0; b < B; ++b) {
-                float hv = h[(size_t)b * m + jj[q]];
-                if (mask && !mask[(size_t)b * mask_stride + jj[q]]) hv = 0.f;
-                V::axpy(hv, wv[q], acc[b]);
+                hv[b] = h[(size_t)b * m + j];
+                mk[b] = mask ? mask[(size_t)b * mask_stride + j] : (unsigned char)1;
             }
-        }
-    }
-    for (; i < r1; ++i) {
-        int j = list[i];
-        vec_t wv1 = col_ok ? w[((size_t)j * 3 + 2) * nvec + col] : V::zero();
 #pragma unroll
-        for (int b = 0; b < B; ++b) {
-            float hv = h[(size_t)b * m + j];
-            if (mask && !mask[(size_t)b * mask_stride + j]) hv = 0.f;
-            V::axpy(hv, wv1, acc[b]);
+            for (int b = 0; b < B; ++b) hs[b][i] = mk[b] ? hv[b] : 0.f;
+        }
+        __syncthreads();
+        // rows of this wave within the chunk
+        const int per_wave = (nc + 3) / 4;
+        const int r0 = min(nc, wave * per_wave), r1 = min(nc, r0 + per_wave);
+        int i = r0;
+        for (; i + kDownUnroll <= r1; i += kDownUnroll) {
+            vec_t wv[kDownUnroll];
+#pragma unroll
+            for (int q = 0; q < kDownUnroll; ++q)
+                wv[q] = col_ok ? w[((size_t)js[i + q] * 3 + 2) * nvec + col] : V::zero();
+#pragma unroll
+            for (int q = 0; q < kDownUnroll; ++q)
+#pragma unroll
+                for (int b = 0; b < B; ++b) V::axpy(hs[b][i + q], wv[q], acc[b]);
+        }
+        for (; i < r1; ++i) {
+            const vec_t wv1 = col_ok ? w[((size_t)js[i] * 3 + 2) * nvec + col] : V::zero();
+#pragma unroll
+            for (int b = 0; b < B; ++b) V::axpy(hs[b][i], wv1, acc[b]);
         }
     }
 
     // combine the 4 waves in wave order, one sequence at a time
 #pragma unroll
     for (int b = 0; b < B; ++b) {
+        __syncthreads();
         if (wave > 0) {
 #pragma unroll
             for (int e = 0; e < E; ++e) red[wave - 1][e * kWave + lane] = acc[b][e];
@@ -205,7 +223,6 @@ __global__ __launch_bounds__(256) void down_kernel(const typename V::vec_t *__re
                 dst[e] = v;
             }
         }
-        __syncthreads();
     }
 }
 

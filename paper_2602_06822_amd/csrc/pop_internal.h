@@ -54,17 +54,16 @@ hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, u
                             int *cand_idx, hipStream_t s);
 // Per sequence b (grid = B): select k.k[b] of n_cand candidates by cscore[b*cs_stride + i]; writes the candidate
 // bytes of mask[b][m], active_idx[b*act_stride + n_ret .. n_ret+k), n_active[b], sel_idx (sequence 0, only when
-// active_idx is null), each if non-null.
+// active_idx is null), each if non-null.  With union_list non-null also: selflag [B][n_cand] (scratch), and the
+// union of the B selections: union_list[n_ret..] = candidates selected by any b (ascending), *n_union = n_ret +
+// their number; the prefix union_list[0..n_ret) = ret_idx is written by the caller once per partition.  union_ctr
+// is a zeroed counter that the kernel leaves at zero.
 hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, int n_cand, int n_ret, int m, int B,
                        BatchK k, int act_stride, unsigned char *mask, int *active_idx, int *n_active, int *sel_idx,
-                       hipStream_t s);
+                       unsigned char *selflag, int *union_ctr, int *union_list, int *n_union, hipStream_t s);
 // Partition-constant step state: mask[b][j] = (region[j] == retained), active_idx[b][0..n_ret) = ret_idx.
 hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
                                   int act_stride, unsigned char *mask, int *active_idx, hipStream_t s);
-// Union of B active sets for the batched down projection: list[n_ret..] = candidates selected by any b; the
-// prefix list[0..n_ret) = ret_idx is written by the caller once per partition.
-hipError_t launch_union(const unsigned char *mask, int m, int B, int n_ret, const int *cand_idx, int n_cand, int *list,
-                        int *n_list, hipStream_t s);
 // mask rows -> ascending list of channels active in any row.
 hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s);
 
@@ -73,7 +72,7 @@ hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *
 // also get cscore[b][pos] = nrm[j] * |h|.  n_rows_dev (optional) overrides n_rows with a device-side count.
 hipError_t launch_gateup(const void *w, int is_bf16, int d, int m, const void *x, int B, const int *rows, int n_rows,
                          const int *n_rows_dev, float *h, const float *nrm, float *cscore, int cs_stride, int n_score,
-                         hipStream_t s);
+                         int n_cu, hipStream_t s);
 // y[b][:] = sum_{i<n} hm(b, list[i]) * w[list[i]][2][:], hm = h[b][j] (masked by mask[b][j] when mask != null).
 // Two stages: slab partials then a fixed-order reduction; y written as float32 or bf16.
 hipError_t launch_down(const void *w, int is_bf16, int d, int m, const int *list, const int *n_dev, int n_host,

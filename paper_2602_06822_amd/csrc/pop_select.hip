@@ -102,27 +102,58 @@ hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, u
 // One workgroup per sequence b.  Only candidate-dependent state is written: the candidate bytes of mask[b][:]
 // and the selected suffix of active_idx[b][:]; the retained / pruned bytes and the retained prefix are constant
 // for a partition (step_state_init_kernel).
+// With a union request (B > 1) every workgroup also leaves one byte per candidate position, and the workgroup
+// that finishes last (an arrival counter; nobody waits) compacts the candidates selected by any sequence into
+// list[n_ret..] and rewinds the counter.
 __global__ __launch_bounds__(1024) void topk_kernel(const float *__restrict__ cscore, int cs_stride,
                                                     const int *__restrict__ cand_idx, int n_cand, int n_ret, int m,
                                                     BatchK kk, int act_stride, unsigned char *__restrict__ mask,
                                                     int *__restrict__ active_idx, int *__restrict__ n_active,
-                                                    int *__restrict__ sel_idx)
+                                                    int *__restrict__ sel_idx, unsigned char *selflag,
+                                                    int *union_ctr, int *__restrict__ union_list,
+                                                    int *__restrict__ n_union)
 {
     __shared__ SelShared sh;
-    const int b = blockIdx.x, k = kk.k[b];
+    __shared__ int s_last;
+    const int b = blockIdx.x, B = gridDim.x, k = kk.k[b];
     unsigned char *mk = mask ? mask + (size_t)b * m : nullptr;
     int *act = active_idx ? active_idx + (size_t)b * act_stride + n_ret : (b == 0 ? sel_idx : nullptr);
-    block_select_candidates(cscore + (size_t)b * cs_stride, cand_idx, n_cand, k, mk, act, sh);
+    // selflag: [n_cand][POP_MAX_BATCH], one 8-byte word per candidate position
+    block_select_candidates(cscore + (size_t)b * cs_stride, cand_idx, n_cand, k, mk, act, sh, SelectNoHook(),
+                            SelectNoHook(), nullptr, selflag ? selflag + b : nullptr, POP_MAX_BATCH);
     if (n_active && threadIdx.x == 0) n_active[b] = n_ret + k;
+    if (!union_list) return;
+    // the flags of this sequence are written; the last workgroup to get here sees every sequence's flags
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = atomicAdd(union_ctr, 1) == B - 1;
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    static_assert(POP_MAX_BATCH == 8, "one 64-bit word of flags per candidate position");
+    const unsigned long long live = B >= 8 ? ~0ull : ((1ull << (8 * B)) - 1ull);  // bytes of sequences >= B are stale
+    const unsigned long long *flags = reinterpret_cast<const unsigned long long *>(selflag);
+    int E = (n_cand + blockDim.x - 1) / blockDim.x;
+    int lo = min(n_cand, (int)threadIdx.x * E), hi = min(n_cand, lo + E);
+    int c[1] = {0}, tot[1];
+    for (int i = lo; i < hi; ++i) c[0] += (flags[i] & live) != 0;
+    block_excl_scan<1>(c, tot, sh);
+    int p = n_ret + c[0];
+    for (int i = lo; i < hi; ++i)
+        if ((flags[i] & live) != 0) union_list[p++] = cand_idx[i];
+    if (threadIdx.x == 0) {
+        *n_union = n_ret + tot[0];
+        *union_ctr = 0;
+    }
 }
 
 hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, int n_cand, int n_ret, int m, int B,
                        BatchK k, int act_stride, unsigned char *mask, int *active_idx, int *n_active, int *sel_idx,
-                       hipStream_t s)
+                       unsigned char *selflag, int *union_ctr, int *union_list, int *n_union, hipStream_t s)
 {
     int threads = n_cand <= 2048 ? 256 : 1024;
     hipLaunchKernelGGL(topk_kernel, dim3(B), dim3(threads), 0, s, cscore, cs_stride, cand_idx, n_cand, n_ret, m, k,
-                       act_stride, mask, active_idx, n_active, sel_idx);
+                       act_stride, mask, active_idx, n_active, sel_idx, selflag, union_ctr, union_list, n_union);
     return hipGetLastError();
 }
 
@@ -162,43 +193,7 @@ hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s)
     return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- list compactions
-// list[n_ret..] = { cand_idx[i] : mask[b][cand_idx[i]] for some b }, n_list = n_ret + their number.  The prefix
-// list[0..n_ret) = ret_idx is constant for a partition and is written by the caller when the partition is made.
-__global__ __launch_bounds__(1024) void union_kernel(const unsigned char *__restrict__ mask, int m, int B,
-                                                     int n_ret,
-                                                     const int *__restrict__ cand_idx, int n_cand,
-                                                     int *__restrict__ list, int *__restrict__ n_list)
-{
-    __shared__ SelShared sh;
-    int E = (n_cand + blockDim.x - 1) / blockDim.x;
-    int lo = min(n_cand, (int)threadIdx.x * E), hi = min(n_cand, lo + E);
-    int c[1] = {0}, tot[1];
-    for (int i = lo; i < hi; ++i) {
-        int j = cand_idx[i];
-        int any = 0;
-        for (int b = 0; b < B; ++b) any |= mask[(size_t)b * m + j];
-        c[0] += (any != 0);
-    }
-    block_excl_scan<1>(c, tot, sh);
-    int p = n_ret + c[0];
-    for (int i = lo; i < hi; ++i) {
-        int j = cand_idx[i];
-        int any = 0;
-        for (int b = 0; b < B; ++b) any |= mask[(size_t)b * m + j];
-        if (any) list[p++] = j;
-    }
-    if (threadIdx.x == 0) *n_list = n_ret + tot[0];
-}
-
-hipError_t launch_union(const unsigned char *mask, int m, int B, int n_ret, const int *cand_idx, int n_cand, int *list,
-                        int *n_list, hipStream_t s)
-{
-    int threads = n_cand <= 2048 ? 256 : 1024;
-    hipLaunchKernelGGL(union_kernel, dim3(1), dim3(threads), 0, s, mask, m, B, n_ret, cand_idx, n_cand, list, n_list);
-    return hipGetLastError();
-}
-
+// ---------------------------------------------------------------- list compaction
 // list = ascending channels j with mask[r][j] != 0 for some row r < rows.
 __global__ __launch_bounds__(1024) void mask_to_list_kernel(const unsigned char *__restrict__ mask, int rows, int m,
                                                             int *__restrict__ list, int *__restrict__ n_list)

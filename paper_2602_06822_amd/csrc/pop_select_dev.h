@@ -174,7 +174,7 @@ struct SelectNoHook {
 // Select the best k of n_cand candidates (cs[i] is the score of channel cand_idx[i], cand_idx ascending).
 // Writes, each if non-null: mk[cand_idx[i]] = selected (candidate bytes only; the bytes of retained and pruned
 // channels are constant for a partition and written when the partition is made), act_sel[0..k) = selected
-// channels ascending.  on_selected(i) is called for every selected position before any of those global writes,
+// channels ascending, selpos[i] = selected (by position in cand_idx).  on_selected(i) is called for every selected position before any of those global writes,
 // then after_selected() by every thread (it may contain barriers): callers that only need the positions get
 // them without waiting for the index loads.  All threads of the block must call.
 // kCoherentScores: the scores were just written by other workgroups of the same kernel with write-through stores;
@@ -185,7 +185,9 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
                                                         int *__restrict__ act_sel, SelShared &sh,
                                                         OnSelected on_selected = OnSelected(),
                                                         AfterSelected after_selected = AfterSelected(),
-                                                        unsigned long long *tr = nullptr)
+                                                        unsigned long long *tr = nullptr,
+                                                        unsigned char *__restrict__ selpos = nullptr,
+                                                        int selpos_stride = 1)
 {
 #define SEL_STAMP(k) do { if (tr && threadIdx.x == 0) tr[k] = wall_clock64(); } while (0)
     SEL_STAMP(0);
@@ -239,8 +241,28 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
     after_selected();
     SEL_STAMP(5);
     // position of a selected element = (# greater before it) + (# admitted equal before it)
+    // the channel numbers of this thread's range are requested together, not one trip to memory per element
+    constexpr int kPre = 8;
+    int jpre[kPre];
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) jpre[u] = lo + u < hi ? cand_idx[lo + u] : 0;
     int eq = cnt[0], gt = cnt[1];
-    for (int i = lo; i < hi; ++i) {
+#pragma unroll
+    for (int u = 0; u < kPre; ++u) {
+        const int i = lo + u;
+        if (i < hi) {
+            uint32_t kv = key(i);
+            bool sel = (kv > kth) || (kv == kth && eq < take);
+            int pos = gt + min(eq, take);
+            eq += (kv == kth);
+            gt += (kv > kth);
+            const int j = jpre[u];
+            if (mk) mk[j] = sel ? 1 : 0;
+            if (selpos) selpos[(size_t)i * selpos_stride] = sel ? 1 : 0;  // the same decision by candidate position
+            if (sel && act_sel) act_sel[pos] = j;
+        }
+    }
+    for (int i = lo + kPre; i < hi; ++i) {
         uint32_t kv = key(i);
         bool sel = (kv > kth) || (kv == kth && eq < take);
         int pos = gt + min(eq, take);
@@ -248,6 +270,7 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
         gt += (kv > kth);
         int j = cand_idx[i];
         if (mk) mk[j] = sel ? 1 : 0;
+        if (selpos) selpos[(size_t)i * selpos_stride] = sel ? 1 : 0;
         if (sel && act_sel) act_sel[pos] = j;
     }
 }
