@@ -449,3 +449,103 @@ def test_config4_llama13b_layer_batched_full_size(pop, oracle):
 def test_config5_mixtral_expert_full_size(pop, oracle):
     """One Mixtral-shaped expert (d 4096, m 14336), bf16, a ragged share of the prompt tokens, sparsity .35."""
     _full_size_case(pop, oracle, synth.CFG5, 300, 0.35, [1], n_sample=128)
+
+
+# ---------------------------------------------------------------- mixture-of-experts layer (harness-side routing)
+
+def _route_top2(logits: np.ndarray):
+    """Top-2 experts per token (ties to the lower index) and the softmax over those two logits.  The router is
+    not part of the pruned-FFN path: it lives in the harness, on both sides of the comparison."""
+    order = np.argsort(-logits.astype(np.float64), axis=1, kind="stable")[:, :2]
+    top = np.take_along_axis(logits.astype(np.float64), order, axis=1)
+    e = np.exp(top - top.max(axis=1, keepdims=True))
+    return order, e / e.sum(axis=1, keepdims=True)
+
+
+def _moe_case(pop, oracle, cfg, n_experts, T, steps, r, n_sample, f_cand=0.10):
+    """One MoE layer: every expert is an independent pruned FFN with its own partition, made from the prompt
+    tokens routed to it (not weighted by the router); a decode token runs its two experts' steps and the outputs
+    are combined with the router weights.  Each expert step is checked as in the single-layer tests, the combined
+    output against the oracle's combined output."""
+    dtype, m, d = cfg.dtype, cfg.m, cfg.d
+    experts = [synth.make_layer(cfg, layer_id=100 + e) for e in range(n_experts)]
+    x = synth.make_activations(experts[0], T, "moe_prompt")
+    xt = synth.make_activations(experts[0], steps, "moe_decode")
+    route_p, _ = _route_top2(synth.make_router_logits(cfg, T, n_experts, "prompt"))
+    route_d, prob_d = _route_top2(synth.make_router_logits(cfg, steps, n_experts, "decode"))
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 1.0 - r - f_cand / 2, f_cand)
+    k = pop.pop_k_for_ratio(m, r, n_ret, n_cand)
+    layers, parts = [], []
+    try:
+        for e, L in enumerate(experts):
+            tok = np.flatnonzero((route_p == e).any(axis=1))
+            G = GpuLayer(pop, L, max_tokens=max(len(tok), 1), max_batch=1)
+            layers.append(G)
+            if len(tok) == 0:  # an expert nobody was routed to: all-zero scores, partition by channel order
+                pytest.skip("synthetic routing left an expert without tokens")
+            xe = np.ascontiguousarray(x[tok])
+            scores, region, ret, cand = G.prefill(xe, n_ret, n_cand)
+            sample = np.sort(synth.rng("moe_sample", e).choice(m, size=n_sample, replace=False)).astype(np.int32)
+            H = oracle.hidden(xe, L.w_gate, L.w_up, dtype, chan=sample)
+            s_ref = oracle.importance(L.w_down, dtype, H, chan=sample)[sample]
+            assert score_rel_err(scores[sample], s_ref, eps=1e-6) <= SCORE_TOL
+            r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+            assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1)
+            parts.append((region, cand))
+        assert len({p[0].tobytes() for p in parts}) == n_experts  # the experts' partitions really differ
+        for t in range(steps):
+            y_gpu = np.zeros(d)
+            y_ref = np.zeros(d)
+            for slot in range(2):
+                e = int(route_d[t, slot])
+                region, cand = parts[e]
+                out = _check_decode(oracle, layers[e], experts[e], region, cand, xt[t:t + 1], k, ydtype=F32)
+                ref = oracle.decode(xt[t], experts[e].w_gate, experts[e].w_up, experts[e].w_down, dtype, region, cand,
+                                    k, want_y=False)
+                y_e = oracle.down(ref["h"].reshape(1, -1), experts[e].w_down, dtype, out["mask"][0])[0]
+                y_gpu += prob_d[t, slot] * out["y"][0]
+                y_ref += prob_d[t, slot] * y_e
+            assert max_abs_rel(y_gpu, y_ref) <= Y_TOL[dtype]
+    finally:
+        for G in layers:
+            G.close()
+
+
+def test_moe_layer_small(pop, oracle):
+    """Four small experts, top-2 routing: every expert gets its own partition from its own tokens."""
+    _moe_case(pop, oracle, synth.small_config("moe_small", 512, 640, BF16, n_outlier=2, heavy_tail=True), 4, 96, 4,
+              0.35, n_sample=40)
+
+
+def test_config5_mixtral_moe_layer_full_size(pop, oracle):
+    """Mixtral-shaped MoE layer: 8 experts (d 4096, m 14336, bf16), top-2 softmax router over random logits, prompt
+    1024, sparsity .35 per expert; a few of the 128 decode steps."""
+    _moe_case(pop, oracle, synth.CFG5, 8, 1024, 4, 0.35, n_sample=24)
+
+
+def test_config3_stack_of_layers(pop, oracle):
+    """A stack of Llama-2-7B-shaped layers with independent weights, inputs and partitions, run back to back on one
+    stream as the decode loop of the 32-layer configuration does (4 layers here; the layers are independent, so
+    more of them add time, not coverage).  Every layer's step is checked against the oracle."""
+    cfg = synth.CFG3
+    r, f_cand, T = 0.35, 0.10, 256
+    n_ret, n_cand, _ = pop.pop_region_counts(cfg.m, 1.0 - r - f_cand / 2, f_cand)
+    k = pop.pop_k_for_ratio(cfg.m, r, n_ret, n_cand)
+    stack = []
+    try:
+        for li in range(4):
+            L = synth.make_layer(cfg, layer_id=li)
+            G = GpuLayer(pop, L, max_tokens=T, max_batch=1)
+            stack.append((L, G))
+            scores, region, ret, cand = G.prefill(synth.make_activations(L, T, "prompt", li), n_ret, n_cand)
+            r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+            assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1)
+            G.part = (region, cand)
+        assert len({G.part[0].tobytes() for _, G in stack}) == len(stack)  # per-layer independent partitions
+        for t in range(2):
+            for li, (L, G) in enumerate(stack):
+                xt = synth.make_activations(L, 2, "decode", li)[t:t + 1]
+                _check_decode(oracle, G, L, G.part[0], G.part[1], xt, k)
+    finally:
+        for _, G in stack:
+            G.close()
