@@ -204,7 +204,16 @@ def run(args):
                         avg_launch_us=round(fused_us, 3), tail_kernel_us=round(main["probe_ffn_us"], 3),
                         note="event-bracketed durations include the launch gap of each call")
 
-    cpu = None if args.no_cpu_baseline else cpu_baseline(synth, layers[0].host_layer, n_ret, n_cand, k, args.cpu_tokens)
+    other_configs = None
+    host_layer0 = layers[0].host_layer
+    if not args.quick:
+        for L in layers:
+            L.close()
+        layers = []
+        torch.cuda.empty_cache()
+        other_configs = time_other_shapes(pop, synth, lib, stream)
+
+    cpu = None if args.no_cpu_baseline else cpu_baseline(synth, host_layer0, n_ret, n_cand, k, args.cpu_tokens)
 
     if args.pmc_calibration:
         # a plain device-to-device copy of known size, for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters
@@ -242,10 +251,66 @@ def run(args):
         "warm_us_per_token": None if warm is None else round(warm, 3),
         "other_sparsities": extra,
         "single_launch_step_us_per_token": None if single is None else round(single, 3),
+        "other_shapes": other_configs,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
     print(json.dumps(result))
+
+
+def time_other_shapes(pop, synth, lib, stream):
+    """Decode step time of the other workload shapes (the parity tests cover them; these are the timings):
+    Llama-2-13B-shaped layer at batch 1, 4 and 8 (sparsity .50) and one Mixtral-shaped expert at batch 1 (.35).
+    Four independent layers rotated per step (cache-cold weights), short prompt for the partition."""
+    sp = C.c_void_p(stream.cuda_stream)
+    out = {}
+    for name, cfg, r, batches in (("llama2_13b_layer_r0.50", synth.CFG4, 0.50, (1, 4, 8)),
+                                  ("mixtral_expert_r0.35", synth.CFG5, 0.35, (1,))):
+        n_layers, T = 4, 128
+        to_dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda()  # noqa: E731
+        n_ret, n_cand, _ = pop.pop_region_counts(cfg.m, *region_fractions(r))
+        k = pop.pop_k_for_ratio(cfg.m, r, n_ret, n_cand)
+        hs, xds = [], []
+        for i in range(n_layers):
+            L = synth.make_layer(cfg, i)
+            h = pop.pop_layer_create(cfg.d, cfg.m, pop.POP_BF16, to_dev(L.w_gate), to_dev(L.w_up), to_dev(L.w_down),
+                                     T, max(batches))
+            pop.pop_prefill_partition(h, to_dev(synth.make_activations(L, T, "prompt", i)), T, n_ret, n_cand)
+            hs.append(h)
+            xds.append(to_dev(synth.make_activations(L, 64, "decode", i)))
+            del L
+        bm = byte_model(cfg.d, n_ret, n_cand, k)
+        res = {}
+        for B in batches:
+            y = torch.empty(B * cfg.d, dtype=torch.int16, device="cuda")
+            karr = (C.c_int * B)(*([k] * B))
+            steps = 64 // B
+
+            def loop():
+                for t in range(steps):
+                    for h, xd in zip(hs, xds):
+                        xt = C.c_void_p(xd.data_ptr() + t * B * cfg.d * 2)
+                        rc = lib.pop_decode_mask(h, xt, B, karr, None, None, None, None, sp)
+                        rc = rc or lib.pop_pruned_ffn(h, None, B, None, 0, C.c_void_p(y.data_ptr()), pop.POP_BF16, sp)
+                        if rc:
+                            raise pop.PopError(rc, "bench")
+            loop()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            loop()
+            loop()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (2 * steps * n_layers)
+            res[f"B={B}"] = dict(us_per_step=round(us, 2), us_per_token=round(us / B, 2),
+                                 tokens_per_s=round(1e6 * B / us, 1),
+                                 active_GBps_one_sequence=round(bm["active"] / us / 1e3, 1))
+        for h in hs:
+            pop.pop_layer_destroy(h)
+        torch.cuda.empty_cache()
+        out[name] = dict(d=cfg.d, m=cfg.m, n_ret=n_ret, n_cand=n_cand, k=k, layers_rotated=n_layers, **res)
+    return out
 
 
 def measured_traffic():
