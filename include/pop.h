@@ -150,14 +150,6 @@ int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
 /* Host only.  See pop_decode_step. */
 int pop_layer_set_single_launch(pop_layer_t *layer, int on);
-/* Host only.  Schedule of the fused single-sequence decode kernel.  By default (on != 0) every workgroup's share of
- * the retained channels is dealt in advance, so the order in which y is added up is fixed and y is bit-reproducible
- * from call to call.  on == 0: only half of each share is dealt in advance and the rest is drawn from shared pools at
- * run time, which evens out the workgroups' finishing times; y can then differ in the last float32 bits between two
- * calls with the same inputs (scores, h, masks and index lists never do).  Measured on MI355X at the Llama-2-7B
- * shape the pool's ticket traffic costs more than the evening-out gains, hence the default.
- * Takes effect at once if the layer has a partition, else at the next pop_prefill_partition. */
-int pop_layer_set_fixed_order(pop_layer_t *layer, int on);
 /* Host only.  Which implementation the last successful pop_decode_mask on this layer used: 0 = none yet,
  * 1 = the fused single-sequence kernel, 2 = the batch-general kernels.  If workgroups != NULL it receives the
  * fused kernel's grid size for the current partition (0 when the fused kernel does not apply). */

@@ -49,7 +49,6 @@ _SIGS = {
     "pop_layer_sync_status": (_i, [_vp, _vp]),
     "pop_layer_step_kind": (_i, [_vp, _ip]),
     "pop_layer_set_single_launch": (_i, [_vp, _i]),
-    "pop_layer_set_fixed_order": (_i, [_vp, _i]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -185,10 +184,6 @@ def pop_layer_sync_status(layer, stream=None):
 
 def pop_layer_set_single_launch(layer, on: bool):
     _check(_lib.pop_layer_set_single_launch(layer, 1 if on else 0), "pop_layer_set_single_launch")
-
-
-def pop_layer_set_fixed_order(layer, on: bool):
-    _check(_lib.pop_layer_set_fixed_order(layer, 1 if on else 0), "pop_layer_set_fixed_order")
 
 
 def pop_layer_step_kind(layer):

@@ -17,9 +17,6 @@ SOURCES = ["pop_api.hip", "pop_setup.hip", "pop_select.hip", "pop_gemv.hip", "po
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # keep a uniform-address atomic a single instruction whose result is used a round later (the wave-level
-         # rewrite reads the result back at once, which would wait for every outstanding load)
-         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 

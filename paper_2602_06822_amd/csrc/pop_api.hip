@@ -40,9 +40,7 @@ struct pop_layer {
     int d = 0, m = 0, esize = 0, is_bf16 = 0, max_tokens = 0, max_batch = 0;
     void *w = nullptr;     // [m][3][d]: gate row, up row, down column of each channel
     float *nrm = nullptr;  // [m]
-    int n_cu = 0, wg_target = 0, lds_max = 0;
-    int static_pct = 100;        // share of a worker's retained rounds dealt statically by the fused kernel
-    int pool_static_pct = 50;    // that share when the run-time pool is switched on
+    int n_cu = 0, wg_target = 0;
     bool single_launch = false;  // pop_decode_step at B = 1: sum the partial outputs inside the fused kernel
     // partition
     bool has_partition = false;
@@ -80,23 +78,14 @@ namespace {
 // Launch shape of the fused single-sequence step for the layer's current region sizes, sized to be co-resident.
 int plan_fused_step(pop_layer *L)
 {
-    hipError_t err = hipSuccess;
-    L->fused_ok = fused_plan(L->d, L->is_bf16, L->n_ret, L->n_cand, L->wg_target, L->static_pct, (size_t)L->lds_max,
-                             &L->plan, &err);
-    POP_HIP(err);
+    L->fused_ok = fused_plan(L->d, L->is_bf16, L->n_ret, L->n_cand, L->wg_target, &L->plan);
     if (L->fused_ok) {
         int max_wg = 0;
         POP_HIP(fused_resident_limit(L->is_bf16, L->plan, L->n_cu, &max_wg));
         if (max_wg < 2) {
             L->fused_ok = false;
         } else if (L->plan.n_wg > max_wg) {
-            L->fused_ok = fused_plan(L->d, L->is_bf16, L->n_ret, L->n_cand, max_wg, L->static_pct, (size_t)L->lds_max,
-                                     &L->plan, &err) && L->plan.n_wg <= max_wg;
-            POP_HIP(err);
-            if (L->fused_ok) {  // the pool size changed with the grid: make sure the new shape is resident too
-                POP_HIP(fused_resident_limit(L->is_bf16, L->plan, L->n_cu, &max_wg));
-                if (L->plan.n_wg > max_wg) L->fused_ok = false;
-            }
+            L->fused_ok = fused_plan(L->d, L->is_bf16, L->n_ret, L->n_cand, max_wg, &L->plan) && L->plan.n_wg <= max_wg;
         }
     }
     return POP_OK;
@@ -240,7 +229,6 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     L->tiles_cap = prefill_num_tiles(max_tokens, is_bf16);
     L->n_slabs = down_num_slabs(d, is_bf16);
     L->n_cu = n_cu;
-    L->lds_max = lds_max;
     L->wg_target = n_cu;  // one workgroup per compute unit; POP_FUSED_WGS overrides (tuning)
     if (const char *e = getenv("POP_FUSED_WGS")) {
         int v = atoi(e);
@@ -248,10 +236,6 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     }
     if (L->wg_target > fused_max_workgroups()) L->wg_target = fused_max_workgroups();
     if (const char *e = getenv("POP_SINGLE_LAUNCH")) L->single_launch = atoi(e) != 0;
-    if (const char *e = getenv("POP_FUSED_STATIC_PCT")) {  // tuning: static share used by pop_layer_set_fixed_order(0)
-        int v = atoi(e);
-        if (v >= 0 && v <= 100) L->pool_static_pct = v;
-    }
 
     const size_t mm = (size_t)m, B = (size_t)max_batch;
     struct Req { void **p; size_t bytes; };
@@ -274,7 +258,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         {(void **)&L->n_ulist, 4},
         {(void **)&L->partial, ((size_t)L->n_slabs * B > (size_t)fused_max_workgroups() ? (size_t)L->n_slabs * B
                                                                                         : (size_t)fused_max_workgroups()) * d * 4},
-        {(void **)&L->sync, (size_t)fused_sync_ints() * 4},
+        {(void **)&L->sync, 64},
         {(void **)&L->deferred, (size_t)fused_max_workgroups() * 4},
         {(void **)&L->selbits, (size_t)fused_selbits_ints() * 4},
     };
@@ -288,7 +272,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     }
     hipStream_t s = as_stream(stream);
     hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w, L->nrm, is_bf16, s);
-    if (e == hipSuccess) e = launch_fill_int(L->sync, fused_sync_ints(), 0, s);
+    if (e == hipSuccess) e = launch_fill_int(L->sync, 16, 0, s);
     if (e == hipSuccess) e = launch_fill_int(L->deferred, fused_max_workgroups(), 0, s);
     if (e == hipSuccess) e = launch_fill_int(L->selbits, fused_selbits_ints(), 0, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
@@ -322,7 +306,7 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
     L->n_ret = n_ret;
     L->n_cand = n_cand;
     { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
-    POP_HIP(launch_fill_int(L->sync, fused_sync_ints(), 0, s));
+    POP_HIP(launch_fill_int(L->sync, 16, 0, s));
     POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
@@ -499,17 +483,6 @@ int pop_layer_set_single_launch(pop_layer_t *L, int on)
 {
     if (!L) return POP_EINVAL;
     L->single_launch = on != 0;
-    return POP_OK;
-}
-
-int pop_layer_set_fixed_order(pop_layer_t *L, int on)
-{
-    if (!L) return POP_EINVAL;
-    L->static_pct = on ? 100 : L->pool_static_pct;
-    if (L->has_partition) {
-        L->has_step = false;  // a pending pop_pruned_ffn(mask = NULL) would read partial rows of the old grid
-        return plan_fused_step(L);
-    }
     return POP_OK;
 }
 

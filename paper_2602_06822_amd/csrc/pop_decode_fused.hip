@@ -16,11 +16,11 @@
 //   - first the workgroup's share of the candidate channels, two per round (gate+up only): h_j and the step score
 //     I_j(t) = n_j |h_j| (Eq. 3 with one token) are published to global memory with write-through stores;
 //   - later, once the selection is known, the down rows of those of its own candidates that were selected.
-// Candidates are dealt round-robin to all workgroups.  Retained rounds are dealt round-robin for the first
-// n_static rounds of every worker; the rest form a shared pool that workers draw from with an atomic ticket counter
-// (requested four rounds ahead, so the counter's latency is never waited for), which evens out the finishing
-// times of workgroups whose memory requests happened to be served more slowly.  With an empty pool the schedule,
-// and with it the summation order of y, is fixed (bit-reproducible output).
+// Candidates are dealt round-robin to all workgroups, retained rounds round-robin to the workers: the schedule,
+// and with it the summation order of y, is fixed (bit-reproducible output).  (Letting workers draw part of their
+// rounds from shared ticket counters at run time was tried: the requests have to be issued several rounds ahead to
+// keep their latency out of the stream, and with that much claimed-ahead work the finishing times did not even
+// out; it measured 3 % slower.)
 //
 //   select   workgroup 0 owns no retained rows.  It waits until all workgroups have published their candidate
 //            results (bounded spin on a counter; nobody waits for anything before that point), runs the top-k
@@ -37,6 +37,7 @@
 // Waiting is safe because the launch is sized to be co-resident (host checks the occupancy) and every wait is
 // bounded; nothing spins without an exit.
 #include <limits.h>
+#include <type_traits>
 #include <stdlib.h>
 
 #include "pop_select_dev.h"
@@ -50,7 +51,6 @@ constexpr int kSpinLimit = 1 << 16;
 constexpr int kMaxStatic = 64;   // statically dealt rounds per workgroup (staged in LDS)
 constexpr int kKeep = 64;        // rounds whose hidden activations are staged in LDS between flushes
 constexpr int kMaxASlots = 30;   // candidate slots per workgroup: they must fit the selection word next to the valid bit
-constexpr int kNoTicket = INT_MAX;
 
 // Optional per-workgroup timestamps (100 MHz wall clock), compiled in only for profiling builds.
 #ifdef POP_TRACE
@@ -179,30 +179,15 @@ constexpr int kStage = 4096;  // floats of a partial output row staged in LDS at
 constexpr int kBitsStride = 1024;    // ints between the selection words of two workgroups
 constexpr int kGoWord = 64;          // offset of a workgroup's end-of-step "go" word from its selection word
 constexpr int kBitsValid = 1 << 31;  // set in a selection word once the selection of this step is known
-constexpr int kSyncDone = 1024;      // sync[kSyncDone]: workers that have stopped drawing tickets
-constexpr int kSyncPool = 2048;      // sync[kSyncPool + 1024 g]: ticket counter of pool group g
-constexpr int kPoolGroups = 8;       // The pool of retained rounds is split into groups, each with its own counter
-                                     // and its own share of the workers: requests to one address are served one
-                                     // after the other by the memory side, a few hundred per round would take
-                                     // longer than the round.
-constexpr int kScratchWord = 128;    // offset from a workgroup's selection word of a word it may scribble on
-// Number of pool groups for a number of workers: every group must have at least one worker.
-__host__ __device__ inline int fused_pool_groups(int n_workers)
-{
-    const int octets = (n_workers + 7) / 8;
-    return octets < kPoolGroups ? (octets < 1 ? 1 : octets) : kPoolGroups;
-}
-
 template <class V, int PER, int MAXB>
 __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 {
     typedef typename V::vec_t vec_t;
     typedef typename V::acc_t acc_t;
     constexpr int E = V::kElems;
-    extern __shared__ int pool_j[];  // retained channels of the shared pool, round by round (-1 = empty slot)
     __shared__ SelShared sh;
     __shared__ int s_flag;
-    __shared__ int mb_ticket[4], mb_bits[2];  // thread 0 -> everyone, handed over at the round's barrier
+    __shared__ int mb_bits[2];  // thread 0 -> everyone, handed over at the round's barrier
     __shared__ acc_t part[2][2 * kRB + kXL][kSelMaxWaves];
     __shared__ int j_s[(kMaxStatic + 1) * kRB];                     // statically dealt retained channels
     __shared__ int j_a[32];                                         // this workgroup's candidates, by slot
@@ -240,28 +225,14 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     // ---- this workgroup's share
     // candidates: slot s of workgroup b is candidate s * n_wg + b
     const int n_aslots = b < p.n_cand ? (p.n_cand - b + n_wg - 1) / n_wg : 0;
-    // retained: static round i of worker wb covers ret_idx[(i * n_workers + wb) * kRB ..], below static_end;
-    // pool round t covers ret_idx[static_end + t * kRB ..]
-    // of this worker's pool group (eight consecutive workers, one per XCD, go to the same group, so that every
-    // group has workers on every XCD): rounds [group * per_group, ..) of the pool
+    // retained: round i of worker wb covers ret_idx[(i * n_workers + wb) * kRB ..]
     const int n_static = wb >= 0 ? p.n_static : 0;
-    const int n_groups = fused_pool_groups(n_workers);
-    const int group = wb >= 0 ? (wb / 8) % n_groups : 0;
-    const int per_group = (p.pool_rounds + n_groups - 1) / n_groups;
-    const int pool_first = group * per_group;
-    const int pool_rounds = wb >= 0 ? max(0, min(per_group, p.pool_rounds - pool_first)) : 0;
-    const int static_end = p.pool_rounds > 0 ? p.n_static * n_workers * kRB : p.n_ret;
-    int *const pool_ctr = &p.sync[kSyncPool + group * 1024];
+    const int static_end = p.n_ret;
     if (tid < 32) j_a[tid] = tid < n_aslots ? p.cand_idx[tid * n_wg + b] : -1;
     for (int e = tid; e < (n_static + 1) * kRB; e += blockDim.x) {
         const int r = ((e / kRB) * n_workers + wb) * kRB + e % kRB;
         j_s[e] = (e / kRB < n_static && r < static_end) ? p.ret_idx[r] : -1;
     }
-    for (int e = tid; e < pool_rounds * kRB; e += blockDim.x) {
-        const int r = static_end + pool_first * kRB + e;
-        pool_j[e] = r < p.n_ret ? p.ret_idx[r] : -1;
-    }
-    if (tid < 4) mb_ticket[tid] = kNoTicket;
     if (tid < 2) mb_bits[tid] = 0;
     __syncthreads();
 
@@ -277,16 +248,13 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     int ia = 0;                 // next candidate slot to evaluate
     int rem_d = 0;              // selected slots whose down rows are still to be added (valid once bits_known)
     bool bits_known = false;    // the selection word of this step has been seen
-    bool pool_end = pool_rounds == 0;
     int n_st = 0;               // rounds staged in j_st / h_st
     int a_pub = n_aslots == 0 ? -2 : -1;  // round after which the candidate results were stored (-1: not yet)
     bool arrived = false;       // the arrival has been signalled to the selector
-    // thread 0 only: results of the ticket request and of the poll issued in the previous round
-    int tk_ret = kNoTicket, poll_ret = 0;
-    bool tk_wanted = false, claim_more = pool_rounds > 0;
+    // thread 0 only: results of the polls of the selection word issued in the previous two rounds (by parity)
+    int poll_ret[2] = {0, 0};
 
-    // Descriptor of round r.  Called once per round, in order; a pool round's ticket was requested four rounds
-    // earlier and handed over through LDS one round before this call.
+    // Descriptor of round r.  Called once per round, in order.
     auto make_desc = [&](RoundDesc &ds, int r) {
         bool work = false;
 #pragma unroll
@@ -295,15 +263,6 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 #pragma unroll
             for (int t = 0; t < kRB; ++t) ds.jb[t] = uniform(j_s[r * kRB + t]);
             work = ds.jb[0] >= 0;
-        } else if (!pool_end) {
-            const int tk = uniform(mb_ticket[r & 3]);
-            if (tk < pool_rounds) {
-#pragma unroll
-                for (int t = 0; t < kRB; ++t) ds.jb[t] = uniform(pool_j[tk * kRB + t]);
-                work = true;
-            } else {
-                pool_end = true;  // the counter only grows: every later ticket is beyond the pool too
-            }
         }
 #pragma unroll
         for (int t = 0; t < kRB; ++t) ds.boff[t] = (uint32_t)max(ds.jb[t], 0) * 3u * (uint32_t)nvec;
@@ -356,8 +315,8 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     // nothing stands between the arrival of one round and the request for the next); the descriptor of round i + 2
     // is prepared into dn2 while that request is in flight.
     auto step = [&](RoundBuf<V, PER> &cur, const RoundDesc &dc, RoundBuf<V, PER> &nxt, const RoundDesc &dn1,
-                    RoundDesc &dn2, int i, float nrm_mine) {
-        const int par = i & 1;
+                    RoundDesc &dn2, int i, float nrm_mine, auto parity) {
+        constexpr int par = decltype(parity)::value;  // i & 1
         const int xkind = dc.xkind();
         acc_t ag[kRB], au[kRB], ax[kXL];
 #pragma unroll
@@ -370,13 +329,14 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                 au[t] = V::dot(cur.u[t][q], xv[q], au[t]);
             }
         }
-        if (xkind == 1) {
+        // The extra rows are multiplied in every round, needed or not (16 instructions): a register that is loaded
+        // on some paths and read on others would count as "possibly still in flight" for the rest of the loop,
+        // and the compiler would then wait for every outstanding request before reusing it.
 #pragma unroll
-            for (int a = 0; a < kXL; ++a) {
-                ax[a] = 0;
+        for (int a = 0; a < kXL; ++a) {
+            ax[a] = 0;
 #pragma unroll
-                for (int q = 0; q < PER; ++q) ax[a] = V::dot(cur.xl[a][q], xv[q], ax[a]);
-            }
+            for (int q = 0; q < PER; ++q) ax[a] = V::dot(cur.xl[a][q], xv[q], ax[a]);
         }
         asm volatile("" ::: "memory");  // everything below stays behind the uses of this round's gate/up rows
         // Candidate results stored in the previous round: the explicit wait below finds them acknowledged.
@@ -391,30 +351,19 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
         load_round<V, PER>(nxt, dn1, w, nvec, col, ok);  // an empty round requests the dummy vector only
         asm volatile("" ::: "memory");
         if (tid == 0) {
-            // What thread 0 requested in the previous round (ticket for round i + 3, poll) arrived with this
-            // round's rows: hand it to the others at this round's barrier.
-            const int tk = tk_wanted ? tk_ret : kNoTicket;
-            mb_ticket[(i + 3) & 3] = tk;
-            mb_bits[par] = poll_ret;
+            // The poll thread 0 issued two rounds ago has had two rounds to arrive: hand it to the others at this
+            // round's barrier.  Then poll the selection word again (zero until the selector has written it),
+            // straight into the register it is read from two rounds later.
+            mb_bits[par] = poll_ret[par];
 #ifdef POP_TRACE
-            if ((poll_ret & kBitsValid) && p.trace && p.trace[(size_t)blockIdx.x * 8 + 5] == 0) POP_STAMP(5);
+            if ((poll_ret[par] & kBitsValid) && p.trace && p.trace[(size_t)blockIdx.x * 8 + 5] == 0) POP_STAMP(5);
 #endif
-            if (tk_wanted && tk >= pool_rounds) claim_more = false;
-            // Poll of the selection word (zero until the selector has written it), ticket for round i + 4.  Both
-            // are issued unconditionally, straight into the registers they are read from a round later: an
-            // unwanted ticket request adds zero to a word of this workgroup's own and its result is ignored.
-#ifndef POP_NO_POLL
-            poll_ret = coherent_load(my_word);
-#endif
-            tk_wanted = claim_more && i + 4 >= n_static;
-            if (p.pool_rounds > 0)
-                tk_ret = __hip_atomic_fetch_add(tk_wanted ? pool_ctr : my_word + kScratchWord, tk_wanted ? 1 : 0,
-                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            poll_ret[par] = coherent_load(my_word);
         }
         asm volatile("" ::: "memory");
         // descriptor of round i + 2, from what thread 0 handed over at the previous barrier
         if (!bits_known && i >= 1) {
-            const int v = uniform(mb_bits[par ^ 1]);
+            const int v = uniform(mb_bits[par ^ 1]);  // handed over at the previous round's barrier
             if (v & kBitsValid) {
                 bits_known = true;
                 rem_d = v & ~kBitsValid;
@@ -512,6 +461,10 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     };
 
     RoundBuf<V, PER> buf_a, buf_b;  // ping-pong: one is reduced while the other's loads are in flight
+#pragma unroll
+    for (int a = 0; a < kXL; ++a)
+#pragma unroll
+        for (int q = 0; q < PER; ++q) buf_a.xl[a][q] = buf_b.xl[a][q] = V::zero();  // read before the first extra rows
     RoundDesc d0, d1, d2;           // descriptors of the round being reduced, the one in flight, the one after
     make_desc(d0, 0);
     load_round<V, PER>(buf_a, d0, w, nvec, col, ok);
@@ -522,12 +475,12 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     int i = 0;
     // a round without work can still be followed by one with work (selected rows, once the selection is known)
     while (d0.work || d1.work) {
-        step(buf_a, d0, buf_b, d1, d2, i, nrm_mine);
+        step(buf_a, d0, buf_b, d1, d2, i, nrm_mine, std::integral_constant<int, 0>{});
         ++i;
         d0 = d1;
         d1 = d2;
         if (!(d0.work || d1.work)) break;
-        step(buf_b, d0, buf_a, d1, d2, i, nrm_mine);
+        step(buf_b, d0, buf_a, d1, d2, i, nrm_mine, std::integral_constant<int, 1>{});
         ++i;
         d0 = d1;
         d1 = d2;
@@ -753,15 +706,6 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
             p.sync[2] = 1;
             coherent_store(&p.sync[3], 1);
         }
-        if (p.pool_rounds > 0) {
-            // every ticket request of this workgroup has returned; the last worker to get here rewinds the
-            // counters for the next launch
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (atomicAdd(&p.sync[kSyncDone], 1) == n_workers - 1) {
-                for (int g = 0; g < kPoolGroups; ++g) coherent_store(&p.sync[kSyncPool + g * 1024], 0);
-                coherent_store(&p.sync[kSyncDone], 0);
-            }
-        }
     }
     __syncthreads();
     for (int e = tid; e < n_st * kRB; e += blockDim.x)
@@ -835,25 +779,14 @@ __global__ __launch_bounds__(1024) void decode_tail_kernel(const float *__restri
 template <class V, int PER, int MAXB>
 static hipError_t fused_launch(const FusedPlan &pl, FusedParams &p, hipStream_t s)
 {
-    hipLaunchKernelGGL((decode_fused_kernel<V, PER, MAXB>), dim3(pl.n_wg), dim3(pl.block), pl.lds_dynamic, s, p);
+    hipLaunchKernelGGL((decode_fused_kernel<V, PER, MAXB>), dim3(pl.n_wg), dim3(pl.block), 0, s, p);
     return hipGetLastError();
 }
 
 template <class V, int PER, int MAXB>
-static hipError_t fused_kernel_info(int block, size_t lds_dynamic, int *blocks_per_cu, size_t *lds_static)
+static hipError_t fused_occupancy(int block, int *blocks_per_cu)
 {
-    const void *fn = reinterpret_cast<const void *>(&decode_fused_kernel<V, PER, MAXB>);
-    hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, fn);
-    if (e != hipSuccess) return e;
-    if (lds_static) *lds_static = attr.sharedSizeBytes;
-    if (!blocks_per_cu) return hipSuccess;
-    if (lds_dynamic > 0) {
-        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_dynamic);
-        if (e != hipSuccess) return e;
-    }
-    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_fused_kernel<V, PER, MAXB>, block,
-                                                        lds_dynamic);
+    return hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, decode_fused_kernel<V, PER, MAXB>, block, 0);
 }
 
 // Calls fn.template operator()<V, PER, MAXB>() for the plan's variant.
@@ -869,15 +802,13 @@ static hipError_t fused_dispatch(int is_bf16, int per, int block, Fn fn)
     return small ? fn.template operator()<VecF32, 2, 512>() : fn.template operator()<VecF32, 2, 1024>();
 }
 
-struct FusedInfoFn {
+struct FusedOccupancyFn {
     int block;
-    size_t lds_dynamic;
     int *blocks_per_cu;
-    size_t *lds_static;
     template <class V, int PER, int MAXB>
     hipError_t operator()() const
     {
-        return fused_kernel_info<V, PER, MAXB>(block, lds_dynamic, blocks_per_cu, lds_static);
+        return fused_occupancy<V, PER, MAXB>(block, blocks_per_cu);
     }
 };
 struct FusedLaunchFn {
@@ -891,24 +822,15 @@ struct FusedLaunchFn {
     }
 };
 
-static hipError_t fused_info(int is_bf16, int per, int block, size_t lds_dynamic, int *blocks_per_cu, size_t *lds_static)
-{
-    return fused_dispatch(is_bf16, per, block, FusedInfoFn{block, lds_dynamic, blocks_per_cu, lds_static});
-}
-
 int fused_max_workgroups() { return 1024; }
 int fused_selbits_ints() { return 1024 * kBitsStride; }
-int fused_sync_ints() { return (2 + kPoolGroups) * 1024; }
 
-// Chooses the launch shape and the split of the retained rounds into a statically dealt part and a shared pool
-// (static_pct = 100: no pool); false when the fused kernel does not support this shape.
-bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, int static_pct, size_t lds_limit,
-                FusedPlan *pl, hipError_t *err)
+// Chooses the launch shape; false when the fused kernel does not support this shape.
+bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl)
 {
-    *err = hipSuccess;
     const int E = is_bf16 ? 8 : 4, nvec = d / E;
     // one vector column per thread up to 512 threads, then two (a workgroup of up to 512 threads has twice the
-    // registers per thread); POP_FUSED_PER=1 keeps one column per thread up to 1024 threads (tuning)
+    // registers per thread); POP_FUSED_PER=1 / 2 overrides for 128 <= d/E <= 1024 (tuning)
     int per = nvec > 512 ? 2 : 1;
     if (nvec <= 1024 && nvec >= 128)
         if (const char *e = getenv("POP_FUSED_PER")) per = atoi(e) == 1 ? 1 : 2;
@@ -921,41 +843,16 @@ bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, int st
     if (workers < 1) workers = 1;
     if (workers > wg_target - 1) workers = wg_target - 1;
     pl->n_wg = workers + 1;
+    // a workgroup's candidate slots must fit its selection word, its retained rounds the staged list
     if ((n_cand + pl->n_wg - 1) / pl->n_wg > kMaxASlots) return false;
-    size_t lds_static = 0;
-    *err = fused_info(is_bf16, per, pl->block, 0, nullptr, &lds_static);
-    if (*err != hipSuccess) return false;
-    const int per_worker = rounds_total / workers;  // every worker can get this many static rounds
-    int n_static = (rounds_total + workers - 1) / workers, pool_rounds = 0;
-    if (static_pct < 100 && per_worker >= 5) {
-        n_static = per_worker * (static_pct < 0 ? 0 : static_pct) / 100;
-        if (n_static < 4) n_static = 4;  // tickets are requested four rounds ahead
-        if (n_static > kMaxStatic) n_static = kMaxStatic;
-        // the pool's channel list lives in LDS
-        // a workgroup keeps the channel list of its pool group in LDS
-        const int n_groups = fused_pool_groups(workers);
-        auto group_bytes = [&](int ns) {
-            return (size_t)((rounds_total - ns * workers + n_groups - 1) / n_groups) * kRB * 4;
-        };
-        while (n_static < per_worker && lds_static + group_bytes(n_static) > lds_limit) ++n_static;
-        pool_rounds = rounds_total - n_static * workers;
-        if (pool_rounds <= 0 || lds_static + group_bytes(n_static) > lds_limit) {
-            n_static = (rounds_total + workers - 1) / workers;
-            pool_rounds = 0;
-        }
-    }
-    if (n_static > kMaxStatic) return false;
-    pl->n_static = n_static;
-    pl->pool_rounds = pool_rounds;
-    const int n_groups_final = fused_pool_groups(workers);
-    pl->lds_dynamic = (size_t)((pool_rounds + n_groups_final - 1) / n_groups_final) * kRB * 4;
-    return true;
+    pl->n_static = (rounds_total + workers - 1) / workers;
+    return pl->n_static <= kMaxStatic;
 }
 
 hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int *max_wg)
 {
     int per_cu = 0;
-    hipError_t e = fused_info(is_bf16, pl.per, pl.block, pl.lds_dynamic, &per_cu, nullptr);
+    hipError_t e = fused_dispatch(is_bf16, pl.per, pl.block, FusedOccupancyFn{pl.block, &per_cu});
     if (e != hipSuccess) return e;
     *max_wg = per_cu * n_cu;
     return hipSuccess;
@@ -964,7 +861,6 @@ hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int 
 hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p, hipStream_t s)
 {
     p.n_static = pl.n_static;
-    p.pool_rounds = pl.pool_rounds;
     return fused_dispatch(is_bf16, pl.per, pl.block, FusedLaunchFn{pl, p, s});
 }
 

@@ -98,9 +98,8 @@ struct FusedParams {
     float *partial;          // [n_wg][d]
     int *sync;               // [0] arrivals of candidate results, [2] sticky error flag, [3] some workgroup deferred
                              // its share in this step, [6] end-of-step arrivals (single-launch step only),
-                             // [1024] workers done with the round pool, [2048 + 1024 g] ticket counter of pool group g.
-                             // All counters are back at zero when the kernel ends.
-    int n_static, pool_rounds;  // retained rounds dealt statically per worker / rounds in the shared pool
+                             // [8] arrivals of the batched top-k.  All counters are back at zero when a kernel ends.
+    int n_static;            // retained rounds per worker
     int *selbits;            // [n_wg] per-workgroup selection word (valid bit + selected candidate slots);
                              // each workgroup clears its own word after use, so a launch can be replayed
     unsigned long long *trace;  // profiling builds only: 8 timestamps per workgroup, else null
@@ -113,17 +112,12 @@ struct FusedParams {
 
 struct FusedPlan {
     int n_wg, block, per;
-    int n_static, pool_rounds;  // split of the retained rounds: dealt round-robin / drawn from a shared pool
-    size_t lds_dynamic;         // bytes of the pool's channel list
+    int n_static;  // retained rounds per worker
 };
 int fused_max_workgroups();
 int fused_selbits_ints();  // size of the selection-word buffer (one word per workgroup, spaced apart)
-int fused_sync_ints();     // size of the counter buffer
-// Launch shape for (d, dtype, region sizes); static_pct = share of a worker's retained rounds that is dealt
-// statically (100: all of them, fixed summation order).  false when the fused kernel does not support the shape
-// (or a HIP query failed: *err).
-bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, int static_pct, size_t lds_limit,
-                FusedPlan *pl, hipError_t *err);
+// Launch shape for (d, dtype, region sizes); false when the fused kernel does not support the shape.
+bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl);
 // Largest grid of this shape that is co-resident on n_cu compute units.
 hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int *max_wg);
 hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p, hipStream_t s);

@@ -27,17 +27,14 @@ def bf16_out_to_f64(t: torch.Tensor) -> np.ndarray:
 class GpuLayer:
     """A synthetic layer resident on the device plus its library handle."""
 
-    def __init__(self, pop, layer: synth.Layer, max_tokens: int, max_batch: int = 1, fixed_order: bool = True):
+    def __init__(self, pop, layer: synth.Layer, max_tokens: int, max_batch: int = 1):
         self.pop = pop
-        self.fixed_order = fixed_order
         self.layer = layer
         cfg = layer.cfg
         self.d, self.m, self.dtype = cfg.d, cfg.m, cfg.dtype
         wg, wu, wd = dev(layer.w_gate), dev(layer.w_up), dev(layer.w_down)
         self.handle = pop.pop_layer_create(cfg.d, cfg.m, cfg.dtype, wg, wu, wd, max_tokens, max_batch)
         del wg, wu, wd
-        if not fixed_order:
-            pop.pop_layer_set_fixed_order(self.handle, False)  # run-time pool of retained rounds
         self.n_ret = self.n_cand = None
 
     def close(self):

@@ -115,33 +115,23 @@ def _check_decode(oracle, G, L, region, cand, x_t, ks, ydtype=None):
         y_ref = oracle.down(ref["h"].reshape(1, -1), L.w_down, dtype, mask1)[0]
         yerr = max_abs_rel(out["y"][b], y_ref)
         assert yerr <= Y_TOL[dtype], f"y error {yerr:.3e}"
-    # the whole step in one call: same selection, scores and h bit for bit.  With the fixed schedule its default
-    # form issues the same launches (y bit for bit) and the single-launch form sums y in another (fixed) order;
-    # with the run-time pool y agrees to float32 rounding
-    def y_close(ya, yb, what):
-        for b in range(B):
-            ref_scale = float(np.max(np.abs(yb[b]))) or 1.0
-            ystep = float(np.max(np.abs(ya[b] - yb[b]))) / ref_scale
-            lim = 1e-5 if (G.dtype if ydtype is None else ydtype) == F32 else 1e-2
-            assert ystep <= lim, f"{what}: y differs by {ystep:.3e}"
-
+    # the whole step in one call: same selection, scores and h bit for bit.  Its default form issues the same
+    # launches (y bit for bit); the single-launch form sums y in another (fixed) order
     for form in (True, "single_launch"):
         one = G.decode(x_t, ks, ydtype, one_call=form)
         for key in ("mask", "active_idx", "n_active", "cscore"):
             assert np.array_equal(one[key], out[key]), (form, key)
         assert np.array_equal(one["h"][:, rc], out["h"][:, rc]), form
         if form is True:
-            if G.fixed_order:
-                assert np.array_equal(one["y"], out["y"])
-            else:
-                y_close(one["y"], out["y"], "one call vs two calls")
+            assert np.array_equal(one["y"], out["y"])
             continue
         again = G.decode(x_t, ks, ydtype, one_call=form)
-        if G.fixed_order:
-            assert np.array_equal(one["y"], again["y"]), "single-launch y is not reproducible"
-        else:
-            y_close(again["y"], one["y"], "single launch, repeated")
-        y_close(one["y"], out["y"], "single launch vs two calls")
+        assert np.array_equal(one["y"], again["y"]), "single-launch y is not reproducible"
+        for b in range(B):
+            ref_scale = float(np.max(np.abs(out["y"][b]))) or 1.0
+            ystep = float(np.max(np.abs(one["y"][b] - out["y"][b]))) / ref_scale
+            lim = 1e-5 if (G.dtype if ydtype is None else ydtype) == F32 else 1e-2
+            assert ystep <= lim, f"single-launch y differs from two-call y by {ystep:.3e}"
     return out
 
 
@@ -172,12 +162,10 @@ def test_small_layer_end_to_end(pop, oracle, name, d, m, dtype, T, fr, r):
         _check_decode(oracle, G, L, region, cand, xt[1:3], [k, k], ydtype=F32)
 
 
-@pytest.mark.parametrize("fixed", [True, False])
 @pytest.mark.parametrize("dtype,wgs", [(BF16, 6), (F32, 6), (BF16, 4), (BF16, 40)])
-def test_fused_step_many_rounds_per_workgroup(pop, oracle, monkeypatch, dtype, wgs, fixed):
+def test_fused_step_many_rounds_per_workgroup(pop, oracle, monkeypatch, dtype, wgs):
     """Few workgroups => many rounds each: exercises the ping-pong stream, the candidate and selected rows that
-    ride along with the retained rounds, the shared round pool (fixed = False) and, with 4 workgroups, many
-    candidate slots per workgroup."""
+    ride along with the retained rounds and, with 4 workgroups, many candidate slots per workgroup."""
     monkeypatch.setenv("POP_FUSED_WGS", str(wgs))
     d, m, T = 512, 768, 40
     L = synth.make_layer(synth.small_config(f"many_rounds_{wgs}", d, m, dtype, n_outlier=2, heavy_tail=dtype == BF16))
@@ -185,26 +173,18 @@ def test_fused_step_many_rounds_per_workgroup(pop, oracle, monkeypatch, dtype, w
     xt = synth.make_activations(L, 6, "decode")
     n_ret, n_cand, _ = pop.pop_region_counts(m, 0.25 if wgs == 4 else 0.6, 0.1)
     k = n_cand // 2
-    with GpuLayer(pop, L, max_tokens=T, max_batch=1, fixed_order=fixed) as G:
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
         scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
         outs = [_check_decode(oracle, G, L, region, cand, xt[t:t + 1], kk)
                 for t, kk in enumerate([k, k, 0, n_cand, 1, k])]
         assert pop.pop_layer_step_kind(G.handle) == (1, wgs)  # the fused kernel ran, with the forced grid
-        # the same step again gives the same bits (the in-kernel flags and counters were rearmed correctly); with
-        # the fixed schedule the summation order of y is fixed too
+        # the same step again gives the same bits (the in-kernel flags were rearmed correctly; the assignment
+        # of channels to workgroups is fixed, so the summation order of y is too)
         first = outs[5]
         for _ in range(3):
             again = G.decode(xt[5:6], k)
-            for key in ("mask", "active_idx", "cscore") + (("y",) if fixed else ()):
+            for key in ("mask", "active_idx", "y", "cscore"):
                 assert np.array_equal(first[key], again[key]), key
-            assert np.array_equal(first["h"][:, region != 2], again["h"][:, region != 2])
-            assert max_abs_rel(again["y"], first["y"]) <= (1e-5 if dtype == F32 else 1e-2)
-        # switching the schedule on a live partition works
-        pop.pop_layer_set_fixed_order(G.handle, not fixed)
-        other = G.decode(xt[5:6], k)
-        for key in ("mask", "active_idx", "cscore"):
-            assert np.array_equal(first[key], other[key]), key
-        assert max_abs_rel(other["y"], first["y"]) <= (1e-5 if dtype == F32 else 1e-2)
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
@@ -326,7 +306,7 @@ def test_determinism_and_poisoned_scratch(pop, oracle):
                 assert np.array_equal(o1[key][:, rc], o2[key][:, rc]), key
             else:
                 assert np.array_equal(o1[key], o2[key]), key
-        # single-sequence steps (fused kernel with the fixed schedule): bit-identical y as well
+        # single-sequence steps (fused kernel): bit-identical y as well
         s1 = G.decode(xt[:1], k)
         G.ffn(xt, (synth.rng("dirty2").random((4, m)) < 0.5).astype(np.uint8))
         G.prefill(x, n_ret, n_cand)
