@@ -88,7 +88,7 @@ def run(args):
         return n_ret, n_cand, pop.pop_k_for_ratio(m, r, n_ret, n_cand)
 
     def make_calls(r):
-        n_ret, n_cand, k = counts(r)
+        n_ret, n_cand, k = r if isinstance(r, tuple) else counts(r)  # explicit region sizes, or a sparsity
         karr = (C.c_int * 1)(k)
         prefill, decode = [], []
         for L in layers:
@@ -177,6 +177,27 @@ def run(args):
             extra[f"r={r:.2f}"] = dict(us_per_token=round(t["decode_us_per_token"], 3),
                                        active_GBps=round(b["active"] / t["decode_us_per_token"] / 1e3, 1),
                                        frac_of_peak_active=round(b["active"] / t["decode_us_per_token"] / 1e3 / HBM_PEAK_GBS, 4))
+    # The paper's ablation of the decode strategy (Sec. 5, trade-off table), in time and bytes on this shape: a
+    # static prefill mask (Variant 1: no candidates), POP with candidate bands of 5 / 10 / 20 % of the channels,
+    # and re-scoring every channel at each step (Variant 2: every channel a candidate); all at r = 0.35.
+    ablation = None
+    if not args.quick:
+        a_act = n_ret + k
+        rows = [("dense", (m, 0, 0)), ("variant1_static_mask", (a_act, 0, 0))]
+        for g in (0.05, 0.10, 0.20):
+            nr, nc, _ = pop.pop_region_counts(m, 1.0 - r_main - g / 2, g)
+            rows.append((f"pop_gamma_{g:.2f}", (nr, nc, pop.pop_k_for_ratio(m, r_main, nr, nc))))
+        rows.append(("variant2_rescore_all", (0, m, a_act)))
+        ablation = {}
+        for name, cnt in rows:
+            t = timed(cnt, 1, 1)["decode_us_per_token"]
+            ablation[name] = dict(n_ret=cnt[0], n_cand=cnt[1], k=cnt[2], us_per_token=round(t, 3),
+                                  MB_per_token=round(byte_model(d, *cnt)["algorithmic"] / 1e6, 2))
+        base_t = ablation["variant1_static_mask"]["us_per_token"]
+        base_b = ablation["variant1_static_mask"]["MB_per_token"]
+        for name, row in ablation.items():
+            row["overhead_vs_static_mask_pct"] = dict(time=round(100 * (row["us_per_token"] / base_t - 1), 2),
+                                                      bytes=round(100 * (row["MB_per_token"] / base_b - 1), 2))
     # cache-warm single-layer figure (same layer every token)
     warm = None
     if not args.quick and len(layers) > 1:
@@ -251,6 +272,7 @@ def run(args):
         "warm_us_per_token": None if warm is None else round(warm, 3),
         "other_sparsities": extra,
         "single_launch_step_us_per_token": None if single is None else round(single, 3),
+        "ablation_r0.35": ablation,
         "other_shapes": other_configs,
         "roofline": roofline,
         "cpu_baseline": cpu,
