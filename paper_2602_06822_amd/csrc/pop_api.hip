@@ -338,16 +338,25 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         POP_HIP(launch_decode_fused(L->plan, L->is_bf16, p, s));
         L->step_fused = true;
     } else {
-        POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
-                              L->cscore, m, n_cand, L->n_cu, s));
         if (B > 1) {
             if (!L->ulist_prefix_ok && n_ret)
                 POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
             L->ulist_prefix_ok = true;
         }
-        // B > 1: the kernel also builds the union of the B selections for the batched down projection
-        POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx, L->n_active,
-                            nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist, s));
+        bool sel_inside = false;
+        if (B > 1)  // per-sequence top-k and their union inside the gate/up kernel, behind the retained channels
+            POP_HIP(launch_gateup_select(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, L->h, L->nrm, L->cscore, m,
+                                         L->cand_idx, n_cand, n_ret, kk, m, L->mask, L->active_idx, L->n_active,
+                                         L->selflag, L->ulist, L->n_ulist, L->sync + 10, L->sync + 2, L->n_cu,
+                                         &sel_inside, s));
+        if (!sel_inside) {
+            POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
+                                  L->cscore, m, n_cand, L->n_cu, s));
+            // B > 1: the kernel also builds the union of the B selections for the batched down projection
+            POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx,
+                                L->n_active, nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
+                                s));
+        }
         L->step_fused = false;
     }
     { int rc = copy_step_outputs(L, B, cand_scores, mask, active_idx, n_active, s); if (rc != POP_OK) return rc; }

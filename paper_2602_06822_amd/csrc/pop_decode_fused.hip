@@ -47,7 +47,6 @@ namespace pop {
 
 constexpr int kRB = 2;           // retained channels per round
 constexpr int kXL = 4;           // extra rows per round: 2 candidates x (gate, up), or 4 selected down rows
-constexpr int kSpinLimit = 1 << 16;
 constexpr int kMaxStatic = 64;   // statically dealt rounds per workgroup (staged in LDS)
 constexpr int kKeep = 64;        // rounds whose hidden activations are staged in LDS between flushes
 constexpr int kMaxASlots = 30;   // candidate slots per workgroup: they must fit the selection word next to the valid bit
@@ -63,17 +62,6 @@ constexpr int kMaxASlots = 30;   // candidate slots per workgroup: they must fit
     do {                \
     } while (0)
 #endif
-
-// Bounded wait until *addr >= target.
-__device__ __forceinline__ bool spin_until(const int *addr, int target)
-{
-    for (int it = 0; it < kSpinLimit; ++it) {
-        int v = __hip_atomic_load(addr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (v >= target) return true;
-        __builtin_amdgcn_s_sleep(2);
-    }
-    return false;
-}
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 
@@ -154,18 +142,6 @@ __device__ __forceinline__ float wave_total(float v)
 }
 __device__ __forceinline__ double wave_total(double v) { return wave_sum(v); }
 
-__device__ __forceinline__ int coherent_load(const int *p)
-{
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void coherent_store(int *p, int v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void coherent_store(float *p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 // 16-byte write-through store (device scope), p 16-byte aligned.  Not tracked by the compiler's wait counting:
 // follow with an explicit wait before relying on it.
 __device__ __forceinline__ void coherent_store4(float *p, float4 v)

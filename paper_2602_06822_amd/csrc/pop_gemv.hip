@@ -10,12 +10,74 @@
 //
 // A wave owns a whole row at a time (gateup) or a 64-vector column chunk of a slab of rows (down); lanes
 // stride the row in 16-byte vectors, so each wave-level load instruction fetches 1 KiB of contiguous HBM.
+#include "pop_select_dev.h"
 #include "pop_vec.h"
 
 namespace pop {
 
 // ---------------------------------------------------------------- gate/up GEMV
 constexpr int kGuUnroll = 8;  // 16-byte loads per matrix in flight per lane within one group
+
+// One listed channel j (list position p), one wave: h[b][j] = silu(x_b . gate_j) * (x_b . up_j) for the B sequences
+// whose x is staged in LDS (xs [B][nvec]); positions p < n_score also get their step score.  kCoherent: the scores
+// are written through, for workgroups of the same launch to read.
+template <class V, int B, bool kCoherent>
+__device__ __forceinline__ void gateup_row(const typename V::vec_t *__restrict__ w, int nvec,
+                                           const typename V::vec_t *xs, int j, int p, int lane, float *__restrict__ h,
+                                           int m, const float *__restrict__ nrm, float *cscore, int cs_stride,
+                                           int n_score)
+{
+    typedef typename V::vec_t vec_t;
+    const int group = kWave * kGuUnroll;
+    const int nvec_full = nvec / group * group;
+    const vec_t *g = w + (size_t)j * 3 * nvec;
+    const vec_t *u = g + nvec;
+    typename V::acc_t ag[B], au[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) ag[b] = au[b] = 0;
+
+    for (int c0 = 0; c0 < nvec_full; c0 += group) {
+        vec_t wg[kGuUnroll], wu[kGuUnroll];
+#pragma unroll
+        for (int q = 0; q < kGuUnroll; ++q) {
+            wg[q] = g[c0 + q * kWave + lane];
+            wu[q] = u[c0 + q * kWave + lane];
+        }
+#pragma unroll
+        for (int q = 0; q < kGuUnroll; ++q) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                vec_t xv = xs[b * nvec + c0 + q * kWave + lane];
+                ag[b] = V::dot(wg[q], xv, ag[b]);
+                au[b] = V::dot(wu[q], xv, au[b]);
+            }
+        }
+    }
+    for (int c = nvec_full + lane; c < nvec; c += kWave) {
+        vec_t wg = g[c], wu = u[c];
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            vec_t xv = xs[b * nvec + c];
+            ag[b] = V::dot(wg, xv, ag[b]);
+            au[b] = V::dot(wu, xv, au[b]);
+        }
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        float gs = (float)wave_sum(ag[b]), us = (float)wave_sum(au[b]);
+        if (lane == 0) {
+            float hv = silu_mul(gs, us);
+            h[(size_t)b * m + j] = hv;
+            if (p < n_score) {
+                const float sc = nrm[j] * fabsf(hv);
+                if (kCoherent)
+                    coherent_store(&cscore[(size_t)b * cs_stride + p], sc);
+                else
+                    cscore[(size_t)b * cs_stride + p] = sc;
+            }
+        }
+    }
+}
 
 template <class V, int B>
 __global__ __launch_bounds__(1024) void gateup_kernel(const typename V::vec_t *__restrict__ w, int nvec,
@@ -35,52 +97,123 @@ __global__ __launch_bounds__(1024) void gateup_kernel(const typename V::vec_t *_
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     const int n_waves = gridDim.x * (blockDim.x / kWave);
-    const int group = kWave * kGuUnroll;
-    const int nvec_full = nvec / group * group;
 
-    for (int p = blockIdx.x * (blockDim.x / kWave) + wave; p < n; p += n_waves) {
-        const int j = rows[p];
-        const vec_t *g = w + (size_t)j * 3 * nvec;
-        const vec_t *u = g + nvec;
-        typename V::acc_t ag[B], au[B];
-#pragma unroll
-        for (int b = 0; b < B; ++b) ag[b] = au[b] = 0;
+    for (int p = blockIdx.x * (blockDim.x / kWave) + wave; p < n; p += n_waves)
+        gateup_row<V, B, false>(w, nvec, xs, rows[p], p, lane, h, m, nrm, cscore, cs_stride, n_score);
+}
 
-        for (int c0 = 0; c0 < nvec_full; c0 += group) {
-            vec_t wg[kGuUnroll], wu[kGuUnroll];
-#pragma unroll
-            for (int q = 0; q < kGuUnroll; ++q) {
-                wg[q] = g[c0 + q * kWave + lane];
-                wu[q] = u[c0 + q * kWave + lane];
-            }
-#pragma unroll
-            for (int q = 0; q < kGuUnroll; ++q) {
-#pragma unroll
-                for (int b = 0; b < B; ++b) {
-                    vec_t xv = xs[b * nvec + c0 + q * kWave + lane];
-                    ag[b] = V::dot(wg[q], xv, ag[b]);
-                    au[b] = V::dot(wu[q], xv, au[b]);
-                }
+// Batched decode with the selection inside: rows = candidates (n_cand) then retained channels (n_ret).  All but
+// the last B workgroups evaluate the rows, candidates first, and signal an arrival once their candidate scores are
+// acknowledged.  The last B workgroups wait, bounded, for all arrivals and run one sequence's top-k each, the last of
+// them also the union of the selections, while the others go on with the retained channels: the selection costs
+// no time of its own.  All workgroups are resident (at most one per compute unit is launched), so the wait ends;
+// if it ever expires the sticky error flag is raised.
+struct GateupSelectArgs {
+    const int *cand_idx;
+    int n_cand, n_ret;
+    BatchK k;
+    int act_stride;
+    unsigned char *mask;
+    int *active_idx, *n_active;
+    unsigned char *selflag;
+    int *union_list, *n_union;
+    int *counters;  // [0] arrivals, [1] selectors done
+    int *err_flag;
+};
+
+template <class V, int B>
+__global__ __launch_bounds__(1024) void gateup_select_kernel(const typename V::vec_t *__restrict__ w, int nvec,
+                                                            const typename V::vec_t *__restrict__ x,
+                                                            const int *__restrict__ rows, float *__restrict__ h, int m,
+                                                            const float *__restrict__ nrm, float *cscore, int cs_stride,
+                                                            GateupSelectArgs sa)
+{
+    typedef typename V::vec_t vec_t;
+    extern __shared__ uint4 xs_raw[];
+    __shared__ SelShared sh;
+    __shared__ int s_flag;
+    vec_t *xs = reinterpret_cast<vec_t *>(xs_raw);  // [B][nvec]
+    for (int i = threadIdx.x; i < B * nvec; i += blockDim.x) xs[i] = x[i];
+    __syncthreads();
+
+    const int lane = threadIdx.x % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wpb = blockDim.x / kWave, n_wg = gridDim.x;
+    const int n_cand = sa.n_cand, n = sa.n_cand + sa.n_ret;
+
+    const int n_work = n_wg - B;  // workgroups that evaluate rows; the last B select
+    if ((int)blockIdx.x < n_work) {
+        // Rows are dealt to the waves of the working workgroups in list order, candidates first.  A workgroup
+        // signals its arrival after its last round that holds a candidate (at once if it has none): its scores are
+        // then acknowledged (write-through stores, counter wait, barrier).
+        const int wg = blockIdx.x, stride = n_work * wpb;
+        const int cand_rounds = wg * wpb < n_cand ? (n_cand - wg * wpb + stride - 1) / stride : 0;
+        if (cand_rounds == 0 && threadIdx.x == 0) atomicAdd(&sa.counters[0], 1);
+        for (int it = 0; it * stride + wg * wpb < n; ++it) {
+            const int p = it * stride + wg * wpb + wave;
+            if (p < n_cand)
+                gateup_row<V, B, true>(w, nvec, xs, rows[p], p, lane, h, m, nrm, cscore, cs_stride, n_cand);
+            else if (p < n)
+                gateup_row<V, B, false>(w, nvec, xs, rows[p], p, lane, h, m, nrm, cscore, cs_stride, n_cand);
+            if (it == cand_rounds - 1) {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wave's scores are acknowledged
+                __syncthreads();
+                if (threadIdx.x == 0) atomicAdd(&sa.counters[0], 1);
             }
         }
-        for (int c = nvec_full + lane; c < nvec; c += kWave) {
-            vec_t wg = g[c], wu = u[c];
+        return;
+    }
+
+    const int b = blockIdx.x - n_work;  // this workgroup selects for sequence b
+    if (threadIdx.x == 0) {
+        const bool ok = spin_until(&sa.counters[0], n_work);
+        if (!ok) *sa.err_flag = 1;
+        s_flag = ok ? 1 : 0;
+    }
+    __syncthreads();
+    if (s_flag) {
+        block_select_candidates<true, SelectNoHook, SelectNoHook, true>(
+            cscore + (size_t)b * cs_stride, sa.cand_idx, n_cand, sa.k.k[b], sa.mask + (size_t)b * m,
+            sa.active_idx + (size_t)b * sa.act_stride + sa.n_ret, sh, SelectNoHook(), SelectNoHook(), nullptr,
+            sa.selflag + b, POP_MAX_BATCH);
+        if (threadIdx.x == 0) sa.n_active[b] = sa.n_ret + sa.k.k[b];
+    }
+    // The flags went out as write-through stores; once they are acknowledged the selector signs off.  The last
+    // selector to do so reads every sequence's flags (coherent loads): union of the selections, counters rewound.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) s_flag = atomicAdd(&sa.counters[1], 1) == B - 1;
+    __syncthreads();
+    if (!s_flag) return;
+    static_assert(POP_MAX_BATCH == 8, "one 64-bit word of flags per candidate position");
+    const unsigned long long live = B >= 8 ? ~0ull : ((1ull << (8 * B)) - 1ull);
+    const unsigned long long *flags = reinterpret_cast<const unsigned long long *>(sa.selflag);
+    // this thread's candidate positions: flags and channel numbers requested together
+    constexpr int kPre = 4;
+    const int E = (n_cand + blockDim.x - 1) / blockDim.x;
+    const int lo = min(n_cand, (int)threadIdx.x * E), hi = min(n_cand, lo + E);
+    unsigned long long fpre[kPre];
+    int jpre[kPre];
 #pragma unroll
-            for (int b = 0; b < B; ++b) {
-                vec_t xv = xs[b * nvec + c];
-                ag[b] = V::dot(wg, xv, ag[b]);
-                au[b] = V::dot(wu, xv, au[b]);
-            }
-        }
+    for (int u = 0; u < kPre; ++u) {
+        fpre[u] = lo + u < hi ? coherent_load(&flags[lo + u]) & live : 0ull;
+        jpre[u] = lo + u < hi ? sa.cand_idx[lo + u] : 0;
+    }
+    int c[1] = {0}, tot[1];
 #pragma unroll
-        for (int b = 0; b < B; ++b) {
-            float gs = (float)wave_sum(ag[b]), us = (float)wave_sum(au[b]);
-            if (lane == 0) {
-                float hv = silu_mul(gs, us);
-                h[(size_t)b * m + j] = hv;
-                if (p < n_score) cscore[(size_t)b * cs_stride + p] = nrm[j] * fabsf(hv);
-            }
-        }
+    for (int u = 0; u < kPre; ++u) c[0] += fpre[u] != 0;
+    for (int i = lo + kPre; i < hi; ++i) c[0] += (coherent_load(&flags[i]) & live) != 0;
+    block_excl_scan<1>(c, tot, sh);
+    int pos = sa.n_ret + c[0];
+#pragma unroll
+    for (int u = 0; u < kPre; ++u)
+        if (fpre[u] != 0) sa.union_list[pos++] = jpre[u];
+    for (int i = lo + kPre; i < hi; ++i)
+        if ((coherent_load(&flags[i]) & live) != 0) sa.union_list[pos++] = sa.cand_idx[i];
+    if (threadIdx.x == 0) {
+        *sa.n_union = sa.n_ret + tot[0];
+        sa.counters[0] = 0;
+        sa.counters[1] = 0;
     }
 }
 
@@ -126,6 +259,53 @@ hipError_t launch_gateup(const void *w, int is_bf16, int d, int m, const void *x
                                         n_score, n_cu, s);
     return gateup_dispatch<VecF32>(w, d / 4, x, B, rows, n_rows, n_rows_dev, h, m, nrm, cscore, cs_stride, n_score,
                                    n_cu, s);
+}
+
+template <class V>
+static hipError_t gateup_select_dispatch(const void *w, int nvec, const void *x, int B, const int *rows, float *h, int m,
+                                         const float *nrm, float *cscore, int cs_stride, const GateupSelectArgs &sa,
+                                         int n_cu, bool *fused, hipStream_t s)
+{
+    typedef typename V::vec_t vec_t;
+    *fused = false;
+    const int n_rows = sa.n_cand + sa.n_ret, threads = 1024, wpb = threads / kWave;
+    const size_t lds = (size_t)B * nvec * sizeof(vec_t);
+    int blocks = (n_rows + wpb - 1) / wpb;
+    if (blocks > n_cu) blocks = n_cu;
+    if (B < 2 || blocks < 2 * B || sa.n_cand < 1) return hipSuccess;  // too small to set workgroups aside
+#define POP_GS(BB)                                                                                                  \
+    case BB: {                                                                                                      \
+        const void *fn = reinterpret_cast<const void *>(&gateup_select_kernel<V, BB>);                               \
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                \
+        if (e != hipSuccess) return e;                                                                               \
+        int per_cu = 0;                                                                                              \
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, gateup_select_kernel<V, BB>, threads, lds);        \
+        if (e != hipSuccess) return e;                                                                               \
+        if (per_cu < 1) return hipSuccess; /* not resident: the caller uses the two-launch form */                   \
+        hipLaunchKernelGGL((gateup_select_kernel<V, BB>), dim3(blocks), dim3(threads), lds, s, (const vec_t *)w,     \
+                           nvec, (const vec_t *)x, rows, h, m, nrm, cscore, cs_stride, sa);                          \
+        break;                                                                                                       \
+    }
+    switch (B) {
+        POP_GS(2) POP_GS(3) POP_GS(4) POP_GS(5) POP_GS(6) POP_GS(7) POP_GS(8)
+        default: return hipErrorInvalidValue;
+    }
+#undef POP_GS
+    *fused = true;
+    return hipGetLastError();
+}
+
+hipError_t launch_gateup_select(const void *w, int is_bf16, int d, int m, const void *x, int B, const int *rows,
+                                float *h, const float *nrm, float *cscore, int cs_stride, const int *cand_idx,
+                                int n_cand, int n_ret, BatchK k, int act_stride, unsigned char *mask, int *active_idx,
+                                int *n_active, unsigned char *selflag, int *union_list, int *n_union, int *counters,
+                                int *err_flag, int n_cu, bool *fused, hipStream_t s)
+{
+    GateupSelectArgs sa = {cand_idx, n_cand, n_ret, k, act_stride, mask, active_idx, n_active, selflag,
+                           union_list, n_union, counters, err_flag};
+    if (is_bf16)
+        return gateup_select_dispatch<VecBF16>(w, d / 8, x, B, rows, h, m, nrm, cscore, cs_stride, sa, n_cu, fused, s);
+    return gateup_select_dispatch<VecF32>(w, d / 4, x, B, rows, h, m, nrm, cscore, cs_stride, sa, n_cu, fused, s);
 }
 
 // ---------------------------------------------------------------- down projection

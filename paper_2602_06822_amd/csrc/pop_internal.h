@@ -43,6 +43,40 @@ struct BatchK {
     int k[POP_MAX_BATCH];
 };
 
+// Device-coherent (agent scope) accesses for values that workgroups of one kernel hand to each other: the
+// loads bypass stale cache lines, the stores write through, so no cache write-back or invalidation is needed.
+__device__ __forceinline__ int coherent_load(const int *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(int *p, int v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(float *p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void coherent_store(unsigned char *p, unsigned char v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long coherent_load(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Bounded wait until *addr >= target (a launch that waits is sized so that all its workgroups are resident).
+constexpr int kSpinLimit = 1 << 16;
+__device__ __forceinline__ bool spin_until(const int *addr, int target)
+{
+    for (int it = 0; it < kSpinLimit; ++it) {
+        if (coherent_load(addr) >= target) return true;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    return false;
+}
+
 // ---- setup (pop_setup.hip) ----
 // w[j][0][:] = w_gate[j][:], w[j][1][:] = w_up[j][:], w[j][2][o] = w_down[o][j];  nrm[j] = ||w_down[:,j]||.
 hipError_t launch_repack(const void *w_gate, const void *w_up, const void *w_down, int d, int m, int esize,
@@ -79,6 +113,17 @@ hipError_t launch_down(const void *w, int is_bf16, int d, int m, const int *list
                        const float *h, const unsigned char *mask, int mask_stride, int B, float *partial, int n_slabs,
                        void *y, int y_bf16, hipStream_t s);
 int down_num_slabs(int d, int is_bf16);
+// Batched decode (2 <= B <= POP_MAX_BATCH) with the per-sequence selection inside the gate/up kernel: the listed
+// rows are the n_cand candidates followed by the n_ret retained channels; all workgroups evaluate the candidates
+// first, then the last B workgroups wait (bounded) for everybody's candidate scores and select for one sequence
+// each while the others evaluate the retained channels.  Outputs as launch_gateup + launch_topk with a union
+// request.  counters: [0] arrivals, [1] selectors done (both zero between launches); err_flag is set if a wait
+// expired.  *fused = false (and nothing launched) when the shape does not allow it: use the two launches.
+hipError_t launch_gateup_select(const void *w, int is_bf16, int d, int m, const void *x, int B, const int *rows,
+                                float *h, const float *nrm, float *cscore, int cs_stride, const int *cand_idx,
+                                int n_cand, int n_ret, BatchK k, int act_stride, unsigned char *mask, int *active_idx,
+                                int *n_active, unsigned char *selflag, int *union_list, int *n_union, int *counters,
+                                int *err_flag, int n_cu, bool *fused, hipStream_t s);
 
 // ---- fused single-sequence decode step (pop_decode_fused.hip) ----
 struct FusedParams {

@@ -52,17 +52,19 @@ __device__ __forceinline__ void pf_row_channel(int r, int &ch, int &which)
     }
 }
 
-template <int BM>
-__global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__restrict__ w,
+template <int BM, int NW>
+__global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ x, int T, int d, int m,
                                                            int n_ttiles, int chunk, int n_items, int per_xcd,
                                                            float *__restrict__ s2_part)
 {
-    constexpr int MT = BM / 64;  // 32-token fragments per wave
+    constexpr int TW = NW / 2;          // waves along the tokens (2 along the B rows)
+    constexpr int MT = BM / (32 * TW);  // 32-token fragments per wave
+    constexpr int RP = NW * 8;          // rows one staging pass of the workgroup covers
     extern __shared__ __attribute__((aligned(16))) uint16_t pf_lds[];
     uint16_t *As = pf_lds;                       // [2][BM * kPfLd]
     uint16_t *Bs = pf_lds + 2 * BM * kPfLd;      // [2][kPfRows * kPfLd]
-    __shared__ float colsum[2][kPfChunk];
+    __shared__ float colsum[TW][kPfChunk];
 
     const int logical = xcd_logical_block(blockIdx.x, per_xcd);
     if (logical >= n_items) return;
@@ -71,22 +73,23 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__res
     const int cn = min(chunk, m - c0);  // channels in this chunk
 
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    const int wm = wave / 2, wn = wave % 2;  // wave tile: tokens wm*BM/2.., B rows wn*96..
+    const int wm = wave / 2, wn = wave % 2;  // wave tile: tokens wm*BM/TW.., B rows wn*96..
 
-    // global -> LDS staging: 8 vectors of 16 bytes per 64-element row; 256 threads cover 32 rows per pass
+    // global -> LDS staging: 8 vectors of 16 bytes per 64-element row; the workgroup covers RP rows per pass
     const int ld_row = tid / 8, ld_kv = tid % 8;
-    constexpr int PA = BM / 32, PB = kPfRows / 32;
+    constexpr int PA = BM / RP, PB = kPfRows / RP;
+    static_assert(BM % RP == 0 && kPfRows % RP == 0, "whole staging passes");
     uint4 ra[PA], rb[PB];
     const uint16_t *pa[PA], *pb[PB];  // row starts (null: a row of zeros)
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
-        const int t = t0 + ld_row + p * 32;
+        const int t = t0 + ld_row + p * RP;
         pa[p] = t < T ? x + (size_t)t * d : nullptr;
     }
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
         int ch, which;
-        pf_row_channel(ld_row + p * 32, ch, which);
+        pf_row_channel(ld_row + p * RP, ch, which);
         pb[p] = ch < cn ? w + ((size_t)(c0 + ch) * 3 + which) * d : nullptr;
     }
     auto load_global = [&](int k0) {
@@ -102,10 +105,10 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__res
     auto store_lds = [&](int buf) {
 #pragma unroll
         for (int p = 0; p < PA; ++p)
-            *reinterpret_cast<uint4 *>(&As[(buf * BM + ld_row + p * 32) * kPfLd + ld_kv * 8]) = ra[p];
+            *reinterpret_cast<uint4 *>(&As[(buf * BM + ld_row + p * RP) * kPfLd + ld_kv * 8]) = ra[p];
 #pragma unroll
         for (int p = 0; p < PB; ++p)
-            *reinterpret_cast<uint4 *>(&Bs[(buf * kPfRows + ld_row + p * 32) * kPfLd + ld_kv * 8]) = rb[p];
+            *reinterpret_cast<uint4 *>(&Bs[(buf * kPfRows + ld_row + p * RP) * kPfLd + ld_kv * 8]) = rb[p];
     };
 
     f32x16_t acc[MT][3];  // [token fragment][0 = gate 0..31, 1 = up 0..31, 2 = gate 32..47 | up 32..47]
@@ -117,7 +120,7 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__res
             for (int v = 0; v < 16; ++v) acc[a][f][v] = 0.f;
 
     const int n_k = (d + kPfBK - 1) / kPfBK;
-    const int arow = wm * (BM / 2) + (lane % 32), brow = wn * 96 + (lane % 32), koff = (lane / 32) * 8;
+    const int arow = wm * (BM / TW) + (lane % 32), brow = wn * 96 + (lane % 32), koff = (lane / 32) * 8;
     auto multiply = [&](int buf) {
         const uint16_t *Ab = As + (buf * BM + arow) * kPfLd + koff;
         const uint16_t *Bb = Bs + (buf * kPfRows + brow) * kPfLd + koff;
@@ -165,10 +168,14 @@ __global__ __launch_bounds__(256) void prefill_bf16_kernel(const uint16_t *__res
     ss01 += __shfl_xor(ss01, 32, kWave);
     ss2 += __shfl_xor(ss2, 32, kWave);
     if (lane < 32) colsum[wm][wn * 48 + lane] = ss01;
-    __syncthreads();  // (columns 32..47 of a wave are written by other lanes: separate the two stores' readers)
     if (lane < 16) colsum[wm][wn * 48 + 32 + lane] = ss2;
     __syncthreads();
-    if (tid < cn) s2_part[(size_t)ttile * m + c0 + tid] = colsum[0][tid] + colsum[1][tid];
+    if (tid < cn) {
+        float tot = 0.f;
+#pragma unroll
+        for (int q = 0; q < TW; ++q) tot += colsum[q][tid];
+        s2_part[(size_t)ttile * m + c0 + tid] = tot;
+    }
 }
 
 // float32: 64 tokens x 32 channels per workgroup; thread (tx = channel, ty = group of 8 tokens).
@@ -255,17 +262,19 @@ hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const
         const int total = n_tt * n_ct, per_xcd = (total + 7) / 8;
         const size_t lds = (size_t)2 * (bm + kPfRows) * kPfLd * sizeof(uint16_t);
         hipError_t e;
+        // 256-token tiles run with 8 waves (two per SIMD: one wave's waits for staging loads, LDS writes and the
+        // k-step barrier are covered by the other's products), 128-token tiles with 4
         if (bm == 256) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<256>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<256, 8>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(prefill_bf16_kernel<256>, dim3(per_xcd * 8), dim3(256), lds, s, (const uint16_t *)w,
+            hipLaunchKernelGGL((prefill_bf16_kernel<256, 8>), dim3(per_xcd * 8), dim3(512), lds, s, (const uint16_t *)w,
                                (const uint16_t *)x, T, d, m, n_tt, chunk, total, per_xcd, s2_part);
         } else {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<128>),
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<128, 4>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
-            hipLaunchKernelGGL(prefill_bf16_kernel<128>, dim3(per_xcd * 8), dim3(256), lds, s, (const uint16_t *)w,
+            hipLaunchKernelGGL((prefill_bf16_kernel<128, 4>), dim3(per_xcd * 8), dim3(256), lds, s, (const uint16_t *)w,
                                (const uint16_t *)x, T, d, m, n_tt, chunk, total, per_xcd, s2_part);
         }
     } else {

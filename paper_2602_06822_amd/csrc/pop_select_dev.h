@@ -178,8 +178,10 @@ struct SelectNoHook {
 // then after_selected() by every thread (it may contain barriers): callers that only need the positions get
 // them without waiting for the index loads.  All threads of the block must call.
 // kCoherentScores: the scores were just written by other workgroups of the same kernel with write-through stores;
-// read them with device-coherent loads (no cache invalidation needed).
-template <bool kCoherentScores = false, class OnSelected = SelectNoHook, class AfterSelected = SelectNoHook>
+// read them with device-coherent loads (no cache invalidation needed).  kCoherentFlags: selpos is written through,
+// for another workgroup of the same kernel to read.
+template <bool kCoherentScores = false, class OnSelected = SelectNoHook, class AfterSelected = SelectNoHook,
+          bool kCoherentFlags = false>
 __device__ __forceinline__ void block_select_candidates(const float *__restrict__ cs, const int *__restrict__ cand_idx,
                                                         int n_cand, int k, unsigned char *__restrict__ mk,
                                                         int *__restrict__ act_sel, SelShared &sh,
@@ -258,7 +260,12 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
             gt += (kv > kth);
             const int j = jpre[u];
             if (mk) mk[j] = sel ? 1 : 0;
-            if (selpos) selpos[(size_t)i * selpos_stride] = sel ? 1 : 0;  // the same decision by candidate position
+            if (selpos) {  // the same decision by candidate position
+                if (kCoherentFlags)
+                    coherent_store(&selpos[(size_t)i * selpos_stride], (unsigned char)(sel ? 1 : 0));
+                else
+                    selpos[(size_t)i * selpos_stride] = sel ? 1 : 0;
+            }
             if (sel && act_sel) act_sel[pos] = j;
         }
     }
@@ -270,7 +277,12 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
         gt += (kv > kth);
         int j = cand_idx[i];
         if (mk) mk[j] = sel ? 1 : 0;
-        if (selpos) selpos[(size_t)i * selpos_stride] = sel ? 1 : 0;
+        if (selpos) {
+            if (kCoherentFlags)
+                coherent_store(&selpos[(size_t)i * selpos_stride], (unsigned char)(sel ? 1 : 0));
+            else
+                selpos[(size_t)i * selpos_stride] = sel ? 1 : 0;
+        }
         if (sel && act_sel) act_sel[pos] = j;
     }
 }
