@@ -133,9 +133,18 @@ __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, Sel
         if (blockDim.x < 256)
             for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) next[i] = 0;
         const int n_round = (n + blockDim.x - 1) / blockDim.x * blockDim.x;  // whole waves take part in the ballots
-        for (int i = threadIdx.x; i < n_round; i += blockDim.x) {
-            const uint32_t k = i < n ? key(i) : 0u;
-            wave_hist_add(hist, (k >> shift) & 255u, i < n && (k & known) == prefix);
+        if (pass == 0) {
+            // leading digit: scores of one layer crowd into a few values of it
+            for (int i = threadIdx.x; i < n_round; i += blockDim.x) {
+                const uint32_t k = i < n ? key(i) : 0u;
+                wave_hist_add(hist, (k >> shift) & 255u, i < n && (k & known) == prefix);
+            }
+        } else {
+            // later digits are spread out (and few keys are left): one atomic each
+            for (int i = threadIdx.x; i < n; i += blockDim.x) {
+                const uint32_t k = key(i);
+                if ((k & known) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+            }
         }
         __syncthreads();
         // lane l owns the four digits 255-4l .. 252-4l, scanned from the largest digit down
