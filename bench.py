@@ -212,6 +212,31 @@ def run(args):
             pop.pop_layer_set_single_launch(L.handle, True)
         single = timed(r_main, max(1, args.steps // 2), 1, single=True)["decode_us_per_token"]
 
+    # the prefilling stage with its output (pop_prefill_forward: contraction that keeps H, partition, prefill mask,
+    # gathered columns, down-projection GEMM over the active channels), rotated over the layers
+    forward = None
+    if not args.quick:
+        yp = torch.empty((PROMPT, d), dtype=torch.int16, device="cuda")
+        fcalls = [(L.handle, C.c_void_p(L.x_prompt.data_ptr()), PROMPT, n_ret, n_cand, k, C.c_void_p(yp.data_ptr()),
+                   pop.POP_BF16, None, None, None, None, None, sp) for L in layers]
+        for a in fcalls:
+            check(lib.pop_prefill_forward(*a))
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 4
+        e0.record(stream)
+        for _ in range(reps):
+            for a in fcalls:
+                check(lib.pop_prefill_forward(*a))
+        e1.record(stream)
+        torch.cuda.synchronize()
+        f_us = 1e3 * e0.elapsed_time(e1) / (reps * len(layers))
+        f_flop = 4.0 * PROMPT * m * d + 2.0 * PROMPT * (n_ret + k) * d
+        forward = dict(us_per_layer=round(f_us, 2), flop=f_flop, TFLOPs=round(f_flop / f_us / 1e6, 1),
+                       frac_of_bf16_mfma_peak=round(f_flop / f_us / 1e6 / 2500.0, 4),
+                       note="whole call: both GEMMs, partition, mask, gather and the small kernels between them")
+        del yp
+
     fused_us = main.get("probe_mask_us")
     roofline = None
     if fused_us:
@@ -266,6 +291,7 @@ def run(args):
                    "n_ret": n_ret, "n_cand": n_cand, "k": k},
         "tokens_per_s_per_layer": round(1e6 / us, 1),
         "prefill_us_per_layer": round(main["prefill_us_per_layer"], 2),
+        "prefill_forward": forward,
         "active_GBps": round(bm["active"] / us / 1e3, 1),
         "algorithmic_GBps": round(bm["algorithmic"] / us / 1e3, 1),
         "frac_of_peak_active_bytes": round(bm["active"] / us / 1e3 / HBM_PEAK_GBS, 4),

@@ -83,6 +83,21 @@ int pop_layer_destroy(pop_layer_t *layer);
 int pop_prefill_partition(pop_layer_t *layer, const void *x, int T, int n_ret, int n_cand,
                           float *scores, unsigned char *region, int *ret_idx, int *cand_idx, void *stream);
 
+/* Prefilling stage with its output (Sec. 3.3 "Prefilling Stage", Sec. 3.4: the prompt's forward pass runs under the
+ * pruning structure the prompt itself determines).  Everything pop_prefill_partition does, with the same outputs
+ * and errors, and then the pruned FFN of the T prompt tokens, y: dev [T][d] of dtype ydtype, under the prefill mask:
+ * the retained channels plus the best k0 candidates by prefill score (same order as above), i.e. the n_ret + k0
+ * channels of highest prefill importance.  mask: dev [m], 1 = active (may be NULL).
+ * On bf16 layers with T >= 32 the hidden activations of the contraction are kept (rounded to bf16), the active
+ * columns are gathered, and the down projection runs as one matrix-core GEMM; otherwise the call is
+ * pop_prefill_partition followed by pop_pruned_ffn(mask).  Scratch for H (2 x T x m x 2 bytes, plus up to
+ * 8 x 256 x d x 4 bytes of partial outputs) is allocated at the first call and when T grows, which synchronises
+ * the device; it stays with the layer.
+ * Errors: as pop_prefill_partition; k0 < 0 or k0 > n_cand -> POP_ESHAPE; y == NULL or bad ydtype -> POP_EINVAL. */
+int pop_prefill_forward(pop_layer_t *layer, const void *x, int T, int n_ret, int n_cand, int k0,
+                        void *y, pop_dtype_t ydtype, float *scores, unsigned char *region, int *ret_idx,
+                        int *cand_idx, unsigned char *mask, void *stream);
+
 /* Decode step, mask part (Sec. 3.3 "Decoding Stage", Sec. 3.4 two-step decoding).  x_t: dev [B][d].
  * Pass 1 evaluates h_j = silu(g_j) * u_j for every retained and candidate channel, for each of the B
  * sequences; candidates are re-scored, I_j(t) = n_j * |h_j|, and for sequence b the best k[b] (host array [B],
@@ -101,7 +116,10 @@ int pop_decode_mask(pop_layer_t *layer, const void *x_t, int B, const int *k,
  *       (T must equal its B; x is not read again):  y_b = sum over active j of h_bj * W_down[:, j].
  *   mask != NULL: stand-alone pruned FFN of x (dev [T][d]) under the given masks, dev [mask_rows][m],
  *       mask_rows == 1 (shared by all tokens) or == T (one per token); any T >= 1.  Does not need a
- *       partition.  An all-ones mask gives the dense FFN.
+ *       partition.  An all-ones mask gives the dense FFN.  bf16 layers with T >= 32 run this on the matrix
+ *       cores: gate/up over the channels active in any row, H rounded to bf16, then one GEMM over those channels
+ *       (scratch is allocated at the first such call and when T grows, which synchronises the device); smaller
+ *       T and float32 layers take the decode kernels, eight tokens at a time, and keep H in float32.
  * Errors: mask == NULL without a preceding decode step -> POP_ESTATE; T mismatch, bad mask_rows -> POP_ESHAPE. */
 int pop_pruned_ffn(pop_layer_t *layer, const void *x, int T, const unsigned char *mask, int mask_rows,
                    void *y, pop_dtype_t ydtype, void *stream);

@@ -38,6 +38,7 @@ _SIGS = {
     "pop_layer_create": (_i, [C.POINTER(_vp), _i, _i, _i, _vp, _vp, _vp, _i, _i, _vp]),
     "pop_layer_destroy": (_i, [_vp]),
     "pop_prefill_partition": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
+    "pop_prefill_forward": (_i, [_vp, _vp, _i, _i, _i, _i, _vp, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pop_decode_mask": (_i, [_vp, _vp, _i, _ip, _vp, _vp, _vp, _vp, _vp]),
     "pop_decode_step": (_i, [_vp, _vp, _i, _ip, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
     "pop_pruned_ffn": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _vp]),
@@ -131,6 +132,12 @@ def pop_prefill_partition(layer, x, T, n_ret, n_cand, scores=None, region=None, 
                           stream=None):
     _check(_lib.pop_prefill_partition(layer, _ptr(x), T, n_ret, n_cand, _ptr(scores), _ptr(region),
                                       _ptr(ret_idx), _ptr(cand_idx), _stream(stream)), "pop_prefill_partition")
+
+
+def pop_prefill_forward(layer, x, T, n_ret, n_cand, k0, y, ydtype, scores=None, region=None, ret_idx=None,
+                        cand_idx=None, mask=None, stream=None):
+    _check(_lib.pop_prefill_forward(layer, _ptr(x), T, n_ret, n_cand, k0, _ptr(y), ydtype, _ptr(scores), _ptr(region),
+                                    _ptr(ret_idx), _ptr(cand_idx), _ptr(mask), _stream(stream)), "pop_prefill_forward")
 
 
 def _k_array(k, B):

@@ -71,6 +71,14 @@ struct pop_layer {
     int *n_ulist = nullptr;            // [1]
     float *partial = nullptr;          // max([n_slabs][max_batch][d], [fused workgroups][d])
     int n_slabs = 0;
+    // whole-prompt pruned FFN on the matrix cores (bf16 layers), allocated at its first use
+    uint16_t *ffn_hc = nullptr;        // [tokens][ldh] bf16: H of the active channels, compact
+    size_t ffn_hc_cap = 0;             // elements
+    uint16_t *ffn_hall = nullptr;      // [tokens][ldh] bf16: H of all channels, kept by pop_prefill_forward
+    size_t ffn_hall_cap = 0;           // elements
+    float *ffn_part = nullptr;         // [splits][tokens][d]: partial outputs of the split contraction
+    size_t ffn_part_cap = 0;           // elements
+    unsigned char *ffn_any = nullptr;  // [m]: channels active in any row of a per-token mask
 };
 
 namespace {
@@ -104,6 +112,82 @@ int copy_step_outputs(pop_layer *L, int B, float *cand_scores, unsigned char *ma
         POP_HIP(hipMemcpy2DAsync(active_idx, (size_t)(n_ret + n_cand) * 4, L->active_idx, (size_t)m * 4,
                                  (size_t)(n_ret + n_cand) * 4, B, hipMemcpyDeviceToDevice, s));
     if (n_active) POP_HIP(hipMemcpyAsync(n_active, L->n_active, (size_t)B * 4, hipMemcpyDeviceToDevice, s));
+    return POP_OK;
+}
+
+// From this many tokens on a bf16 layer's stand-alone pruned FFN runs on the matrix cores (below it, the decode
+// kernels take the tokens eight at a time).
+constexpr int kFfnMfmaMinTokens = 32;
+
+// Whole-prompt pruned FFN (Sec. 3.4: forward pass under the pruning structure): active list from the mask(s),
+// gate/up over the listed channels with H written in compact bf16 form, then the K-gathered down-projection GEMM.
+// Scratch grows on demand; growing synchronises the device (hipFree).
+int grow(void **p, size_t *cap, size_t need, size_t esize)
+{
+    if (need <= *cap) return POP_OK;
+    if (*p) POP_HIP(hipFree(*p));
+    *p = nullptr, *cap = 0;
+    if (hipMalloc(p, need * esize) != hipSuccess) return POP_ENOMEM;
+    *cap = need;
+    return POP_OK;
+}
+
+int ffn_scratch(pop_layer *L, int T, bool keep_all, int *ldh, int *n_split)
+{
+    *ldh = (L->m + 7) / 8 * 8;
+    *n_split = down_gemm_splits(T, L->d, L->n_cu);
+    int rc = grow((void **)&L->ffn_hc, &L->ffn_hc_cap, (size_t)T * *ldh, sizeof(uint16_t));
+    if (rc == POP_OK && *n_split > 1)
+        rc = grow((void **)&L->ffn_part, &L->ffn_part_cap, (size_t)*n_split * T * L->d, sizeof(float));
+    if (rc == POP_OK && keep_all) rc = grow((void **)&L->ffn_hall, &L->ffn_hall_cap, (size_t)T * *ldh, sizeof(uint16_t));
+    if (rc == POP_OK && !L->ffn_any && hipMalloc((void **)&L->ffn_any, ((size_t)L->m + 3) / 4 * 4) != hipSuccess)
+        rc = POP_ENOMEM;
+    return rc;
+}
+
+int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mask, int mask_rows, void *y, int y_bf16,
+                    hipStream_t s)
+{
+    const int m = L->m, d = L->d;
+    int ldh, n_split;
+    { int rc = ffn_scratch(L, T, false, &ldh, &n_split); if (rc != POP_OK) return rc; }
+    const unsigned char *tmask = nullptr;
+    if (mask_rows == 1) {
+        POP_HIP(launch_mask_to_list(mask, 1, m, L->ulist, L->n_ulist, s));
+    } else {
+        POP_HIP(launch_mask_any(mask, T, m, L->ffn_any, s));
+        POP_HIP(launch_mask_to_list(L->ffn_any, 1, m, L->ulist, L->n_ulist, s));
+        tmask = mask;
+    }
+    POP_HIP(launch_gateup_list_bf16(L->w, d, m, x, T, L->ulist, L->n_ulist, tmask, L->ffn_hc, ldh, L->n_cu, s));
+    POP_HIP(launch_down_gemm_bf16(L->w, d, L->ulist, L->n_ulist, L->ffn_hc, ldh, T, n_split, L->ffn_part, y, y_bf16, s));
+    return POP_OK;
+}
+
+// Scores, partition and partition-constant step state from s2_part (the second half of the prefilling stage).
+int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, unsigned char *region, int *ret_idx,
+                     int *cand_idx, hipStream_t s)
+{
+    const int m = L->m;
+    POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16), m, L->nrm, L->scores, s));
+    POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s));
+    if (n_cand) POP_HIP(hipMemcpyAsync(L->rc_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
+    if (n_ret) POP_HIP(hipMemcpyAsync(L->rc_idx + n_cand, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    // partition-constant step state: retained bytes of every mask row, retained prefix of every active list
+    POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s));
+    if (n_ret) POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    L->ulist_prefix_ok = true;
+    L->n_ret = n_ret;
+    L->n_cand = n_cand;
+    { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
+    POP_HIP(launch_fill_int(L->sync, 16, 0, s));
+    POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
+    if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
+    if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
+    if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    if (cand_idx && n_cand)
+        POP_HIP(hipMemcpyAsync(cand_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
+    L->has_partition = true;
     return POP_OK;
 }
 
@@ -192,7 +276,7 @@ int pop_layer_destroy(pop_layer_t *L)
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
                     L->h,      L->cscore, L->mask, L->selflag, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
-                    L->sync,   L->deferred, L->selbits};
+                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -295,28 +379,51 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
     L->has_partition = false;
     L->has_step = false;
     POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s));
-    POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16), m, L->nrm, L->scores, s));
-    POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s));
-    if (n_cand) POP_HIP(hipMemcpyAsync(L->rc_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
-    if (n_ret) POP_HIP(hipMemcpyAsync(L->rc_idx + n_cand, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
-    // partition-constant step state: retained bytes of every mask row, retained prefix of every active list
-    POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s));
-    if (n_ret) POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
-    L->ulist_prefix_ok = true;
-    L->n_ret = n_ret;
-    L->n_cand = n_cand;
-    { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
-    POP_HIP(launch_fill_int(L->sync, 16, 0, s));
-    POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
-    if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
-    if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
-    if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
-    if (cand_idx && n_cand)
-        POP_HIP(hipMemcpyAsync(cand_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
-    L->n_ret = n_ret;
-    L->n_cand = n_cand;
-    L->has_partition = true;
-    return POP_OK;
+    return finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s);
+}
+
+int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_cand, int k0, void *y, pop_dtype_t ydtype,
+                        float *scores, unsigned char *region, int *ret_idx, int *cand_idx, unsigned char *mask,
+                        void *stream)
+{
+    if (!L || !x || !y) return POP_EINVAL;
+    if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
+    if (T < 1 || T > L->max_tokens) return POP_ESHAPE;
+    if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
+    if (k0 < 0 || k0 > n_cand) return POP_ESHAPE;
+    hipStream_t s = as_stream(stream);
+    const int m = L->m, d = L->d;
+    const bool keep = L->is_bf16 && T >= kFfnMfmaMinTokens;  // H is kept and the output runs on the matrix cores
+    L->has_partition = false;
+    L->has_step = false;
+    int ldh = 0, n_split = 1;
+    if (keep) {
+        int rc = ffn_scratch(L, T, true, &ldh, &n_split);
+        if (rc != POP_OK) return rc;
+        POP_HIP(launch_prefill_gateup_keep_bf16(L->w, d, m, x, T, L->s2_part, L->ffn_hall, ldh, L->n_cu, s));
+    } else {
+        if (!L->ffn_any && hipMalloc((void **)&L->ffn_any, ((size_t)m + 3) / 4 * 4) != hipSuccess) return POP_ENOMEM;
+        POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, d, m, x, T, L->s2_part, L->n_cu, s));
+    }
+    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s); if (rc != POP_OK) return rc; }
+    // prefill mask: retained channels plus the best k0 candidates by prefill score; the active list (retained, then
+    // selected) lands in row 0 of the step's list, which the next decode step rewrites anyway
+    unsigned char *pm = L->ffn_any;
+    BatchK kk = {};
+    kk.k[0] = k0;
+    POP_HIP(launch_gather_f32(L->scores, L->cand_idx, n_cand, L->cscore, s));
+    POP_HIP(launch_step_state_init(L->region, m, nullptr, 0, 1, 0, pm, nullptr, s));
+    POP_HIP(launch_topk(L->cscore, n_cand, L->cand_idx, n_cand, n_ret, m, 1, kk, m, pm, L->active_idx, L->n_active,
+                        nullptr, nullptr, nullptr, nullptr, nullptr, s));
+    if (mask) POP_HIP(hipMemcpyAsync(mask, pm, (size_t)m, hipMemcpyDeviceToDevice, s));
+    if (keep) {
+        POP_HIP(launch_compact_hidden(L->ffn_hall, ldh, T, L->active_idx, L->n_active, n_ret + k0, L->ffn_hc, ldh, s));
+        POP_HIP(launch_down_gemm_bf16(L->w, d, L->active_idx, L->n_active, L->ffn_hc, ldh, T, n_split, L->ffn_part, y,
+                                      ydtype == POP_BF16, s));
+        return POP_OK;
+    }
+    const int rc = pop_pruned_ffn(L, x, T, pm, 1, y, ydtype, stream);
+    return rc;
 }
 
 int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float *cand_scores, unsigned char *mask,
@@ -421,6 +528,7 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
     if (mask_rows != 1 && mask_rows != T) return POP_ESHAPE;
     L->has_step = false;  // the step scratch is reused below
     L->ulist_prefix_ok = false;
+    if (L->is_bf16 && T >= kFfnMfmaMinTokens) return pruned_ffn_mfma(L, x, T, mask, mask_rows, y, y_bf16, s);
     if (mask_rows == 1) POP_HIP(launch_mask_to_list(mask, 1, m, L->ulist, L->n_ulist, s));
     for (int t0 = 0; t0 < T; t0 += L->max_batch) {
         const int Bc = (T - t0 < L->max_batch) ? T - t0 : L->max_batch;

@@ -1,0 +1,273 @@
+// Down projection of a whole prompt under the pruning structure (Sec. 3.4: the forward pass over the active channels):
+//     Y[t][n] = sum over list positions c < a of  Hc[t][c] * W_down[n][list[c]],
+// a K-gathered bf16 MFMA GEMM: the contraction runs over the a active channels, whose down columns are the rows
+// w[list[c]][2][:] of the channel-major weights, contiguous along n.
+//
+// The matrix cores want both operands with the contraction index fastest inside a lane (8 consecutive k per lane for
+// the 32x32x16 tile).  Hc is stored that way; the weight rows are not (n is contiguous, k jumps from row to row).
+// They are staged into LDS as they come, [k][n], and fetched with the transposing LDS read of this chip: a block of
+// 16 lanes points at a 4 (k) x 16 (n) patch, lane i at the 4 values of row i / 4 starting at column 4 (i % 4), and
+// receives it transposed, lane j the 4 k-values of column j.  Two such reads make the 8 values of one B fragment.
+// The LDS row stride (160 elements) puts the 4 rows of a patch, and the two patches a read instruction's half-wave
+// touches, into disjoint banks.
+//
+// Workgroup: 256 tokens x 128 columns, 8 waves (4 along the tokens x 2 along n), wave tile 64 x 64 = 2 x 2 MFMA
+// tiles, k-steps of 64 channels, LDS double buffer filled through registers; channel numbers are fetched two steps
+// ahead so the weight loads never wait for them.  Short prompts do not give enough tiles to fill the chip, so the
+// contraction is split into n_split ranges whose float32 partial results are summed, in split order, by a second
+// kernel (deterministic).
+#include "pop_internal.h"
+
+namespace pop {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+constexpr int kDgBM = 256;            // tokens per workgroup tile
+constexpr int kDgBN = 128;            // output columns per workgroup tile
+constexpr int kDgBK = 64;             // channels per k-step
+constexpr int kDgLdA = kDgBK + 8;     // LDS row stride of the Hc tile in elements (144 B: conflict-free 16-byte reads)
+constexpr int kDgLdB = kDgBN + 32;    // LDS row stride of the weight tile in elements (320 B)
+constexpr int kDgMaxSplit = 8;
+
+__device__ __forceinline__ int dg_xcd_logical_block(int bid, int per_xcd) { return (bid % 8) * per_xcd + bid / 8; }
+
+__global__ __launch_bounds__(512) void down_gemm_bf16_kernel(const uint16_t *__restrict__ w, int d,
+                                                             const int *__restrict__ list,
+                                                             const int *__restrict__ n_list,
+                                                             const uint16_t *__restrict__ hc, int ldh, int T, int n_tt,
+                                                             int n_nt, int n_split, int per_xcd,
+                                                             float *__restrict__ part, void *__restrict__ y, int y_bf16)
+{
+    extern __shared__ __attribute__((aligned(16))) uint16_t dg_lds[];
+    uint16_t *As = dg_lds;                          // [2][kDgBM * kDgLdA]
+    uint16_t *Bs = dg_lds + 2 * kDgBM * kDgLdA;     // [2][kDgBK * kDgLdB]
+
+    const int logical = dg_xcd_logical_block(blockIdx.x, per_xcd);
+    if (logical >= n_tt * n_nt * n_split) return;
+    // token tiles of one (split, column tile) are neighbours: they share its weight rows in the XCD's L2
+    const int ttile = logical % n_tt, ntile = (logical / n_tt) % n_nt, split = logical / (n_tt * n_nt);
+    const int t0 = ttile * kDgBM, n0 = ntile * kDgBN;
+
+    const int a = *n_list;
+    const int steps_all = (a + kDgBK - 1) / kDgBK, steps_per = (steps_all + n_split - 1) / n_split;
+    const int ks0 = min(split * steps_per, steps_all), ks1 = min(ks0 + steps_per, steps_all);
+
+    const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int wm = wave / 2, wn = wave % 2;
+
+    // staging.  Hc tile: 8 vectors of 16 bytes per row, 64 rows per pass, 4 passes; weight tile: 16 vectors per row,
+    // 32 rows per pass, 2 passes
+    const int a_row = tid / 8, a_kv = tid % 8;
+    const int b_row = tid / 16, b_nv = tid % 16;
+    const uint16_t *pa[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int t = t0 + a_row + p * 64;
+        pa[p] = t < T ? hc + (size_t)t * ldh : nullptr;
+    }
+    const bool n_ok = n0 + b_nv * 8 < d;
+    uint4 ra[4], rb[2];
+    int ch_next[2];  // channels of this thread's two weight rows in the step after the one being loaded
+    auto load_channels = [&](int ks) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int c = ks * kDgBK + b_row + p * 32;
+            ch_next[p] = (ks < ks1 && c < a) ? list[c] : -1;
+        }
+    };
+    auto load_global = [&](int ks) {
+        const int k = ks * kDgBK + a_kv * 8;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            uint4 v = (k < a && pa[p]) ? *reinterpret_cast<const uint4 *>(pa[p] + k) : make_uint4(0, 0, 0, 0);
+            if (k + 8 > a && k < a) {
+                // columns at and beyond a hold no data: clear them (16-bit elements, two per word)
+                const int keep = a - k;  // 1..7
+                uint32_t e[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (2 * q >= keep) e[q] = 0;
+                    else if (2 * q + 1 >= keep) e[q] &= 0xffffu;
+                }
+                v = make_uint4(e[0], e[1], e[2], e[3]);
+            }
+            ra[p] = v;
+        }
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+            rb[p] = (ch_next[p] >= 0 && n_ok)
+                        ? *reinterpret_cast<const uint4 *>(w + ((size_t)ch_next[p] * 3 + 2) * d + n0 + b_nv * 8)
+                        : make_uint4(0, 0, 0, 0);
+    };
+    auto store_lds = [&](int buf) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            *reinterpret_cast<uint4 *>(&As[(buf * kDgBM + a_row + p * 64) * kDgLdA + a_kv * 8]) = ra[p];
+#pragma unroll
+        for (int p = 0; p < 2; ++p)
+            *reinterpret_cast<uint4 *>(&Bs[(buf * kDgBK + b_row + p * 32) * kDgLdB + b_nv * 8]) = rb[p];
+    };
+
+    f32x16_t acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][f][v] = 0.f;
+
+    // A fragment: row lane % 32 of the token fragment, k = kk + 8 (lane / 32) .. + 7.
+    // B fragment, read r (k = kk + 8 (lane / 32) + 4 r .. + 3): this lane points at row (lane % 16) / 4 of that
+    // group, columns 16 ((lane / 16) % 2) + 4 (lane % 4) .. + 3 of the fragment, and receives column lane % 32.
+    const int a_off = (wm * 64 + lane % 32) * kDgLdA + (lane / 32) * 8;
+    const int b_off = ((lane / 32) * 8 + (lane % 16) / 4) * kDgLdB + wn * 64 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
+    auto multiply = [&](int buf) {
+        const uint16_t *Ab = As + buf * kDgBM * kDgLdA + a_off;
+        const uint16_t *Bb = Bs + buf * kDgBK * kDgLdB + b_off;
+#pragma unroll
+        for (int kk = 0; kk < kDgBK; kk += 16) {
+            bf16x8_t af[2], bf[2];
+#pragma unroll
+            for (int f = 0; f < 2; ++f) {
+                const uint16_t *q = Bb + kk * kDgLdB + f * 32;
+                const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (s16x4_t __attribute__((address_space(3))) *)(q));
+                const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (s16x4_t __attribute__((address_space(3))) *)(q + 4 * kDgLdB));
+                const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                bf[f] = __builtin_bit_cast(bf16x8_t, both);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) af[i] = *reinterpret_cast<const bf16x8_t *>(Ab + i * 32 * kDgLdA + kk);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int f = 0; f < 2; ++f)
+                    acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[f], acc[i][f], 0, 0, 0);
+        }
+    };
+
+    if (ks0 < ks1) {
+        load_channels(ks0);
+        load_global(ks0);
+        load_channels(ks0 + 1);
+        store_lds(0);
+        __syncthreads();
+        for (int ks = ks0; ks < ks1; ++ks) {
+            const int buf = (ks - ks0) & 1;
+            if (ks + 1 < ks1) {
+                load_global(ks + 1);
+                load_channels(ks + 2);
+            }
+            multiply(buf);
+            if (ks + 1 < ks1) store_lds(buf ^ 1);
+            __syncthreads();
+        }
+    }
+
+    // register v of a fragment is token row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32
+    float *yp = part ? part + (size_t)split * T * d : nullptr;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            const int n = n0 + wn * 64 + f * 32 + lane % 32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int t = t0 + wm * 64 + i * 32 + (v / 4) * 8 + (lane / 32) * 4 + v % 4;
+                if (t < T && n < d) {
+                    const size_t o = (size_t)t * d + n;
+                    if (yp) yp[o] = acc[i][f][v];
+                    else if (y_bf16) ((uint16_t *)y)[o] = f32_to_bf16(acc[i][f][v]);
+                    else ((float *)y)[o] = acc[i][f][v];
+                }
+            }
+        }
+}
+
+// y = sum over the splits, in split order, of part[split]; n4 = T * d / 4 vectors.
+__global__ __launch_bounds__(256) void down_gemm_reduce_kernel(const float4 *__restrict__ part, int n_split, size_t n4,
+                                                               void *__restrict__ y, int y_bf16)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n4) return;
+    float4 s = part[i];
+    for (int q = 1; q < n_split; ++q) {
+        const float4 v = part[(size_t)q * n4 + i];
+        s.x += v.x, s.y += v.y, s.z += v.z, s.w += v.w;
+    }
+    if (y_bf16) {
+        uint2 o;
+        o.x = (uint32_t)f32_to_bf16(s.x) | ((uint32_t)f32_to_bf16(s.y) << 16);
+        o.y = (uint32_t)f32_to_bf16(s.z) | ((uint32_t)f32_to_bf16(s.w) << 16);
+        ((uint2 *)y)[i] = o;
+    } else {
+        ((float4 *)y)[i] = s;
+    }
+}
+
+// hc[t][c] = h_all[t][list[c]] for c < *n_list: the columns of the active channels moved next to each other, so that
+// the contraction index of the GEMM above is contiguous.  A thread owns two adjacent positions (one 32-bit store)
+// and kCompactRows tokens, whose rows it walks with the two channel numbers in registers.
+constexpr int kCompactRows = 8;
+__global__ __launch_bounds__(256) void compact_hidden_kernel(const uint16_t *__restrict__ h_all, int ldh, int T,
+                                                             const int *__restrict__ list,
+                                                             const int *__restrict__ n_list,
+                                                             uint16_t *__restrict__ hc, int ldhc)
+{
+    const int a = *n_list;
+    const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 2;
+    if (c >= a) return;
+    const int j0 = list[c], j1 = c + 1 < a ? list[c + 1] : -1;
+    const int t0 = blockIdx.y * kCompactRows, t1 = min(T, t0 + kCompactRows);
+    for (int t = t0; t < t1; ++t) {
+        const uint16_t *row = h_all + (size_t)t * ldh;
+        const uint32_t v = (uint32_t)row[j0] | (j1 >= 0 ? (uint32_t)row[j1] << 16 : 0u);
+        *reinterpret_cast<uint32_t *>(hc + (size_t)t * ldhc + c) = v;
+    }
+}
+
+// max_list: upper bound of the list length (sizes the grid); ldhc even.
+hipError_t launch_compact_hidden(const uint16_t *h_all, int ldh, int T, const int *list, const int *n_list, int max_list,
+                                 uint16_t *hc, int ldhc, hipStream_t s)
+{
+    if (max_list < 1) return hipSuccess;
+    dim3 grid((max_list + 511) / 512, (T + kCompactRows - 1) / kCompactRows);
+    hipLaunchKernelGGL(compact_hidden_kernel, grid, dim3(256), 0, s, h_all, ldh, T, list, n_list, hc, ldhc);
+    return hipGetLastError();
+}
+
+// Ranges the contraction is split into so that the tiles fill the compute units.
+int down_gemm_splits(int T, int d, int n_cu)
+{
+    const int tiles = ((T + kDgBM - 1) / kDgBM) * ((d + kDgBN - 1) / kDgBN);
+    int n_split = n_cu / tiles;
+    if (n_split < 1) n_split = 1;
+    if (n_split > kDgMaxSplit) n_split = kDgMaxSplit;
+    return n_split;
+}
+
+// bf16 only; d % 8 == 0, ldh % 8 == 0.  part: float32 [n_split][T][d], needed when n_split > 1.
+hipError_t launch_down_gemm_bf16(const void *w, int d, const int *list, const int *n_list, const uint16_t *hc, int ldh,
+                                 int T, int n_split, float *part, void *y, int y_bf16, hipStream_t s)
+{
+    const int n_tt = (T + kDgBM - 1) / kDgBM, n_nt = (d + kDgBN - 1) / kDgBN;
+    const int total = n_tt * n_nt * n_split, per_xcd = (total + 7) / 8;
+    const size_t lds = (size_t)2 * (kDgBM * kDgLdA + kDgBK * kDgLdB) * sizeof(uint16_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&down_gemm_bf16_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(down_gemm_bf16_kernel, dim3(per_xcd * 8), dim3(512), lds, s, (const uint16_t *)w, d, list, n_list,
+                       hc, ldh, T, n_tt, n_nt, n_split, per_xcd, n_split > 1 ? part : nullptr, y, y_bf16);
+    e = hipGetLastError();
+    if (e != hipSuccess || n_split <= 1) return e;
+    const size_t n4 = (size_t)T * d / 4;
+    hipLaunchKernelGGL(down_gemm_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, s, (const float4 *)part,
+                       n_split, n4, y, y_bf16);
+    return hipGetLastError();
+}
+
+}  // namespace pop

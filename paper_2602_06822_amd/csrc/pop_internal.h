@@ -177,6 +177,26 @@ int prefill_num_tiles(int T, int is_bf16);  // upper bound on the rows used, for
 int prefill_rows_used(int T, int is_bf16);  // rows the launch below writes for this T
 hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
                                  int n_cu, hipStream_t s);
+// bf16 layers: gate/up over the channels of a device-resident list (n_list: its length, on the device);
+// hc[t][c] = bf16(H[t][list[c]]), times tmask[t][list[c]] if tmask ([T][m]) is given.  ldh % 8 == 0.
+hipError_t launch_gateup_list_bf16(const void *w, int d, int m, const void *x, int T, const int *list, const int *n_list,
+                                   const unsigned char *tmask, uint16_t *hc, int ldh, int n_cu, hipStream_t s);
+// y[t][n] = sum_c hc[t][c] * w[list[c]][2][n] on the matrix cores; part (float32 [n_split][T][d]) is needed when
+// n_split = down_gemm_splits(...) > 1.
+int down_gemm_splits(int T, int d, int n_cu);
+hipError_t launch_down_gemm_bf16(const void *w, int d, const int *list, const int *n_list, const uint16_t *hc, int ldh,
+                                 int T, int n_split, float *part, void *y, int y_bf16, hipStream_t s);
+// bf16 layers: the prefill contraction (s2_part as in launch_prefill_gateup) that also keeps H:
+// h_all[t][j] = bf16(H[t][j]), row stride ldh.
+hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const void *x, int T, float *s2_part,
+                                           uint16_t *h_all, int ldh, int n_cu, hipStream_t s);
+// hc[t][c] = h_all[t][list[c]] for c < *n_list <= max_list.
+hipError_t launch_compact_hidden(const uint16_t *h_all, int ldh, int T, const int *list, const int *n_list, int max_list,
+                                 uint16_t *hc, int ldhc, hipStream_t s);
+// out[i] = src[idx[i]], i < n
+hipError_t launch_gather_f32(const float *src, const int *idx, int n, float *out, hipStream_t s);
+// any[j] = 1 if mask[t][j] != 0 for some t < rows, else 0
+hipError_t launch_mask_any(const unsigned char *mask, int rows, int m, unsigned char *any, hipStream_t s);
 // scores[j] = nrm[j] * sqrt(sum_tile s2_part[tile][j])
 hipError_t launch_scores_from_partials(const float *s2_part, int n_tiles, int m, const float *nrm, float *scores,
                                        hipStream_t s);

@@ -12,6 +12,10 @@
 // whose halves meet through one cross-lane move in the epilogue.  Each accumulator lane holds 16 token rows of one
 // channel column, so the token reduction is in-register adds, one cross-half shuffle and a 2-wave LDS combine.
 // Token tiles write separate partial rows that are summed in tile order.
+// The same kernel, instantiated with kStore, serves the pruned FFN of a whole prompt (Sec. 3.4: the forward pass
+// under the pruning structure): its chunks run over a device-resident list of active channels instead of all m,
+// and the epilogue writes H (rounded to bf16, optionally times a per-token mask) in compact form [T][list position]
+// for the down projection instead of reducing its squares.
 // float32: plain FMA tiles with the same structure (64 tokens x 32 channels per workgroup).
 #include "pop_internal.h"
 
@@ -21,7 +25,6 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kPfBMmin = 128;     // smallest token tile (sizes the partial-row buffer)
-constexpr int kPfRows = 192;      // B rows per workgroup tile (96 channels: gate + up)
 constexpr int kPfChunk = 96;      // channels per workgroup tile at most
 constexpr int kPfBK = 64;         // k elements per stage
 constexpr int kPfLd = kPfBK + 8;  // padded LDS row stride in elements (144 B): conflict-free 16-byte reads
@@ -39,12 +42,14 @@ int prefill_num_tiles(int T, int is_bf16)
 // of one channel chunk, which share the weight rows) land on the same XCD and meet in its L2.
 __device__ __forceinline__ int xcd_logical_block(int bid, int per_xcd) { return (bid % 8) * per_xcd + bid / 8; }
 
-// Channel (relative to the chunk) and matrix (0 gate, 1 up) of B row r of the workgroup tile.
+// Channel (relative to the chunk) and matrix (0 gate, 1 up) of B row r of the workgroup tile.  A wave owns NF
+// fragments of 32 rows: gate and up of its channels 0..31 and, with NF = 3, the mixed fragment of channels 32..47.
+template <int NF>
 __device__ __forceinline__ void pf_row_channel(int r, int &ch, int &which)
 {
-    const int half = r / 96, rr = r % 96;
+    const int half = r / (NF * 32), rr = r % (NF * 32);
     if (rr < 64) {
-        ch = half * 48 + rr % 32;
+        ch = half * (NF * 16) + rr % 32;
         which = rr / 32;
     } else {
         ch = half * 48 + 32 + rr % 16;
@@ -52,33 +57,88 @@ __device__ __forceinline__ void pf_row_channel(int r, int &ch, int &which)
     }
 }
 
-template <int BM, int NW>
+// Tile geometry: channel chunks of at most 96 channels (three fragments per wave) or at most 64 (two fragments), as
+// many as make the tiles a whole number per compute unit; of the two forms the one that is cheaper on the busiest
+// compute unit.  The kernel is bound by its LDS fragment reads, so a tile's cost is taken as the reads per k-slice
+// of a wave: 2 token fragments + the B fragments (measured: a two-fragment tile takes 0.8 of a three-fragment one).
+// Host and device share this because the list form learns its channel count on the device.
+struct PfGeom {
+    int chunk, n_ct, total, per_xcd, nf;
+};
+__host__ __device__ inline PfGeom prefill_geometry_nf(int n_ch, int n_tt, int n_cu, int nf)
+{
+    PfGeom g;
+    g.nf = nf;
+    const int cap = nf * 32;
+    const int min_ct = (n_ch + cap - 1) / cap;
+    const int per_cu = (min_ct * n_tt + n_cu - 1) / n_cu;
+    int n_ct = per_cu * n_cu / n_tt;
+    if (n_ct < min_ct) n_ct = min_ct;
+    if (n_ct > n_ch) n_ct = n_ch;
+    g.chunk = (n_ch + n_ct - 1) / n_ct;
+    g.n_ct = (n_ch + g.chunk - 1) / g.chunk;
+    g.total = n_tt * g.n_ct;
+    g.per_xcd = (g.total + 7) / 8;
+    return g;
+}
+__host__ __device__ inline PfGeom prefill_geometry(int n_ch, int n_tt, int n_cu)
+{
+    if (n_ch <= 0) return PfGeom{1, 0, 0, 0, 3};
+    const PfGeom g3 = prefill_geometry_nf(n_ch, n_tt, n_cu, 3), g2 = prefill_geometry_nf(n_ch, n_tt, n_cu, 2);
+    const int cost3 = (g3.total + n_cu - 1) / n_cu * 5, cost2 = (g2.total + n_cu - 1) / n_cu * 4;
+    return cost2 < cost3 ? g2 : g3;
+}
+
+// What the list form adds to the plain prefill arguments.
+struct PfStore {
+    const int *list;            // active channels, ascending
+    const int *n_list;          // their number (device)
+    uint16_t *hc;               // [T][ldh] bf16: H of list position c in column c
+    int ldh;
+    const unsigned char *tmask; // per-token masks [T][m], or null
+    int n_cu;
+};
+
+// kMode 0: scores only (s2_part).  1: channels from st.list, H stored compact (no s2_part).  2: all m channels,
+// s2_part and H stored as [T][m padded].
+template <int BM, int NW, int NF, int kMode>
 __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ x, int T, int d, int m,
                                                            int n_ttiles, int chunk, int n_items, int per_xcd,
-                                                           float *__restrict__ s2_part)
+                                                           float *__restrict__ s2_part, PfStore st)
 {
     constexpr int TW = NW / 2;          // waves along the tokens (2 along the B rows)
     constexpr int MT = BM / (32 * TW);  // 32-token fragments per wave
     constexpr int RP = NW * 8;          // rows one staging pass of the workgroup covers
+    constexpr int BR = NF * 64;         // B rows of the workgroup tile
+    constexpr int WC = NF * 16;         // channels per wave
     extern __shared__ __attribute__((aligned(16))) uint16_t pf_lds[];
     uint16_t *As = pf_lds;                       // [2][BM * kPfLd]
-    uint16_t *Bs = pf_lds + 2 * BM * kPfLd;      // [2][kPfRows * kPfLd]
+    uint16_t *Bs = pf_lds + 2 * BM * kPfLd;      // [2][BR * kPfLd]
     __shared__ float colsum[TW][kPfChunk];
 
+    constexpr bool kList = kMode == 1, kStore = kMode != 0;
+    int n_ch = m;  // channels the chunks run over
+    if (kList) {
+        n_ch = *st.n_list;
+        const PfGeom g = prefill_geometry(n_ch, n_ttiles, st.n_cu);
+        if (g.nf != NF) return;  // the other instantiation runs this list length
+        chunk = g.chunk, n_items = g.total, per_xcd = g.per_xcd;
+        if ((int)blockIdx.x >= per_xcd * 8) return;  // the grid was sized for the longest list
+    }
     const int logical = xcd_logical_block(blockIdx.x, per_xcd);
     if (logical >= n_items) return;
     const int ctile = logical / n_ttiles, ttile = logical % n_ttiles;
     const int t0 = ttile * BM, c0 = ctile * chunk;
-    const int cn = min(chunk, m - c0);  // channels in this chunk
+    const int cn = min(chunk, n_ch - c0);  // channels in this chunk
 
     const int tid = threadIdx.x, lane = tid % kWave, wave = tid / kWave;
-    const int wm = wave / 2, wn = wave % 2;  // wave tile: tokens wm*BM/TW.., B rows wn*96..
+    const int wm = wave / 2, wn = wave % 2;  // wave tile: tokens wm*BM/TW.., B rows wn*NF*32..
 
     // global -> LDS staging: 8 vectors of 16 bytes per 64-element row; the workgroup covers RP rows per pass
     const int ld_row = tid / 8, ld_kv = tid % 8;
-    constexpr int PA = BM / RP, PB = kPfRows / RP;
-    static_assert(BM % RP == 0 && kPfRows % RP == 0, "whole staging passes");
+    constexpr int PA = BM / RP, PB = BR / RP;
+    static_assert(BM % RP == 0 && BR % RP == 0, "whole staging passes");
     uint4 ra[PA], rb[PB];
     const uint16_t *pa[PA], *pb[PB];  // row starts (null: a row of zeros)
 #pragma unroll
@@ -89,8 +149,13 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
         int ch, which;
-        pf_row_channel(ld_row + p * RP, ch, which);
-        pb[p] = ch < cn ? w + ((size_t)(c0 + ch) * 3 + which) * d : nullptr;
+        pf_row_channel<NF>(ld_row + p * RP, ch, which);
+        if (ch < cn) {
+            const int j = kList ? st.list[c0 + ch] : c0 + ch;
+            pb[p] = w + ((size_t)j * 3 + which) * d;
+        } else {
+            pb[p] = nullptr;
+        }
     }
     auto load_global = [&](int k0) {
         const int k = k0 + ld_kv * 8;
@@ -108,33 +173,33 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
             *reinterpret_cast<uint4 *>(&As[(buf * BM + ld_row + p * RP) * kPfLd + ld_kv * 8]) = ra[p];
 #pragma unroll
         for (int p = 0; p < PB; ++p)
-            *reinterpret_cast<uint4 *>(&Bs[(buf * kPfRows + ld_row + p * RP) * kPfLd + ld_kv * 8]) = rb[p];
+            *reinterpret_cast<uint4 *>(&Bs[(buf * BR + ld_row + p * RP) * kPfLd + ld_kv * 8]) = rb[p];
     };
 
-    f32x16_t acc[MT][3];  // [token fragment][0 = gate 0..31, 1 = up 0..31, 2 = gate 32..47 | up 32..47]
+    f32x16_t acc[MT][NF];  // [token fragment][0 = gate 0..31, 1 = up 0..31, 2 = gate 32..47 | up 32..47]
 #pragma unroll
     for (int a = 0; a < MT; ++a)
 #pragma unroll
-        for (int f = 0; f < 3; ++f)
+        for (int f = 0; f < NF; ++f)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[a][f][v] = 0.f;
 
     const int n_k = (d + kPfBK - 1) / kPfBK;
-    const int arow = wm * (BM / TW) + (lane % 32), brow = wn * 96 + (lane % 32), koff = (lane / 32) * 8;
+    const int arow = wm * (BM / TW) + (lane % 32), brow = wn * (NF * 32) + (lane % 32), koff = (lane / 32) * 8;
     auto multiply = [&](int buf) {
         const uint16_t *Ab = As + (buf * BM + arow) * kPfLd + koff;
-        const uint16_t *Bb = Bs + (buf * kPfRows + brow) * kPfLd + koff;
+        const uint16_t *Bb = Bs + (buf * BR + brow) * kPfLd + koff;
 #pragma unroll
         for (int kk = 0; kk < kPfBK; kk += 16) {
-            bf16x8_t bf[3], af[MT];
+            bf16x8_t bf[NF], af[MT];
 #pragma unroll
-            for (int f = 0; f < 3; ++f) bf[f] = *reinterpret_cast<const bf16x8_t *>(Bb + f * 32 * kPfLd + kk);
+            for (int f = 0; f < NF; ++f) bf[f] = *reinterpret_cast<const bf16x8_t *>(Bb + f * 32 * kPfLd + kk);
 #pragma unroll
             for (int a = 0; a < MT; ++a) af[a] = *reinterpret_cast<const bf16x8_t *>(Ab + a * 32 * kPfLd + kk);
 #pragma unroll
             for (int a = 0; a < MT; ++a)
 #pragma unroll
-                for (int f = 0; f < 3; ++f)
+                for (int f = 0; f < NF; ++f)
                     acc[a][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[f], acc[a][f], 0, 0, 0);
         }
     };
@@ -152,6 +217,39 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
 
     // epilogue: lane holds 16 * MT token rows of column (lane % 32) of each fragment; rows of padded tokens and
     // columns of padded channels are exactly 0
+    if (kStore) {
+        // register v of a fragment is token row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32
+        const int col = lane % 32;
+        const int c01 = wn * WC + col, c2 = wn * WC + 32 + col;
+        const bool ok01 = c01 < cn, ok2 = NF == 3 && col < 16 && c2 < cn;
+        const int j01 = (kList && st.tmask && ok01) ? st.list[c0 + c01] : 0;
+        const int j2 = (kList && st.tmask && ok2) ? st.list[c0 + c2] : 0;
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int t = t0 + wm * (BM / TW) + a * 32 + (v / 4) * 8 + (lane / 32) * 4 + v % 4;
+                float h01 = silu_mul(acc[a][0][v], acc[a][1][v]);
+                float h2 = 0.f;
+                if (NF == 3) {
+                    const float g2 = acc[a][NF - 1][v];
+                    const float u2 = __shfl_xor(g2, 16, kWave);
+                    h2 = silu_mul(g2, u2);
+                }
+                if (t < T) {
+                    uint16_t *row = st.hc + (size_t)t * st.ldh + c0;
+                    if (ok01) {
+                        if (kList && st.tmask && !st.tmask[(size_t)t * m + j01]) h01 = 0.f;
+                        row[c01] = f32_to_bf16(h01);
+                    }
+                    if (ok2) {
+                        if (kList && st.tmask && !st.tmask[(size_t)t * m + j2]) h2 = 0.f;
+                        row[c2] = f32_to_bf16(h2);
+                    }
+                }
+            }
+        if (kList) return;
+    }
     float ss01 = 0.f, ss2 = 0.f;
 #pragma unroll
     for (int a = 0; a < MT; ++a)
@@ -159,16 +257,18 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
         for (int v = 0; v < 16; ++v) {
             const float hv = silu_mul(acc[a][0][v], acc[a][1][v]);
             ss01 = fmaf(hv, hv, ss01);
-            // mixed fragment: the up value of column c < 16 sits in lane c + 16, same register
-            const float g2 = acc[a][2][v];
-            const float u2 = __shfl_xor(g2, 16, kWave);
-            const float h2 = silu_mul(g2, u2);
-            ss2 = fmaf(h2, h2, ss2);
+            if (NF == 3) {
+                // mixed fragment: the up value of column c < 16 sits in lane c + 16, same register
+                const float g2 = acc[a][NF - 1][v];
+                const float u2 = __shfl_xor(g2, 16, kWave);
+                const float h2 = silu_mul(g2, u2);
+                ss2 = fmaf(h2, h2, ss2);
+            }
         }
     ss01 += __shfl_xor(ss01, 32, kWave);
     ss2 += __shfl_xor(ss2, 32, kWave);
-    if (lane < 32) colsum[wm][wn * 48 + lane] = ss01;
-    if (lane < 16) colsum[wm][wn * 48 + 32 + lane] = ss2;
+    if (lane < 32) colsum[wm][wn * WC + lane] = ss01;
+    if (NF == 3 && lane < 16) colsum[wm][wn * WC + 32 + lane] = ss2;
     __syncthreads();
     if (tid < cn) {
         float tot = 0.f;
@@ -245,44 +345,77 @@ int prefill_rows_used(int T, int is_bf16)
     return (T + bm - 1) / bm;
 }
 
+template <int BM, int NW, int NF, int kMode>
+static hipError_t launch_pf_bf16(int blocks, hipStream_t s, const void *w, const void *x, int T, int d, int m, int n_tt,
+                                 const PfGeom &g, float *s2_part, const PfStore &st)
+{
+    const size_t lds = (size_t)2 * (BM + NF * 64) * kPfLd * sizeof(uint16_t);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<BM, NW, NF, kMode>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((prefill_bf16_kernel<BM, NW, NF, kMode>), dim3(blocks), dim3(NW * 64), lds, s,
+                       (const uint16_t *)w, (const uint16_t *)x, T, d, m, n_tt, g.chunk, g.total, g.per_xcd, s2_part, st);
+    return hipGetLastError();
+}
+
+template <int kMode>
+static hipError_t launch_pf_bf16_all(const void *w, int d, int m, const void *x, int T, float *s2_part, int n_cu,
+                                     const PfStore &st, hipStream_t s)
+{
+    const int bm = prefill_token_tile(T);
+    const int n_tt = (T + bm - 1) / bm;
+    const PfGeom g = prefill_geometry(m, n_tt, n_cu);
+    const int blocks = g.per_xcd * 8;
+    // 256-token tiles run with 8 waves (two per SIMD: one wave's waits for staging loads, LDS writes and the
+    // k-step barrier are covered by the other's products), 128-token tiles with 4
+    if (bm == 256 && g.nf == 3) return launch_pf_bf16<256, 8, 3, kMode>(blocks, s, w, x, T, d, m, n_tt, g, s2_part, st);
+    if (bm == 256) return launch_pf_bf16<256, 8, 2, kMode>(blocks, s, w, x, T, d, m, n_tt, g, s2_part, st);
+    if (g.nf == 3) return launch_pf_bf16<128, 4, 3, kMode>(blocks, s, w, x, T, d, m, n_tt, g, s2_part, st);
+    return launch_pf_bf16<128, 4, 2, kMode>(blocks, s, w, x, T, d, m, n_tt, g, s2_part, st);
+}
+
+// bf16 only: the prefill contraction that also keeps H, h_all[t][j] = bf16(H[t][j]) with row stride ldh.
+hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const void *x, int T, float *s2_part,
+                                           uint16_t *h_all, int ldh, int n_cu, hipStream_t s)
+{
+    PfStore st{nullptr, nullptr, h_all, ldh, nullptr, n_cu};
+    return launch_pf_bf16_all<2>(w, d, m, x, T, s2_part, n_cu, st, s);
+}
+
 hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
                                  int n_cu, hipStream_t s)
 {
-    if (is_bf16) {
-        const int bm = prefill_token_tile(T);
-        const int n_tt = (T + bm - 1) / bm;
-        // channel chunks of at most kPfChunk channels, as many as make the tiles a whole number per compute unit
-        const int min_ct = (m + kPfChunk - 1) / kPfChunk;
+    if (is_bf16) return launch_pf_bf16_all<0>(w, d, m, x, T, s2_part, n_cu, PfStore{}, s);
+    dim3 grid((m + kPf32BC - 1) / kPf32BC, (T + kPf32BM - 1) / kPf32BM);
+    hipLaunchKernelGGL(prefill_f32_kernel, grid, dim3(256), 0, s, (const float *)w, (const float *)x, T, d, m, s2_part);
+    return hipGetLastError();
+}
+
+// bf16 only.  Gate/up over the channels of a device-resident list; hc[t][c] = bf16(H[t][list[c]]) (times
+// tmask[t][list[c]] if tmask is given).  The list's length is known on the device only: both tile forms are
+// launched, each sized for the longest possible list (m channels), and the one the length does not call for exits
+// at once.
+hipError_t launch_gateup_list_bf16(const void *w, int d, int m, const void *x, int T, const int *list, const int *n_list,
+                                   const unsigned char *tmask, uint16_t *hc, int ldh, int n_cu, hipStream_t s)
+{
+    const int bm = prefill_token_tile(T);
+    const int n_tt = (T + bm - 1) / bm;
+    PfStore st{list, n_list, hc, ldh, tmask, n_cu};
+    PfGeom g{};
+    hipError_t e = hipSuccess;
+    for (int nf = 3; nf >= 2 && e == hipSuccess; --nf) {
+        // an upper bound of the tile count over all list lengths <= m (the count before chunks are evened out)
+        const int min_ct = (m + nf * 32 - 1) / (nf * 32);
         const int per_cu = (min_ct * n_tt + n_cu - 1) / n_cu;
         int n_ct = per_cu * n_cu / n_tt;
         if (n_ct < min_ct) n_ct = min_ct;
-        if (n_ct > m) n_ct = m;
-        const int chunk = (m + n_ct - 1) / n_ct;
-        n_ct = (m + chunk - 1) / chunk;
-        const int total = n_tt * n_ct, per_xcd = (total + 7) / 8;
-        const size_t lds = (size_t)2 * (bm + kPfRows) * kPfLd * sizeof(uint16_t);
-        hipError_t e;
-        // 256-token tiles run with 8 waves (two per SIMD: one wave's waits for staging loads, LDS writes and the
-        // k-step barrier are covered by the other's products), 128-token tiles with 4
-        if (bm == 256) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<256, 8>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL((prefill_bf16_kernel<256, 8>), dim3(per_xcd * 8), dim3(512), lds, s, (const uint16_t *)w,
-                               (const uint16_t *)x, T, d, m, n_tt, chunk, total, per_xcd, s2_part);
-        } else {
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<128, 4>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return e;
-            hipLaunchKernelGGL((prefill_bf16_kernel<128, 4>), dim3(per_xcd * 8), dim3(256), lds, s, (const uint16_t *)w,
-                               (const uint16_t *)x, T, d, m, n_tt, chunk, total, per_xcd, s2_part);
-        }
-    } else {
-        dim3 grid((m + kPf32BC - 1) / kPf32BC, (T + kPf32BM - 1) / kPf32BM);
-        hipLaunchKernelGGL(prefill_f32_kernel, grid, dim3(256), 0, s, (const float *)w, (const float *)x, T, d, m,
-                           s2_part);
+        const int blocks = (n_tt * n_ct + 7) / 8 * 8;
+        if (bm == 256 && nf == 3) e = launch_pf_bf16<256, 8, 3, 1>(blocks, s, w, x, T, d, m, n_tt, g, nullptr, st);
+        else if (bm == 256) e = launch_pf_bf16<256, 8, 2, 1>(blocks, s, w, x, T, d, m, n_tt, g, nullptr, st);
+        else if (nf == 3) e = launch_pf_bf16<128, 4, 3, 1>(blocks, s, w, x, T, d, m, n_tt, g, nullptr, st);
+        else e = launch_pf_bf16<128, 4, 2, 1>(blocks, s, w, x, T, d, m, n_tt, g, nullptr, st);
     }
-    return hipGetLastError();
+    return e;
 }
 
 // scores[j] = nrm[j] * sqrt(sum over token tiles, in tile order, of s2_part[tile][j])   (Eq. 3)

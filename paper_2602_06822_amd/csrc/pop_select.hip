@@ -223,4 +223,46 @@ hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *
     return hipGetLastError();
 }
 
+// any[j] = 1 where mask[r][j] != 0 for some row r.  any is cleared first; a thread owns 4 adjacent channels and a
+// group of 32 rows and writes 1 where it saw a set byte (writers of one byte all write the same value).
+constexpr int kAnyRows = 32;
+__global__ __launch_bounds__(256) void mask_any_kernel(const unsigned char *__restrict__ mask, int rows, int m,
+                                                       unsigned char *__restrict__ any)
+{
+    const int j = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (j >= m) return;
+    const int n = min(4, m - j);
+    const int r0 = blockIdx.y * kAnyRows, r1 = min(rows, r0 + kAnyRows);
+    unsigned char acc[4] = {0, 0, 0, 0};
+    for (int r = r0; r < r1; ++r)
+        for (int q = 0; q < n; ++q) acc[q] |= mask[(size_t)r * m + j + q];
+    for (int q = 0; q < n; ++q)
+        if (acc[q]) any[j + q] = 1;
+}
+
+// any must have room for m rounded up to a multiple of 4 bytes.
+hipError_t launch_mask_any(const unsigned char *mask, int rows, int m, unsigned char *any, hipStream_t s)
+{
+    hipError_t e = launch_fill_int((int *)any, (m + 3) / 4, 0, s);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(mask_any_kernel, dim3((m + 1023) / 1024, (rows + kAnyRows - 1) / kAnyRows), dim3(256), 0, s, mask,
+                       rows, m, any);
+    return hipGetLastError();
+}
+
+// out[i] = src[idx[i]]
+__global__ __launch_bounds__(256) void gather_f32_kernel(const float *__restrict__ src, const int *__restrict__ idx, int n,
+                                                         float *__restrict__ out)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) out[i] = src[idx[i]];
+}
+
+hipError_t launch_gather_f32(const float *src, const int *idx, int n, float *out, hipStream_t s)
+{
+    if (n < 1) return hipSuccess;
+    hipLaunchKernelGGL(gather_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, src, idx, n, out);
+    return hipGetLastError();
+}
+
 }  // namespace pop

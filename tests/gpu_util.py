@@ -63,6 +63,22 @@ class GpuLayer:
         self.n_ret, self.n_cand = n_ret, n_cand
         return host(scores), host(region), host(ret)[:n_ret], host(cand)[:n_cand]
 
+    def prefill_forward(self, x: np.ndarray, n_ret: int, n_cand: int, k0: int, ydtype=None):
+        """pop_prefill_forward: returns (scores, region, ret_idx, cand_idx, mask, y as float64)."""
+        T = x.shape[0]
+        ydtype = self.dtype if ydtype is None else ydtype
+        scores = torch.empty(self.m, dtype=torch.float32, device="cuda")
+        region = torch.empty(self.m, dtype=torch.uint8, device="cuda")
+        mask = torch.full((self.m,), 7, dtype=torch.uint8, device="cuda")
+        ret = torch.empty(max(n_ret, 1), dtype=torch.int32, device="cuda")
+        cand = torch.empty(max(n_cand, 1), dtype=torch.int32, device="cuda")
+        y = torch.full((T, self.d), 12345, dtype=torch.float32 if ydtype == synth.F32 else torch.int16, device="cuda")
+        self.pop.pop_prefill_forward(self.handle, dev(x), T, n_ret, n_cand, k0, y, ydtype, scores, region, ret, cand,
+                                     mask)
+        self.n_ret, self.n_cand = n_ret, n_cand
+        yh = host(y).astype(np.float64) if ydtype == synth.F32 else bf16_out_to_f64(y)
+        return host(scores), host(region), host(ret)[:n_ret], host(cand)[:n_cand], host(mask), yh
+
     def decode(self, x_t: np.ndarray, k, ydtype=None, one_call=False):
         """x_t: [B][d] storage.  Returns dict of host arrays (cscore, mask, active_idx, n_active, h, y).
         one_call: use pop_decode_step instead of pop_decode_mask + pop_pruned_ffn (True: its default form;

@@ -224,6 +224,124 @@ def test_pruned_ffn_standalone(pop, oracle, dtype):
         assert e.value.status == pop.POP_ESTATE
 
 
+# From 32 tokens on a bf16 layer's stand-alone pruned FFN runs on the matrix cores and rounds H to bf16 before the
+# down projection (relative error 2^-9 per term, adding in quadrature over the active channels): float32 outputs of
+# that path are held to 4e-3 of max|y|, well inside the 2e-2 allowed for bf16 layers; bf16 outputs to the 2e-2.
+FFN_MFMA_TOL_F32 = 4e-3
+
+
+@pytest.mark.parametrize("T", [32, 150, 300])
+def test_pruned_ffn_prompt_sized_bf16(pop, oracle, T):
+    """Stand-alone pruned FFN of many tokens (forward pass of a prompt under a mask; Sec. 3.4): token tiles with
+    a ragged tail, channel counts that are no multiple of the k-step, an empty mask, per-token masks."""
+    d, m = 264, 301
+    L = synth.make_layer(synth.small_config("ffn_prompt", d, m, BF16))
+    x = synth.make_activations(L, T, "tokens")
+    g = synth.rng("ffn_prompt_masks", T)
+    one = np.zeros(m, np.uint8)
+    one[17] = 1
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        for mask in (np.ones(m, np.uint8), (g.random(m) < 0.4).astype(np.uint8), np.zeros(m, np.uint8), one,
+                     (g.random((T, m)) < 0.5).astype(np.uint8)):
+            y_ref = oracle.pruned_ffn(x, L.w_gate, L.w_up, L.w_down, BF16, mask)
+            for ydtype in (F32, BF16):
+                y = G.ffn(x, mask, ydtype)
+                if not y_ref.any():
+                    assert not y.any()
+                else:
+                    err = max_abs_rel(y, y_ref)
+                    assert err <= (Y_TOL[BF16] if ydtype == BF16 else FFN_MFMA_TOL_F32), f"T={T} err {err:.3e}"
+        # a second, smaller prompt on the same handle reuses the scratch
+        y = G.ffn(x[:40], np.ones(m, np.uint8), F32)
+        y_ref = oracle.pruned_ffn(x[:40], L.w_gate, L.w_up, L.w_down, BF16, np.ones(m, np.uint8))
+        assert max_abs_rel(y, y_ref) <= FFN_MFMA_TOL_F32
+
+
+def test_pruned_ffn_prompt_full_size(pop, oracle):
+    """Llama-2-7B-shaped layer: the prompt's forward pass under the prefill mask (retained channels plus the best
+    k candidates by prefill score), checked on a sample of tokens; and wider-than-one-tile shapes of the split
+    contraction (T = 512: 4 splits; T = 2048: none)."""
+    cfg, r, f_cand = synth.CFG2, 0.35, 0.10
+    L = synth.make_layer(cfg, layer_id=0)
+    m = cfg.m
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 1.0 - r - f_cand / 2, f_cand)
+    k = pop.pop_k_for_ratio(m, r, n_ret, n_cand)
+    for T in (512, 2048):
+        x = synth.make_activations(L, T, "prompt")
+        with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+            scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+            mask, sel, _ = oracle.select(region, scores[cand], cand, k)
+            assert int(mask.sum()) == n_ret + k
+            y = G.ffn(x, mask, F32)
+            rows = np.sort(synth.rng("ffn_rows", T).choice(T, size=6, replace=False))
+            y_ref = oracle.pruned_ffn(x[rows], L.w_gate, L.w_up, L.w_down, BF16, mask)
+            err = max_abs_rel(y[rows], y_ref)
+            assert err <= FFN_MFMA_TOL_F32, f"T={T} err {err:.3e}"
+
+
+def _check_prefill_forward(oracle, G, L, x, n_ret, n_cand, k0, ydtype, y_tol, rows=None):
+    """Whole prefilling stage in one call: scores and partition as in the two-call form; the prefill mask must be
+    the oracle's selection on the GPU's own scores (retained + best k0 candidates by prefill score); y against the
+    oracle's pruned FFN under that mask."""
+    dtype = L.cfg.dtype
+    scores, region, ret, cand, mask, y = G.prefill_forward(x, n_ret, n_cand, k0, ydtype)
+    r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+    assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1)
+    mask1, _, _ = oracle.select(region, scores[cand], cand, k0)
+    assert np.array_equal(mask, mask1)
+    assert int(mask.sum()) == n_ret + k0
+    rows = np.arange(x.shape[0]) if rows is None else rows
+    y_ref = oracle.pruned_ffn(x[rows], L.w_gate, L.w_up, L.w_down, dtype, mask)
+    if not y_ref.any():
+        assert not y[rows].any()
+    else:
+        err = max_abs_rel(y[rows], y_ref)
+        assert err <= y_tol, f"prefill forward y error {err:.3e}"
+    return scores, region, ret, cand
+
+
+@pytest.mark.parametrize("dtype,T", [(F32, 40), (BF16, 20), (BF16, 150), (BF16, 290)])
+def test_prefill_forward_small(pop, oracle, dtype, T):
+    """Partition + pruned output of the prompt in one call: float32 and short prompts (decode kernels), bf16
+    prompts of 32 tokens and more (kept H, gathered columns, matrix-core GEMM); degenerate region sizes; the
+    partition it leaves serves the decode steps that follow."""
+    d, m = (264, 301) if dtype == BF16 else (260, 301)
+    L = synth.make_layer(synth.small_config("prefill_forward", d, m, dtype))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 1, "decode")
+    mfma = dtype == BF16 and T >= 32
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        for n_ret, n_cand, k0 in ((150, 60, 25), (150, 60, 0), (150, 60, 60), (0, 301, 100), (301, 0, 0), (0, 0, 0),
+                                  (0, 40, 1)):
+            for ydtype in (F32, dtype):
+                tol = Y_TOL[BF16] if ydtype == BF16 else (FFN_MFMA_TOL_F32 if mfma else 1e-4)
+                scores, region, ret, cand = _check_prefill_forward(oracle, G, L, x, n_ret, n_cand, k0, ydtype, tol)
+            # same scores as the two-call form, bit for bit (the contraction is the same kernel)
+            s2, region2, _, _ = G.prefill(x, n_ret, n_cand)
+            assert np.array_equal(scores, s2) and np.array_equal(region, region2)
+            _check_decode(oracle, G, L, region, cand, xt, min(k0, n_cand))
+
+
+def test_prefill_forward_full_size(pop, oracle):
+    """Llama-2-7B-shaped layer, prompt 512: prefill scores on a sample of channels, partition and prefill mask
+    on all channels, the prompt's output on a sample of tokens, then a decode step on the partition."""
+    cfg, r, f_cand, T = synth.CFG2, 0.35, 0.10, 512
+    L = synth.make_layer(cfg, layer_id=0)
+    m = cfg.m
+    x = synth.make_activations(L, T, "prompt")
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 1.0 - r - f_cand / 2, f_cand)
+    k = pop.pop_k_for_ratio(m, r, n_ret, n_cand)
+    rows = np.sort(synth.rng("prefill_forward_rows").choice(T, size=6, replace=False))
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        scores, region, ret, cand = _check_prefill_forward(oracle, G, L, x, n_ret, n_cand, k, F32, FFN_MFMA_TOL_F32,
+                                                           rows=rows)
+        sample = np.sort(synth.rng("full_size_sample", cfg.name).choice(m, size=64, replace=False)).astype(np.int32)
+        H = oracle.hidden(x, L.w_gate, L.w_up, cfg.dtype, chan=sample)
+        s_ref = oracle.importance(L.w_down, cfg.dtype, H, chan=sample)[sample]
+        assert score_rel_err(scores[sample], s_ref, eps=1e-6) <= SCORE_TOL
+        _check_decode(oracle, G, L, region, cand, synth.make_activations(L, 1, "decode_b1"), [k])
+
+
 def test_importance_reduce_standalone(pop, oracle):
     T, m = 77, 1000
     g = synth.rng("impred")
