@@ -168,6 +168,12 @@ int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
 /* Host only.  See pop_decode_step. */
 int pop_layer_set_single_launch(pop_layer_t *layer, int on);
+/* Host only.  How a decode step with B > 1 scores its candidates.  off (default): every sequence by its own
+ * activation, I_j = n_j |h_bj|, its own top-k and mask.  on: the activation norm of Eq. 3 runs over the step's B
+ * sequences ("tokens and samples", Sec. 3.1), I_j = n_j sqrt(sum_b h_bj^2), and one selection serves the whole
+ * batch: all k[b] must be equal (else POP_ESHAPE), every row of cand_scores, mask and active_idx comes out the
+ * same.  B == 1 is unaffected.  Invalidates a cached decode step. */
+int pop_layer_set_shared_batch_mask(pop_layer_t *layer, int on);
 /* Host only.  Which implementation the last successful pop_decode_mask on this layer used: 0 = none yet,
  * 1 = the fused single-sequence kernel, 2 = the batch-general kernels.  If workgroups != NULL it receives the
  * fused kernel's grid size for the current partition (0 when the fused kernel does not apply). */

@@ -50,6 +50,7 @@ _SIGS = {
     "pop_layer_sync_status": (_i, [_vp, _vp]),
     "pop_layer_step_kind": (_i, [_vp, _ip]),
     "pop_layer_set_single_launch": (_i, [_vp, _i]),
+    "pop_layer_set_shared_batch_mask": (_i, [_vp, _i]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -191,6 +192,10 @@ def pop_layer_sync_status(layer, stream=None):
 
 def pop_layer_set_single_launch(layer, on: bool):
     _check(_lib.pop_layer_set_single_launch(layer, 1 if on else 0), "pop_layer_set_single_launch")
+
+
+def pop_layer_set_shared_batch_mask(layer, on: bool):
+    _check(_lib.pop_layer_set_shared_batch_mask(layer, 1 if on else 0), "pop_layer_set_shared_batch_mask")
 
 
 def pop_layer_step_kind(layer):

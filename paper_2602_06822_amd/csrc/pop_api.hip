@@ -42,6 +42,7 @@ struct pop_layer {
     float *nrm = nullptr;  // [m]
     int n_cu = 0, wg_target = 0;
     bool single_launch = false;  // pop_decode_step at B = 1: sum the partial outputs inside the fused kernel
+    bool shared_mask = false;    // B > 1: one selection for the batch from scores aggregated over its sequences
     // partition
     bool has_partition = false;
     int n_ret = 0, n_cand = 0;
@@ -451,7 +452,11 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
             L->ulist_prefix_ok = true;
         }
         bool sel_inside = false;
-        if (B > 1)  // per-sequence top-k and their union inside the gate/up kernel, behind the retained channels
+        const bool shared = B > 1 && L->shared_mask;
+        if (shared)
+            for (int b = 1; b < B; ++b)
+                if (kk.k[b] != kk.k[0]) return POP_ESHAPE;
+        if (B > 1 && !shared)  // per-sequence top-k and their union inside the gate/up kernel, behind the retained channels
             POP_HIP(launch_gateup_select(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, L->h, L->nrm, L->cscore, m,
                                          L->cand_idx, n_cand, n_ret, kk, m, L->mask, L->active_idx, L->n_active,
                                          L->selflag, L->ulist, L->n_ulist, L->sync + 10, L->sync + 2, L->n_cu,
@@ -459,6 +464,9 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         if (!sel_inside) {
             POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
                                   L->cscore, m, n_cand, L->n_cu, s));
+            // one mask for the batch: every sequence's row gets the scores aggregated over the batch, so the B
+            // selections below come out identical
+            if (shared) POP_HIP(launch_aggregate_scores(L->cscore, m, B, n_cand, s));
             // B > 1: the kernel also builds the union of the B selections for the batched down projection
             POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx,
                                 L->n_active, nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
@@ -594,6 +602,14 @@ int pop_layer_sync_status(pop_layer_t *L, void *stream)
     POP_HIP(hipMemcpyAsync(&flag, L->sync + 2, 4, hipMemcpyDeviceToHost, as_stream(stream)));
     POP_HIP(hipStreamSynchronize(as_stream(stream)));
     return flag ? POP_EDEVICE : POP_OK;
+}
+
+int pop_layer_set_shared_batch_mask(pop_layer_t *L, int on)
+{
+    if (!L) return POP_EINVAL;
+    L->shared_mask = on != 0;
+    L->has_step = false;
+    return POP_OK;
 }
 
 int pop_layer_set_single_launch(pop_layer_t *L, int on)

@@ -193,6 +193,8 @@ hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const vo
 // hc[t][c] = h_all[t][list[c]] for c < *n_list <= max_list.
 hipError_t launch_compact_hidden(const uint16_t *h_all, int ldh, int T, const int *list, const int *n_list, int max_list,
                                  uint16_t *hc, int ldhc, hipStream_t s);
+// cs[b][p] <- sqrt(sum over b' < B of cs[b'][p]^2) for every b < B, p < n
+hipError_t launch_aggregate_scores(float *cs, int cs_stride, int B, int n, hipStream_t s);
 // out[i] = src[idx[i]], i < n
 hipError_t launch_gather_f32(const float *src, const int *idx, int n, float *out, hipStream_t s);
 // any[j] = 1 if mask[t][j] != 0 for some t < rows, else 0

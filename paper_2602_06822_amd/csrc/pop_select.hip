@@ -265,4 +265,26 @@ hipError_t launch_gather_f32(const float *src, const int *idx, int n, float *out
     return hipGetLastError();
 }
 
+// Scores of one batch step aggregated over its B sequences (Eq. 3 with the step's tokens and samples):
+// cs[b][p] = n_j |h_bj| on entry; on exit every row holds sqrt(sum_b cs[b][p]^2) = n_j * ||h_{:,j}||_2.
+__global__ __launch_bounds__(256) void aggregate_scores_kernel(float *__restrict__ cs, int cs_stride, int B, int n)
+{
+    const int p = blockIdx.x * blockDim.x + threadIdx.x;
+    if (p >= n) return;
+    double acc = 0.0;
+    for (int b = 0; b < B; ++b) {
+        const double v = (double)cs[(size_t)b * cs_stride + p];
+        acc += v * v;
+    }
+    const float r = (float)sqrt(acc);
+    for (int b = 0; b < B; ++b) cs[(size_t)b * cs_stride + p] = r;
+}
+
+hipError_t launch_aggregate_scores(float *cs, int cs_stride, int B, int n, hipStream_t s)
+{
+    if (n < 1) return hipSuccess;
+    hipLaunchKernelGGL(aggregate_scores_kernel, dim3((n + 255) / 256), dim3(256), 0, s, cs, cs_stride, B, n);
+    return hipGetLastError();
+}
+
 }  // namespace pop

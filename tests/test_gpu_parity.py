@@ -342,6 +342,45 @@ def test_prefill_forward_full_size(pop, oracle):
         _check_decode(oracle, G, L, region, cand, synth.make_activations(L, 1, "decode_b1"), [k])
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_shared_batch_mask(pop, oracle, dtype):
+    """B > 1 with one mask for the batch: candidate scores are Eq. 3 over the step's B activations (the literal
+    double sum of the oracle), one selection, every sequence's output under that mask."""
+    d, m, T, B = 264 if dtype == BF16 else 260, 301, 24, 5
+    L = synth.make_layer(synth.small_config("shared_mask", d, m, dtype))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, B, "decode")
+    n_ret, n_cand, k = 140, 90, 37
+    with GpuLayer(pop, L, max_tokens=T, max_batch=8) as G:
+        scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        pop.pop_layer_set_shared_batch_mask(G.handle, True)
+        for one_call in (False, True):
+            out = G.decode(xt, k, one_call=one_call)
+            H = oracle.hidden(xt, L.w_gate, L.w_up, dtype)
+            s_ref = oracle.importance(L.w_down, dtype, H)[cand]
+            mask1, sel1, act1 = oracle.select(region, out["cscore"][0], cand, k)
+            rc = region != 2
+            for b in range(B):
+                assert score_rel_err(out["cscore"][b], s_ref, eps=DECODE_FLOOR[dtype]) <= SCORE_TOL
+                assert np.array_equal(out["cscore"][b], out["cscore"][0])
+                assert score_rel_err(out["h"][b][rc], H[b][rc], eps=DECODE_FLOOR[dtype]) <= SCORE_TOL
+                assert np.array_equal(out["mask"][b], mask1)
+                assert out["n_active"][b] == n_ret + k
+                assert np.array_equal(out["active_idx"][b][:n_ret + k], act1)
+                y_ref = oracle.down(H[b:b + 1], L.w_down, dtype, mask1)[0]
+                assert max_abs_rel(out["y"][b], y_ref) <= Y_TOL[dtype]
+        # the aggregated score is not any single sequence's score
+        per_seq = oracle.decode(xt[0], L.w_gate, L.w_up, L.w_down, dtype, region, cand, k, want_y=False)["cscore"]
+        assert not np.allclose(per_seq, s_ref, rtol=1e-3)
+        with pytest.raises(pop.PopError) as e:
+            G.decode(xt, [k, k, k + 1, k, k])
+        assert e.value.status == pop.POP_ESHAPE
+        # one sequence: nothing to aggregate, the usual step
+        _check_decode(oracle, G, L, region, cand, xt[:1], k)
+        pop.pop_layer_set_shared_batch_mask(G.handle, False)
+        _check_decode(oracle, G, L, region, cand, xt, k)
+
+
 def test_importance_reduce_standalone(pop, oracle):
     T, m = 77, 1000
     g = synth.rng("impred")
