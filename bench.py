@@ -182,12 +182,11 @@ def run(args):
     # and re-scoring every channel at each step (Variant 2: every channel a candidate); all at r = 0.35.
     ablation = None
     if not args.quick:
-        a_act = n_ret + k
-        rows = [("dense", (m, 0, 0)), ("variant1_static_mask", (a_act, 0, 0))]
+        rows = [("dense", (m, 0, 0)),
+                ("variant1_static_mask", pop.pop_strategy_counts(pop.POP_STRATEGY_STATIC_MASK, m, r_main, 0.0))]
         for g in (0.05, 0.10, 0.20):
-            nr, nc, _ = pop.pop_region_counts(m, 1.0 - r_main - g / 2, g)
-            rows.append((f"pop_gamma_{g:.2f}", (nr, nc, pop.pop_k_for_ratio(m, r_main, nr, nc))))
-        rows.append(("variant2_rescore_all", (0, m, a_act)))
+            rows.append((f"pop_gamma_{g:.2f}", pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r_main, g)))
+        rows.append(("variant2_rescore_all", pop.pop_strategy_counts(pop.POP_STRATEGY_RESCORE_ALL, m, r_main, 0.0)))
         ablation = {}
         for name, cnt in rows:
             t = timed(cnt, 1, 1)["decode_us_per_token"]

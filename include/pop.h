@@ -64,6 +64,18 @@ int pop_region_counts(int m, double f_ret, double f_cand, int *n_ret, int *n_can
  * floor((1-r)*m + 1/2) (Sec. 3.3 "Decoding Stage"), clamped to [0, n_cand]. */
 int pop_k_for_ratio(int m, double r, int n_ret, int n_cand, int *k);
 
+/* Host only.  Region sizes and per-token k of the decode strategies compared in the paper's ablation (Sec. 5,
+ * trade-off table), all with floor((1-r)*m + 1/2) active channels per token:
+ *   POP_STRATEGY_POP          the method: candidate band of gamma*m channels centred on the sparsity quantile
+ *                             (f_ret = 1-r-gamma/2, f_cand = gamma; counts and k as in the two functions above);
+ *   POP_STRATEGY_STATIC_MASK  Variant (1): the prefill mask is reused at every step (n_cand = 0, all active
+ *                             channels retained): no re-scoring, no selection, no overhead;
+ *   POP_STRATEGY_RESCORE_ALL  Variant (2): every channel is a candidate at every step (n_ret = 0, n_cand = m).
+ * The counts go to pop_prefill_partition / pop_decode_mask unchanged.  gamma is ignored by the two variants.
+ * Errors: a band that leaves [0, 1] or an unknown strategy -> POP_EINVAL. */
+enum { POP_STRATEGY_POP = 0, POP_STRATEGY_STATIC_MASK = 1, POP_STRATEGY_RESCORE_ALL = 2 };
+int pop_strategy_counts(int strategy, int m, double r, double gamma, int *n_ret, int *n_cand, int *k);
+
 /* Create a layer.  w_gate, w_up: dev [m][d]; w_down: dev [d][m]; all of dtype wdtype, read once, on `stream`,
  * and repacked channel-major (one contiguous gate+up row pair and one contiguous down column per channel).
  * Also computes the data-free weight factor n_j = ||W_down[:,j]||_2 of Eq. 3.

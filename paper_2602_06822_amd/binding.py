@@ -35,6 +35,7 @@ _SIGS = {
     "pop_last_hip_error": (C.c_char_p, []),
     "pop_region_counts": (_i, [_i, _dbl, _dbl, _ip, _ip, _ip]),
     "pop_k_for_ratio": (_i, [_i, _dbl, _i, _i, _ip]),
+    "pop_strategy_counts": (_i, [_i, _i, _dbl, _dbl, _ip, _ip, _ip]),
     "pop_layer_create": (_i, [C.POINTER(_vp), _i, _i, _i, _vp, _vp, _vp, _i, _i, _vp]),
     "pop_layer_destroy": (_i, [_vp]),
     "pop_prefill_partition": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
@@ -116,6 +117,16 @@ def pop_k_for_ratio(m: int, r: float, n_ret: int, n_cand: int) -> int:
     k = C.c_int()
     _check(_lib.pop_k_for_ratio(m, r, n_ret, n_cand, C.byref(k)), "pop_k_for_ratio")
     return k.value
+
+
+POP_STRATEGY_POP, POP_STRATEGY_STATIC_MASK, POP_STRATEGY_RESCORE_ALL = 0, 1, 2
+
+
+def pop_strategy_counts(strategy: int, m: int, r: float, gamma: float):
+    """(n_ret, n_cand, k) of a decode strategy of the ablation."""
+    a, b, c = C.c_int(), C.c_int(), C.c_int()
+    _check(_lib.pop_strategy_counts(strategy, m, r, gamma, C.byref(a), C.byref(b), C.byref(c)), "pop_strategy_counts")
+    return a.value, b.value, c.value
 
 
 def pop_layer_create(d, m, wdtype, w_gate, w_up, w_down, max_tokens, max_batch, stream=None):

@@ -272,6 +272,30 @@ int pop_k_for_ratio(int m, double r, int n_ret, int n_cand, int *k)
     return POP_OK;
 }
 
+int pop_strategy_counts(int strategy, int m, double r, double gamma, int *n_ret, int *n_cand, int *k)
+{
+    if (!n_ret || !n_cand || !k) return POP_EINVAL;
+    if (m <= 0 || !(r >= 0.0) || !(r <= 1.0) || !(gamma >= 0.0) || !(gamma <= 1.0)) return POP_EINVAL;
+    const int a = (int)floor((1.0 - r) * (double)m + 0.5);  // active channels per token
+    switch (strategy) {
+    case POP_STRATEGY_STATIC_MASK:
+        *n_ret = a, *n_cand = 0, *k = 0;
+        return POP_OK;
+    case POP_STRATEGY_RESCORE_ALL:
+        *n_ret = 0, *n_cand = m, *k = a;
+        return POP_OK;
+    case POP_STRATEGY_POP: {
+        if (1.0 - r - gamma / 2 < 0.0 || 1.0 - r + gamma / 2 > 1.0) return POP_EINVAL;
+        int n_prn = 0;
+        int rc = pop_region_counts(m, 1.0 - r - gamma / 2, gamma, n_ret, n_cand, &n_prn);
+        if (rc != POP_OK) return rc;
+        return pop_k_for_ratio(m, r, *n_ret, *n_cand, k);
+    }
+    default:
+        return POP_EINVAL;
+    }
+}
+
 int pop_layer_destroy(pop_layer_t *L)
 {
     if (!L) return POP_EINVAL;

@@ -4,6 +4,7 @@ import ctypes
 import os
 import re
 
+import numpy as np
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -62,6 +63,28 @@ def test_host_logic_matches_oracle(lib, oracle):
     with pytest.raises(pop.PopError):
         pop.pop_k_for_ratio(10, 1.5, 3, 3)
     assert pop.pop_strerror(0) == "ok" and "order" in pop.pop_strerror(pop.POP_ESTATE)
+
+
+def test_strategy_counts(lib, oracle):
+    """Region sizes of the ablation's decode strategies: the method's band from the oracle's count rules, the static
+    prefill mask as "everything active is retained", full re-scoring as "everything is a candidate"; all three keep
+    the same number of active channels per token."""
+    from paper_2602_06822_amd import binding as pop
+    for m in (7, 1376, 11008, 14336):
+        for r in (0.2, 0.35, 0.5):
+            a = int(np.floor((1.0 - r) * m + 0.5))
+            for gamma in (0.05, 0.1, 0.2):
+                n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r, gamma)
+                assert (n_ret, n_cand) == oracle.region_counts(m, 1.0 - r - gamma / 2, gamma)[:2]
+                assert k == oracle.k_for_ratio(m, r, n_ret, n_cand)
+                if n_cand >= 2:
+                    assert n_ret + k == a
+            assert pop.pop_strategy_counts(pop.POP_STRATEGY_STATIC_MASK, m, r, 0.1) == (a, 0, 0)
+            assert pop.pop_strategy_counts(pop.POP_STRATEGY_RESCORE_ALL, m, r, 0.1) == (0, m, a)
+    for bad in ((7, 100, 0.3, 0.1), (pop.POP_STRATEGY_POP, 100, 0.01, 0.1), (pop.POP_STRATEGY_POP, 100, 0.99, 0.1),
+                (pop.POP_STRATEGY_POP, 0, 0.3, 0.1)):
+        with pytest.raises(pop.PopError):
+            pop.pop_strategy_counts(*bad)
 
 
 def test_null_handle_is_an_error_not_a_crash(lib):
