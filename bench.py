@@ -236,6 +236,12 @@ def run(args):
                        note="whole call: both GEMMs, partition, mask, gather and the small kernels between them")
         del yp
 
+    # configs[2]: a 32-layer stack of this layer shape, one token through all layers (each layer its own weights,
+    # partition and input), as eager calls and as one captured HIP graph of 32 single-launch steps
+    stack = None
+    if not args.quick:
+        stack = time_layer_stack(pop, synth, lib, layers, counts(r_main), 32)
+
     fused_us = main.get("probe_mask_us")
     roofline = None
     if fused_us:
@@ -291,6 +297,7 @@ def run(args):
         "tokens_per_s_per_layer": round(1e6 / us, 1),
         "prefill_us_per_layer": round(main["prefill_us_per_layer"], 2),
         "prefill_forward": forward,
+        "stack_of_32_layers": stack,
         "active_GBps": round(bm["active"] / us / 1e3, 1),
         "algorithmic_GBps": round(bm["algorithmic"] / us / 1e3, 1),
         "frac_of_peak_active_bytes": round(bm["active"] / us / 1e3 / HBM_PEAK_GBS, 4),
@@ -303,6 +310,71 @@ def run(args):
         "cpu_baseline": cpu,
     }
     print(json.dumps(result))
+
+
+def time_layer_stack(pop, synth, lib, bench_layers, cnt, n_layers):
+    """One decode token through n_layers independent layers of the benchmark shape (device copies of the bench
+    layers' weights, each with its own partition and its own inputs): per-token time of the eager call sequence
+    (two launches per layer), of the single-launch steps, and of one captured graph of the single-launch steps."""
+    n_ret, n_cand, k = cnt
+    cfg = bench_layers[0].host_layer.cfg
+    d = cfg.d
+    to_dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda()  # noqa: E731
+    hs, xs = [], []
+    for i in range(n_layers):
+        src = bench_layers[i % len(bench_layers)]
+        L = src.host_layer
+        h = pop.pop_layer_create(cfg.d, cfg.m, pop.POP_BF16, to_dev(L.w_gate), to_dev(L.w_up), to_dev(L.w_down),
+                                 PROMPT, 1)
+        pop.pop_prefill_partition(h, src.x_prompt, PROMPT, n_ret, n_cand)
+        hs.append(h)
+        xs.append(src.x_decode[i // len(bench_layers)].clone())
+    y = torch.empty(d, dtype=torch.int16, device="cuda")
+    karr = (C.c_int * 1)(k)
+    side = torch.cuda.Stream()
+    out = {"layers": n_layers}
+    torch.cuda.synchronize()
+
+    def token(sp, single):
+        for h, x in zip(hs, xs):
+            if single:
+                rc = lib.pop_decode_step(h, C.c_void_p(x.data_ptr()), 1, karr, C.c_void_p(y.data_ptr()), pop.POP_BF16,
+                                         None, None, None, None, sp)
+            else:
+                rc = lib.pop_decode_mask(h, C.c_void_p(x.data_ptr()), 1, karr, None, None, None, None, sp)
+                rc = rc or lib.pop_pruned_ffn(h, None, 1, None, 0, C.c_void_p(y.data_ptr()), pop.POP_BF16, sp)
+            if rc:
+                raise pop.PopError(rc, "bench stack")
+
+    def timeit(fn, reps=8):
+        fn()
+        side.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(side)
+        for _ in range(reps):
+            fn()
+        e1.record(side)
+        side.synchronize()
+        return 1e3 * e0.elapsed_time(e1) / reps
+
+    with torch.cuda.stream(side):
+        sp = C.c_void_p(side.cuda_stream)
+        out["eager_two_launch_us_per_token"] = round(timeit(lambda: token(sp, False)), 1)
+        for h in hs:
+            pop.pop_layer_set_single_launch(h, True)
+        out["eager_single_launch_us_per_token"] = round(timeit(lambda: token(sp, True)), 1)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            token(C.c_void_p(torch.cuda.current_stream().cuda_stream), True)
+        out["graph_us_per_token"] = round(timeit(g.replay), 1)
+        for h in hs:
+            if pop.raw().pop_layer_sync_status(h, sp) != 0:
+                raise RuntimeError("a bounded wait expired during the stack benchmark")
+    del g
+    for h in hs:
+        pop.pop_layer_destroy(h)
+    torch.cuda.empty_cache()
+    return out
 
 
 def time_other_shapes(pop, synth, lib, stream):
