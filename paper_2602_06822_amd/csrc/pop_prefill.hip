@@ -1,21 +1,22 @@
 // Prefill: gate/up contraction over all m channels and all T prompt tokens, fused with the column-wise
 // importance reduction  s2[j] = sum_t H[t][j]^2  (Sec. 3.3 "Prefilling Stage"; Eq. 3: activation norm over
-// tokens and samples).  H itself is never written to memory.
+// tokens and samples).  In its plain form H is never written to memory.
 //
-// bf16: MFMA 32x32x16 tiles.  A workgroup (4 waves, 2 x 2) owns BM tokens (256, or 128 for short prompts) and a
-// chunk of up to 96 channels, i.e. up to 192 rows of the B operand (gate and up rows of the channel-major blocks
-// w[j] = [gate row | up row | down column]); a wave owns BM/2 tokens x 48 channels = 96 B rows, so each pair of LDS
-// fragment reads feeds about two MFMAs, which keeps the LDS port below the matrix cores' demand.  The chunk size is
-// chosen so that the tiles divide evenly over the compute units (one or a whole number of tiles each).  The 96 B
-// rows of a wave are three fragments: gate of its channels 0..31, up of the same channels (same lane and register
-// slot in the two accumulators, so silu(g)*u needs no exchange), and a mixed fragment [gate 32..47 | up 32..47]
-// whose halves meet through one cross-lane move in the epilogue.  Each accumulator lane holds 16 token rows of one
-// channel column, so the token reduction is in-register adds, one cross-half shuffle and a 2-wave LDS combine.
-// Token tiles write separate partial rows that are summed in tile order.
-// The same kernel, instantiated with kStore, serves the pruned FFN of a whole prompt (Sec. 3.4: the forward pass
-// under the pruning structure): its chunks run over a device-resident list of active channels instead of all m,
-// and the epilogue writes H (rounded to bf16, optionally times a per-token mask) in compact form [T][list position]
-// for the down projection instead of reducing its squares.
+// bf16: MFMA 32x32x16 tiles.  A workgroup owns BM tokens (256 with 8 waves, 4 along the tokens x 2 along the B rows;
+// 128 with 4 waves for short prompts) and a chunk of up to 96 channels, i.e. up to 192 rows of the B operand (gate
+// and up rows of the channel-major blocks w[j] = [gate row | up row | down column]); a wave owns 64 tokens x 48
+// channels = 96 B rows.  The 96 B rows of a wave are three fragments: gate of its channels 0..31, up of the same
+// channels (same lane and register slot in the two accumulators, so silu(g)*u needs no exchange), and a mixed
+// fragment [gate 32..47 | up 32..47] whose halves meet through one cross-lane move in the epilogue.  A second
+// tile form drops the mixed fragment (64 channels per chunk, 64 B rows per wave).  The chunk size is chosen so
+// that the tiles divide evenly over the compute units (one or a whole number of tiles each).  Each accumulator
+// lane holds 16 token rows of one channel column, so the token reduction is in-register adds, one cross-half
+// shuffle and an LDS combine of the token waves.  Token tiles write separate partial rows that are summed in
+// tile order.  The kernel is bound by its LDS fragment reads (two waves per SIMD cover each other's waits).
+// Two more forms of the same kernel serve the forward pass of a whole prompt under the pruning structure
+// (Sec. 3.4): one also writes H (rounded to bf16) as [T][m]; one runs its chunks over a device-resident list of
+// active channels instead of all m and writes H (optionally times a per-token mask) in compact form
+// [T][list position] for the down projection instead of reducing its squares.
 // float32: plain FMA tiles with the same structure (64 tokens x 32 channels per workgroup).
 #include "pop_internal.h"
 
