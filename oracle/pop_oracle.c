@@ -13,7 +13,9 @@
  *     H[T][m] = silu(X W_gate^T) * (X W_up^T); the importance of intermediate
  *     channel j aggregates the element scores |W_down[o][j]| * ||H[:,j]||_2 over
  *     o with an l2 norm.  With T = 1 this is the decode-step score taken from
- *     H_t (Sec. 3.4, two-step decoding).
+ *     H_t (Sec. 3.4, two-step decoding).  The alternative reading (Eq. 1-2
+ *     literally on the first projections and the FFN input) is
+ *     pop_oracle_importance_input_side.
  *   - Sec. 3.3 "Prefilling Stage": retained / candidate / pruned regions.  The
  *     quantile thresholds are realised as exact rank counts (n_ret, n_cand) in
  *     the total order (score descending, channel index ascending).
@@ -143,6 +145,43 @@ int pop_oracle_importance(const void *w_down, int dtype, int d, int m, const dou
         }
         I[j] = sqrt(acc);
     }
+    return ORACLE_OK;
+}
+
+/* The other reading of Sec. 3.1 (Eq. 1-2 taken literally for the FFN's first projections): the linear maps are
+ * W_gate and W_up [m][d], their input is the FFN input X[T][d], intermediate channel j is output channel j of both:
+ *   s_k       = sqrt(sum_t X[t][k]^2)                 (input activation norm over tokens and samples)
+ *   I^g_{j,k} = |W_gate[j][k]| * s_k,  I^u_{j,k} = |W_up[j][k]| * s_k      (element scores, Eq. 1)
+ *   I_j       = sqrt(sum_k (I^g_{j,k})^2 + (I^u_{j,k})^2)                  (l2 aggregate over the channel's weights)
+ * A channel is removed from both matrices at once, so its weights are both rows.  With T = 1, s_k = |x_k|: the
+ * decode-step score under this reading.  Only the listed channels are written (chan == NULL: all). */
+int pop_oracle_importance_input_side(const void *x, const void *w_gate, const void *w_up, int dtype, int T, int d,
+                                     int m, const int *chan, int n_chan, double *I)
+{
+    if (T < 0 || d <= 0 || m <= 0) return ORACLE_EINVAL;
+    double *s = (double *)malloc(sizeof(double) * (size_t)d);
+    if (!s) return ORACLE_EINVAL;
+    for (int k = 0; k < d; ++k) {
+        double s2 = 0.0;
+        for (int t = 0; t < T; ++t) {
+            double v = load_elem(x, dtype, (size_t)t * d + k);
+            s2 += v * v;
+        }
+        s[k] = sqrt(s2);
+    }
+    int n = chan ? n_chan : m;
+#pragma omp parallel for schedule(static)
+    for (int c = 0; c < n; ++c) {
+        int j = chan ? chan[c] : c;
+        double acc = 0.0;
+        for (int k = 0; k < d; ++k) {
+            double eg = fabs(load_elem(w_gate, dtype, (size_t)j * d + k)) * s[k];
+            double eu = fabs(load_elem(w_up, dtype, (size_t)j * d + k)) * s[k];
+            acc += eg * eg + eu * eu;
+        }
+        I[j] = sqrt(acc);
+    }
+    free(s);
     return ORACLE_OK;
 }
 

@@ -94,6 +94,21 @@ def importance(w_down, dtype, H, chan=None):
     return I
 
 
+def importance_input_side(x, w_gate, w_up, dtype, chan=None):
+    """Importance under the input-side reading of Eq. 1-2: I_j = || [W_gate[j,:], W_up[j,:]] * s ||_2 with
+    s_k = ||X[:,k]||_2 over the T rows of x."""
+    x, w_gate, w_up = _storage(x, dtype), _storage(w_gate, dtype), _storage(w_up, dtype)
+    T, d = x.shape
+    m = w_gate.shape[0]
+    assert w_gate.shape == (m, d) and w_up.shape == (m, d)
+    I = np.zeros(m, dtype=np.float64)
+    ch = None if chan is None else np.ascontiguousarray(chan, dtype=np.int32)
+    _check(lib().pop_oracle_importance_input_side(_p(x), _p(w_gate), _p(w_up), C.c_int(dtype), C.c_int(T),
+                                                  C.c_int(d), C.c_int(m), _p(ch), C.c_int(0 if ch is None else len(ch)),
+                                                  _p(I)), "importance_input_side")
+    return I
+
+
 def down_norms(w_down, dtype):
     w_down = _storage(w_down, dtype)
     d, m = w_down.shape

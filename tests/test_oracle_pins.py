@@ -149,6 +149,66 @@ def test_importance_token_order_and_sign_invariance(oracle):
     assert np.array_equal(np.delete(I2, 3), np.delete(I0, 3))
 
 
+# ---------------------------------------------------------------- importance, input-side reading of Eq. 1-2
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_input_side_importance_against_norms_and_loops(oracle, dtype):
+    """I_j = || [W_gate[j,:], W_up[j,:]] * s ||_2, s_k = ||X[:,k]||_2: numpy's norm routine on the weighted rows,
+    and the element scores of Eq. 1 summed one by one in Python on a few channels."""
+    d, m, T = 24, 30, 7
+    L = _tiny_layer(d, m, dtype, "inside")
+    x = synth.make_activations(L, T, "inside")
+    I = oracle.importance_input_side(x, L.w_gate, L.w_up, dtype)
+    X, Wg, Wu = (synth.storage_to_f64(a, dtype) for a in (x, L.w_gate, L.w_up))
+    s = np.linalg.norm(X, axis=0)
+    ref = np.linalg.norm(np.concatenate([Wg * s, Wu * s], axis=1), axis=1)
+    np.testing.assert_allclose(I, ref, rtol=1e-12)
+    for j in (0, 11, m - 1):
+        acc = 0.0
+        for k in range(d):
+            for t in range(T):
+                acc += (abs(Wg[j, k]) * abs(X[t, k])) ** 2 + (abs(Wu[j, k]) * abs(X[t, k])) ** 2
+        assert math.isclose(I[j], math.sqrt(acc), rel_tol=1e-12)
+    # listed channels only
+    part = oracle.importance_input_side(x, L.w_gate, L.w_up, dtype, chan=np.array([3, 9], np.int32))
+    assert part[3] == I[3] and part[9] == I[9] and not part[[0, 1, 2, 4]].any()
+
+
+def test_input_side_importance_closed_forms(oracle):
+    """One-hot input: I_j = |c| * hypot(W_gate[j,k0], W_up[j,k0]).  All-ones input over T tokens with W_up = 0:
+    I_j = sqrt(T) * ||W_gate[j,:]||.  Scaling x by a scales every score by |a|; scaling one channel's rows by b
+    scales that score alone; token order and signs do not matter."""
+    d, m, T = 16, 20, 5
+    L = _tiny_layer(d, m, F32, "inside_cf")
+    Wg, Wu = L.w_gate.astype(np.float64), L.w_up.astype(np.float64)
+    x = np.zeros((T, d), np.float32)
+    x[2, 5] = -3.0
+    I = oracle.importance_input_side(x, L.w_gate, L.w_up, F32)
+    np.testing.assert_allclose(I, 3.0 * np.hypot(Wg[:, 5], Wu[:, 5]), rtol=1e-13)
+    ones = np.ones((T, d), np.float32)
+    I = oracle.importance_input_side(ones, L.w_gate, np.zeros_like(L.w_up), F32)
+    np.testing.assert_allclose(I, math.sqrt(T) * np.linalg.norm(Wg, axis=1), rtol=1e-13)
+    x = synth.make_activations(L, T, "inside_cf")
+    I = oracle.importance_input_side(x, L.w_gate, L.w_up, F32)
+    np.testing.assert_allclose(oracle.importance_input_side(-2.0 * x, L.w_gate, L.w_up, F32), 2.0 * I, rtol=1e-13)
+    wg2, wu2 = L.w_gate.copy(), L.w_up.copy()
+    wg2[7] *= 4.0
+    wu2[7] *= 4.0
+    I2 = oracle.importance_input_side(x, wg2, wu2, F32)
+    assert math.isclose(I2[7], 4.0 * I[7], rel_tol=1e-13)
+    assert np.array_equal(np.delete(I2, 7), np.delete(I, 7))
+    perm = np.array([4, 0, 3, 1, 2])
+    flip = np.array([1, -1, 1, -1, -1], np.float32)[:, None]
+    np.testing.assert_allclose(oracle.importance_input_side(x[perm] * flip, L.w_gate, L.w_up, F32), I, rtol=1e-13)
+    # one token: s = |x|
+    I1 = oracle.importance_input_side(x[:1], L.w_gate, L.w_up, F32)
+    xa = np.abs(x[0].astype(np.float64))
+    np.testing.assert_allclose(I1, np.sqrt(((Wg * xa) ** 2 + (Wu * xa) ** 2).sum(axis=1)), rtol=1e-13)
+    # it is a different quantity from the output-side importance
+    H = oracle.hidden(x, L.w_gate, L.w_up, F32)
+    assert not np.allclose(I, oracle.importance(L.w_down, F32, H), rtol=1e-2)
+
+
 def test_directed_weight_scaling_moves_channel(oracle):
     """Scaling a channel's down-projection column by 1e3 puts it in R; zeroing it puts it in P."""
     d, m, T = 32, 64, 8
