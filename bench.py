@@ -255,6 +255,17 @@ def run(args):
                         avg_launch_us=round(fused_us, 3), tail_kernel_us=round(main["probe_ffn_us"], 3),
                         note="event-bracketed durations include the launch gap of each call")
 
+    # the same workload under the input-side reading of the importance (selection first, then the forward pass over
+    # retained + selected channels; separate launches, no fused kernel); last use of these layers
+    input_side = None
+    if not args.quick:
+        for L in layers:
+            pop.pop_layer_set_importance(L.handle, pop.POP_IMPORTANCE_INPUT_SIDE)
+        t = timed(r_main, 1, 1, single=True)
+        input_side = dict(decode_us_per_token=round(t["decode_us_per_token"], 3),
+                          prefill_us_per_layer=round(t["prefill_us_per_layer"], 2),
+                          MB_per_token=round((3 * (n_ret + k) + 2 * (n_cand - k)) * d * 2 / 1e6, 2))
+
     other_configs = None
     host_layer0 = layers[0].host_layer
     if not args.quick:
@@ -298,6 +309,7 @@ def run(args):
         "prefill_us_per_layer": round(main["prefill_us_per_layer"], 2),
         "prefill_forward": forward,
         "stack_of_32_layers": stack,
+        "input_side_importance_reading": input_side,
         "active_GBps": round(bm["active"] / us / 1e3, 1),
         "algorithmic_GBps": round(bm["algorithmic"] / us / 1e3, 1),
         "frac_of_peak_active_bytes": round(bm["active"] / us / 1e3 / HBM_PEAK_GBS, 4),

@@ -180,6 +180,19 @@ int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
 /* Host only.  See pop_decode_step. */
 int pop_layer_set_single_launch(pop_layer_t *layer, int on);
+/* Host only.  Which reading of Sec. 3.1 defines channel importance on this layer (the paper's equations admit two):
+ *   POP_IMPORTANCE_OUTPUT_SIDE (default)  the down projection and the intermediate activations, as at the top of
+ *       this file; the decode step scores candidates from h (Sec. 3.4's two-step decoding).
+ *   POP_IMPORTANCE_INPUT_SIDE             Eq. 1-2 literally on the first projections and the FFN input:
+ *       I_j = || [W_gate[j,:], W_up[j,:]] * s ||_2,  s_k = sqrt(sum over tokens of x[t][k]^2)  (a channel is removed
+ *       from both matrices, so its weights are both rows); at a decode step s_k = |x_k|, per sequence.  Prefill
+ *       then needs no contraction (one pass over the gate and up rows), and a decode step selects first and runs
+ *       the forward pass over retained and selected channels only: h of an unselected candidate is not computed,
+ *       and pop_layer_get_hidden is defined on active channels only.  The step runs as separate launches (no fused
+ *       kernel); the shared batch mask is not available (POP_EUNSUPPORTED).
+ * Changing the reading discards the layer's partition (prefill again).  Errors: unknown value -> POP_EINVAL. */
+enum { POP_IMPORTANCE_OUTPUT_SIDE = 0, POP_IMPORTANCE_INPUT_SIDE = 1 };
+int pop_layer_set_importance(pop_layer_t *layer, int reading);
 /* Host only.  How a decode step with B > 1 scores its candidates.  off (default): every sequence by its own
  * activation, I_j = n_j |h_bj|, its own top-k and mask.  on: the activation norm of Eq. 3 runs over the step's B
  * sequences ("tokens and samples", Sec. 3.1), I_j = n_j sqrt(sum_b h_bj^2), and one selection serves the whole

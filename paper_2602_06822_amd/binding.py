@@ -52,6 +52,7 @@ _SIGS = {
     "pop_layer_step_kind": (_i, [_vp, _ip]),
     "pop_layer_set_single_launch": (_i, [_vp, _i]),
     "pop_layer_set_shared_batch_mask": (_i, [_vp, _i]),
+    "pop_layer_set_importance": (_i, [_vp, _i]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _fn = getattr(_lib, _name)
@@ -203,6 +204,13 @@ def pop_layer_sync_status(layer, stream=None):
 
 def pop_layer_set_single_launch(layer, on: bool):
     _check(_lib.pop_layer_set_single_launch(layer, 1 if on else 0), "pop_layer_set_single_launch")
+
+
+POP_IMPORTANCE_OUTPUT_SIDE, POP_IMPORTANCE_INPUT_SIDE = 0, 1
+
+
+def pop_layer_set_importance(layer, reading: int):
+    _check(_lib.pop_layer_set_importance(layer, reading), "pop_layer_set_importance")
 
 
 def pop_layer_set_shared_batch_mask(layer, on: bool):

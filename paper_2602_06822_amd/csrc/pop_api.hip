@@ -43,6 +43,9 @@ struct pop_layer {
     int n_cu = 0, wg_target = 0;
     bool single_launch = false;  // pop_decode_step at B = 1: sum the partial outputs inside the fused kernel
     bool shared_mask = false;    // B > 1: one selection for the batch from scores aggregated over its sequences
+    bool input_side = false;     // importance from the first projections and the FFN input (pop_layer_set_importance)
+    float *in_s2 = nullptr;      // [max_batch][d]: squared input norms (input-side importance)
+    double *in_part = nullptr;   // [row groups][d]: their partial sums over a prompt
     // partition
     bool has_partition = false;
     int n_ret = 0, n_cand = 0;
@@ -170,7 +173,8 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
                      int *cand_idx, hipStream_t s)
 {
     const int m = L->m;
-    POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16), m, L->nrm, L->scores, s));
+    if (!L->input_side)  // (the input-side scores are already in place)
+        POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16), m, L->nrm, L->scores, s));
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s));
     if (n_cand) POP_HIP(hipMemcpyAsync(L->rc_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
     if (n_ret) POP_HIP(hipMemcpyAsync(L->rc_idx + n_cand, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
@@ -181,6 +185,7 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     L->n_ret = n_ret;
     L->n_cand = n_cand;
     { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
+    if (L->input_side) L->fused_ok = false;  // the fused kernel scores candidates from h
     POP_HIP(launch_fill_int(L->sync, 16, 0, s));
     POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
@@ -301,7 +306,7 @@ int pop_layer_destroy(pop_layer_t *L)
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
                     L->h,      L->cscore, L->mask, L->selflag, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
-                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall};
+                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -403,7 +408,12 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
     const int m = L->m;
     L->has_partition = false;
     L->has_step = false;
-    POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s));
+    if (L->input_side) {
+        POP_HIP(launch_input_norms(x, L->is_bf16, T, L->d, L->in_part, L->in_s2, s));
+        POP_HIP(launch_input_side_scores(L->w, L->is_bf16, L->d, L->in_s2, 1, nullptr, m, L->scores, m, s));
+    } else {
+        POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s));
+    }
     return finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s);
 }
 
@@ -418,7 +428,9 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     if (k0 < 0 || k0 > n_cand) return POP_ESHAPE;
     hipStream_t s = as_stream(stream);
     const int m = L->m, d = L->d;
-    const bool keep = L->is_bf16 && T >= kFfnMfmaMinTokens;  // H is kept and the output runs on the matrix cores
+    // H of the importance contraction is kept and the output runs on the matrix cores (the input-side importance
+    // has no such contraction: partition first, then the masked FFN)
+    const bool keep = L->is_bf16 && T >= kFfnMfmaMinTokens && !L->input_side;
     L->has_partition = false;
     L->has_step = false;
     int ldh = 0, n_split = 1;
@@ -428,7 +440,12 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
         POP_HIP(launch_prefill_gateup_keep_bf16(L->w, d, m, x, T, L->s2_part, L->ffn_hall, ldh, L->n_cu, s));
     } else {
         if (!L->ffn_any && hipMalloc((void **)&L->ffn_any, ((size_t)m + 3) / 4 * 4) != hipSuccess) return POP_ENOMEM;
-        POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, d, m, x, T, L->s2_part, L->n_cu, s));
+        if (L->input_side) {
+            POP_HIP(launch_input_norms(x, L->is_bf16, T, d, L->in_part, L->in_s2, s));
+            POP_HIP(launch_input_side_scores(L->w, L->is_bf16, d, L->in_s2, 1, nullptr, m, L->scores, m, s));
+        } else {
+            POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, d, m, x, T, L->s2_part, L->n_cu, s));
+        }
     }
     { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s); if (rc != POP_OK) return rc; }
     // prefill mask: retained channels plus the best k0 candidates by prefill score; the active list (retained, then
@@ -474,6 +491,28 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
             if (!L->ulist_prefix_ok && n_ret)
                 POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
             L->ulist_prefix_ok = true;
+        }
+        if (L->input_side) {
+            // candidates are scored from their gate and up rows and |x_t| alone, so the selection comes first and
+            // the forward pass runs over retained and selected channels only
+            if (B > 1 && L->shared_mask) return POP_EUNSUPPORTED;
+            POP_HIP(launch_input_squares(x_t, L->is_bf16, B, L->d, L->in_s2, s));
+            POP_HIP(launch_input_side_scores(L->w, L->is_bf16, L->d, L->in_s2, B, L->cand_idx, n_cand, L->cscore, m, s));
+            POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx,
+                                L->n_active, nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
+                                s));
+            if (B == 1)
+                POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, 1, L->active_idx, n_ret + kk.k[0], nullptr, L->h,
+                                      nullptr, nullptr, 0, 0, L->n_cu, s));
+            else
+                POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, B, L->ulist, m, L->n_ulist, L->h, nullptr, nullptr,
+                                      0, 0, L->n_cu, s));
+            L->step_fused = false;
+            { int rc = copy_step_outputs(L, B, cand_scores, mask, active_idx, n_active, s); if (rc != POP_OK) return rc; }
+            L->step_B = B;
+            L->step_k = kk;
+            L->has_step = true;
+            return POP_OK;
         }
         bool sel_inside = false;
         const bool shared = B > 1 && L->shared_mask;
@@ -626,6 +665,21 @@ int pop_layer_sync_status(pop_layer_t *L, void *stream)
     POP_HIP(hipMemcpyAsync(&flag, L->sync + 2, 4, hipMemcpyDeviceToHost, as_stream(stream)));
     POP_HIP(hipStreamSynchronize(as_stream(stream)));
     return flag ? POP_EDEVICE : POP_OK;
+}
+
+int pop_layer_set_importance(pop_layer_t *L, int reading)
+{
+    if (!L) return POP_EINVAL;
+    if (reading != POP_IMPORTANCE_OUTPUT_SIDE && reading != POP_IMPORTANCE_INPUT_SIDE) return POP_EINVAL;
+    if (reading == POP_IMPORTANCE_INPUT_SIDE && !L->in_s2) {
+        const size_t groups = (size_t)input_side_groups(L->max_tokens);
+        if (hipMalloc((void **)&L->in_s2, (size_t)L->max_batch * L->d * sizeof(float)) != hipSuccess) return POP_ENOMEM;
+        if (hipMalloc((void **)&L->in_part, groups * L->d * sizeof(double)) != hipSuccess) return POP_ENOMEM;
+    }
+    L->input_side = reading == POP_IMPORTANCE_INPUT_SIDE;
+    L->has_partition = false;
+    L->has_step = false;
+    return POP_OK;
 }
 
 int pop_layer_set_shared_batch_mask(pop_layer_t *L, int on)

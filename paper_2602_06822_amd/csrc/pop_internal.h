@@ -193,6 +193,15 @@ hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const vo
 // hc[t][c] = h_all[t][list[c]] for c < *n_list <= max_list.
 hipError_t launch_compact_hidden(const uint16_t *h_all, int ldh, int T, const int *list, const int *n_list, int max_list,
                                  uint16_t *hc, int ldhc, hipStream_t s);
+// ---- input-side importance (pop_input_side.hip) ----
+int input_side_groups(int T);  // row groups of a T-token prompt (sizes part below: [groups][d] doubles)
+// s2[k] = sum_t x[t][k]^2 over the T rows (fixed summation order)
+hipError_t launch_input_norms(const void *x, int is_bf16, int T, int d, double *part, float *s2, hipStream_t s);
+// s2[b][k] = x[b][k]^2
+hipError_t launch_input_squares(const void *x, int is_bf16, int B, int d, float *s2, hipStream_t s);
+// out[q][p] = sqrt(sum_k (w_gate[j][k]^2 + w_up[j][k]^2) s2[q][k]), j = rows ? rows[p] : p, q < S, p < n_rows
+hipError_t launch_input_side_scores(const void *w, int is_bf16, int d, const float *s2, int S, const int *rows,
+                                    int n_rows, float *out, int out_stride, hipStream_t s);
 // cs[b][p] <- sqrt(sum over b' < B of cs[b'][p]^2) for every b < B, p < n
 hipError_t launch_aggregate_scores(float *cs, int cs_stride, int B, int n, hipStream_t s);
 // out[i] = src[idx[i]], i < n

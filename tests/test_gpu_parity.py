@@ -381,6 +381,63 @@ def test_shared_batch_mask(pop, oracle, dtype):
         _check_decode(oracle, G, L, region, cand, xt, k)
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_input_side_importance(pop, oracle, dtype):
+    """The other reading of Eq. 1-2 (first projections and the FFN input): prefill scores and partition, decode
+    steps that select first and then run the forward pass over retained + selected channels, per-sequence masks
+    at B > 1, the prompt's pruned output; and back to the default reading on the same handle."""
+    d, m, T = 264 if dtype == BF16 else 260, 301, 45
+    L = synth.make_layer(synth.small_config("input_side", d, m, dtype))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 3, "decode")
+    n_ret, n_cand, k = 140, 90, 37
+    with GpuLayer(pop, L, max_tokens=T, max_batch=4) as G:
+        pop.pop_layer_set_importance(G.handle, pop.POP_IMPORTANCE_INPUT_SIDE)
+        with pytest.raises(pop.PopError) as e:  # the partition of another reading is gone
+            G.n_ret, G.n_cand = n_ret, n_cand
+            G.decode(xt[:1], k)
+        assert e.value.status == pop.POP_ESTATE
+        scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+        s_ref = oracle.importance_input_side(x, L.w_gate, L.w_up, dtype)
+        assert score_rel_err(scores, s_ref, eps=1e-6) <= SCORE_TOL
+        r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+        assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1)
+        for xb, ks in ((xt[:1], [k]), (xt, [k, 0, n_cand])):
+            for one_call in (False, True):
+                out = G.decode(xb, ks, one_call=one_call)
+                assert pop.pop_layer_step_kind(G.handle)[0] == 2
+                for b in range(xb.shape[0]):
+                    c_ref = oracle.importance_input_side(xb[b:b + 1], L.w_gate, L.w_up, dtype, chan=cand)[cand]
+                    assert score_rel_err(out["cscore"][b], c_ref, eps=1e-6) <= SCORE_TOL
+                    mask1, sel1, act1 = oracle.select(region, out["cscore"][b], cand, ks[b])
+                    assert np.array_equal(out["mask"][b], mask1)
+                    assert out["n_active"][b] == n_ret + ks[b]
+                    assert np.array_equal(out["active_idx"][b][:n_ret + ks[b]], act1)
+                    active = np.flatnonzero(mask1).astype(np.int32)
+                    H = oracle.hidden(xb[b:b + 1], L.w_gate, L.w_up, dtype, chan=active)
+                    assert score_rel_err(out["h"][b][active], H[0][active], eps=DECODE_FLOOR[dtype]) <= SCORE_TOL
+                    y_ref = oracle.down(H, L.w_down, dtype, mask1)[0]
+                    assert max_abs_rel(out["y"][b], y_ref) <= Y_TOL[dtype]
+        # the prompt's own forward pass under this reading's prefill mask
+        tol = Y_TOL[BF16] if dtype == BF16 else 1e-4
+        sc2, region2, _, cand2, mask, y = G.prefill_forward(x, n_ret, n_cand, 20, F32)
+        assert np.array_equal(sc2, scores) and np.array_equal(region2, region)
+        mask1, _, _ = oracle.select(region, scores[cand], cand, 20)
+        assert np.array_equal(mask, mask1)
+        y_ref = oracle.pruned_ffn(x, L.w_gate, L.w_up, L.w_down, dtype, mask)
+        assert max_abs_rel(y, y_ref) <= (FFN_MFMA_TOL_F32 if dtype == BF16 else tol)
+        pop.pop_layer_set_shared_batch_mask(G.handle, True)
+        with pytest.raises(pop.PopError) as e:
+            G.decode(xt, k)
+        assert e.value.status == pop.POP_EUNSUPPORTED
+        pop.pop_layer_set_shared_batch_mask(G.handle, False)
+        # back to the default reading
+        pop.pop_layer_set_importance(G.handle, pop.POP_IMPORTANCE_OUTPUT_SIDE)
+        _, region_b, _, cand_b, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        assert not np.array_equal(region_b, region)
+        _check_decode(oracle, G, L, region_b, cand_b, xt[:1], k)
+
+
 def test_importance_reduce_standalone(pop, oracle):
     T, m = 77, 1000
     g = synth.rng("impred")
