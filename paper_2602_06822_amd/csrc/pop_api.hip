@@ -173,20 +173,27 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
                      int *cand_idx, hipStream_t s)
 {
     const int m = L->m;
-    if (!L->input_side)  // (the input-side scores are already in place)
+    // the partition launch also forms the scores from the contraction's partial rows (the input-side scores are
+    // already in place) and clears the step counters; one more launch writes everything that is constant per
+    // partition: retained bytes of every mask row, retained prefix of every active list and of the union list, the
+    // candidate-then-retained list
+    PartitionExtra ex;
+    const bool from_partials = !L->input_side && partition_takes_partials(m);
+    if (!L->input_side && !from_partials)
         POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16), m, L->nrm, L->scores, s));
-    POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s));
-    if (n_cand) POP_HIP(hipMemcpyAsync(L->rc_idx, L->cand_idx, (size_t)n_cand * 4, hipMemcpyDeviceToDevice, s));
-    if (n_ret) POP_HIP(hipMemcpyAsync(L->rc_idx + n_cand, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
-    // partition-constant step state: retained bytes of every mask row, retained prefix of every active list
-    POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s));
-    if (n_ret) POP_HIP(hipMemcpyAsync(L->ulist, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
+    if (from_partials) {
+        ex.s2_part = L->s2_part, ex.n_tiles = prefill_rows_used(T, L->is_bf16), ex.nrm = L->nrm;
+        ex.scores_out = L->scores;
+    }
+    ex.sync = L->sync, ex.n_sync = 16;
+    POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s, &ex));
+    POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s,
+                                   L->cand_idx, n_cand, L->rc_idx, L->ulist));
     L->ulist_prefix_ok = true;
     L->n_ret = n_ret;
     L->n_cand = n_cand;
     { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
     if (L->input_side) L->fused_ok = false;  // the fused kernel scores candidates from h
-    POP_HIP(launch_fill_int(L->sync, 16, 0, s));
     POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));

@@ -83,9 +83,21 @@ hipError_t launch_repack(const void *w_gate, const void *w_up, const void *w_dow
                          void *w, float *nrm, int is_bf16, hipStream_t s);
 
 // ---- selection (pop_select.hip) ----
-// Regions by rank of scores[m]; outputs may be null.
+// Regions by rank of scores[m]; outputs may be null.  Two things the prefill call needs can ride in the same
+// launch: the scores themselves from the prefill kernel's partial rows (scores[j] = nrm[j] * sqrt(sum over tiles,
+// in order, of s2_part[tile][j]), written to scores_out and used instead of the scores argument; only when
+// partition_takes_partials(m)), and n_sync <= 1024 counters to clear.
+struct PartitionExtra {
+    const float *s2_part = nullptr;
+    int n_tiles = 0;
+    const float *nrm = nullptr;
+    float *scores_out = nullptr;
+    int *sync = nullptr;
+    int n_sync = 0;
+};
+bool partition_takes_partials(int m);
 hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
-                            int *cand_idx, hipStream_t s);
+                            int *cand_idx, hipStream_t s, const PartitionExtra *extra = nullptr);
 // Per sequence b (grid = B): select k.k[b] of n_cand candidates by cscore[b*cs_stride + i]; writes the candidate
 // bytes of mask[b][m], active_idx[b*act_stride + n_ret .. n_ret+k), n_active[b], sel_idx (sequence 0, only when
 // active_idx is null), each if non-null.  With union_list non-null also: selflag [B][n_cand] (scratch), and the
@@ -96,8 +108,11 @@ hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, 
                        BatchK k, int act_stride, unsigned char *mask, int *active_idx, int *n_active, int *sel_idx,
                        unsigned char *selflag, int *union_ctr, int *union_list, int *n_union, hipStream_t s);
 // Partition-constant step state: mask[b][j] = (region[j] == retained), active_idx[b][0..n_ret) = ret_idx.
+// With cand_idx / rc_idx / ulist given it also writes rc_idx = cand_idx ++ ret_idx and ulist[0..n_ret) = ret_idx.
 hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
-                                  int act_stride, unsigned char *mask, int *active_idx, hipStream_t s);
+                                  int act_stride, unsigned char *mask, int *active_idx, hipStream_t s,
+                                  const int *cand_idx = nullptr, int n_cand = 0, int *rc_idx = nullptr,
+                                  int *ulist = nullptr);
 // mask rows -> ascending list of channels active in any row.
 hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s);
 

@@ -16,12 +16,44 @@ constexpr int kPartLdsKeys = 24576;  // 96 KiB of keys
 
 __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict__ scores, int m, int n_ret, int n_cand,
                                                          unsigned char *__restrict__ region, int *__restrict__ ret_idx,
-                                                         int *__restrict__ cand_idx)
+                                                         int *__restrict__ cand_idx, PartitionExtra ex)
 {
     __shared__ SelShared sh;
     extern __shared__ uint32_t part_keys[];  // [m] when m <= kPartLdsKeys
     const bool in_lds = m <= kPartLdsKeys;
-    if (in_lds) {
+    if (ex.sync && threadIdx.x < ex.n_sync) ex.sync[threadIdx.x] = 0;
+    if (in_lds && ex.s2_part) {
+        // scores straight from the prefill kernel's partial rows (Eq. 3), kept for the caller as well
+        for (int base = 0; base < m; base += 4 * blockDim.x) {
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            float nr[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * blockDim.x + threadIdx.x;
+                nr[u] = ex.nrm[i < m ? i : 0];
+            }
+            for (int t = 0; t < ex.n_tiles; ++t) {
+                float v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int i = base + u * blockDim.x + threadIdx.x;
+                    v[u] = ex.s2_part[(size_t)t * m + (i < m ? i : 0)];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[u] += (double)v[u];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = base + u * blockDim.x + threadIdx.x;
+                if (i < m) {
+                    const float sc = (float)((double)nr[u] * sqrt(acc[u]));
+                    ex.scores_out[i] = sc;
+                    part_keys[i] = score_key(sc);
+                }
+            }
+        }
+        __syncthreads();
+    } else if (in_lds) {
         for (int base = 0; base < m; base += 8 * blockDim.x) {
             float v[8];
 #pragma unroll
@@ -85,16 +117,21 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
     }
 }
 
+bool partition_takes_partials(int m) { return m <= kPartLdsKeys; }
+
 hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
-                            int *cand_idx, hipStream_t s)
+                            int *cand_idx, hipStream_t s, const PartitionExtra *extra)
 {
+    PartitionExtra ex = extra ? *extra : PartitionExtra{};
+    if (ex.s2_part && !partition_takes_partials(m)) return hipErrorInvalidValue;
     const size_t lds = m <= kPartLdsKeys ? (size_t)m * 4 : 0;
     if (lds > 32 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&partition_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(partition_kernel, dim3(1), dim3(1024), lds, s, scores, m, n_ret, n_cand, region, ret_idx, cand_idx);
+    hipLaunchKernelGGL(partition_kernel, dim3(1), dim3(1024), lds, s, scores, m, n_ret, n_cand, region, ret_idx, cand_idx,
+                       ex);
     return hipGetLastError();
 }
 
@@ -158,25 +195,35 @@ hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, 
 }
 
 // Partition-constant part of the step state, for `rows` sequences: mask[b][j] = 1 for retained channels, 0 for
-// pruned and (until a step selects them) candidate channels; active_idx[b][0..n_ret) = ret_idx.
+// pruned and (until a step selects them) candidate channels; active_idx[b][0..n_ret) = ret_idx.  Row 0's workgroups
+// also write the candidate-then-retained list rc_idx and the retained prefix of the union list, when given.
 __global__ __launch_bounds__(256) void step_state_init_kernel(const unsigned char *__restrict__ region, int m,
                                                               const int *__restrict__ ret_idx, int n_ret, int rows,
                                                               int act_stride, unsigned char *__restrict__ mask,
-                                                              int *__restrict__ active_idx)
+                                                              int *__restrict__ active_idx,
+                                                              const int *__restrict__ cand_idx, int n_cand,
+                                                              int *__restrict__ rc_idx, int *__restrict__ ulist)
 {
     const int b = blockIdx.y;
     for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < m; j += gridDim.x * blockDim.x) {
         if (mask) mask[(size_t)b * m + j] = region[j] == POP_REGION_RETAINED ? 1 : 0;
-        if (active_idx && j < n_ret) active_idx[(size_t)b * act_stride + j] = ret_idx[j];
+        if (j < n_ret) {
+            const int r = ret_idx[j];
+            if (active_idx) active_idx[(size_t)b * act_stride + j] = r;
+            if (b == 0 && rc_idx) rc_idx[n_cand + j] = r;
+            if (b == 0 && ulist) ulist[j] = r;
+        }
+        if (b == 0 && rc_idx && j < n_cand) rc_idx[j] = cand_idx[j];
     }
 }
 
 hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
-                                  int act_stride, unsigned char *mask, int *active_idx, hipStream_t s)
+                                  int act_stride, unsigned char *mask, int *active_idx, hipStream_t s,
+                                  const int *cand_idx, int n_cand, int *rc_idx, int *ulist)
 {
     dim3 grid((m + 255) / 256, rows);
     hipLaunchKernelGGL(step_state_init_kernel, grid, dim3(256), 0, s, region, m, ret_idx, n_ret, rows, act_stride, mask,
-                       active_idx);
+                       active_idx, cand_idx, n_cand, rc_idx, ulist);
     return hipGetLastError();
 }
 

@@ -568,6 +568,17 @@ def test_error_paths(pop):
         mask = torch.ones((2, m), dtype=torch.uint8, device="cuda")
         assert status(pop.pop_pruned_ffn, G.handle, x, 4, mask, 2, y, F32) == pop.POP_ESHAPE
         assert status(pop.pop_pruned_ffn, G.handle, None, 2, mask, 2, y, F32) == pop.POP_EINVAL
+        y8 = torch.empty((8, d), dtype=torch.float32, device="cuda")
+        assert status(pop.pop_prefill_forward, G.handle, x, 8, 10, 10, 11, y8, F32) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_forward, G.handle, x, 8, 10, 10, -1, y8, F32) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_forward, G.handle, x, 9, 10, 10, 5, y8, F32) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_forward, G.handle, x, 8, 10, 10, 5, None, F32) == pop.POP_EINVAL
+        assert status(pop.pop_prefill_forward, G.handle, x, 8, 10, 10, 5, y8, 3) == pop.POP_EINVAL
+        assert status(pop.pop_layer_set_importance, G.handle, 2) == pop.POP_EINVAL
+        assert status(pop.pop_layer_set_importance, None, 0) == pop.POP_EINVAL
+        assert status(pop.pop_layer_set_shared_batch_mask, None, 1) == pop.POP_EINVAL
+        # a failed call leaves the earlier partition usable
+        pop.pop_decode_mask(G.handle, x, 2, [3, 4])
         torch.cuda.synchronize()
     s = torch.zeros(10, dtype=torch.float32, device="cuda")
     assert status(pop.pop_partition_from_scores, s, 10, 6, 5) == pop.POP_ESHAPE
