@@ -214,7 +214,7 @@ def run(args):
     # the prefilling stage with its output (pop_prefill_forward: contraction that keeps H, partition, prefill mask,
     # gathered columns, down-projection GEMM over the active channels), rotated over the layers
     forward = None
-    if not args.quick:
+    if not args.quick or args.forward:
         yp = torch.empty((PROMPT, d), dtype=torch.int16, device="cuda")
         fcalls = [(L.handle, C.c_void_p(L.x_prompt.data_ptr()), PROMPT, n_ret, n_cand, k, C.c_void_p(yp.data_ptr()),
                    pop.POP_BF16, None, None, None, None, None, sp) for L in layers]
@@ -482,6 +482,7 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=384)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 256 MiB device copies")
+    ap.add_argument("--forward", action="store_true", help="with --quick: keep the prefill-forward section")
     ap.add_argument("--quick", action="store_true", help="main line only: skip other sparsities and the warm figure")
     args = ap.parse_args()
     if args.gpus != 1:
