@@ -126,12 +126,21 @@ constexpr int kFfnMfmaMinTokens = 32;
 // Whole-prompt pruned FFN (Sec. 3.4: forward pass under the pruning structure): active list from the mask(s),
 // gate/up over the listed channels with H written in compact bf16 form, then the K-gathered down-projection GEMM.
 // Scratch grows on demand; growing synchronises the device (hipFree).
+// hipMalloc that leaves no pending error behind when it fails (a later launch check would report it as its own).
+bool dev_alloc(void **p, size_t bytes)
+{
+    if (hipMalloc(p, bytes) == hipSuccess) return true;
+    (void)hipGetLastError();
+    *p = nullptr;
+    return false;
+}
+
 int grow(void **p, size_t *cap, size_t need, size_t esize)
 {
     if (need <= *cap) return POP_OK;
     if (*p) POP_HIP(hipFree(*p));
     *p = nullptr, *cap = 0;
-    if (hipMalloc(p, need * esize) != hipSuccess) return POP_ENOMEM;
+    if (!dev_alloc(p, need * esize)) return POP_ENOMEM;
     *cap = need;
     return POP_OK;
 }
@@ -144,7 +153,7 @@ int ffn_scratch(pop_layer *L, int T, bool keep_all, int *ldh, int *n_split)
     if (rc == POP_OK && *n_split > 1)
         rc = grow((void **)&L->ffn_part, &L->ffn_part_cap, (size_t)*n_split * T * L->d, sizeof(float));
     if (rc == POP_OK && keep_all) rc = grow((void **)&L->ffn_hall, &L->ffn_hall_cap, (size_t)T * *ldh, sizeof(uint16_t));
-    if (rc == POP_OK && !L->ffn_any && hipMalloc((void **)&L->ffn_any, ((size_t)L->m + 3) / 4 * 4) != hipSuccess)
+    if (rc == POP_OK && !L->ffn_any && !dev_alloc((void **)&L->ffn_any, ((size_t)L->m + 3) / 4 * 4))
         rc = POP_ENOMEM;
     return rc;
 }
@@ -446,7 +455,7 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
         if (rc != POP_OK) return rc;
         POP_HIP(launch_prefill_gateup_keep_bf16(L->w, d, m, x, T, L->s2_part, L->ffn_hall, ldh, L->n_cu, s));
     } else {
-        if (!L->ffn_any && hipMalloc((void **)&L->ffn_any, ((size_t)m + 3) / 4 * 4) != hipSuccess) return POP_ENOMEM;
+        if (!L->ffn_any && !dev_alloc((void **)&L->ffn_any, ((size_t)m + 3) / 4 * 4)) return POP_ENOMEM;
         if (L->input_side) {
             POP_HIP(launch_input_norms(x, L->is_bf16, T, d, L->in_part, L->in_s2, s));
             POP_HIP(launch_input_side_scores(L->w, L->is_bf16, d, L->in_s2, 1, nullptr, m, L->scores, m, s));
@@ -678,10 +687,12 @@ int pop_layer_set_importance(pop_layer_t *L, int reading)
 {
     if (!L) return POP_EINVAL;
     if (reading != POP_IMPORTANCE_OUTPUT_SIDE && reading != POP_IMPORTANCE_INPUT_SIDE) return POP_EINVAL;
-    if (reading == POP_IMPORTANCE_INPUT_SIDE && !L->in_s2) {
+    if (reading == POP_IMPORTANCE_INPUT_SIDE) {
         const size_t groups = (size_t)input_side_groups(L->max_tokens);
-        if (hipMalloc((void **)&L->in_s2, (size_t)L->max_batch * L->d * sizeof(float)) != hipSuccess) return POP_ENOMEM;
-        if (hipMalloc((void **)&L->in_part, groups * L->d * sizeof(double)) != hipSuccess) return POP_ENOMEM;
+        if (!L->in_s2 && !dev_alloc((void **)&L->in_s2, (size_t)L->max_batch * L->d * sizeof(float)))
+            return POP_ENOMEM;
+        if (!L->in_part && !dev_alloc((void **)&L->in_part, groups * L->d * sizeof(double)))
+            return POP_ENOMEM;
     }
     L->input_side = reading == POP_IMPORTANCE_INPUT_SIDE;
     L->has_partition = false;
