@@ -72,8 +72,12 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
     auto key = [&](int i) { return in_lds ? part_keys[i] : score_key(scores[i]); };
     uint32_t kth_a, kth_b;
     int take_a, take_b;
-    radix_threshold(key, m, n_ret, sh, kth_a, take_a);
-    radix_threshold(key, m, n_ret + n_cand, sh, kth_b, take_b);
+    if (n_ret > 0 && n_cand > 0) {
+        radix_threshold2(key, m, n_ret, n_ret + n_cand, sh, kth_a, take_a, kth_b, take_b);
+    } else {
+        radix_threshold(key, m, n_ret, sh, kth_a, take_a);
+        radix_threshold(key, m, n_ret + n_cand, sh, kth_b, take_b);
+    }
 
     // index-ordered pass: thread t owns channels [t*E, (t+1)*E)
     int E = (m + blockDim.x - 1) / blockDim.x;

@@ -14,6 +14,7 @@ constexpr int kSelLdsKeys = 4096;  // candidate keys staged in LDS when they fit
 
 struct SelShared {
     unsigned int hist[3][256];  // digit histograms of three consecutive radix passes (see radix_threshold)
+    unsigned int hist2[3][256]; // the second threshold's histograms when two are sought in one sweep
     int wave_tot[4][kSelMaxWaves];
     int digit;
     int remaining;
@@ -173,6 +174,99 @@ __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, Sel
     __syncthreads();  // the caller may reuse the histograms
     kth = prefix;
     take_eq = remaining;
+}
+
+// Two thresholds in the same sweeps: the keys of the n_a-th and of the n_b-th best element, 0 < n_a < n_b <= n, with
+// their take counts, as two calls of radix_threshold would give them.  The common leading bits and the leading digit's
+// histogram serve both; from the second digit on a key is counted for the threshold(s) whose prefix it matches.
+template <class KeyFn>
+__device__ __forceinline__ void radix_threshold2(KeyFn key, int n, int n_a, int n_b, SelShared &sh, uint32_t &kth_a,
+                                                 int &take_a, uint32_t &kth_b, int &take_b)
+{
+    unsigned int *scratch = &sh.hist[2][0];
+    if (threadIdx.x == 0) scratch[0] = 0;
+    if (threadIdx.x < 256) sh.hist[0][threadIdx.x] = 0;
+    if (blockDim.x < 256)
+        for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) sh.hist[0][i] = 0;
+    __syncthreads();
+    const uint32_t k0 = key(0);
+    uint32_t diff = 0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) diff |= key(i) ^ k0;
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0xB1, 0xf, 0xf, true);   // quad_perm 1,0,3,2
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x4E, 0xf, 0xf, true);   // quad_perm 2,3,0,1
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x141, 0xf, 0xf, true);  // row_half_mirror
+    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x140, 0xf, 0xf, true);  // row_mirror
+    if (threadIdx.x % 16 == 0 && diff) atomicOr(&scratch[0], diff);
+    __syncthreads();
+    diff = scratch[0];
+    if (diff == 0) {  // all keys equal
+        __syncthreads();
+        kth_a = kth_b = k0;
+        take_a = n_a;
+        take_b = n_b;
+        return;
+    }
+    const int top_bit = 31 - __builtin_clz(diff);
+    const int n_pass = top_bit / 8 + 1;
+    uint32_t known = top_bit == 31 ? 0u : ~((2u << top_bit) - 1u);
+    uint32_t prefix[2] = {k0 & known, k0 & known};
+    int remaining[2] = {n_a, n_b};
+    const int lane = threadIdx.x % kWave;
+    int pass = 0;
+    for (int shift = (n_pass - 1) * 8; shift >= 0; shift -= 8, ++pass) {
+        unsigned int *hist[2] = {sh.hist[pass % 3], pass == 0 ? sh.hist[0] : sh.hist2[pass % 3]};
+        if (threadIdx.x < 256) {
+            sh.hist[(pass + 1) % 3][threadIdx.x] = 0;
+            sh.hist2[(pass + 1) % 3][threadIdx.x] = 0;
+        }
+        if (blockDim.x < 256)
+            for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) {
+                sh.hist[(pass + 1) % 3][i] = 0;
+                sh.hist2[(pass + 1) % 3][i] = 0;
+            }
+        const int n_round = (n + blockDim.x - 1) / blockDim.x * blockDim.x;
+        if (pass == 0) {
+            for (int i = threadIdx.x; i < n_round; i += blockDim.x) {
+                const uint32_t k = i < n ? key(i) : 0u;
+                wave_hist_add(hist[0], (k >> shift) & 255u, i < n && (k & known) == prefix[0]);
+            }
+        } else {
+            for (int i = threadIdx.x; i < n; i += blockDim.x) {
+                const uint32_t k = key(i);
+                const uint32_t kk = k & known, dg = (k >> shift) & 255u;
+                if (kk == prefix[0]) atomicAdd(&hist[0][dg], 1u);
+                if (kk == prefix[1]) atomicAdd(&hist[1][dg], 1u);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            int c[4], lane_tot = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                c[q] = (int)hist[t][255 - (4 * lane + q)];
+                lane_tot += c[q];
+            }
+            int before = wave_incl_scan(lane_tot) - lane_tot;
+            int digit = -1, rem_new = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (before < remaining[t] && remaining[t] <= before + c[q]) {
+                    digit = 255 - (4 * lane + q);
+                    rem_new = remaining[t] - before;
+                }
+                before += c[q];
+            }
+            const int owner = __builtin_ctzll(__ballot(digit >= 0));
+            digit = __builtin_amdgcn_readlane(digit, owner);
+            remaining[t] = __builtin_amdgcn_readlane(rem_new, owner);
+            prefix[t] |= ((uint32_t)digit) << shift;
+        }
+        known |= 255u << shift;
+    }
+    __syncthreads();
+    kth_a = prefix[0], take_a = remaining[0];
+    kth_b = prefix[1], take_b = remaining[1];
 }
 
 struct SelectNoHook {
