@@ -123,9 +123,6 @@ int copy_step_outputs(pop_layer *L, int B, float *cand_scores, unsigned char *ma
 // kernels take the tokens eight at a time).
 constexpr int kFfnMfmaMinTokens = 32;
 
-// Whole-prompt pruned FFN (Sec. 3.4: forward pass under the pruning structure): active list from the mask(s),
-// gate/up over the listed channels with H written in compact bf16 form, then the K-gathered down-projection GEMM.
-// Scratch grows on demand; growing synchronises the device (hipFree).
 // hipMalloc that leaves no pending error behind when it fails (a later launch check would report it as its own).
 bool dev_alloc(void **p, size_t bytes)
 {
@@ -135,6 +132,8 @@ bool dev_alloc(void **p, size_t bytes)
     return false;
 }
 
+// Makes *p hold at least `need` elements of esize bytes; the old contents are dropped.  Growing frees first, which
+// synchronises the device.
 int grow(void **p, size_t *cap, size_t need, size_t esize)
 {
     if (need <= *cap) return POP_OK;
@@ -145,6 +144,8 @@ int grow(void **p, size_t *cap, size_t need, size_t esize)
     return POP_OK;
 }
 
+// Scratch of the prompt-sized forward pass for T tokens: compact H, split partials, the byte mask; with keep_all
+// also H of all channels.  Returns the row stride of the H buffers and the number of contraction splits.
 int ffn_scratch(pop_layer *L, int T, bool keep_all, int *ldh, int *n_split)
 {
     *ldh = (L->m + 7) / 8 * 8;
@@ -158,6 +159,8 @@ int ffn_scratch(pop_layer *L, int T, bool keep_all, int *ldh, int *n_split)
     return rc;
 }
 
+// Whole-prompt pruned FFN (Sec. 3.4: forward pass under the pruning structure): active list from the mask(s),
+// gate/up over the listed channels with H written in compact bf16 form, then the K-gathered down-projection GEMM.
 int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mask, int mask_rows, void *y, int y_bf16,
                     hipStream_t s)
 {
