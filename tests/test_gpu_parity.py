@@ -322,6 +322,21 @@ def test_prefill_forward_small(pop, oracle, dtype, T):
             _check_decode(oracle, G, L, region, cand, xt, min(k0, n_cand))
 
 
+@pytest.mark.parametrize("cfg_name,T,r", [("CFG4", 1024, 0.50), ("CFG5", 300, 0.35)])
+def test_prefill_forward_other_shapes(pop, oracle, cfg_name, T, r):
+    """The prompt's forward pass on the Llama-2-13B-shaped layer (d = 5120: 40 column tiles, 4 token tiles, no
+    split) and on a Mixtral-shaped expert with a ragged share of the prompt (128-token tiles, the last one short)."""
+    cfg = getattr(synth, cfg_name)
+    L = synth.make_layer(cfg, layer_id=0)
+    m = cfg.m
+    x = synth.make_activations(L, T, "prompt")
+    n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r, 0.10)
+    rows = np.sort(synth.rng("prefill_forward_rows", cfg_name).choice(T, size=5, replace=False))
+    rows[-1] = T - 1
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        _check_prefill_forward(oracle, G, L, x, n_ret, n_cand, k, BF16, Y_TOL[BF16], rows=rows)
+
+
 def test_prefill_forward_full_size(pop, oracle):
     """Llama-2-7B-shaped layer, prompt 512: prefill scores on a sample of channels, partition and prefill mask
     on all channels, the prompt's output on a sample of tokens, then a decode step on the partition."""
