@@ -148,6 +148,8 @@ def run(args):
             one_request(calls, evs[s], probe, single)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
+        for L in layers:  # raises if a bounded in-kernel wait expired during the last request
+            pop.pop_layer_sync_status(L.handle)
         prefill_ms = sum(e[0].elapsed_time(e[1]) for e in evs)
         decode_ms = sum(e[1].elapsed_time(e[2]) for e in evs)
         n_tok_layers = steps * DECODE_STEPS * len(layers)
@@ -270,6 +272,8 @@ def run(args):
         pop.pop_layer_set_single_launch(L.handle, False)
     fused_us = kernel_only("mask")
     tail_us = kernel_only("ffn")
+    for L in layers:  # no in-kernel bounded wait may have expired anywhere above
+        pop.pop_layer_sync_status(L.handle)
     roofline = None
     if fused_us:
         # dominant kernel: the fused decode kernel behind pop_decode_mask (B = 1).  It streams every weight byte of
