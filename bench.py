@@ -312,6 +312,27 @@ def run(args):
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(synth, host_layer0, n_ret, n_cand, k, args.cpu_tokens)
 
+    # the box's own copy bandwidth (plain device-to-device copy of 1 GiB, bytes read + written per second), as a
+    # second yardstick next to the published peak
+    copy_gbps = None
+    if not args.quick:
+        ca = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        cb = torch.empty_like(ca)
+        for _ in range(2):
+            cb.copy_(ca)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(5):
+            cb.copy_(ca)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        copy_gbps = 5 * 2.0 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        del ca, cb
+        if roofline:
+            roofline["measured_copy_GBps"] = round(copy_gbps, 1)
+            roofline["frac_of_measured_copy"] = round(roofline["achieved"] / copy_gbps, 4)
+
     if args.pmc_calibration:
         # a plain device-to-device copy of known size, for scaling the rocprofv3 FETCH_SIZE / WRITE_SIZE counters
         a = torch.zeros(256 << 20, dtype=torch.uint8, device="cuda")
