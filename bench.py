@@ -162,6 +162,8 @@ def run(args):
             out["probe_mask_us"] = float(np.mean(mk))
             out["probe_ffn_us"] = float(np.mean(dn))
             out["probe_n"] = len(mk)
+            tot = np.asarray(mk) + np.asarray(dn)
+            out["probe_token_us_p10_p50_p90"] = [round(float(np.percentile(tot, q)), 3) for q in (10, 50, 90)]
         return out
 
     r_main = 0.35
@@ -363,6 +365,8 @@ def run(args):
                    "n_ret": n_ret, "n_cand": n_cand, "k": k},
         "tokens_per_s_per_layer": round(1e6 / us, 1),
         "prefill_us_per_layer": round(main["prefill_us_per_layer"], 2),
+        "prefill_TFLOPs_whole_call": round(4.0 * PROMPT * m * d / main["prefill_us_per_layer"] / 1e6, 1),
+        "probed_token_us_p10_p50_p90": main.get("probe_token_us_p10_p50_p90"),
         "prefill_forward": forward,
         "stack_of_32_layers": stack,
         "input_side_importance_reading": input_side,
@@ -512,8 +516,10 @@ def measured_traffic():
     return None
 
 
-def cpu_baseline(synth, L, n_ret, n_cand, k, n_tokens):
-    """The oracle's decode step (double precision, as it stands) timed on the host cores for a few tokens."""
+def cpu_baseline(synth, L, n_ret, n_cand, k, n_tokens, n_prompt=64):
+    """The oracle (double precision, as it stands) timed on the host cores: decode steps of one layer for n_tokens
+    tokens, and the prefilling stage (hidden activations of all channels, importance, partition) for the first
+    n_prompt prompt tokens."""
     from oracle import pop_oracle as oracle
     oracle.build()
     region, ret, cand = oracle.partition(synth.make_scores(L.cfg.m, "cpu_baseline_scores", "none"), n_ret, n_cand)
@@ -523,9 +529,15 @@ def cpu_baseline(synth, L, n_ret, n_cand, k, n_tokens):
     for t in range(n_tokens):
         oracle.decode(xt[t], L.w_gate, L.w_up, L.w_down, L.cfg.dtype, region, cand, k)
     dt = time.perf_counter() - t0
+    xp = synth.make_activations(L, n_prompt, "prompt")
+    t0 = time.perf_counter()
+    oracle.prefill(xp, L.w_gate, L.w_up, L.w_down, L.cfg.dtype, n_ret, n_cand)
+    dp = time.perf_counter() - t0
     return {"value": round(1e6 * dt / n_tokens, 1), "unit": "us/token", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"{n_tokens} decode tokens of one layer (pass 1 over retained+candidate channels, re-score, "
-                      f"top-k, down projection), same shape and sparsity; prefill not included"}
+                      f"top-k, down projection), same shape and sparsity; prefill timed apart",
+            "prefill_us_per_prompt_token": round(1e6 * dp / n_prompt, 1),
+            "prefill_sample": f"prefilling stage of one layer on the first {n_prompt} of the {PROMPT} prompt tokens"}
 
 
 def main():
@@ -535,7 +547,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--layers", type=int, default=8, help="independent layers rotated per token (cache-cold weights)")
     ap.add_argument("--probe-every", type=int, default=8, help="bracket every n-th decode call pair with events")
-    ap.add_argument("--cpu-tokens", type=int, default=384)
+    ap.add_argument("--cpu-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 256 MiB device copies")
     ap.add_argument("--forward", action="store_true", help="with --quick: keep the prefill-forward section")
