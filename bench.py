@@ -494,9 +494,21 @@ def time_other_shapes(pop, synth, lib, stream):
             e1.record(stream)
             torch.cuda.synchronize()
             us = e0.elapsed_time(e1) * 1e3 / (2 * steps * n_layers)
+            # bytes the step really streams: gate+up rows of retained and candidate channels, down rows of the
+            # retained channels and of the union of the B selections (data-dependent; taken from one step's masks)
+            mk = torch.empty((B, cfg.m), dtype=torch.uint8, device="cuda")
+            rc = lib.pop_decode_mask(hs[0], C.c_void_p(xds[0].data_ptr()), B, karr, None, C.c_void_p(mk.data_ptr()),
+                                     None, None, sp)
+            if rc:
+                raise pop.PopError(rc, "bench")
+            torch.cuda.synchronize()
+            union = int(mk.any(dim=0).sum().item())
+            streamed = (2 * (n_ret + n_cand) + union) * cfg.d * 2
             res[f"B={B}"] = dict(us_per_step=round(us, 2), us_per_token=round(us / B, 2),
                                  tokens_per_s=round(1e6 * B / us, 1),
-                                 active_GBps_one_sequence=round(bm["active"] / us / 1e3, 1))
+                                 active_GBps_one_sequence=round(bm["active"] / us / 1e3, 1),
+                                 union_channels=union, MB_streamed=round(streamed / 1e6, 2),
+                                 streamed_GBps=round(streamed / us / 1e3, 1))
         for h in hs:
             pop.pop_layer_destroy(h)
         torch.cuda.empty_cache()
