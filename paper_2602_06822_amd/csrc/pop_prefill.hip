@@ -12,12 +12,17 @@
 // that the tiles divide evenly over the compute units (one or a whole number of tiles each).  Each accumulator
 // lane holds 16 token rows of one channel column, so the token reduction is in-register adds, one cross-half
 // shuffle and an LDS combine of the token waves.  Token tiles write separate partial rows that are summed in
-// tile order.  The kernel is bound by its LDS fragment reads (two waves per SIMD cover each other's waits).
+// tile order.  Operand rows that are whole k-steps long (d a multiple of 64) go from global memory straight into LDS
+// (global_load_lds, 1 KB = 8 unpadded rows per wave instruction, 16-byte units XOR-swizzled by row pair so that the
+// fragment reads stay conflict-free); fetching them through registers costs a quarter more time even when every load
+// hits the cache, and remains the path for other row lengths.
 // Two more forms of the same kernel serve the forward pass of a whole prompt under the pruning structure
 // (Sec. 3.4): one also writes H (rounded to bf16) as [T][m]; one runs its chunks over a device-resident list of
 // active channels instead of all m and writes H (optionally times a per-token mask) in compact form
 // [T][list position] for the down projection instead of reducing its squares.
 // float32: plain FMA tiles with the same structure (64 tokens x 32 channels per workgroup).
+#include <stdlib.h>
+
 #include "pop_internal.h"
 
 namespace pop {
@@ -102,7 +107,7 @@ struct PfStore {
 
 // kMode 0: scores only (s2_part).  1: channels from st.list, H stored compact (no s2_part).  2: all m channels,
 // s2_part and H stored as [T][m padded].
-template <int BM, int NW, int NF, int kMode>
+template <int BM, int NW, int NF, int kMode, bool kDma = false>
 __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ x, int T, int d, int m,
                                                            int n_ttiles, int chunk, int n_items, int per_xcd,
@@ -113,9 +118,12 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
     constexpr int RP = NW * 8;          // rows one staging pass of the workgroup covers
     constexpr int BR = NF * 64;         // B rows of the workgroup tile
     constexpr int WC = NF * 16;         // channels per wave
+    // LDS rows: 64 elements padded to 72 (register staging), or exactly 64 with the 16-byte units of row r stored
+    // at unit ^ ((r / 2) % 8) (direct global -> LDS loads, which fill 1 KB = 8 whole rows per wave instruction)
+    constexpr int LD = kDma ? kPfBK : kPfLd;
     extern __shared__ __attribute__((aligned(16))) uint16_t pf_lds[];
-    uint16_t *As = pf_lds;                       // [2][BM * kPfLd]
-    uint16_t *Bs = pf_lds + 2 * BM * kPfLd;      // [2][BR * kPfLd]
+    uint16_t *As = pf_lds;                    // [2][BM * LD]
+    uint16_t *Bs = pf_lds + 2 * BM * LD;      // [2][BR * LD]
     __shared__ float colsum[TW][kPfChunk];
 
     constexpr bool kList = kMode == 1, kStore = kMode != 0;
@@ -171,10 +179,28 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
     auto store_lds = [&](int buf) {
 #pragma unroll
         for (int p = 0; p < PA; ++p)
-            *reinterpret_cast<uint4 *>(&As[(buf * BM + ld_row + p * RP) * kPfLd + ld_kv * 8]) = ra[p];
+            *reinterpret_cast<uint4 *>(&As[(buf * BM + ld_row + p * RP) * LD + ld_kv * 8]) = ra[p];
 #pragma unroll
         for (int p = 0; p < PB; ++p)
-            *reinterpret_cast<uint4 *>(&Bs[(buf * BR + ld_row + p * RP) * kPfLd + ld_kv * 8]) = rb[p];
+            *reinterpret_cast<uint4 *>(&Bs[(buf * BR + ld_row + p * RP) * LD + ld_kv * 8]) = rb[p];
+    };
+    // direct loads: this lane's 16 bytes land at LDS unit ld_kv of row ld_row of the pass, so it fetches the k-vector
+    // that belongs there under the swizzle; rows without data are skipped (their LDS rows stay zero)
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const int src_kv = (ld_kv ^ ((ld_row / 2) % 8)) * 8;  // (passes are 64 rows apart: the swizzle term is the same)
+    auto dma_load = [&](int buf, int k0) {
+        typedef __attribute__((address_space(3))) void lds_t;
+        typedef __attribute__((address_space(1))) const void glb_t;
+#pragma unroll
+        for (int p = 0; p < PA; ++p)
+            if (pa[p])
+                __builtin_amdgcn_global_load_lds((glb_t *)(pa[p] + k0 + src_kv),
+                                                 (lds_t *)(As + (buf * BM + p * RP + wave_u * 8) * LD), 16, 0, 0);
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+            if (pb[p])
+                __builtin_amdgcn_global_load_lds((glb_t *)(pb[p] + k0 + src_kv),
+                                                 (lds_t *)(Bs + (buf * BR + p * RP + wave_u * 8) * LD), 16, 0, 0);
     };
 
     f32x16_t acc[MT][NF];  // [token fragment][0 = gate 0..31, 1 = up 0..31, 2 = gate 32..47 | up 32..47]
@@ -187,16 +213,20 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
 
     const int n_k = (d + kPfBK - 1) / kPfBK;
     const int arow = wm * (BM / TW) + (lane % 32), brow = wn * (NF * 32) + (lane % 32), koff = (lane / 32) * 8;
+    const int a_sw = (arow / 2) % 8, b_sw = (brow / 2) % 8;  // (fragments are 32 rows apart: same swizzle term)
     auto multiply = [&](int buf) {
-        const uint16_t *Ab = As + (buf * BM + arow) * kPfLd + koff;
-        const uint16_t *Bb = Bs + (buf * BR + brow) * kPfLd + koff;
+        const uint16_t *Ab = As + (buf * BM + arow) * LD + (kDma ? 0 : koff);
+        const uint16_t *Bb = Bs + (buf * BR + brow) * LD + (kDma ? 0 : koff);
 #pragma unroll
         for (int kk = 0; kk < kPfBK; kk += 16) {
             bf16x8_t bf[NF], af[MT];
+            // element offset of this lane's 8 k-values within its row
+            const int ka = kDma ? (((kk / 8 + lane / 32) ^ a_sw) * 8) : kk;
+            const int kb = kDma ? (((kk / 8 + lane / 32) ^ b_sw) * 8) : kk;
 #pragma unroll
-            for (int f = 0; f < NF; ++f) bf[f] = *reinterpret_cast<const bf16x8_t *>(Bb + f * 32 * kPfLd + kk);
+            for (int f = 0; f < NF; ++f) bf[f] = *reinterpret_cast<const bf16x8_t *>(Bb + f * 32 * LD + kb);
 #pragma unroll
-            for (int a = 0; a < MT; ++a) af[a] = *reinterpret_cast<const bf16x8_t *>(Ab + a * 32 * kPfLd + kk);
+            for (int a = 0; a < MT; ++a) af[a] = *reinterpret_cast<const bf16x8_t *>(Ab + a * 32 * LD + ka);
 #pragma unroll
             for (int a = 0; a < MT; ++a)
 #pragma unroll
@@ -204,16 +234,31 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
                     acc[a][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[f], acc[a][f], 0, 0, 0);
         }
     };
-    // step ks multiplies LDS buffer ks % 2 while the rows of step ks + 1 are on their way through registers
-    load_global(0);
-    store_lds(0);
-    __syncthreads();
-    for (int ks = 0; ks < n_k; ++ks) {
-        const int buf = ks & 1;
-        if (ks + 1 < n_k) load_global((ks + 1) * kPfBK);
-        multiply(buf);
-        if (ks + 1 < n_k) store_lds(buf ^ 1);
+    if (kDma) {
+        // (needs d % 64 == 0.)  Rows that no load ever writes must read as zeros
+        for (int i = tid; i < 2 * (BM + BR) * LD / 8; i += NW * 64) reinterpret_cast<uint4 *>(pf_lds)[i] = make_uint4(0, 0, 0, 0);
         __syncthreads();
+        // step ks multiplies LDS buffer ks % 2 while the rows of step ks + 1 land in the other one
+        dma_load(0, 0);
+        __syncthreads();  // (waits for this wave's loads, then for everybody's)
+        for (int ks = 0; ks < n_k; ++ks) {
+            const int buf = ks & 1;
+            if (ks + 1 < n_k) dma_load(buf ^ 1, (ks + 1) * kPfBK);
+            multiply(buf);
+            __syncthreads();
+        }
+    } else {
+        // step ks multiplies LDS buffer ks % 2 while the rows of step ks + 1 are on their way through registers
+        load_global(0);
+        store_lds(0);
+        __syncthreads();
+        for (int ks = 0; ks < n_k; ++ks) {
+            const int buf = ks & 1;
+            if (ks + 1 < n_k) load_global((ks + 1) * kPfBK);
+            multiply(buf);
+            if (ks + 1 < n_k) store_lds(buf ^ 1);
+            __syncthreads();
+        }
     }
 
     // epilogue: lane holds 16 * MT token rows of column (lane % 32) of each fragment; rows of padded tokens and
@@ -350,6 +395,19 @@ template <int BM, int NW, int NF, int kMode>
 static hipError_t launch_pf_bf16(int blocks, hipStream_t s, const void *w, const void *x, int T, int d, int m, int n_tt,
                                  const PfGeom &g, float *s2_part, const PfStore &st)
 {
+    // rows that are whole k-steps long go from global memory straight into LDS (POP_PF_DMA=0 keeps them on the
+    // register-staged path, for comparison)
+    static const int use_dma = getenv("POP_PF_DMA") ? atoi(getenv("POP_PF_DMA")) : 1;
+    if (use_dma && d % kPfBK == 0) {
+        const size_t lds_d = (size_t)2 * (BM + NF * 64) * kPfBK * sizeof(uint16_t);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<BM, NW, NF, kMode, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_d);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL((prefill_bf16_kernel<BM, NW, NF, kMode, true>), dim3(blocks), dim3(NW * 64), lds_d, s,
+                           (const uint16_t *)w, (const uint16_t *)x, T, d, m, n_tt, g.chunk, g.total, g.per_xcd, s2_part,
+                           st);
+        return hipGetLastError();
+    }
     const size_t lds = (size_t)2 * (BM + NF * 64) * kPfLd * sizeof(uint16_t);
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<BM, NW, NF, kMode>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
