@@ -337,6 +337,26 @@ def test_prefill_forward_other_shapes(pop, oracle, cfg_name, T, r):
         _check_prefill_forward(oracle, G, L, x, n_ret, n_cand, k, BF16, Y_TOL[BF16], rows=rows)
 
 
+@pytest.mark.parametrize("d,m,T", [(192, 301, 20), (128, 130, 150), (192, 301, 300), (320, 97, 257)])
+def test_prefill_rows_of_whole_k_steps(pop, oracle, d, m, T):
+    """bf16 layers whose rows are a whole number of 64-element k-steps take the prefill kernel's direct global -> LDS
+    staging: every score against the oracle, with ragged token tiles, channel chunks that do not fill a tile, both
+    tile forms and both token-tile sizes; then the forward pass (kept H, list form) and a decode step."""
+    L = synth.make_layer(synth.small_config("whole_k_steps", d, m, BF16))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 1, "decode")
+    n_ret, n_cand, k = m // 2, m // 4, m // 8
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        tol = FFN_MFMA_TOL_F32 if T >= 32 else 1e-4
+        _check_prefill_forward(oracle, G, L, x, n_ret, n_cand, k, F32, tol)
+        mask = (synth.rng("whole_k_steps_mask", d, m).random(m) < 0.5).astype(np.uint8)
+        y = G.ffn(x, mask, F32)
+        y_ref = oracle.pruned_ffn(x, L.w_gate, L.w_up, L.w_down, BF16, mask)
+        assert max_abs_rel(y, y_ref) <= tol
+        _check_decode(oracle, G, L, region, cand, xt, k)
+
+
 def test_prefill_forward_full_size(pop, oracle):
     """Llama-2-7B-shaped layer, prompt 512: prefill scores on a sample of channels, partition and prefill mask
     on all channels, the prompt's output on a sample of tokens, then a decode step on the partition."""
