@@ -206,7 +206,7 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     L->n_cand = n_cand;
     { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
     if (L->input_side) L->fused_ok = false;  // the fused kernel scores candidates from h
-    POP_HIP(launch_fill_int(L->selbits, fused_selbits_ints(), 0, s));
+    POP_HIP(launch_selbits_clear(L->selbits, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));

@@ -176,6 +176,7 @@ struct FusedPlan {
 };
 int fused_max_workgroups();
 int fused_selbits_ints();  // size of the selection-word buffer (one word per workgroup, spaced apart)
+hipError_t launch_selbits_clear(int *selbits, hipStream_t s);  // zeroes the words of that buffer that are in use
 // Launch shape for (d, dtype, region sizes); false when the fused kernel does not support the shape.
 bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl);
 // Largest grid of this shape that is co-resident on n_cu compute units.
