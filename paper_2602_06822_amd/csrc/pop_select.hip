@@ -79,45 +79,37 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
         radix_threshold(key, m, n_ret + n_cand, sh, kth_b, take_b);
     }
 
-    // index-ordered pass: thread t owns channels [t*E, (t+1)*E)
+    // index-ordered passes: thread t owns channels [t*E, (t+1)*E).  A channel above a threshold key is in; one equal to
+    // it is in while fewer than `take` equal ones precede it.  So with the numbers of greater and of equal channels
+    // before a thread's range (one scan of four streams) every channel's region and list position follow directly.
     int E = (m + blockDim.x - 1) / blockDim.x;
     int lo = min(m, (int)threadIdx.x * E), hi = min(m, lo + E);
-    int cnt[2] = {0, 0}, tot[2];
+    int cnt[4] = {0, 0, 0, 0}, tot[4];  // greater than a, equal to a, greater than b, equal to b
     for (int j = lo; j < hi; ++j) {
-        uint32_t k = key(j);
-        cnt[0] += (k == kth_a);
-        cnt[1] += (k == kth_b);
+        const uint32_t k = key(j);
+        cnt[0] += (k > kth_a);
+        cnt[1] += (k == kth_a);
+        cnt[2] += (k > kth_b);
+        cnt[3] += (k == kth_b);
     }
-    block_excl_scan<2>(cnt, tot, sh);
-    int eq_a = cnt[0], eq_b = cnt[1];
-    int nr[2] = {0, 0};
+    block_excl_scan<4>(cnt, tot, sh);
+    int gt_a = cnt[0], eq_a = cnt[1], gt_b = cnt[2], eq_b = cnt[3];
     for (int j = lo; j < hi; ++j) {
-        uint32_t k = key(j);
-        bool in_r = (k > kth_a) || (k == kth_a && eq_a < take_a);
-        bool in_rc = (k > kth_b) || (k == kth_b && eq_b < take_b);
-        eq_a += (k == kth_a);
-        eq_b += (k == kth_b);
-        nr[0] += in_r;
-        nr[1] += (!in_r && in_rc);
-    }
-    block_excl_scan<2>(nr, tot, sh);
-    int pr = nr[0], pc = nr[1];
-    eq_a = cnt[0];
-    eq_b = cnt[1];
-    for (int j = lo; j < hi; ++j) {
-        uint32_t k = key(j);
-        bool in_r = (k > kth_a) || (k == kth_a && eq_a < take_a);
-        bool in_rc = (k > kth_b) || (k == kth_b && eq_b < take_b);
-        eq_a += (k == kth_a);
-        eq_b += (k == kth_b);
+        const uint32_t k = key(j);
+        const bool in_r = (k > kth_a) || (k == kth_a && eq_a < take_a);
+        const bool in_rc = (k > kth_b) || (k == kth_b && eq_b < take_b);
+        // channels of the retained set / of retained + candidate before this one
+        const int n_r = gt_a + min(eq_a, take_a), n_rc = gt_b + min(eq_b, take_b);
         if (region) region[j] = in_r ? POP_REGION_RETAINED : (in_rc ? POP_REGION_CANDIDATE : POP_REGION_PRUNED);
         if (in_r) {
-            if (ret_idx) ret_idx[pr] = j;
-            ++pr;
+            if (ret_idx) ret_idx[n_r] = j;
         } else if (in_rc) {
-            if (cand_idx) cand_idx[pc] = j;
-            ++pc;
+            if (cand_idx) cand_idx[n_rc - n_r] = j;
         }
+        gt_a += (k > kth_a);
+        eq_a += (k == kth_a);
+        gt_b += (k > kth_b);
+        eq_b += (k == kth_b);
     }
 }
 
