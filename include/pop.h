@@ -23,6 +23,8 @@
  *   - index lists are int32, ascending by channel; regions are one byte per channel.
  *   - dtype of x, weights: the layer's wdtype (float32, or bf16 stored as 16-bit patterns).
  *     bf16 layers need d % 8 == 0, float32 layers d % 4 == 0 (128-bit loads), else POP_EUNSUPPORTED.
+ *   - device pointers to activations (x, x_t), weights and outputs y must be 16-byte aligned (the kernels use
+ *     128-bit accesses); a misaligned one is rejected with POP_EINVAL.
  *   - inputs must be finite; with non-finite inputs results are deterministic but unspecified.
  */
 #ifndef POP_H

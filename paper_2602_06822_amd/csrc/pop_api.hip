@@ -1,6 +1,7 @@
 // C ABI of the POP pruned-FFN library: argument validation, layer state and kernel sequencing.
 // Every step of the path runs in the HIP kernels of the sibling files; nothing here computes on the host
 // except the integer region counts.
+#include <stdint.h>
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -29,6 +30,9 @@ int hip_fail(hipError_t e, const char *what)
     } while (0)
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+// The kernels read activations and weights, and write y, with 16-byte accesses.
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 #ifdef POP_TRACE
 unsigned long long *g_trace = nullptr;  // profiling builds: device buffer the fused kernel stamps into
@@ -338,6 +342,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     if (!out) return POP_EINVAL;
     *out = nullptr;
     if (!w_gate || !w_up || !w_down) return POP_EINVAL;
+    if (!aligned16(w_gate) || !aligned16(w_up) || !aligned16(w_down)) return POP_EINVAL;
     if (wdtype != POP_F32 && wdtype != POP_BF16) return POP_EINVAL;
     if (d <= 0 || m <= 0 || max_tokens < 1) return POP_ESHAPE;
     if (max_batch < 1 || max_batch > POP_MAX_BATCH) return POP_ESHAPE;
@@ -420,7 +425,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
 int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n_cand, float *scores,
                           unsigned char *region, int *ret_idx, int *cand_idx, void *stream)
 {
-    if (!L || !x) return POP_EINVAL;
+    if (!L || !x || !aligned16(x)) return POP_EINVAL;
     if (T < 1 || T > L->max_tokens) return POP_ESHAPE;
     if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
     hipStream_t s = as_stream(stream);
@@ -440,7 +445,7 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
                         float *scores, unsigned char *region, int *ret_idx, int *cand_idx, unsigned char *mask,
                         void *stream)
 {
-    if (!L || !x || !y) return POP_EINVAL;
+    if (!L || !x || !y || !aligned16(x) || !aligned16(y)) return POP_EINVAL;
     if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
     if (T < 1 || T > L->max_tokens) return POP_ESHAPE;
     if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
@@ -490,7 +495,7 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
 int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float *cand_scores, unsigned char *mask,
                     int *active_idx, int *n_active, void *stream)
 {
-    if (!L || !x_t || !k) return POP_EINVAL;
+    if (!L || !x_t || !k || !aligned16(x_t)) return POP_EINVAL;
     if (!L->has_partition) return POP_ESTATE;
     if (B < 1 || B > L->max_batch) return POP_ESHAPE;
     BatchK kk = {};
@@ -566,7 +571,7 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
 int pop_decode_step(pop_layer_t *L, const void *x_t, int B, const int *k, void *y, pop_dtype_t ydtype,
                     float *cand_scores, unsigned char *mask, int *active_idx, int *n_active, void *stream)
 {
-    if (!L || !x_t || !k || !y) return POP_EINVAL;
+    if (!L || !x_t || !k || !y || !aligned16(x_t) || !aligned16(y)) return POP_EINVAL;
     if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
     if (!L->has_partition) return POP_ESTATE;
     if (B < 1 || B > L->max_batch) return POP_ESHAPE;
@@ -595,7 +600,7 @@ int pop_decode_step(pop_layer_t *L, const void *x_t, int B, const int *k, void *
 int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *mask, int mask_rows, void *y,
                    pop_dtype_t ydtype, void *stream)
 {
-    if (!L || !y) return POP_EINVAL;
+    if (!L || !y || !aligned16(y)) return POP_EINVAL;
     if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
     hipStream_t s = as_stream(stream);
     const int m = L->m, d = L->d, y_bf16 = ydtype == POP_BF16, ysize = y_bf16 ? 2 : 4;
@@ -613,7 +618,7 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
                                 L->n_slabs, y, y_bf16, s));
         return POP_OK;
     }
-    if (!x) return POP_EINVAL;
+    if (!x || !aligned16(x)) return POP_EINVAL;
     if (T < 1) return POP_ESHAPE;
     if (mask_rows != 1 && mask_rows != T) return POP_ESHAPE;
     L->has_step = false;  // the step scratch is reused below

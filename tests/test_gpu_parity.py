@@ -609,6 +609,11 @@ def test_error_paths(pop):
         assert status(pop.pop_prefill_forward, G.handle, x, 9, 10, 10, 5, y8, F32) == pop.POP_ESHAPE
         assert status(pop.pop_prefill_forward, G.handle, x, 8, 10, 10, 5, None, F32) == pop.POP_EINVAL
         assert status(pop.pop_prefill_forward, G.handle, x, 8, 10, 10, 5, y8, 3) == pop.POP_EINVAL
+        # misaligned activations or outputs are rejected on the host (the kernels use 16-byte accesses)
+        xb = torch.zeros(8 * d + 4, dtype=torch.float32, device="cuda")
+        assert status(pop.pop_prefill_partition, G.handle, xb.data_ptr() + 4, 8, 10, 10) == pop.POP_EINVAL
+        assert status(pop.pop_decode_mask, G.handle, xb.data_ptr() + 8, 1, 1) == pop.POP_EINVAL
+        assert status(pop.pop_pruned_ffn, G.handle, None, 2, None, 0, y.data_ptr() + 4, F32) == pop.POP_EINVAL
         assert status(pop.pop_layer_set_importance, G.handle, 2) == pop.POP_EINVAL
         assert status(pop.pop_layer_set_importance, None, 0) == pop.POP_EINVAL
         assert status(pop.pop_layer_set_shared_batch_mask, None, 1) == pop.POP_EINVAL
