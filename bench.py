@@ -78,6 +78,10 @@ def run(args):
     lib = pop.raw()
     stream = torch.cuda.current_stream()
     sp = C.c_void_p(stream.cuda_stream)
+    if args.other_shapes_only:
+        # only the timings of the other workload shapes (for kernel traces of the batched decode kernels)
+        print(json.dumps({"other_shapes": time_other_shapes(pop, synth, lib, stream)}))
+        return
     layers = [BenchLayer(pop, synth, cfg, i, None) for i in range(args.layers)]
     d, m = cfg.d, cfg.m
     torch.cuda.synchronize()
@@ -562,6 +566,8 @@ def main():
     ap.add_argument("--cpu-tokens", type=int, default=2048)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 256 MiB device copies")
+    ap.add_argument("--other-shapes-only", action="store_true",
+                    help="run only the 13B-shaped (B = 1, 4, 8) and Mixtral-expert timings")
     ap.add_argument("--forward", action="store_true", help="with --quick: keep the prefill-forward section")
     ap.add_argument("--quick", action="store_true", help="main line only: skip other sparsities and the warm figure")
     args = ap.parse_args()
