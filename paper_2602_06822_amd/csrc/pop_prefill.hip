@@ -95,6 +95,15 @@ __host__ __device__ inline PfGeom prefill_geometry(int n_ch, int n_tt, int n_cu)
     return cost2 < cost3 ? g2 : g3;
 }
 
+// silu(g) * u for the tile epilogue (96 values per lane, with no other tile to hide behind): hardware exp2 and
+// reciprocal, each good to one unit in the last place, instead of the library exponential and the exact quotient
+// (a fifth of the instructions).  g -> -inf gives g * 0, g -> +inf gives g * 1.
+__device__ __forceinline__ float silu_mul_tile(float g, float u)
+{
+    const float e = __builtin_amdgcn_exp2f(g * -1.44269504088896341f);
+    return g * __builtin_amdgcn_rcpf(1.0f + e) * u;
+}
+
 // What the list form adds to the plain prefill arguments.
 struct PfStore {
     const int *list;            // active channels, ascending
@@ -217,21 +226,29 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
     auto multiply = [&](int buf) {
         const uint16_t *Ab = As + (buf * BM + arow) * LD + (kDma ? 0 : koff);
         const uint16_t *Bb = Bs + (buf * BR + brow) * LD + (kDma ? 0 : koff);
-#pragma unroll
-        for (int kk = 0; kk < kPfBK; kk += 16) {
-            bf16x8_t bf[NF], af[MT];
+        // the fragments of k-slice q + 1 are requested before the products of slice q are issued (two register
+        // sets), so that their LDS latency runs under the matrix pipe
+        bf16x8_t bf[2][NF], af[2][MT];
+        auto fetch = [&](int q, int set) {
             // element offset of this lane's 8 k-values within its row
-            const int ka = kDma ? (((kk / 8 + lane / 32) ^ a_sw) * 8) : kk;
-            const int kb = kDma ? (((kk / 8 + lane / 32) ^ b_sw) * 8) : kk;
+            const int ka = kDma ? (((q * 2 + lane / 32) ^ a_sw) * 8) : q * 16;
+            const int kb = kDma ? (((q * 2 + lane / 32) ^ b_sw) * 8) : q * 16;
 #pragma unroll
-            for (int f = 0; f < NF; ++f) bf[f] = *reinterpret_cast<const bf16x8_t *>(Bb + f * 32 * LD + kb);
+            for (int f = 0; f < NF; ++f) bf[set][f] = *reinterpret_cast<const bf16x8_t *>(Bb + f * 32 * LD + kb);
 #pragma unroll
-            for (int a = 0; a < MT; ++a) af[a] = *reinterpret_cast<const bf16x8_t *>(Ab + a * 32 * LD + ka);
+            for (int a = 0; a < MT; ++a) af[set][a] = *reinterpret_cast<const bf16x8_t *>(Ab + a * 32 * LD + ka);
+        };
+        fetch(0, 0);
+#pragma unroll
+        for (int q = 0; q < kPfBK / 16; ++q) {
+            if (q + 1 < kPfBK / 16) fetch(q + 1, (q + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int a = 0; a < MT; ++a)
 #pragma unroll
                 for (int f = 0; f < NF; ++f)
-                    acc[a][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[a], bf[f], acc[a][f], 0, 0, 0);
+                    acc[a][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[q & 1][a], bf[q & 1][f], acc[a][f], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
     if (kDma) {
@@ -275,12 +292,12 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int t = t0 + wm * (BM / TW) + a * 32 + (v / 4) * 8 + (lane / 32) * 4 + v % 4;
-                float h01 = silu_mul(acc[a][0][v], acc[a][1][v]);
+                float h01 = silu_mul_tile(acc[a][0][v], acc[a][1][v]);
                 float h2 = 0.f;
                 if (NF == 3) {
                     const float g2 = acc[a][NF - 1][v];
                     const float u2 = __shfl_xor(g2, 16, kWave);
-                    h2 = silu_mul(g2, u2);
+                    h2 = silu_mul_tile(g2, u2);
                 }
                 if (t < T) {
                     uint16_t *row = st.hc + (size_t)t * st.ldh + c0;
@@ -301,13 +318,13 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
     for (int a = 0; a < MT; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const float hv = silu_mul(acc[a][0][v], acc[a][1][v]);
+            const float hv = silu_mul_tile(acc[a][0][v], acc[a][1][v]);
             ss01 = fmaf(hv, hv, ss01);
             if (NF == 3) {
                 // mixed fragment: the up value of column c < 16 sits in lane c + 16, same register
                 const float g2 = acc[a][NF - 1][v];
                 const float u2 = __shfl_xor(g2, 16, kWave);
-                const float h2 = silu_mul(g2, u2);
+                const float h2 = silu_mul_tile(g2, u2);
                 ss2 = fmaf(h2, h2, ss2);
             }
         }
