@@ -191,8 +191,8 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     const int m = L->m;
     // the partition launch also forms the scores from the contraction's partial rows (the input-side scores are
     // already in place) and clears the step counters; one more launch writes everything that is constant per
-    // partition: retained bytes of every mask row, retained prefix of every active list and of the union list, the
-    // candidate-then-retained list
+    // partition (retained bytes of every mask row, retained prefix of every active list and of the union list, the
+    // candidate-then-retained list) and zeroes the fused kernel's selection words
     PartitionExtra ex;
     const bool from_partials = !L->input_side && partition_takes_partials(m);
     if (!L->input_side && !from_partials)
@@ -203,14 +203,14 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     }
     ex.sync = L->sync, ex.n_sync = 16;
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s, &ex));
+    const StridedClear clr = fused_selbits_clear(L->selbits);
     POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s,
-                                   L->cand_idx, n_cand, L->rc_idx, L->ulist));
+                                   L->cand_idx, n_cand, L->rc_idx, L->ulist, &clr));
     L->ulist_prefix_ok = true;
     L->n_ret = n_ret;
     L->n_cand = n_cand;
     { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
     if (L->input_side) L->fused_ok = false;  // the fused kernel scores candidates from h
-    POP_HIP(launch_selbits_clear(L->selbits, s));
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));

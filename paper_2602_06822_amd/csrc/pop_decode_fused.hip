@@ -801,18 +801,14 @@ struct FusedLaunchFn {
 int fused_max_workgroups() { return 1024; }
 int fused_selbits_ints() { return 1024 * kBitsStride; }
 
-// Clears the words of the selection-word buffer that the kernels use (the selection word and the "go" word of every
+// The words of the selection-word buffer that the kernels use (the selection word and the "go" word of every
 // workgroup slot), not the padding that keeps them in separate cache lines.
-__global__ __launch_bounds__(128) void selbits_clear_kernel(int *__restrict__ selbits)
+StridedClear fused_selbits_clear(int *selbits)
 {
     static_assert(kGoWord < 128, "both words of a slot lie in its first 128 ints");
-    selbits[(size_t)blockIdx.x * kBitsStride + threadIdx.x] = 0;
-}
-
-hipError_t launch_selbits_clear(int *selbits, hipStream_t s)
-{
-    hipLaunchKernelGGL(selbits_clear_kernel, dim3(1024), dim3(128), 0, s, selbits);
-    return hipGetLastError();
+    StridedClear c;
+    c.p = selbits, c.n = 1024, c.stride = kBitsStride, c.words = 128;
+    return c;
 }
 
 // Chooses the launch shape; false when the fused kernel does not support this shape.

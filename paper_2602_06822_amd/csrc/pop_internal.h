@@ -109,10 +109,15 @@ hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, 
                        unsigned char *selflag, int *union_ctr, int *union_list, int *n_union, hipStream_t s);
 // Partition-constant step state: mask[b][j] = (region[j] == retained), active_idx[b][0..n_ret) = ret_idx.
 // With cand_idx / rc_idx / ulist given it also writes rc_idx = cand_idx ++ ret_idx and ulist[0..n_ret) = ret_idx.
+// With `clear` given the same launch zeroes that buffer's words.
+struct StridedClear {
+    int *p = nullptr;  // n slots of `words` ints (<= 256), `stride` ints apart
+    int n = 0, stride = 0, words = 0;
+};
 hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
                                   int act_stride, unsigned char *mask, int *active_idx, hipStream_t s,
                                   const int *cand_idx = nullptr, int n_cand = 0, int *rc_idx = nullptr,
-                                  int *ulist = nullptr);
+                                  int *ulist = nullptr, const StridedClear *clear = nullptr);
 // mask rows -> ascending list of channels active in any row.
 hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s);
 
@@ -176,7 +181,8 @@ struct FusedPlan {
 };
 int fused_max_workgroups();
 int fused_selbits_ints();  // size of the selection-word buffer (one word per workgroup, spaced apart)
-hipError_t launch_selbits_clear(int *selbits, hipStream_t s);  // zeroes the words of that buffer that are in use
+// The words of that buffer that are in use (the rest is padding between cache lines), as a clearing job.
+StridedClear fused_selbits_clear(int *selbits);
 // Launch shape for (d, dtype, region sizes); false when the fused kernel does not support the shape.
 bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl);
 // Largest grid of this shape that is co-resident on n_cu compute units.
