@@ -22,6 +22,14 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
     extern __shared__ uint32_t part_keys[];  // [m] when m <= kPartLdsKeys
     const bool in_lds = m <= kPartLdsKeys;
     if (ex.sync && threadIdx.x < ex.n_sync) ex.sync[threadIdx.x] = 0;
+    // while the keys pass through registers: the bits set in any key and the bits clear in any key (the radix select
+    // starts below the leading bits that all keys share)
+    __shared__ uint32_t key_or, key_nand;
+    uint32_t my_or = 0, my_nand = 0;
+    if (in_lds) {
+        if (threadIdx.x == 0) key_or = key_nand = 0;
+        __syncthreads();
+    }
     if (in_lds && ex.s2_part) {
         // scores straight from the prefill kernel's partial rows (Eq. 3), kept for the caller as well
         for (int base = 0; base < m; base += 4 * blockDim.x) {
@@ -48,11 +56,12 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
                 if (i < m) {
                     const float sc = (float)((double)nr[u] * sqrt(acc[u]));
                     ex.scores_out[i] = sc;
-                    part_keys[i] = score_key(sc);
+                    const uint32_t k = score_key(sc);
+                    part_keys[i] = k;
+                    my_or |= k, my_nand |= ~k;
                 }
             }
         }
-        __syncthreads();
     } else if (in_lds) {
         for (int base = 0; base < m; base += 8 * blockDim.x) {
             float v[8];
@@ -64,8 +73,19 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 const int i = base + u * blockDim.x + threadIdx.x;
-                if (i < m) part_keys[i] = score_key(v[u]);
+                if (i < m) {
+                    const uint32_t k = score_key(v[u]);
+                    part_keys[i] = k;
+                    my_or |= k, my_nand |= ~k;
+                }
             }
+        }
+    }
+    if (in_lds) {
+        my_or = wave_or_rows(my_or), my_nand = wave_or_rows(my_nand);
+        if (threadIdx.x % 16 == 0) {
+            atomicOr(&key_or, my_or);
+            atomicOr(&key_nand, my_nand);
         }
         __syncthreads();
     }
@@ -73,7 +93,8 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
     uint32_t kth_a, kth_b;
     int take_a, take_b;
     if (n_ret > 0 && n_cand > 0) {
-        radix_threshold2(key, m, n_ret, n_ret + n_cand, sh, kth_a, take_a, kth_b, take_b);
+        radix_threshold2_lists(key, m, n_ret, n_ret + n_cand, sh, kth_a, take_a, kth_b, take_b, in_lds,
+                               in_lds ? key_or & key_nand : 0u);
     } else {
         radix_threshold(key, m, n_ret, sh, kth_a, take_a);
         radix_threshold(key, m, n_ret + n_cand, sh, kth_b, take_b);

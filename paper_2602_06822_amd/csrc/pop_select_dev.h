@@ -62,6 +62,16 @@ __device__ __forceinline__ void block_excl_scan(int (&v)[N], int (&tot)[N], SelS
     __syncthreads();
 }
 
+// OR over each row of 16 lanes (every lane of the row gets it).
+__device__ __forceinline__ uint32_t wave_or_rows(uint32_t v)
+{
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);   // quad_perm 1,0,3,2
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xf, 0xf, true);   // quad_perm 2,3,0,1
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xf, 0xf, true);  // row_half_mirror
+    v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xf, 0xf, true);  // row_mirror
+    return v;
+}
+
 // hist[d] += 1 for every lane with valid set, d < 256.  Lanes of a wave that hold the same digit as its first
 // valid lane are counted by that lane, and again for the rest as long as such a group covers a quarter of the wave;
 // whatever is left adds on its own.  Scores of one layer share their exponent bits, so without this the leading
@@ -179,26 +189,38 @@ __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, Sel
 // Two thresholds in the same sweeps: the keys of the n_a-th and of the n_b-th best element, 0 < n_a < n_b <= n, with
 // their take counts, as two calls of radix_threshold would give them.  The common leading bits and the leading digit's
 // histogram serve both; from the second digit on a key is counted for the threshold(s) whose prefix it matches.
+// Made for a large key set: digits are cut from the highest differing bit down (so the leading digit spreads the
+// keys over all its values even when that bit is not at a byte boundary), and the sweep for the second digit also
+// copies the keys that share a threshold's leading digit into a short list in sh.keys (half of it
+// per threshold), which the sweeps for the remaining digits read instead of all n keys.  A threshold whose leading
+// digit holds more keys than its list can take keeps sweeping all keys.  Must not be used while sh.keys holds data.
 template <class KeyFn>
-__device__ __forceinline__ void radix_threshold2(KeyFn key, int n, int n_a, int n_b, SelShared &sh, uint32_t &kth_a,
-                                                 int &take_a, uint32_t &kth_b, int &take_b)
+__device__ __forceinline__ void radix_threshold2_lists(KeyFn key, int n, int n_a, int n_b, SelShared &sh, uint32_t &kth_a,
+                                                       int &take_a, uint32_t &kth_b, int &take_b, bool have_diff = false,
+                                                       uint32_t diff_in = 0)
 {
+    constexpr int kCap = kSelLdsKeys / 2;
     unsigned int *scratch = &sh.hist[2][0];
-    if (threadIdx.x == 0) scratch[0] = 0;
+    if (threadIdx.x == 0) {
+        scratch[0] = 0;
+        sh.digit = 0;      // length of list 0
+        sh.remaining = 0;  // length of list 1
+    }
     if (threadIdx.x < 256) sh.hist[0][threadIdx.x] = 0;
     if (blockDim.x < 256)
         for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) sh.hist[0][i] = 0;
     __syncthreads();
     const uint32_t k0 = key(0);
-    uint32_t diff = 0;
-    for (int i = threadIdx.x; i < n; i += blockDim.x) diff |= key(i) ^ k0;
-    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0xB1, 0xf, 0xf, true);   // quad_perm 1,0,3,2
-    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x4E, 0xf, 0xf, true);   // quad_perm 2,3,0,1
-    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x141, 0xf, 0xf, true);  // row_half_mirror
-    diff |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)diff, 0x140, 0xf, 0xf, true);  // row_mirror
-    if (threadIdx.x % 16 == 0 && diff) atomicOr(&scratch[0], diff);
-    __syncthreads();
-    diff = scratch[0];
+    // bits in which any two keys differ: from the caller (who had every key in hand), else one sweep
+    uint32_t diff = diff_in;
+    if (!have_diff) {
+        diff = 0;
+        for (int i = threadIdx.x; i < n; i += blockDim.x) diff |= key(i) ^ k0;
+        diff = wave_or_rows(diff);
+        if (threadIdx.x % 16 == 0 && diff) atomicOr(&scratch[0], diff);
+        __syncthreads();
+        diff = scratch[0];
+    }
     if (diff == 0) {  // all keys equal
         __syncthreads();
         kth_a = kth_b = k0;
@@ -211,9 +233,13 @@ __device__ __forceinline__ void radix_threshold2(KeyFn key, int n, int n_a, int 
     uint32_t known = top_bit == 31 ? 0u : ~((2u << top_bit) - 1u);
     uint32_t prefix[2] = {k0 & known, k0 & known};
     int remaining[2] = {n_a, n_b};
+    int matching[2] = {n, n};  // keys that share the threshold's prefix
+    const uint32_t *list[2] = {sh.keys, sh.keys + kCap};
+    bool listed[2] = {false, false};
     const int lane = threadIdx.x % kWave;
-    int pass = 0;
-    for (int shift = (n_pass - 1) * 8; shift >= 0; shift -= 8, ++pass) {
+    for (int pass = 0; pass < n_pass; ++pass) {
+        const int hi = top_bit - 8 * pass, lo = hi >= 7 ? hi - 7 : 0;
+        const uint32_t dmask = (1u << (hi - lo + 1)) - 1u;
         unsigned int *hist[2] = {sh.hist[pass % 3], pass == 0 ? sh.hist[0] : sh.hist2[pass % 3]};
         if (threadIdx.x < 256) {
             sh.hist[(pass + 1) % 3][threadIdx.x] = 0;
@@ -224,18 +250,47 @@ __device__ __forceinline__ void radix_threshold2(KeyFn key, int n, int n_a, int 
                 sh.hist[(pass + 1) % 3][i] = 0;
                 sh.hist2[(pass + 1) % 3][i] = 0;
             }
-        const int n_round = (n + blockDim.x - 1) / blockDim.x * blockDim.x;
         if (pass == 0) {
+            const int n_round = (n + blockDim.x - 1) / blockDim.x * blockDim.x;
             for (int i = threadIdx.x; i < n_round; i += blockDim.x) {
                 const uint32_t k = i < n ? key(i) : 0u;
-                wave_hist_add(hist[0], (k >> shift) & 255u, i < n && (k & known) == prefix[0]);
+                wave_hist_add(hist[0], (k >> lo) & dmask, i < n);
             }
-        } else {
+        } else if (pass == 1) {
+            // the one sweep that also fills the lists; with both thresholds under one leading digit they share list 0
+            const bool same = prefix[0] == prefix[1];
+            const bool fill0 = matching[0] <= kCap, fill1 = !same && matching[1] <= kCap;
             for (int i = threadIdx.x; i < n; i += blockDim.x) {
                 const uint32_t k = key(i);
-                const uint32_t kk = k & known, dg = (k >> shift) & 255u;
-                if (kk == prefix[0]) atomicAdd(&hist[0][dg], 1u);
-                if (kk == prefix[1]) atomicAdd(&hist[1][dg], 1u);
+                const uint32_t kk = k & known, dg = (k >> lo) & dmask;
+                if (kk == prefix[0]) {
+                    atomicAdd(&hist[0][dg], 1u);
+                    if (fill0) sh.keys[atomicAdd(&sh.digit, 1)] = k;
+                }
+                if (kk == prefix[1]) {
+                    atomicAdd(&hist[1][dg], 1u);
+                    if (fill1) sh.keys[kCap + atomicAdd(&sh.remaining, 1)] = k;
+                }
+            }
+            listed[0] = fill0;
+            listed[1] = fill1 || (same && fill0);
+            if (same) list[1] = list[0];
+        } else {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                if (listed[t]) {
+                    // (the list holds the keys that matched after the leading digit: a superset of the current matches)
+                    const int len = list[t] == sh.keys ? sh.digit : sh.remaining;
+                    for (int i = threadIdx.x; i < len; i += blockDim.x) {
+                        const uint32_t k = list[t][i];
+                        if ((k & known) == prefix[t]) atomicAdd(&hist[t][(k >> lo) & dmask], 1u);
+                    }
+                } else {
+                    for (int i = threadIdx.x; i < n; i += blockDim.x) {
+                        const uint32_t k = key(i);
+                        if ((k & known) == prefix[t]) atomicAdd(&hist[t][(k >> lo) & dmask], 1u);
+                    }
+                }
             }
         }
         __syncthreads();
@@ -248,21 +303,23 @@ __device__ __forceinline__ void radix_threshold2(KeyFn key, int n, int n_a, int 
                 lane_tot += c[q];
             }
             int before = wave_incl_scan(lane_tot) - lane_tot;
-            int digit = -1, rem_new = 0;
+            int digit = -1, rem_new = 0, in_digit = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 if (before < remaining[t] && remaining[t] <= before + c[q]) {
                     digit = 255 - (4 * lane + q);
                     rem_new = remaining[t] - before;
+                    in_digit = c[q];
                 }
                 before += c[q];
             }
             const int owner = __builtin_ctzll(__ballot(digit >= 0));
             digit = __builtin_amdgcn_readlane(digit, owner);
             remaining[t] = __builtin_amdgcn_readlane(rem_new, owner);
-            prefix[t] |= ((uint32_t)digit) << shift;
+            matching[t] = __builtin_amdgcn_readlane(in_digit, owner);
+            prefix[t] |= ((uint32_t)digit) << lo;
         }
-        known |= 255u << shift;
+        known |= dmask << lo;
     }
     __syncthreads();
     kth_a = prefix[0], take_a = remaining[0];
