@@ -162,3 +162,33 @@ def make_scores(n: int, tag: str, ties: str = "none") -> np.ndarray:
         s[some] = np.abs(g.standard_normal(int(some.sum()), dtype=np.float32))
         return s
     raise ValueError(ties)
+
+
+SCORE_SHAPES = ("low_byte", "two_bytes", "crowded", "three_values", "narrow_band", "wide_signed")
+
+
+def make_scores_shaped(n: int, tag: str, shape: str) -> np.ndarray:
+    """float32 score vectors whose bit patterns are laid out to reach the corners of a digit-wise rank selection.
+
+    "low_byte": values that differ in their lowest 8 bits only (many ties); "two_bytes": in their lowest 16 bits;
+    "crowded": 70 % one value, the rest log-normal (one digit bucket holds most keys); "three_values": three distinct
+    values; "narrow_band": uniform in [1, 1 + 2^-10) (the ranks of interest share their leading digits);
+    "wide_signed": heavy-tailed with both signs over many binades.
+    """
+    g = rng("scores_shaped", tag, n, shape)
+    one = np.float32(1.0).view(np.uint32)
+    if shape == "low_byte":
+        return (one + g.integers(0, 200, size=n).astype(np.uint32)).view(np.float32)
+    if shape == "two_bytes":
+        return (one + g.integers(0, 60000, size=n).astype(np.uint32)).view(np.float32)
+    if shape == "crowded":
+        s = np.exp(g.standard_normal(n)).astype(np.float32)
+        s[g.random(n) < 0.7] = np.float32(3.0)
+        return s
+    if shape == "three_values":
+        return np.array([0.5, 1.0, 2.0], dtype=np.float32)[g.integers(0, 3, size=n)]
+    if shape == "narrow_band":
+        return (np.float32(1.0) + g.random(n, dtype=np.float32) * np.float32(2.0 ** -10)).astype(np.float32)
+    if shape == "wide_signed":
+        return (np.exp(6.0 * g.standard_normal(n)) * np.where(g.random(n) < 0.3, -1.0, 1.0)).astype(np.float32)
+    raise ValueError(shape)

@@ -55,6 +55,24 @@ def test_partition_from_scores_bit_exact(pop, oracle, ties):
         assert np.array_equal(host(cand)[:n_cand], cand0), (m, n_ret, n_cand, ties)
 
 
+@pytest.mark.parametrize("shape", synth.SCORE_SHAPES)
+def test_partition_from_scores_shaped_keys(pop, oracle, shape):
+    """Score vectors whose keys crowd into few digit values, differ in few bits or span many binades: the two
+    thresholds fall into one digit bucket or into different ones, into short buckets or into ones too long for the
+    selector's key lists, with the keys staged on chip (m <= 24576) or read from memory."""
+    for m in (5000, 11008, 24576, 30000):
+        s = synth.make_scores_shaped(m, f"gpu_part_shaped_{m}", shape)
+        for n_ret, n_cand in ((int(0.6 * m), int(0.1 * m)), (1, 1), (m - 2, 1), (m // 2, 3), (m // 3, m - m // 3)):
+            region = torch.full((m,), 9, dtype=torch.uint8, device="cuda")
+            ret = torch.full((n_ret,), -1, dtype=torch.int32, device="cuda")
+            cand = torch.full((n_cand,), -1, dtype=torch.int32, device="cuda")
+            pop.pop_partition_from_scores(dev(s), m, n_ret, n_cand, region, ret, cand)
+            r0, ret0, cand0 = oracle.partition(s, n_ret, n_cand)
+            assert np.array_equal(host(region), r0), (m, n_ret, n_cand, shape)
+            assert np.array_equal(host(ret), ret0), (m, n_ret, n_cand, shape)
+            assert np.array_equal(host(cand), cand0), (m, n_ret, n_cand, shape)
+
+
 @pytest.mark.parametrize("ties", ["none", "some", "all", "zeros"])
 def test_topk_from_scores_bit_exact(pop, oracle, ties):
     for m, n_ret, n_cand in SEL_CASES:
