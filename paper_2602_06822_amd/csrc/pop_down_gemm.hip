@@ -12,8 +12,9 @@
 // touches, into disjoint banks.
 //
 // Workgroup: 256 tokens x 128 columns, 8 waves (4 along the tokens x 2 along n), wave tile 64 x 64 = 2 x 2 MFMA
-// tiles, k-steps of 64 channels, LDS double buffer filled through registers; channel numbers are fetched two steps
-// ahead so the weight loads never wait for them.  Short prompts do not give enough tiles to fill the chip, so the
+// tiles, k-steps of 64 channels, LDS double buffer filled through registers with the rows of two k-steps in flight
+// (a workgroup's k-step holds too few products to cover the latency of its loads); channel numbers are fetched a
+// step further ahead so the weight loads never wait for them.  Short prompts do not give enough tiles to fill the chip, so the
 // contraction is split into n_split ranges whose float32 partial results are summed, in split order, by a second
 // kernel (deterministic).
 #include "pop_internal.h"
@@ -62,53 +63,60 @@ __global__ __launch_bounds__(512) void down_gemm_bf16_kernel(const uint16_t *__r
     // 32 rows per pass, 2 passes
     const int a_row = tid / 8, a_kv = tid % 8;
     const int b_row = tid / 16, b_nv = tid % 16;
+    // Every load below is unconditional (addresses clamped into valid memory, the value replaced afterwards where it
+    // must not count), so that the loads of two k-steps can be in flight at once: with loads under branches the
+    // compiler can only wait for all of them.  Token rows beyond T are clamped and never stored.
     const uint16_t *pa[4];
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int t = t0 + a_row + p * 64;
-        pa[p] = t < T ? hc + (size_t)t * ldh : nullptr;
-    }
+    for (int p = 0; p < 4; ++p) pa[p] = hc + (size_t)min(t0 + a_row + p * 64, T - 1) * ldh;
     const bool n_ok = n0 + b_nv * 8 < d;
-    uint4 ra[4], rb[2];
-    int ch_next[2];  // channels of this thread's two weight rows in the step after the one being loaded
-    auto load_channels = [&](int ks) {
+    const int n_col = n_ok ? n0 + b_nv * 8 : 0;
+    uint4 ra[2][4], rb[2][2];  // two k-steps on their way through registers, as loaded
+    uint32_t rb_on[2][2];      // all ones where the weight row exists, else 0
+    int chn[2][2], chn_off[2][2];  // channels of this thread's two weight rows, two k-steps, as loaded; -1 where the
+                                   // row does not exist, else 0 (kept apart so that nothing touches the loaded value
+                                   // before its use a step later)
+    auto load_channels = [&](int set, int ks) {
 #pragma unroll
         for (int p = 0; p < 2; ++p) {
             const int c = ks * kDgBK + b_row + p * 32;
-            ch_next[p] = (ks < ks1 && c < a) ? list[c] : -1;
+            chn[set][p] = list[min(c, a - 1)];
+            chn_off[set][p] = -(int)(ks >= ks1 || c >= a);
         }
     };
-    auto load_global = [&](int ks) {
-        const int k = ks * kDgBK + a_kv * 8;
+    auto load_global = [&](int set, int ks) {
+        const int k = min(ks, ks1 - 1) * kDgBK + a_kv * 8;
+        const int kc = k < a ? k : 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) ra[set][p] = *reinterpret_cast<const uint4 *>(pa[p] + kc);
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int j = chn[set][p] | chn_off[set][p];
+            rb[set][p] = *reinterpret_cast<const uint4 *>(w + ((size_t)max(j, 0) * 3 + 2) * d + n_col);
+            rb_on[set][p] = (j >= 0 && n_ok) ? 0xffffffffu : 0u;
+        }
+    };
+    // writes the rows of k-step ks, loaded into set `buf`, to LDS buffer `buf`; what lies beyond the a channels or
+    // the d columns is cleared here, where the loaded values are first touched
+    auto store_lds = [&](int buf, int ks) {
+        const int keep = a - (min(ks, ks1 - 1) * kDgBK + a_kv * 8);  // columns of the Hc vector that hold data
+        uint32_t keep_bits[4];                                       // 16-bit elements, two per word
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            keep_bits[q] = 2 * q >= keep ? 0u : (2 * q + 1 >= keep ? 0xffffu : 0xffffffffu);
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
-            uint4 v = (k < a && pa[p]) ? *reinterpret_cast<const uint4 *>(pa[p] + k) : make_uint4(0, 0, 0, 0);
-            if (k + 8 > a && k < a) {
-                // columns at and beyond a hold no data: clear them (16-bit elements, two per word)
-                const int keep = a - k;  // 1..7
-                uint32_t e[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    if (2 * q >= keep) e[q] = 0;
-                    else if (2 * q + 1 >= keep) e[q] &= 0xffffu;
-                }
-                v = make_uint4(e[0], e[1], e[2], e[3]);
-            }
-            ra[p] = v;
+            const uint4 v = ra[buf][p];
+            *reinterpret_cast<uint4 *>(&As[(buf * kDgBM + a_row + p * 64) * kDgLdA + a_kv * 8]) =
+                make_uint4(v.x & keep_bits[0], v.y & keep_bits[1], v.z & keep_bits[2], v.w & keep_bits[3]);
         }
 #pragma unroll
-        for (int p = 0; p < 2; ++p)
-            rb[p] = (ch_next[p] >= 0 && n_ok)
-                        ? *reinterpret_cast<const uint4 *>(w + ((size_t)ch_next[p] * 3 + 2) * d + n0 + b_nv * 8)
-                        : make_uint4(0, 0, 0, 0);
-    };
-    auto store_lds = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-            *reinterpret_cast<uint4 *>(&As[(buf * kDgBM + a_row + p * 64) * kDgLdA + a_kv * 8]) = ra[p];
-#pragma unroll
-        for (int p = 0; p < 2; ++p)
-            *reinterpret_cast<uint4 *>(&Bs[(buf * kDgBK + b_row + p * 32) * kDgLdB + b_nv * 8]) = rb[p];
+        for (int p = 0; p < 2; ++p) {
+            const uint4 v = rb[buf][p];
+            const uint32_t on = rb_on[buf][p];
+            *reinterpret_cast<uint4 *>(&Bs[(buf * kDgBK + b_row + p * 32) * kDgLdB + b_nv * 8]) =
+                make_uint4(v.x & on, v.y & on, v.z & on, v.w & on);
+        }
     };
 
     f32x16_t acc[2][2];
@@ -150,22 +158,34 @@ __global__ __launch_bounds__(512) void down_gemm_bf16_kernel(const uint16_t *__r
         }
     };
 
-    if (ks0 < ks1) {
-        load_channels(ks0);
-        load_global(ks0);
-        load_channels(ks0 + 1);
-        store_lds(0);
+    // Step ks multiplies LDS buffer (ks - ks0) % 2.  Meanwhile the rows of step ks + 1 are in registers (set of the
+    // other parity, requested one step earlier, written to the other buffer after the products), the rows of step
+    // ks + 2 are requested into the set this buffer was filled from, and the channel numbers of step ks + 3 are
+    // requested ahead of them, so that no wait for an older request also waits for a younger one that is not needed yet.
+    const int n_steps = ks1 - ks0;
+    if (n_steps > 0) {
+        load_channels(0, ks0);
+        load_global(0, ks0);
+        load_channels(1, ks0 + 1);
+        load_global(1, ks0 + 1);
+        load_channels(0, ks0 + 2);
+        store_lds(0, ks0);
         __syncthreads();
-        for (int ks = ks0; ks < ks1; ++ks) {
-            const int buf = (ks - ks0) & 1;
-            if (ks + 1 < ks1) {
-                load_global(ks + 1);
-                load_channels(ks + 2);
-            }
-            multiply(buf);
-            if (ks + 1 < ks1) store_lds(buf ^ 1);
+        auto step = [&](int ks, int b) {
+            load_channels(b ^ 1, ks + 3);
+            load_global(b, ks + 2);
+            __builtin_amdgcn_sched_barrier(0);  // (keeps the requests ahead of the products in the instruction stream)
+            multiply(b);
+            __builtin_amdgcn_sched_barrier(0);
+            store_lds(b ^ 1, ks + 1);
             __syncthreads();
+        };
+        int i = 0;
+        for (; i + 1 < n_steps; i += 2) {
+            step(ks0 + i, 0);
+            step(ks0 + i + 1, 1);
         }
+        if (i < n_steps) multiply(0);  // (an odd last step: its rows were stored by the step before)
     }
 
     // register v of a fragment is token row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32
