@@ -196,9 +196,9 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     PartitionExtra ex;
     const bool from_partials = !L->input_side && partition_takes_partials(m);
     if (!L->input_side && !from_partials)
-        POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16), m, L->nrm, L->scores, s));
+        POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16, m, L->n_cu), m, L->nrm, L->scores, s));
     if (from_partials) {
-        ex.s2_part = L->s2_part, ex.n_tiles = prefill_rows_used(T, L->is_bf16), ex.nrm = L->nrm;
+        ex.s2_part = L->s2_part, ex.n_tiles = prefill_rows_used(T, L->is_bf16, m, L->n_cu), ex.nrm = L->nrm;
         ex.scores_out = L->scores;
     }
     ex.sync = L->sync, ex.n_sync = 16;

@@ -196,7 +196,7 @@ hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s);
 // ---- prefill (pop_prefill.hip) ----
 // s2_part[tile][j] = sum over the tile's tokens of H[t][j]^2, one row per token tile.
 int prefill_num_tiles(int T, int is_bf16);  // upper bound on the rows used, for sizing s2_part
-int prefill_rows_used(int T, int is_bf16);  // rows the launch below writes for this T
+int prefill_rows_used(int T, int is_bf16, int m, int n_cu);  // rows the launch below writes for this T
 hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
                                  int n_cu, hipStream_t s);
 // bf16 layers: gate/up over the channels of a device-resident list (n_list: its length, on the device);

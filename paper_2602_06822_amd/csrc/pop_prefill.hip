@@ -116,7 +116,7 @@ struct PfStore {
 
 // kMode 0: scores only (s2_part).  1: channels from st.list, H stored compact (no s2_part).  2: all m channels,
 // s2_part and H stored as [T][m padded].
-template <int BM, int NW, int NF, int kMode, bool kDma = false>
+template <int BM, int NW, int NF, int kMode, bool kDma = false, int NS = 2>
 __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *__restrict__ w,
                                                            const uint16_t *__restrict__ x, int T, int d, int m,
                                                            int n_ttiles, int chunk, int n_items, int per_xcd,
@@ -131,8 +131,9 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
     // at unit ^ ((r / 2) % 8) (direct global -> LDS loads, which fill 1 KB = 8 whole rows per wave instruction)
     constexpr int LD = kDma ? kPfBK : kPfLd;
     extern __shared__ __attribute__((aligned(16))) uint16_t pf_lds[];
-    uint16_t *As = pf_lds;                    // [2][BM * LD]
-    uint16_t *Bs = pf_lds + 2 * BM * LD;      // [2][BR * LD]
+    static_assert(kDma || NS == 2, "the register-staged path has two LDS buffers");
+    uint16_t *As = pf_lds;                    // [NS][BM * LD]
+    uint16_t *Bs = pf_lds + NS * BM * LD;     // [NS][BR * LD]
     __shared__ float colsum[TW][kPfChunk];
 
     constexpr bool kList = kMode == 1, kStore = kMode != 0;
@@ -158,18 +159,22 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
     constexpr int PA = BM / RP, PB = BR / RP;
     static_assert(BM % RP == 0 && BR % RP == 0, "whole staging passes");
     uint4 ra[PA], rb[PB];
-    const uint16_t *pa[PA], *pb[PB];  // row starts (null: a row of zeros)
+    // Row starts.  Register-staged path: null for a row of zeros (tokens beyond T, channels beyond the chunk).  Direct
+    // path: such rows are pointed at a row that exists instead, so that every wave issues the same number of loads per
+    // k-step (its waits count them); what they produce is left out by the epilogue.
+    const uint16_t *pa[PA], *pb[PB];
 #pragma unroll
     for (int p = 0; p < PA; ++p) {
         const int t = t0 + ld_row + p * RP;
-        pa[p] = t < T ? x + (size_t)t * d : nullptr;
+        pa[p] = kDma ? x + (size_t)min(t, T - 1) * d : (t < T ? x + (size_t)t * d : nullptr);
     }
 #pragma unroll
     for (int p = 0; p < PB; ++p) {
         int ch, which;
         pf_row_channel<NF>(ld_row + p * RP, ch, which);
-        if (ch < cn) {
-            const int j = kList ? st.list[c0 + ch] : c0 + ch;
+        if (ch < cn || kDma) {
+            const int cc = min(ch, cn - 1);
+            const int j = kList ? st.list[c0 + cc] : c0 + cc;
             pb[p] = w + ((size_t)j * 3 + which) * d;
         } else {
             pb[p] = nullptr;
@@ -194,22 +199,20 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
             *reinterpret_cast<uint4 *>(&Bs[(buf * BR + ld_row + p * RP) * LD + ld_kv * 8]) = rb[p];
     };
     // direct loads: this lane's 16 bytes land at LDS unit ld_kv of row ld_row of the pass, so it fetches the k-vector
-    // that belongs there under the swizzle; rows without data are skipped (their LDS rows stay zero)
+    // that belongs there under the swizzle
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-    const int src_kv = (ld_kv ^ ((ld_row / 2) % 8)) * 8;  // (passes are 64 rows apart: the swizzle term is the same)
+    const int src_kv = (ld_kv ^ ((ld_row / 2) % 8)) * 8;  // (passes are RP rows apart, a multiple of 16: same swizzle term)
     auto dma_load = [&](int buf, int k0) {
         typedef __attribute__((address_space(3))) void lds_t;
         typedef __attribute__((address_space(1))) const void glb_t;
 #pragma unroll
         for (int p = 0; p < PA; ++p)
-            if (pa[p])
-                __builtin_amdgcn_global_load_lds((glb_t *)(pa[p] + k0 + src_kv),
-                                                 (lds_t *)(As + (buf * BM + p * RP + wave_u * 8) * LD), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_t *)(pa[p] + k0 + src_kv),
+                                             (lds_t *)(As + (buf * BM + p * RP + wave_u * 8) * LD), 16, 0, 0);
 #pragma unroll
         for (int p = 0; p < PB; ++p)
-            if (pb[p])
-                __builtin_amdgcn_global_load_lds((glb_t *)(pb[p] + k0 + src_kv),
-                                                 (lds_t *)(Bs + (buf * BR + p * RP + wave_u * 8) * LD), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((glb_t *)(pb[p] + k0 + src_kv),
+                                             (lds_t *)(Bs + (buf * BR + p * RP + wave_u * 8) * LD), 16, 0, 0);
     };
 
     f32x16_t acc[MT][NF];  // [token fragment][0 = gate 0..31, 1 = up 0..31, 2 = gate 32..47 | up 32..47]
@@ -252,18 +255,25 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
         }
     };
     if (kDma) {
-        // (needs d % 64 == 0.)  Rows that no load ever writes must read as zeros
-        for (int i = tid; i < 2 * (BM + BR) * LD / 8; i += NW * 64) reinterpret_cast<uint4 *>(pf_lds)[i] = make_uint4(0, 0, 0, 0);
-        __syncthreads();
-        // step ks multiplies LDS buffer ks % 2 while the rows of step ks + 1 land in the other one
-        dma_load(0, 0);
-        __syncthreads();  // (waits for this wave's loads, then for everybody's)
+        // (needs d % 64 == 0.)  A ring of NS LDS buffers: step ks multiplies buffer ks % NS while the rows of steps
+        // ks + 1 .. ks + NS - 1 are landing in or on their way to the others.  Per step: wait until this wave's loads
+        // of step ks have landed (all but the (NS - 2) (PA + PB) younger ones), meet the other waves (now everybody's
+        // have, and everybody is done reading the buffer of step ks - 1), request step ks + NS - 1 into that buffer,
+        // multiply.  Steps beyond the last are requested again from the last step's columns, so the count holds.
+        constexpr int kYounger = (NS - 2) * (PA + PB);
+        static_assert(kYounger < 64, "vmcnt is a 6-bit counter");
+        // s_waitcnt with only the vector-memory counter set: vmcnt[3:0] | expcnt 7 << 4 | lgkmcnt 15 << 8 | vmcnt[5:4] << 14
+        constexpr int kWaitImm = (kYounger & 15) | (7 << 4) | (15 << 8) | ((kYounger >> 4) << 14);
+#pragma unroll
+        for (int q = 0; q < NS - 1; ++q) dma_load(q, min(q, n_k - 1) * kPfBK);
         for (int ks = 0; ks < n_k; ++ks) {
-            const int buf = ks & 1;
-            if (ks + 1 < n_k) dma_load(buf ^ 1, (ks + 1) * kPfBK);
-            multiply(buf);
-            __syncthreads();
+            __builtin_amdgcn_s_waitcnt(kWaitImm);
+            asm volatile("s_barrier" ::: "memory");  // (no fence: a fence would wait for the younger loads too)
+            dma_load((ks + NS - 1) % NS, min(ks + NS - 1, n_k - 1) * kPfBK);
+            multiply(ks % NS);
         }
+        __builtin_amdgcn_s_waitcnt((0 & 15) | (7 << 4) | (15 << 8));  // the surplus requests, before LDS is reused
+        __syncthreads();
     } else {
         // step ks multiplies LDS buffer ks % 2 while the rows of step ks + 1 are on their way through registers
         load_global(0);
@@ -278,8 +288,9 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
         }
     }
 
-    // epilogue: lane holds 16 * MT token rows of column (lane % 32) of each fragment; rows of padded tokens and
-    // columns of padded channels are exactly 0
+    // epilogue: lane holds 16 * MT token rows of column (lane % 32) of each fragment.  Register-staged path: rows of
+    // padded tokens and columns of padded channels are exactly 0.  Direct path: they hold products of the rows their
+    // loads were pointed at; padded tokens are left out of the sums below, padded channels are never written.
     if (kStore) {
         // register v of a fragment is token row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32
         const int col = lane % 32;
@@ -314,18 +325,20 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
         if (kList) return;
     }
     float ss01 = 0.f, ss2 = 0.f;
+    const int t_left = T - (t0 + wm * (BM / TW) + (lane / 32) * 4);  // this lane's rows below t_left are tokens
 #pragma unroll
     for (int a = 0; a < MT; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
+            const bool live = !kDma || a * 32 + (v / 4) * 8 + v % 4 < t_left;
             const float hv = silu_mul_tile(acc[a][0][v], acc[a][1][v]);
-            ss01 = fmaf(hv, hv, ss01);
+            ss01 = fmaf(hv, live ? hv : 0.f, ss01);
             if (NF == 3) {
                 // mixed fragment: the up value of column c < 16 sits in lane c + 16, same register
                 const float g2 = acc[a][NF - 1][v];
                 const float u2 = __shfl_xor(g2, 16, kWave);
                 const float h2 = silu_mul_tile(g2, u2);
-                ss2 = fmaf(h2, h2, ss2);
+                ss2 = fmaf(h2, live ? h2 : 0.f, ss2);
             }
         }
     ss01 += __shfl_xor(ss01, 32, kWave);
@@ -394,17 +407,28 @@ __global__ __launch_bounds__(256) void prefill_f32_kernel(const float *__restric
     }
 }
 
-// Token tile: 256 tokens unless the padding to whole tiles would then cost over 15 % more rows than with 128.
-static int prefill_token_tile(int T)
+// Token tile: 256 or 128 tokens, whichever gives the cheaper schedule: tiles per compute unit on the busiest one
+// (after the chunks are evened out) times a tile's measured relative cost - 1 for 256 tokens x three fragments, 0.8
+// with two fragments, and 0.6 of either for the 128-token form (half the products, a ring of three LDS buffers).
+// At config 2 this picks 128 up to 256 tokens and 256 from there on.  POP_PF_BM=128 / 256 overrides (tuning).
+static int prefill_token_tile(int T, int n_ch, int n_cu)
 {
-    const int pad256 = (T + 255) / 256 * 256, pad128 = (T + 127) / 128 * 128;
-    return (double)pad256 <= 1.15 * (double)pad128 ? 256 : 128;
+    if (const char *e = getenv("POP_PF_BM")) return atoi(e) == 128 ? 128 : 256;
+    int best_bm = 256;
+    long best = -1;
+    for (int bm = 256; bm >= 128; bm -= 128) {
+        const PfGeom g = prefill_geometry(n_ch, (T + bm - 1) / bm, n_cu);
+        const long waves = (g.total + n_cu - 1) / n_cu;
+        const long cost = waves * (g.nf == 3 ? 5 : 4) * (bm == 256 ? 5 : 3);
+        if (best < 0 || cost < best) best = cost, best_bm = bm;
+    }
+    return best_bm;
 }
 
-int prefill_rows_used(int T, int is_bf16)
+int prefill_rows_used(int T, int is_bf16, int m, int n_cu)
 {
     if (!is_bf16) return (T + kPf32BM - 1) / kPf32BM;
-    const int bm = prefill_token_tile(T);
+    const int bm = prefill_token_tile(T, m, n_cu);
     return (T + bm - 1) / bm;
 }
 
@@ -413,14 +437,18 @@ static hipError_t launch_pf_bf16(int blocks, hipStream_t s, const void *w, const
                                  const PfGeom &g, float *s2_part, const PfStore &st)
 {
     // rows that are whole k-steps long go from global memory straight into LDS (POP_PF_DMA=0 keeps them on the
-    // register-staged path, for comparison)
+    // register-staged path, for comparison).  The 128-token tile is small enough for a ring of three LDS buffers:
+    // short prompts are bound by the weight stream from memory, and two k-steps in flight per compute unit carry
+    // twice the bytes of one.
     static const int use_dma = getenv("POP_PF_DMA") ? atoi(getenv("POP_PF_DMA")) : 1;
     if (use_dma && d % kPfBK == 0) {
-        const size_t lds_d = (size_t)2 * (BM + NF * 64) * kPfBK * sizeof(uint16_t);
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<BM, NW, NF, kMode, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_d);
+        constexpr int NS = BM <= 128 ? 3 : 2;
+        const size_t lds_d = (size_t)NS * (BM + NF * 64) * kPfBK * sizeof(uint16_t);
+        hipError_t e =
+            hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_bf16_kernel<BM, NW, NF, kMode, true, NS>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_d);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL((prefill_bf16_kernel<BM, NW, NF, kMode, true>), dim3(blocks), dim3(NW * 64), lds_d, s,
+        hipLaunchKernelGGL((prefill_bf16_kernel<BM, NW, NF, kMode, true, NS>), dim3(blocks), dim3(NW * 64), lds_d, s,
                            (const uint16_t *)w, (const uint16_t *)x, T, d, m, n_tt, g.chunk, g.total, g.per_xcd, s2_part,
                            st);
         return hipGetLastError();
@@ -438,7 +466,7 @@ template <int kMode>
 static hipError_t launch_pf_bf16_all(const void *w, int d, int m, const void *x, int T, float *s2_part, int n_cu,
                                      const PfStore &st, hipStream_t s)
 {
-    const int bm = prefill_token_tile(T);
+    const int bm = prefill_token_tile(T, m, n_cu);
     const int n_tt = (T + bm - 1) / bm;
     const PfGeom g = prefill_geometry(m, n_tt, n_cu);
     const int blocks = g.per_xcd * 8;
@@ -474,7 +502,7 @@ hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const
 hipError_t launch_gateup_list_bf16(const void *w, int d, int m, const void *x, int T, const int *list, const int *n_list,
                                    const unsigned char *tmask, uint16_t *hc, int ldh, int n_cu, hipStream_t s)
 {
-    const int bm = prefill_token_tile(T);
+    const int bm = prefill_token_tile(T, m, n_cu);  // (the list's length is not known here: priced as all m channels)
     const int n_tt = (T + bm - 1) / bm;
     PfStore st{list, n_list, hc, ldh, tmask, n_cu};
     PfGeom g{};
