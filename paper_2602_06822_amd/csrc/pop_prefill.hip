@@ -15,7 +15,10 @@
 // tile order.  Operand rows that are whole k-steps long (d a multiple of 64) go from global memory straight into LDS
 // (global_load_lds, 1 KB = 8 unpadded rows per wave instruction, 16-byte units XOR-swizzled by row pair so that the
 // fragment reads stay conflict-free); fetching them through registers costs a quarter more time even when every load
-// hits the cache, and remains the path for other row lengths.
+// hits the cache, and remains the path for other row lengths.  On the direct path every wave issues the same loads
+// in every k-step (rows that do not exist are pointed at one that does and left out by the epilogue), so a step waits
+// with an exact count for its own rows only, and the 128-token tile runs a ring of three LDS buffers: short prompts
+// are bound by the weight stream from memory, where two k-steps in flight carry twice the bytes of one.
 // Two more forms of the same kernel serve the forward pass of a whole prompt under the pruning structure
 // (Sec. 3.4): one also writes H (rounded to bf16) as [T][m]; one runs its chunks over a device-resident list of
 // active channels instead of all m and writes H (optionally times a per-token mask) in compact form
