@@ -87,6 +87,7 @@ struct pop_layer {
     float *ffn_part = nullptr;         // [splits][tokens][d]: partial outputs of the split contraction
     size_t ffn_part_cap = 0;           // elements
     unsigned char *ffn_any = nullptr;  // [m]: channels active in any row of a per-token mask
+    int *top_list = nullptr;           // [m] + 1: the prompt's own active channels (ascending), then their number
 };
 
 namespace {
@@ -185,8 +186,10 @@ int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mas
 }
 
 // Scores, partition and partition-constant step state from s2_part (the second half of the prefilling stage).
+// n_top >= 0: the same launch also leaves the n_top best channels as a byte mask in ffn_any and as an ascending list
+// with its length in top_list.
 int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, unsigned char *region, int *ret_idx,
-                     int *cand_idx, hipStream_t s)
+                     int *cand_idx, hipStream_t s, int n_top = -1)
 {
     const int m = L->m;
     // the partition launch also forms the scores from the contraction's partial rows (the input-side scores are
@@ -202,6 +205,7 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
         ex.scores_out = L->scores;
     }
     ex.sync = L->sync, ex.n_sync = 16;
+    if (n_top >= 0) ex.n_top = n_top, ex.top_mask = L->ffn_any, ex.top_list = L->top_list, ex.top_count = L->top_list + m;
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s, &ex));
     const StridedClear clr = fused_selbits_clear(L->selbits);
     POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s,
@@ -329,7 +333,7 @@ int pop_layer_destroy(pop_layer_t *L)
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
                     L->h,      L->cscore, L->mask, L->selflag, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
-                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part};
+                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part, L->top_list};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -471,20 +475,15 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
             POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, d, m, x, T, L->s2_part, L->n_cu, s));
         }
     }
-    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s); if (rc != POP_OK) return rc; }
-    // prefill mask: retained channels plus the best k0 candidates by prefill score; the active list (retained, then
-    // selected) lands in row 0 of the step's list, which the next decode step rewrites anyway
+    // prefill mask: retained channels plus the best k0 candidates by prefill score, i.e. the n_ret + k0 best channels
+    // of the partition's own order: the partition launch emits them as well (mask bytes and ascending list)
+    if (!L->top_list && !dev_alloc((void **)&L->top_list, ((size_t)m + 1) * sizeof(int))) return POP_ENOMEM;
+    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, n_ret + k0); if (rc != POP_OK) return rc; }
     unsigned char *pm = L->ffn_any;
-    BatchK kk = {};
-    kk.k[0] = k0;
-    POP_HIP(launch_gather_f32(L->scores, L->cand_idx, n_cand, L->cscore, s));
-    POP_HIP(launch_step_state_init(L->region, m, nullptr, 0, 1, 0, pm, nullptr, s));
-    POP_HIP(launch_topk(L->cscore, n_cand, L->cand_idx, n_cand, n_ret, m, 1, kk, m, pm, L->active_idx, L->n_active,
-                        nullptr, nullptr, nullptr, nullptr, nullptr, s));
     if (mask) POP_HIP(hipMemcpyAsync(mask, pm, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (keep) {
-        POP_HIP(launch_compact_hidden(L->ffn_hall, ldh, T, L->active_idx, L->n_active, n_ret + k0, L->ffn_hc, ldh, s));
-        POP_HIP(launch_down_gemm_bf16(L->w, d, L->active_idx, L->n_active, L->ffn_hc, ldh, T, n_split, L->ffn_part, y,
+        POP_HIP(launch_compact_hidden(L->ffn_hall, ldh, T, L->top_list, L->top_list + m, n_ret + k0, L->ffn_hc, ldh, s));
+        POP_HIP(launch_down_gemm_bf16(L->w, d, L->top_list, L->top_list + m, L->ffn_hc, ldh, T, n_split, L->ffn_part, y,
                                       ydtype == POP_BF16, s));
         return POP_OK;
     }

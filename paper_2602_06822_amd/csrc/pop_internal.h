@@ -94,6 +94,13 @@ struct PartitionExtra {
     float *scores_out = nullptr;
     int *sync = nullptr;
     int n_sync = 0;
+    // with top_list given: the n_top best channels of the same order as well (the prompt's own mask, Sec. 3.4: the
+    // retained channels plus the best candidates by prefill score are the n_top best overall) - top_mask[m] bytes
+    // (optional), their ascending list, *top_count = n_top
+    int n_top = 0;
+    unsigned char *top_mask = nullptr;
+    int *top_list = nullptr;
+    int *top_count = nullptr;
 };
 bool partition_takes_partials(int m);
 hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
@@ -226,8 +233,6 @@ hipError_t launch_input_side_scores(const void *w, int is_bf16, int d, const flo
                                     int n_rows, float *out, int out_stride, hipStream_t s);
 // cs[b][p] <- sqrt(sum over b' < B of cs[b'][p]^2) for every b < B, p < n
 hipError_t launch_aggregate_scores(float *cs, int cs_stride, int B, int n, hipStream_t s);
-// out[i] = src[idx[i]], i < n
-hipError_t launch_gather_f32(const float *src, const int *idx, int n, float *out, hipStream_t s);
 // any[j] = 1 if mask[t][j] != 0 for some t < rows, else 0
 hipError_t launch_mask_any(const unsigned char *mask, int rows, int m, unsigned char *any, hipStream_t s);
 // scores[j] = nrm[j] * sqrt(sum_tile s2_part[tile][j])

@@ -14,6 +14,54 @@ namespace pop {
 // index-ordered passes never go back to memory; beyond kPartLdsKeys channels they are read from global memory.
 constexpr int kPartLdsKeys = 24576;  // 96 KiB of keys
 
+// Index-ordered passes of the partition: thread t owns channels [t*E, (t+1)*E).  A channel above a threshold key is
+// in; one equal to it is in while fewer than `take` equal ones precede it.  So with the numbers of greater and of
+// equal channels before a thread's range (one scan of 2 NT streams) every channel's region and list position follow
+// directly.  NT = 3 also emits the channels within the third threshold: a byte mask, their ascending list, its length.
+template <int NT, class KeyFn>
+__device__ __forceinline__ void partition_emit(KeyFn key, int m, const uint32_t (&kth)[3], const int (&take)[3],
+                                               unsigned char *__restrict__ region, int *__restrict__ ret_idx,
+                                               int *__restrict__ cand_idx, const PartitionExtra &ex, SelShared &sh)
+{
+    const int E = (m + blockDim.x - 1) / blockDim.x;
+    const int lo = min(m, (int)threadIdx.x * E), hi = min(m, lo + E);
+    int cnt[2 * NT], tot[2 * NT];  // per threshold: greater than its key, equal to it
+#pragma unroll
+    for (int q = 0; q < 2 * NT; ++q) cnt[q] = 0;
+    for (int j = lo; j < hi; ++j) {
+        const uint32_t k = key(j);
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            cnt[2 * t] += (k > kth[t]);
+            cnt[2 * t + 1] += (k == kth[t]);
+        }
+    }
+    block_excl_scan<2 * NT>(cnt, tot, sh);
+    for (int j = lo; j < hi; ++j) {
+        const uint32_t k = key(j);
+        bool in[NT];
+        int before[NT];  // channels within threshold t before this one
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            in[t] = (k > kth[t]) || (k == kth[t] && cnt[2 * t + 1] < take[t]);
+            before[t] = cnt[2 * t] + min(cnt[2 * t + 1], take[t]);
+            cnt[2 * t] += (k > kth[t]);
+            cnt[2 * t + 1] += (k == kth[t]);
+        }
+        if (region) region[j] = in[0] ? POP_REGION_RETAINED : (in[1] ? POP_REGION_CANDIDATE : POP_REGION_PRUNED);
+        if (in[0]) {
+            if (ret_idx) ret_idx[before[0]] = j;
+        } else if (in[1]) {
+            if (cand_idx) cand_idx[before[1] - before[0]] = j;
+        }
+        if (NT == 3) {
+            if (ex.top_mask) ex.top_mask[j] = in[NT - 1] ? 1 : 0;
+            if (in[NT - 1]) ex.top_list[before[NT - 1]] = j;
+        }
+    }
+    if (NT == 3 && threadIdx.x == 0 && ex.top_count) *ex.top_count = ex.n_top;
+}
+
 __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict__ scores, int m, int n_ret, int n_cand,
                                                          unsigned char *__restrict__ region, int *__restrict__ ret_idx,
                                                          int *__restrict__ cand_idx, PartitionExtra ex)
@@ -90,48 +138,29 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
         __syncthreads();
     }
     auto key = [&](int i) { return in_lds ? part_keys[i] : score_key(scores[i]); };
-    uint32_t kth_a, kth_b;
-    int take_a, take_b;
-    if (n_ret > 0 && n_cand > 0) {
-        radix_threshold2_lists(key, m, n_ret, n_ret + n_cand, sh, kth_a, take_a, kth_b, take_b, in_lds,
-                               in_lds ? key_or & key_nand : 0u);
+    // thresholds: retained (rank n_ret), retained + candidate (rank n_ret + n_cand) and, on request, the n_top best
+    // channels.  An empty set is sought as a set of one and then closed (key above all keys, nothing taken).
+    const bool top = ex.top_list != nullptr;
+    uint32_t kth[3] = {0xffffffffu, 0xffffffffu, 0xffffffffu};
+    int take[3] = {0, 0, 0};
+    const uint32_t diff = in_lds ? key_or & key_nand : 0u;
+    if (top) {
+        const int cnt[3] = {max(n_ret, 1), max(n_ret + n_cand, 1), max(ex.n_top, 1)};
+        radix_thresholds_lists<3>(key, m, cnt, sh, kth, take, in_lds, diff);
     } else {
-        radix_threshold(key, m, n_ret, sh, kth_a, take_a);
-        radix_threshold(key, m, n_ret + n_cand, sh, kth_b, take_b);
+        const int cnt[2] = {max(n_ret, 1), max(n_ret + n_cand, 1)};
+        uint32_t kth2[2];
+        int take2[2];
+        radix_thresholds_lists<2>(key, m, cnt, sh, kth2, take2, in_lds, diff);
+        kth[0] = kth2[0], kth[1] = kth2[1], take[0] = take2[0], take[1] = take2[1];
     }
-
-    // index-ordered passes: thread t owns channels [t*E, (t+1)*E).  A channel above a threshold key is in; one equal to
-    // it is in while fewer than `take` equal ones precede it.  So with the numbers of greater and of equal channels
-    // before a thread's range (one scan of four streams) every channel's region and list position follow directly.
-    int E = (m + blockDim.x - 1) / blockDim.x;
-    int lo = min(m, (int)threadIdx.x * E), hi = min(m, lo + E);
-    int cnt[4] = {0, 0, 0, 0}, tot[4];  // greater than a, equal to a, greater than b, equal to b
-    for (int j = lo; j < hi; ++j) {
-        const uint32_t k = key(j);
-        cnt[0] += (k > kth_a);
-        cnt[1] += (k == kth_a);
-        cnt[2] += (k > kth_b);
-        cnt[3] += (k == kth_b);
-    }
-    block_excl_scan<4>(cnt, tot, sh);
-    int gt_a = cnt[0], eq_a = cnt[1], gt_b = cnt[2], eq_b = cnt[3];
-    for (int j = lo; j < hi; ++j) {
-        const uint32_t k = key(j);
-        const bool in_r = (k > kth_a) || (k == kth_a && eq_a < take_a);
-        const bool in_rc = (k > kth_b) || (k == kth_b && eq_b < take_b);
-        // channels of the retained set / of retained + candidate before this one
-        const int n_r = gt_a + min(eq_a, take_a), n_rc = gt_b + min(eq_b, take_b);
-        if (region) region[j] = in_r ? POP_REGION_RETAINED : (in_rc ? POP_REGION_CANDIDATE : POP_REGION_PRUNED);
-        if (in_r) {
-            if (ret_idx) ret_idx[n_r] = j;
-        } else if (in_rc) {
-            if (cand_idx) cand_idx[n_rc - n_r] = j;
-        }
-        gt_a += (k > kth_a);
-        eq_a += (k == kth_a);
-        gt_b += (k > kth_b);
-        eq_b += (k == kth_b);
-    }
+    if (n_ret == 0) kth[0] = 0xffffffffu, take[0] = 0;
+    if (n_ret + n_cand == 0) kth[1] = 0xffffffffu, take[1] = 0;
+    if (!top || ex.n_top == 0) kth[2] = 0xffffffffu, take[2] = 0;
+    if (top)
+        partition_emit<3>(key, m, kth, take, region, ret_idx, cand_idx, ex, sh);
+    else
+        partition_emit<2>(key, m, kth, take, region, ret_idx, cand_idx, ex, sh);
 }
 
 bool partition_takes_partials(int m) { return m <= kPartLdsKeys; }
@@ -323,21 +352,6 @@ hipError_t launch_mask_any(const unsigned char *mask, int rows, int m, unsigned 
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(mask_any_kernel, dim3((m + 1023) / 1024, (rows + kAnyRows - 1) / kAnyRows), dim3(256), 0, s, mask,
                        rows, m, any);
-    return hipGetLastError();
-}
-
-// out[i] = src[idx[i]]
-__global__ __launch_bounds__(256) void gather_f32_kernel(const float *__restrict__ src, const int *__restrict__ idx, int n,
-                                                         float *__restrict__ out)
-{
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) out[i] = src[idx[i]];
-}
-
-hipError_t launch_gather_f32(const float *src, const int *idx, int n, float *out, hipStream_t s)
-{
-    if (n < 1) return hipSuccess;
-    hipLaunchKernelGGL(gather_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, src, idx, n, out);
     return hipGetLastError();
 }
 

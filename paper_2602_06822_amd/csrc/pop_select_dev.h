@@ -14,10 +14,12 @@ constexpr int kSelLdsKeys = 4096;  // candidate keys staged in LDS when they fit
 
 struct SelShared {
     unsigned int hist[3][256];  // digit histograms of three consecutive radix passes (see radix_threshold)
-    unsigned int hist2[3][256]; // the second threshold's histograms when two are sought in one sweep
-    int wave_tot[4][kSelMaxWaves];
+    unsigned int hist2[3][256]; // the second threshold's histograms when several are sought in one sweep
+    unsigned int hist3[3][256]; // the third threshold's
+    int wave_tot[6][kSelMaxWaves];
     int digit;
     int remaining;
+    int list_len[3];            // lengths of the key lists of radix_thresholds_lists
     uint32_t keys[kSelLdsKeys];
 };
 
@@ -186,25 +188,27 @@ __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, Sel
     take_eq = remaining;
 }
 
-// Two thresholds in the same sweeps: the keys of the n_a-th and of the n_b-th best element, 0 < n_a < n_b <= n, with
-// their take counts, as two calls of radix_threshold would give them.  The common leading bits and the leading digit's
-// histogram serve both; from the second digit on a key is counted for the threshold(s) whose prefix it matches.
+// NT (2 or 3) thresholds in the same sweeps: kth[t] = key of the n_top[t]-th best element, 1 <= n_top[t] <= n, with
+// its take count, as NT calls of radix_threshold would give them.  The common leading bits and the leading digit's
+// histogram serve all; from the second digit on a key is counted for the threshold(s) whose prefix it matches.
 // Made for a large key set: digits are cut from the highest differing bit down (so the leading digit spreads the
 // keys over all its values even when that bit is not at a byte boundary), and the sweep for the second digit also
-// copies the keys that share a threshold's leading digit into a short list in sh.keys (half of it
-// per threshold), which the sweeps for the remaining digits read instead of all n keys.  A threshold whose leading
-// digit holds more keys than its list can take keeps sweeping all keys.  Must not be used while sh.keys holds data.
-template <class KeyFn>
-__device__ __forceinline__ void radix_threshold2_lists(KeyFn key, int n, int n_a, int n_b, SelShared &sh, uint32_t &kth_a,
-                                                       int &take_a, uint32_t &kth_b, int &take_b, bool have_diff = false,
+// copies the keys that share a threshold's leading digit into a short list in sh.keys (one NT-th of it per
+// threshold; thresholds under one leading digit share a list), which the sweeps for the remaining digits read
+// instead of all n keys.  A threshold whose leading digit holds more keys than its list can take keeps sweeping all
+// keys.  Must not be used while sh.keys holds data.  have_diff: diff_in holds the bits in which any two keys differ.
+template <int NT, class KeyFn>
+__device__ __forceinline__ void radix_thresholds_lists(KeyFn key, int n, const int (&n_top)[NT], SelShared &sh,
+                                                       uint32_t (&kth)[NT], int (&take)[NT], bool have_diff = false,
                                                        uint32_t diff_in = 0)
 {
-    constexpr int kCap = kSelLdsKeys / 2;
+    static_assert(NT == 2 || NT == 3, "two or three thresholds");
+    constexpr int kCap = kSelLdsKeys / NT;
     unsigned int *scratch = &sh.hist[2][0];
     if (threadIdx.x == 0) {
         scratch[0] = 0;
-        sh.digit = 0;      // length of list 0
-        sh.remaining = 0;  // length of list 1
+#pragma unroll
+        for (int t = 0; t < NT; ++t) sh.list_len[t] = 0;
     }
     if (threadIdx.x < 256) sh.hist[0][threadIdx.x] = 0;
     if (blockDim.x < 256)
@@ -223,33 +227,30 @@ __device__ __forceinline__ void radix_threshold2_lists(KeyFn key, int n, int n_a
     }
     if (diff == 0) {  // all keys equal
         __syncthreads();
-        kth_a = kth_b = k0;
-        take_a = n_a;
-        take_b = n_b;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) kth[t] = k0, take[t] = n_top[t];
         return;
     }
     const int top_bit = 31 - __builtin_clz(diff);
     const int n_pass = top_bit / 8 + 1;
     uint32_t known = top_bit == 31 ? 0u : ~((2u << top_bit) - 1u);
-    uint32_t prefix[2] = {k0 & known, k0 & known};
-    int remaining[2] = {n_a, n_b};
-    int matching[2] = {n, n};  // keys that share the threshold's prefix
-    const uint32_t *list[2] = {sh.keys, sh.keys + kCap};
-    bool listed[2] = {false, false};
+    uint32_t prefix[NT];
+    int remaining[NT], matching[NT], list_of[NT];  // list_of[t]: the list threshold t reads (-1: sweeps all keys)
+#pragma unroll
+    for (int t = 0; t < NT; ++t) prefix[t] = k0 & known, remaining[t] = n_top[t], matching[t] = n, list_of[t] = -1;
     const int lane = threadIdx.x % kWave;
     for (int pass = 0; pass < n_pass; ++pass) {
         const int hi = top_bit - 8 * pass, lo = hi >= 7 ? hi - 7 : 0;
         const uint32_t dmask = (1u << (hi - lo + 1)) - 1u;
-        unsigned int *hist[2] = {sh.hist[pass % 3], pass == 0 ? sh.hist[0] : sh.hist2[pass % 3]};
-        if (threadIdx.x < 256) {
-            sh.hist[(pass + 1) % 3][threadIdx.x] = 0;
-            sh.hist2[(pass + 1) % 3][threadIdx.x] = 0;
+        // pass p counts into set p % 3 and clears set (p + 1) % 3, last read in pass p - 2 (one barrier per pass); the
+        // leading digit's histogram is shared
+        unsigned int *hist[3] = {sh.hist[pass % 3], pass == 0 ? sh.hist[0] : sh.hist2[pass % 3],
+                                 pass == 0 ? sh.hist[0] : sh.hist3[pass % 3]};
+        for (int i = threadIdx.x; i < 256; i += blockDim.x) {
+            sh.hist[(pass + 1) % 3][i] = 0;
+            sh.hist2[(pass + 1) % 3][i] = 0;
+            if (NT > 2) sh.hist3[(pass + 1) % 3][i] = 0;
         }
-        if (blockDim.x < 256)
-            for (int i = threadIdx.x + blockDim.x; i < 256; i += blockDim.x) {
-                sh.hist[(pass + 1) % 3][i] = 0;
-                sh.hist2[(pass + 1) % 3][i] = 0;
-            }
         if (pass == 0) {
             const int n_round = (n + blockDim.x - 1) / blockDim.x * blockDim.x;
             for (int i = threadIdx.x; i < n_round; i += blockDim.x) {
@@ -257,32 +258,37 @@ __device__ __forceinline__ void radix_threshold2_lists(KeyFn key, int n, int n_a
                 wave_hist_add(hist[0], (k >> lo) & dmask, i < n);
             }
         } else if (pass == 1) {
-            // the one sweep that also fills the lists; with both thresholds under one leading digit they share list 0
-            const bool same = prefix[0] == prefix[1];
-            const bool fill0 = matching[0] <= kCap, fill1 = !same && matching[1] <= kCap;
+            // the one sweep that also fills the lists; a threshold under the same leading digit as an earlier one
+            // reads that one's list
+            bool fill[NT];
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                int same_as = -1;
+#pragma unroll
+                for (int u = 0; u < t; ++u)
+                    if (same_as < 0 && prefix[u] == prefix[t]) same_as = u;
+                fill[t] = same_as < 0 && matching[t] <= kCap;
+                list_of[t] = same_as >= 0 ? list_of[same_as] : (fill[t] ? t : -1);
+            }
             for (int i = threadIdx.x; i < n; i += blockDim.x) {
                 const uint32_t k = key(i);
                 const uint32_t kk = k & known, dg = (k >> lo) & dmask;
-                if (kk == prefix[0]) {
-                    atomicAdd(&hist[0][dg], 1u);
-                    if (fill0) sh.keys[atomicAdd(&sh.digit, 1)] = k;
-                }
-                if (kk == prefix[1]) {
-                    atomicAdd(&hist[1][dg], 1u);
-                    if (fill1) sh.keys[kCap + atomicAdd(&sh.remaining, 1)] = k;
-                }
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    if (kk == prefix[t]) {
+                        atomicAdd(&hist[t][dg], 1u);
+                        if (fill[t]) sh.keys[t * kCap + atomicAdd(&sh.list_len[t], 1)] = k;
+                    }
             }
-            listed[0] = fill0;
-            listed[1] = fill1 || (same && fill0);
-            if (same) list[1] = list[0];
         } else {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                if (listed[t]) {
+            for (int t = 0; t < NT; ++t) {
+                if (list_of[t] >= 0) {
                     // (the list holds the keys that matched after the leading digit: a superset of the current matches)
-                    const int len = list[t] == sh.keys ? sh.digit : sh.remaining;
+                    const uint32_t *lst = sh.keys + list_of[t] * kCap;
+                    const int len = sh.list_len[list_of[t]];
                     for (int i = threadIdx.x; i < len; i += blockDim.x) {
-                        const uint32_t k = list[t][i];
+                        const uint32_t k = lst[i];
                         if ((k & known) == prefix[t]) atomicAdd(&hist[t][(k >> lo) & dmask], 1u);
                     }
                 } else {
@@ -295,7 +301,7 @@ __device__ __forceinline__ void radix_threshold2_lists(KeyFn key, int n, int n_a
         }
         __syncthreads();
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
+        for (int t = 0; t < NT; ++t) {
             int c[4], lane_tot = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
@@ -322,8 +328,8 @@ __device__ __forceinline__ void radix_threshold2_lists(KeyFn key, int n, int n_a
         known |= dmask << lo;
     }
     __syncthreads();
-    kth_a = prefix[0], take_a = remaining[0];
-    kth_b = prefix[1], take_b = remaining[1];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) kth[t] = prefix[t], take[t] = remaining[t];
 }
 
 struct SelectNoHook {
