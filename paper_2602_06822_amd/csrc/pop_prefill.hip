@@ -416,7 +416,8 @@ __global__ __launch_bounds__(256) void prefill_f32_kernel(const float *__restric
 // At config 2 this picks 128 up to 256 tokens and 256 from there on.  POP_PF_BM=128 / 256 overrides (tuning).
 static int prefill_token_tile(int T, int n_ch, int n_cu)
 {
-    if (const char *e = getenv("POP_PF_BM")) return atoi(e) == 128 ? 128 : 256;
+    static const int forced = getenv("POP_PF_BM") ? atoi(getenv("POP_PF_BM")) : 0;
+    if (forced == 128 || forced == 256) return forced;
     int best_bm = 256;
     long best = -1;
     for (int bm = 256; bm >= 128; bm -= 128) {
