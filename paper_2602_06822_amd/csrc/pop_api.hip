@@ -88,6 +88,7 @@ struct pop_layer {
     size_t ffn_part_cap = 0;           // elements
     unsigned char *ffn_any = nullptr;  // [m]: channels active in any row of a per-token mask
     int *top_list = nullptr;           // [m] + 1: the prompt's own active channels (ascending), then their number
+    uint16_t *zero_row = nullptr;      // 256 bytes of zeros: stands in for weight rows beyond a channel list
 };
 
 namespace {
@@ -153,9 +154,18 @@ int grow(void **p, size_t *cap, size_t need, size_t esize)
 // also H of all channels.  Returns the row stride of the H buffers and the number of contraction splits.
 int ffn_scratch(pop_layer *L, int T, bool keep_all, int *ldh, int *n_split)
 {
-    *ldh = (L->m + 7) / 8 * 8;
+    // rows are whole 64-channel k-steps long, and compact H starts out as zeros: the direct-load GEMM reads the columns
+    // between a list's end and the end of its last k-step (times rows of zeros, so they only have to be finite)
+    *ldh = (L->m + 63) / 64 * 64;
     *n_split = down_gemm_splits(T, L->d, L->n_cu);
+    const size_t hc_before = L->ffn_hc_cap;
     int rc = grow((void **)&L->ffn_hc, &L->ffn_hc_cap, (size_t)T * *ldh, sizeof(uint16_t));
+    if (rc == POP_OK && L->ffn_hc_cap != hc_before)
+        POP_HIP(hipMemset(L->ffn_hc, 0, L->ffn_hc_cap * sizeof(uint16_t)));
+    if (rc == POP_OK && !L->zero_row) {
+        if (!dev_alloc((void **)&L->zero_row, 256)) return POP_ENOMEM;
+        POP_HIP(hipMemset(L->zero_row, 0, 256));
+    }
     if (rc == POP_OK && *n_split > 1)
         rc = grow((void **)&L->ffn_part, &L->ffn_part_cap, (size_t)*n_split * T * L->d, sizeof(float));
     if (rc == POP_OK && keep_all) rc = grow((void **)&L->ffn_hall, &L->ffn_hall_cap, (size_t)T * *ldh, sizeof(uint16_t));
@@ -181,7 +191,8 @@ int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mas
         tmask = mask;
     }
     POP_HIP(launch_gateup_list_bf16(L->w, d, m, x, T, L->ulist, L->n_ulist, tmask, L->ffn_hc, ldh, L->n_cu, s));
-    POP_HIP(launch_down_gemm_bf16(L->w, d, L->ulist, L->n_ulist, L->ffn_hc, ldh, T, n_split, L->ffn_part, y, y_bf16, s));
+    POP_HIP(launch_down_gemm_bf16(L->w, d, L->ulist, L->n_ulist, L->ffn_hc, ldh, T, n_split, L->ffn_part, y, y_bf16, s,
+                                  L->zero_row));
     return POP_OK;
 }
 
@@ -333,7 +344,7 @@ int pop_layer_destroy(pop_layer_t *L)
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
                     L->h,      L->cscore, L->mask, L->selflag, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
-                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part, L->top_list};
+                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part, L->top_list, L->zero_row};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -484,7 +495,7 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     if (keep) {
         POP_HIP(launch_compact_hidden(L->ffn_hall, ldh, T, L->top_list, L->top_list + m, n_ret + k0, L->ffn_hc, ldh, s));
         POP_HIP(launch_down_gemm_bf16(L->w, d, L->top_list, L->top_list + m, L->ffn_hc, ldh, T, n_split, L->ffn_part, y,
-                                      ydtype == POP_BF16, s));
+                                      ydtype == POP_BF16, s, L->zero_row));
         return POP_OK;
     }
     const int rc = pop_pruned_ffn(L, x, T, pm, 1, y, ydtype, stream);

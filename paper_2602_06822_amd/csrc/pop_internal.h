@@ -211,10 +211,13 @@ hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const
 hipError_t launch_gateup_list_bf16(const void *w, int d, int m, const void *x, int T, const int *list, const int *n_list,
                                    const unsigned char *tmask, uint16_t *hc, int ldh, int n_cu, hipStream_t s);
 // y[t][n] = sum_c hc[t][c] * w[list[c]][2][n] on the matrix cores; part (float32 [n_split][T][d]) is needed when
-// n_split = down_gemm_splits(...) > 1.
+// n_split = down_gemm_splits(...) > 1.  With zero_row (256 bytes of zeros), d % 128 == 0 and ldh % 64 == 0 the
+// operands go straight into LDS; that form reads hc columns up to the list length rounded up to 64, which must hold
+// finite values.
 int down_gemm_splits(int T, int d, int n_cu);
 hipError_t launch_down_gemm_bf16(const void *w, int d, const int *list, const int *n_list, const uint16_t *hc, int ldh,
-                                 int T, int n_split, float *part, void *y, int y_bf16, hipStream_t s);
+                                 int T, int n_split, float *part, void *y, int y_bf16, hipStream_t s,
+                                 const uint16_t *zero_row = nullptr);
 // bf16 layers: the prefill contraction (s2_part as in launch_prefill_gateup) that also keeps H:
 // h_all[t][j] = bf16(H[t][j]), row stride ldh.
 hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const void *x, int T, float *s2_part,
