@@ -306,39 +306,56 @@ __global__ __launch_bounds__(512) void down_gemm_dma_kernel(const uint16_t *__re
         const int arow = wm * 64 + lane % 32, a_sw = (arow / 2) % 8;  // (fragments are 32 rows apart: same term)
         const int b_k = (lane / 32) * 8 + (lane % 16) / 4, b_sw = 4 * (b_k % 4);
         const int b_col = wn * 64 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
-        // The transposing reads are issued as inline assembly: as an intrinsic the compiler takes them to alias the
-        // direct loads in flight and waits for all of those first.  It therefore does not count them either: the
-        // explicit wait below covers them, and its own (in-order) counts for the other reads only become stricter.
-        auto tr_read = [&](const uint16_t *q) {
-            s16x4_t v;
+        // The fragment reads are issued as inline assembly: as an intrinsic the compiler takes the transposing read to
+        // alias the direct loads in flight and waits for all of those first.  It therefore does not count these reads
+        // either; the explicit waits below do: the reads of k-slice q + 1 are issued before the products of slice q,
+        // which wait for all reads but those six.
+        auto tr_read = [&](s16x4_t &v, const uint16_t *q) {
             asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(v) : "v"((uint32_t)(uintptr_t)q));
-            return v;
+        };
+        auto a_read = [&](bf16x8_t &v, const uint16_t *q) {
+            asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"((uint32_t)(uintptr_t)q));
         };
         auto multiply = [&](int buf) {
             const uint16_t *Ab = As + buf * kATile + arow * kDgBK;
             const uint16_t *Bb = Bs + buf * kBTile + b_k * kDgBN;
-#pragma unroll
-            for (int kk = 0; kk < kDgBK; kk += 16) {
-                bf16x8_t af[2];
-                s16x4_t lo[2], hi[2];
+            bf16x8_t af[2][2];
+            s16x4_t lo[2][2], hi[2][2];
+            auto fetch = [&](int q, int set) {
 #pragma unroll
                 for (int f = 0; f < 2; ++f) {
                     const int col = b_col + f * 32;
-                    const uint16_t *q = Bb + kk * kDgBN + (((col / 8) ^ b_sw) * 8) + col % 8;
-                    lo[f] = tr_read(q);
-                    hi[f] = tr_read(q + 4 * kDgBN);
+                    const uint16_t *p = Bb + q * 16 * kDgBN + (((col / 8) ^ b_sw) * 8) + col % 8;
+                    tr_read(lo[set][f], p);
+                    tr_read(hi[set][f], p + 4 * kDgBN);
                 }
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
-                    af[i] = *reinterpret_cast<const bf16x8_t *>(Ab + i * 32 * kDgBK + (((kk / 8 + lane / 32) ^ a_sw) * 8));
-                asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(lo[0]), "+v"(hi[0]), "+v"(lo[1]), "+v"(hi[1]) : : "memory");
+                    a_read(af[set][i], Ab + i * 32 * kDgBK + (((q * 2 + lane / 32) ^ a_sw) * 8));
+            };
+            fetch(0, 0);
+#pragma unroll
+            for (int q = 0; q < kDgBK / 16; ++q) {
+                const int c = q & 1;
+                if (q + 1 < kDgBK / 16) {
+                    fetch(q + 1, c ^ 1);
+                    asm volatile("s_waitcnt lgkmcnt(6)"
+                                 : "+v"(lo[c][0]), "+v"(hi[c][0]), "+v"(lo[c][1]), "+v"(hi[c][1]), "+v"(af[c][0]), "+v"(af[c][1])
+                                 :
+                                 : "memory");
+                } else {
+                    asm volatile("s_waitcnt lgkmcnt(0)"
+                                 : "+v"(lo[c][0]), "+v"(hi[c][0]), "+v"(lo[c][1]), "+v"(hi[c][1]), "+v"(af[c][0]), "+v"(af[c][1])
+                                 :
+                                 : "memory");
+                }
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int f = 0; f < 2; ++f) {
                         const bf16x8_t bf = __builtin_bit_cast(
-                            bf16x8_t, __builtin_shufflevector(lo[f], hi[f], 0, 1, 2, 3, 4, 5, 6, 7));
-                        acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf, acc[i][f], 0, 0, 0);
+                            bf16x8_t, __builtin_shufflevector(lo[c][f], hi[c][f], 0, 1, 2, 3, 4, 5, 6, 7));
+                        acc[i][f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[c][i], bf, acc[i][f], 0, 0, 0);
                     }
             }
         };
