@@ -391,8 +391,10 @@ __global__ __launch_bounds__(512) void down_gemm_dma_kernel(const uint16_t *__re
         }
         if (i < n_steps) step(i, 0);
         if (i + 1 < n_steps) step(i + 1, 1);
+        // the surplus requests, before the LDS is given up; the channel registers are operands so that they stay
+        // allocated until the loads into them have landed (the last ones are never used)
+        asm volatile("s_waitcnt vmcnt(0)" : POP_DD_CHN : : "memory");
 #undef POP_DD_CHN
-        __builtin_amdgcn_s_waitcnt((7 << 4) | (15 << 8));  // vmcnt(0): the surplus requests, before the LDS is given up
     }
 
     // register v of a fragment is token row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32
