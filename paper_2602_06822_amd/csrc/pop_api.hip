@@ -197,10 +197,10 @@ int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mas
 }
 
 // Scores, partition and partition-constant step state from s2_part (the second half of the prefilling stage).
-// n_top >= 0: the same launch also leaves the n_top best channels as a byte mask in ffn_any and as an ascending list
-// with its length in top_list.
+// n_top >= 0: the same launch also leaves the n_top best channels as an ascending list with its length in top_list
+// and, with top_mask, as a byte mask in ffn_any.
 int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, unsigned char *region, int *ret_idx,
-                     int *cand_idx, hipStream_t s, int n_top = -1)
+                     int *cand_idx, hipStream_t s, int n_top = -1, bool top_mask = true)
 {
     const int m = L->m;
     // the partition launch also forms the scores from the contraction's partial rows (the input-side scores are
@@ -216,7 +216,10 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
         ex.scores_out = L->scores;
     }
     ex.sync = L->sync, ex.n_sync = 16;
-    if (n_top >= 0) ex.n_top = n_top, ex.top_mask = L->ffn_any, ex.top_list = L->top_list, ex.top_count = L->top_list + m;
+    if (n_top >= 0) {
+        ex.n_top = n_top, ex.top_list = L->top_list, ex.top_count = L->top_list + m;
+        ex.top_mask = top_mask ? L->ffn_any : nullptr;
+    }
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s, &ex));
     const StridedClear clr = fused_selbits_clear(L->selbits);
     POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s,
@@ -489,7 +492,8 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     // prefill mask: retained channels plus the best k0 candidates by prefill score, i.e. the n_ret + k0 best channels
     // of the partition's own order: the partition launch emits them as well (mask bytes and ascending list)
     if (!L->top_list && !dev_alloc((void **)&L->top_list, ((size_t)m + 1) * sizeof(int))) return POP_ENOMEM;
-    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, n_ret + k0); if (rc != POP_OK) return rc; }
+    // (the byte mask only where somebody reads it: the caller, or the path below that works from a mask)
+    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, n_ret + k0, mask || !keep); if (rc != POP_OK) return rc; }
     unsigned char *pm = L->ffn_any;
     if (mask) POP_HIP(hipMemcpyAsync(mask, pm, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (keep) {
