@@ -275,6 +275,27 @@ def test_pruned_ffn_prompt_sized_bf16(pop, oracle, T):
         assert max_abs_rel(y, y_ref) <= FFN_MFMA_TOL_F32
 
 
+@pytest.mark.parametrize("T", [70, 300])
+def test_pruned_ffn_direct_load_gemm_step_counts(pop, oracle, T):
+    """The down-projection GEMM whose operands go straight into a ring of LDS buffers (d a multiple of 128): numbers
+    of active channels that give every split 0, 1, 2, 3 and more k-steps of 64 channels (the ring's first requests
+    and its one- and two-step remainders), whole and ragged last k-steps, prompts of one ragged and of two token
+    tiles; then a short list after a long one on the same handle (the columns behind a list's end hold the longer
+    list's values, which meet rows of zeros)."""
+    d, m = 256, 2000
+    L = synth.make_layer(synth.small_config("ffn_direct_gemm", d, m, BF16))
+    x = synth.make_activations(L, T, "tokens")
+    g = synth.rng("ffn_direct_gemm_masks", T)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        for a in (2000, 1, 64, 130, 700, 1100, 1500, 1536, 65):
+            mask = np.zeros(m, np.uint8)
+            mask[g.choice(m, size=a, replace=False)] = 1
+            y_ref = oracle.pruned_ffn(x, L.w_gate, L.w_up, L.w_down, BF16, mask)
+            y = G.ffn(x, mask, F32)
+            err = max_abs_rel(y, y_ref)
+            assert err <= FFN_MFMA_TOL_F32, f"T={T} a={a} err {err:.3e}"
+
+
 def test_pruned_ffn_prompt_full_size(pop, oracle):
     """Llama-2-7B-shaped layer: the prompt's forward pass under the prefill mask (retained channels plus the best
     k candidates by prefill score), checked on a sample of tokens; and wider-than-one-tile shapes of the split
