@@ -8,15 +8,17 @@
 // They are staged into LDS as they come, [k][n], and fetched with the transposing LDS read of this chip: a block of
 // 16 lanes points at a 4 (k) x 16 (n) patch, lane i at the 4 values of row i / 4 starting at column 4 (i % 4), and
 // receives it transposed, lane j the 4 k-values of column j.  Two such reads make the 8 values of one B fragment.
-// The LDS row stride (160 elements) puts the 4 rows of a patch, and the two patches a read instruction's half-wave
-// touches, into disjoint banks.
 //
 // Workgroup: 256 tokens x 128 columns, 8 waves (4 along the tokens x 2 along n), wave tile 64 x 64 = 2 x 2 MFMA
-// tiles, k-steps of 64 channels, LDS double buffer filled through registers with the rows of two k-steps in flight
-// (a workgroup's k-step holds too few products to cover the latency of its loads); channel numbers are fetched a
-// step further ahead so the weight loads never wait for them.  Short prompts do not give enough tiles to fill the chip, so the
-// contraction is split into n_split ranges whose float32 partial results are summed, in split order, by a second
-// kernel (deterministic).
+// tiles, k-steps of 64 channels.  Short prompts do not give enough tiles to fill the chip, so the contraction is
+// split into n_split ranges whose float32 partial results are summed, in split order, by a second kernel
+// (deterministic).  Two kernels share this tile:
+//  * down_gemm_dma_kernel (d a multiple of 128): both operands go from global memory straight into a ring of three
+//    unpadded, swizzled LDS buffers, with one exact wait per k-step (described at the kernel);
+//  * down_gemm_bf16_kernel (any d): an LDS double buffer filled through registers with the rows of two k-steps in
+//    flight; channel numbers are fetched a step further ahead so the weight loads never wait for them.  Its weight
+//    tile has a row stride of 160 elements, which puts the 4 rows of a patch, and the two patches a read instruction's
+//    half-wave touches, into disjoint banks.
 #include <stdlib.h>
 
 #include "pop_internal.h"
