@@ -160,6 +160,15 @@ int pop_decode_step(pop_layer_t *layer, const void *x_t, int B, const int *k, vo
 int pop_partition_from_scores(const float *scores, int m, int n_ret, int n_cand,
                               unsigned char *region, int *ret_idx, int *cand_idx, void *stream);
 
+/* The same, and in the same launch the n_top best channels of that order, 0 <= n_top <= m: the mask a prompt's own
+ * forward pass runs under (Sec. 3.4; pop_prefill_forward uses n_top = n_ret + k0: the retained channels plus the best
+ * k0 candidates by prefill score are the n_ret + k0 best channels overall).  Outputs (dev): top_mask [m] (1 = among
+ * the n_top best; may be NULL), top_list [n_top] ascending channel numbers (required).
+ * Errors: as pop_partition_from_scores; top_list == NULL -> POP_EINVAL; n_top out of range -> POP_ESHAPE. */
+int pop_partition_top_from_scores(const float *scores, int m, int n_ret, int n_cand, int n_top,
+                                  unsigned char *region, int *ret_idx, int *cand_idx,
+                                  unsigned char *top_mask, int *top_list, void *stream);
+
 /* Step selection from given candidate scores: cand_scores dev [n_cand] in cand_idx order, cand_idx dev [n_cand]
  * ascending, region dev [m].  Outputs (dev, may be NULL): mask [m] (retained + selected), sel_idx [k] ascending. */
 int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_cand, int k,

@@ -44,6 +44,7 @@ _SIGS = {
     "pop_decode_step": (_i, [_vp, _vp, _i, _ip, _vp, _i, _vp, _vp, _vp, _vp, _vp]),
     "pop_pruned_ffn": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _vp]),
     "pop_partition_from_scores": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp, _vp]),
+    "pop_partition_top_from_scores": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pop_topk_from_scores": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp]),
     "pop_importance_reduce": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "pop_layer_get_norms": (_i, [_vp, _vp, _vp]),
@@ -178,6 +179,13 @@ def pop_pruned_ffn(layer, x, T, mask, mask_rows, y, ydtype, stream=None):
 def pop_partition_from_scores(scores, m, n_ret, n_cand, region=None, ret_idx=None, cand_idx=None, stream=None):
     _check(_lib.pop_partition_from_scores(_ptr(scores), m, n_ret, n_cand, _ptr(region), _ptr(ret_idx),
                                           _ptr(cand_idx), _stream(stream)), "pop_partition_from_scores")
+
+
+def pop_partition_top_from_scores(scores, m, n_ret, n_cand, n_top, region=None, ret_idx=None, cand_idx=None,
+                                  top_mask=None, top_list=None, stream=None):
+    _check(_lib.pop_partition_top_from_scores(_ptr(scores), m, n_ret, n_cand, n_top, _ptr(region), _ptr(ret_idx),
+                                              _ptr(cand_idx), _ptr(top_mask), _ptr(top_list), _stream(stream)),
+           "pop_partition_top_from_scores")
 
 
 def pop_topk_from_scores(cand_scores, cand_idx, n_cand, k, region, m, mask=None, sel_idx=None, stream=None):

@@ -661,6 +661,18 @@ int pop_partition_from_scores(const float *scores, int m, int n_ret, int n_cand,
     return POP_OK;
 }
 
+int pop_partition_top_from_scores(const float *scores, int m, int n_ret, int n_cand, int n_top, unsigned char *region,
+                                  int *ret_idx, int *cand_idx, unsigned char *top_mask, int *top_list, void *stream)
+{
+    if (!scores || !top_list) return POP_EINVAL;
+    if (m <= 0 || n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > m) return POP_ESHAPE;
+    if (n_top < 0 || n_top > m) return POP_ESHAPE;
+    PartitionExtra ex;
+    ex.n_top = n_top, ex.top_mask = top_mask, ex.top_list = top_list;
+    POP_HIP(launch_partition(scores, m, n_ret, n_cand, region, ret_idx, cand_idx, as_stream(stream), &ex));
+    return POP_OK;
+}
+
 int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_cand, int k, const unsigned char *region,
                          int m, unsigned char *mask, int *sel_idx, void *stream)
 {

@@ -73,6 +73,33 @@ def test_partition_from_scores_shaped_keys(pop, oracle, shape):
             assert np.array_equal(host(cand), cand0), (m, n_ret, n_cand, shape)
 
 
+@pytest.mark.parametrize("kind", ["none", "some", "all", "zeros"] + list(synth.SCORE_SHAPES))
+def test_partition_top_from_scores_bit_exact(pop, oracle, kind):
+    """The partition launch that also emits the n_top best channels (the prompt's own mask): regions as before, and
+    the top set equal to the retained set of a partition with n_ret = n_top, on tied and on shaped score vectors, with
+    the third rank inside, at the edges of and outside the candidate band."""
+    for m in (301, 5000, 11008, 30000):
+        s = synth.make_scores(m, f"gpu_top_{m}", kind) if kind in ("none", "some", "all", "zeros") \
+            else synth.make_scores_shaped(m, f"gpu_top_{m}", kind)
+        n_ret, n_cand = int(0.6 * m), int(0.1 * m)
+        for nr, nc, n_top in ((n_ret, n_cand, n_ret + n_cand // 2), (n_ret, n_cand, n_ret), (n_ret, n_cand, n_ret + n_cand),
+                              (n_ret, n_cand, 0), (n_ret, n_cand, m), (0, 0, 7), (0, m, 1), (m, 0, m - 1),
+                              (m // 2, 3, m // 2 + 2)):
+            region = torch.full((m,), 9, dtype=torch.uint8, device="cuda")
+            ret = torch.full((max(nr, 1),), -1, dtype=torch.int32, device="cuda")
+            cand = torch.full((max(nc, 1),), -1, dtype=torch.int32, device="cuda")
+            tmask = torch.full((m,), 9, dtype=torch.uint8, device="cuda")
+            tlist = torch.full((max(n_top, 1),), -1, dtype=torch.int32, device="cuda")
+            pop.pop_partition_top_from_scores(dev(s), m, nr, nc, n_top, region, ret, cand, tmask, tlist)
+            r0, ret0, cand0 = oracle.partition(s, nr, nc)
+            rt, top0, _ = oracle.partition(s, n_top, 0)
+            case = (m, nr, nc, n_top, kind)
+            assert np.array_equal(host(region), r0), case
+            assert np.array_equal(host(ret)[:nr], ret0) and np.array_equal(host(cand)[:nc], cand0), case
+            assert np.array_equal(host(tmask), (rt == 0).astype(np.uint8)), case
+            assert np.array_equal(host(tlist)[:n_top], top0), case
+
+
 @pytest.mark.parametrize("ties", ["none", "some", "all", "zeros"])
 def test_topk_from_scores_bit_exact(pop, oracle, ties):
     for m, n_ret, n_cand in SEL_CASES:
@@ -662,6 +689,8 @@ def test_error_paths(pop):
     s = torch.zeros(10, dtype=torch.float32, device="cuda")
     assert status(pop.pop_partition_from_scores, s, 10, 6, 5) == pop.POP_ESHAPE
     assert status(pop.pop_partition_from_scores, None, 10, 6, 4) == pop.POP_EINVAL
+    assert status(pop.pop_partition_top_from_scores, s, 10, 6, 4, 11, None, None, None, None, s) == pop.POP_ESHAPE
+    assert status(pop.pop_partition_top_from_scores, s, 10, 6, 4, 5, None, None, None, None, None) == pop.POP_EINVAL
     assert status(pop.pop_topk_from_scores, s, None, 10, 3, None, 10) == pop.POP_EINVAL
     assert status(pop.pop_topk_from_scores, s, s, 10, 11, None, 10) == pop.POP_ESHAPE
 
