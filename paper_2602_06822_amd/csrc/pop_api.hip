@@ -198,9 +198,10 @@ int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mas
 
 // Scores, partition and partition-constant step state from s2_part (the second half of the prefilling stage).
 // n_top >= 0: the same launch also leaves the n_top best channels as an ascending list with its length in top_list
-// and, with top_mask, as a byte mask in ffn_any.
+// and, with top_mask, as a byte mask in ffn_any; compact: a column gather that the state launch takes along.
 int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, unsigned char *region, int *ret_idx,
-                     int *cand_idx, hipStream_t s, int n_top = -1, bool top_mask = true)
+                     int *cand_idx, hipStream_t s, int n_top = -1, bool top_mask = true,
+                     const CompactJob *compact = nullptr)
 {
     const int m = L->m;
     // the partition launch also forms the scores from the contraction's partial rows (the input-side scores are
@@ -223,7 +224,7 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s, &ex));
     const StridedClear clr = fused_selbits_clear(L->selbits);
     POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s,
-                                   L->cand_idx, n_cand, L->rc_idx, L->ulist, &clr));
+                                   L->cand_idx, n_cand, L->rc_idx, L->ulist, &clr, compact));
     L->ulist_prefix_ok = true;
     L->n_ret = n_ret;
     L->n_cand = n_cand;
@@ -492,12 +493,17 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     // prefill mask: retained channels plus the best k0 candidates by prefill score, i.e. the n_ret + k0 best channels
     // of the partition's own order: the partition launch emits them as well (mask bytes and ascending list)
     if (!L->top_list && !dev_alloc((void **)&L->top_list, ((size_t)m + 1) * sizeof(int))) return POP_ENOMEM;
-    // (the byte mask only where somebody reads it: the caller, or the path below that works from a mask)
-    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, n_ret + k0, mask || !keep); if (rc != POP_OK) return rc; }
+    // (the byte mask only where somebody reads it: the caller, or the path below that works from a mask; the gather of
+    // the active columns of H into compact form rides along with the partition's state launch)
+    CompactJob gather;
+    if (keep) {
+        gather.h_all = L->ffn_hall, gather.ldh = ldh, gather.T = T, gather.list = L->top_list;
+        gather.n_list = L->top_list + m, gather.hc = L->ffn_hc, gather.ldhc = ldh;
+    }
+    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, n_ret + k0, mask || !keep, keep ? &gather : nullptr); if (rc != POP_OK) return rc; }
     unsigned char *pm = L->ffn_any;
     if (mask) POP_HIP(hipMemcpyAsync(mask, pm, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (keep) {
-        POP_HIP(launch_compact_hidden(L->ffn_hall, ldh, T, L->top_list, L->top_list + m, n_ret + k0, L->ffn_hc, ldh, s));
         POP_HIP(launch_down_gemm_bf16(L->w, d, L->top_list, L->top_list + m, L->ffn_hc, ldh, T, n_split, L->ffn_part, y,
                                       ydtype == POP_BF16, s, L->zero_row));
         return POP_OK;

@@ -440,37 +440,6 @@ __global__ __launch_bounds__(256) void down_gemm_reduce_kernel(const float4 *__r
     }
 }
 
-// hc[t][c] = h_all[t][list[c]] for c < *n_list: the columns of the active channels moved next to each other, so that
-// the contraction index of the GEMM above is contiguous.  A thread owns two adjacent positions (one 32-bit store)
-// and kCompactRows tokens, whose rows it walks with the two channel numbers in registers.
-constexpr int kCompactRows = 8;
-__global__ __launch_bounds__(256) void compact_hidden_kernel(const uint16_t *__restrict__ h_all, int ldh, int T,
-                                                             const int *__restrict__ list,
-                                                             const int *__restrict__ n_list,
-                                                             uint16_t *__restrict__ hc, int ldhc)
-{
-    const int a = *n_list;
-    const int c = (blockIdx.x * blockDim.x + threadIdx.x) * 2;
-    if (c >= a) return;
-    const int j0 = list[c], j1 = c + 1 < a ? list[c + 1] : -1;
-    const int t0 = blockIdx.y * kCompactRows, t1 = min(T, t0 + kCompactRows);
-    for (int t = t0; t < t1; ++t) {
-        const uint16_t *row = h_all + (size_t)t * ldh;
-        const uint32_t v = (uint32_t)row[j0] | (j1 >= 0 ? (uint32_t)row[j1] << 16 : 0u);
-        *reinterpret_cast<uint32_t *>(hc + (size_t)t * ldhc + c) = v;
-    }
-}
-
-// max_list: upper bound of the list length (sizes the grid); ldhc even.
-hipError_t launch_compact_hidden(const uint16_t *h_all, int ldh, int T, const int *list, const int *n_list, int max_list,
-                                 uint16_t *hc, int ldhc, hipStream_t s)
-{
-    if (max_list < 1) return hipSuccess;
-    dim3 grid((max_list + 511) / 512, (T + kCompactRows - 1) / kCompactRows);
-    hipLaunchKernelGGL(compact_hidden_kernel, grid, dim3(256), 0, s, h_all, ldh, T, list, n_list, hc, ldhc);
-    return hipGetLastError();
-}
-
 // Ranges the contraction is split into so that the tiles fill the compute units.
 int down_gemm_splits(int T, int d, int n_cu)
 {

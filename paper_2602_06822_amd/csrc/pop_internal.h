@@ -121,10 +121,35 @@ struct StridedClear {
     int *p = nullptr;  // n slots of `words` ints (<= 256), `stride` ints apart
     int n = 0, stride = 0, words = 0;
 };
+// hc[t][c] = h_all[t][list[c]] for c < *n_list, t < T (bf16 bits): the columns of the listed channels moved next to
+// each other.  With `compact` given the same launch does this as well (the list must be final when it starts).
+struct CompactJob {
+    const uint16_t *h_all = nullptr;
+    int ldh = 0, T = 0;
+    const int *list = nullptr, *n_list = nullptr;
+    uint16_t *hc = nullptr;
+    int ldhc = 0;  // even
+};
+constexpr int kCompactRows = 8;  // tokens a workgroup of the compaction walks
+// The compaction's workgroup (bx, by) of 256 threads: positions 512 bx .. + 511, tokens kCompactRows by .. + 7.
+__device__ __forceinline__ void compact_hidden_block(const CompactJob &job, int bx, int by)
+{
+    const int a = *job.n_list;
+    const int c = (bx * 256 + (int)threadIdx.x) * 2;  // a thread owns two adjacent positions (one 32-bit store)
+    if (c >= a) return;
+    const int j0 = job.list[c], j1 = c + 1 < a ? job.list[c + 1] : -1;
+    const int t0 = by * kCompactRows, t1 = min(job.T, t0 + kCompactRows);
+    for (int t = t0; t < t1; ++t) {
+        const uint16_t *row = job.h_all + (size_t)t * job.ldh;
+        const uint32_t v = (uint32_t)row[j0] | (j1 >= 0 ? (uint32_t)row[j1] << 16 : 0u);
+        *reinterpret_cast<uint32_t *>(job.hc + (size_t)t * job.ldhc + c) = v;
+    }
+}
 hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
                                   int act_stride, unsigned char *mask, int *active_idx, hipStream_t s,
                                   const int *cand_idx = nullptr, int n_cand = 0, int *rc_idx = nullptr,
-                                  int *ulist = nullptr, const StridedClear *clear = nullptr);
+                                  int *ulist = nullptr, const StridedClear *clear = nullptr,
+                                  const CompactJob *compact = nullptr);
 // mask rows -> ascending list of channels active in any row.
 hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s);
 
@@ -222,9 +247,6 @@ hipError_t launch_down_gemm_bf16(const void *w, int d, const int *list, const in
 // h_all[t][j] = bf16(H[t][j]), row stride ldh.
 hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const void *x, int T, float *s2_part,
                                            uint16_t *h_all, int ldh, int n_cu, hipStream_t s);
-// hc[t][c] = h_all[t][list[c]] for c < *n_list <= max_list.
-hipError_t launch_compact_hidden(const uint16_t *h_all, int ldh, int T, const int *list, const int *n_list, int max_list,
-                                 uint16_t *hc, int ldhc, hipStream_t s);
 // ---- input-side importance (pop_input_side.hip) ----
 int input_side_groups(int T);  // row groups of a T-token prompt (sizes part below: [groups][d] doubles)
 // s2[k] = sum_t x[t][k]^2 over the T rows (fixed summation order)

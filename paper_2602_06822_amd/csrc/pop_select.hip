@@ -243,18 +243,24 @@ hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, 
 // Partition-constant part of the step state, for `rows` sequences: mask[b][j] = 1 for retained channels, 0 for
 // pruned and (until a step selects them) candidate channels; active_idx[b][0..n_ret) = ret_idx.  Row 0's workgroups
 // also write the candidate-then-retained list rc_idx and the retained prefix of the union list, when given.  One
-// more row of workgroups zeroes a strided word buffer (clr.n slots of clr.words ints, clr.stride ints apart), which
-// saves the partition a launch of its own for that.
+// more row of workgroups zeroes a strided word buffer (clr.n slots of clr.words ints, clr.stride ints apart), and
+// further rows gather the columns of a channel list (job), which saves the partition and the prompt's forward pass a
+// launch of their own for each.
 __global__ __launch_bounds__(256) void step_state_init_kernel(const unsigned char *__restrict__ region, int m,
                                                               const int *__restrict__ ret_idx, int n_ret, int rows,
                                                               int act_stride, unsigned char *__restrict__ mask,
                                                               int *__restrict__ active_idx,
                                                               const int *__restrict__ cand_idx, int n_cand,
                                                               int *__restrict__ rc_idx, int *__restrict__ ulist,
-                                                              StridedClear clr)
+                                                              StridedClear clr, CompactJob job)
 {
     const int b = blockIdx.y;
+    if (b > rows) {
+        compact_hidden_block(job, blockIdx.x, b - rows - 1);
+        return;
+    }
     if (b == rows) {
+        if (!clr.p) return;
         const int per = blockDim.x / clr.words;  // slots a workgroup clears at once
         for (int q = blockIdx.x * per + threadIdx.x / clr.words; q < clr.n && (int)threadIdx.x < per * clr.words;
              q += gridDim.x * per)
@@ -275,13 +281,18 @@ __global__ __launch_bounds__(256) void step_state_init_kernel(const unsigned cha
 
 hipError_t launch_step_state_init(const unsigned char *region, int m, const int *ret_idx, int n_ret, int rows,
                                   int act_stride, unsigned char *mask, int *active_idx, hipStream_t s,
-                                  const int *cand_idx, int n_cand, int *rc_idx, int *ulist, const StridedClear *clear)
+                                  const int *cand_idx, int n_cand, int *rc_idx, int *ulist, const StridedClear *clear,
+                                  const CompactJob *compact)
 {
     StridedClear clr = clear ? *clear : StridedClear{};
+    CompactJob job = compact ? *compact : CompactJob{};
     if (clr.p && (clr.words < 1 || clr.words > 256)) return hipErrorInvalidValue;
-    dim3 grid((m + 255) / 256, rows + (clr.p ? 1 : 0));
+    // rows of workgroups: `rows` of state, one that clears (idle without a buffer, present whenever a later row is),
+    // then the compaction's (its 512 positions per workgroup cover any list of up to m channels in this grid's width)
+    const int job_rows = job.hc ? (job.T + kCompactRows - 1) / kCompactRows : 0;
+    dim3 grid((m + 255) / 256, rows + ((clr.p || job_rows) ? 1 : 0) + job_rows);
     hipLaunchKernelGGL(step_state_init_kernel, grid, dim3(256), 0, s, region, m, ret_idx, n_ret, rows, act_stride, mask,
-                       active_idx, cand_idx, n_cand, rc_idx, ulist, clr);
+                       active_idx, cand_idx, n_cand, rc_idx, ulist, clr, job);
     return hipGetLastError();
 }
 
