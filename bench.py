@@ -274,10 +274,40 @@ def run(args):
         torch.cuda.synchronize()
         return 1e3 * e0.elapsed_time(e1) / (DECODE_STEPS * len(layers))
 
+    # The box's own read ceiling for these bytes: bare read kernels (no arithmetic) launched exactly like the fused
+    # kernel above, back to back over the rotated layers: a contiguous read of the step's algorithmic byte count, and
+    # a gathered read of exactly the step's rows out of each layer's channel-major weights.
+    def read_legs():
+        sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+        nbytes = bm["algorithmic"] // 16 * 16
+        bufs = [torch.ones(nbytes, dtype=torch.uint8, device="cuda") for _ in layers]
+        n_wg = torch.cuda.get_device_properties(0).multi_processor_count
+        out = {}
+        for name in ("bare_read_us", "gathered_read_us"):
+            def sweep():
+                for t in range(DECODE_STEPS):
+                    for li, L in enumerate(layers):
+                        if name == "bare_read_us":
+                            check(lib.pop_probe_read(C.c_void_p(bufs[li].data_ptr()), C.c_size_t(nbytes), n_wg,
+                                                     C.c_void_p(sink.data_ptr()), sp))
+                        else:
+                            check(lib.pop_probe_step_read(L.handle, k, n_wg, C.c_void_p(sink.data_ptr()), sp))
+            sweep()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            sweep()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            out[name] = 1e3 * e0.elapsed_time(e1) / (DECODE_STEPS * len(layers))
+        del bufs
+        return out
+
     for L in layers:
         pop.pop_layer_set_single_launch(L.handle, False)
     fused_us = kernel_only("mask")
     tail_us = kernel_only("ffn")
+    reads = read_legs()
     for L in layers:  # no in-kernel bounded wait may have expired anywhere above
         pop.pop_layer_sync_status(L.handle)
     roofline = None
@@ -292,9 +322,16 @@ def run(args):
                         avg_launch_us=round(fused_us, 3), tail_kernel_us=round(tail_us, 3),
                         in_sequence_probe_us=[round(main.get("probe_mask_us", 0.0), 3),
                                               round(main.get("probe_ffn_us", 0.0), 3)],
+                        bare_read_us=round(reads["bare_read_us"], 3),
+                        gathered_read_us=round(reads["gathered_read_us"], 3),
+                        token_us_over_gathered_read=round(us / reads["gathered_read_us"], 4),
+                        traffic_source="profiles/decode_fused_cfg2_r35_hbm_traffic.txt (committed rocprofv3 "
+                                       "FETCH_SIZE/WRITE_SIZE summary of this command; not read live in this run)",
                         note="avg_launch_us: back-to-back launches of the kernel between two events; "
                              "in_sequence_probe_us: fused and tail launch bracketed one by one inside the timed "
-                             "region (adds the event and launch gaps)")
+                             "region (adds the event and launch gaps); bare_read_us / gathered_read_us: read-only "
+                             "kernels (pop_probe_read: the algorithmic byte count, contiguous; pop_probe_step_read: "
+                             "exactly the step's weight rows) launched the same way over the same rotated layers")
 
     # the same workload under the input-side reading of the importance (selection first, then the forward pass over
     # retained + selected channels; separate launches, no fused kernel); last use of these layers
@@ -537,7 +574,7 @@ def cpu_baseline(synth, L, n_ret, n_cand, k, n_tokens, n_prompt=64):
     tokens, and the prefilling stage (hidden activations of all channels, importance, partition) for the first
     n_prompt prompt tokens."""
     from oracle import pop_oracle as oracle
-    oracle.build()
+    flags = oracle.use_timed_build()  # the same source, compiled -O3 -march=native for the timed leg
     region, ret, cand = oracle.partition(synth.make_scores(L.cfg.m, "cpu_baseline_scores", "none"), n_ret, n_cand)
     xt = synth.make_activations(L, n_tokens, "decode")
     oracle.decode(xt[0], L.w_gate, L.w_up, L.w_down, L.cfg.dtype, region, cand, k)  # warm the pages
@@ -550,6 +587,7 @@ def cpu_baseline(synth, L, n_ret, n_cand, k, n_tokens, n_prompt=64):
     oracle.prefill(xp, L.w_gate, L.w_up, L.w_down, L.cfg.dtype, n_ret, n_cand)
     dp = time.perf_counter() - t0
     return {"value": round(1e6 * dt / n_tokens, 1), "unit": "us/token", "cores": oracle.num_threads(), "kind": "oracle",
+            "compiler_flags": " ".join(flags),
             "sample": f"{n_tokens} decode tokens of one layer (pass 1 over retained+candidate channels, re-score, "
                       f"top-k, down projection), same shape and sparsity; prefill timed apart",
             "prefill_us_per_prompt_token": round(1e6 * dp / n_prompt, 1),

@@ -30,6 +30,8 @@
 #ifndef POP_H
 #define POP_H
 
+#include <stddef.h>
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -93,7 +95,9 @@ int pop_layer_destroy(pop_layer_t *layer);
  * the best n_ret channels are retained, the next n_cand are candidates, the rest are pruned.
  * Outputs (dev, any may be NULL): scores [m] float32; region [m] (POP_REGION_*); ret_idx [n_ret];
  * cand_idx [n_cand].  The partition is also kept inside the layer for the decode calls.
- * Errors: T < 1 or T > max_tokens, n_ret/n_cand < 0 or n_ret + n_cand > m -> POP_ESHAPE. */
+ * T == 0 is allowed (x may then be NULL): with no tokens every importance is zero and the regions follow the
+ * channel order (an expert of a mixture that no prompt token was routed to).
+ * Errors: T < 0 or T > max_tokens, n_ret/n_cand < 0 or n_ret + n_cand > m -> POP_ESHAPE. */
 int pop_prefill_partition(pop_layer_t *layer, const void *x, int T, int n_ret, int n_cand,
                           float *scores, unsigned char *region, int *ret_idx, int *cand_idx, void *stream);
 
@@ -179,6 +183,12 @@ int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_ca
 int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const float *nrm,
                           float *scores, void *stream);
 
+/* Allocates, now, the scratch that pop_prefill_forward and pop_pruned_ffn(mask) need for prompts of up to T tokens
+ * (they otherwise allocate it at their first call and when T grows, which synchronises the device), so that those
+ * calls only enqueue work afterwards.  New buffers are cleared on `stream`.  Sec. 3.4 (the prompt's forward pass).
+ * Errors: T < 1 or T > max_tokens -> POP_ESHAPE; allocation failure -> POP_ENOMEM. */
+int pop_layer_reserve_prompt(pop_layer_t *layer, int T, void *stream);
+
 /* Read-only views of layer state, for tests and callers that build on the partition.
  * Copies are enqueued on `stream`; outputs dev, any may be NULL: nrm [m] float32 (n_j of Eq. 3),
  * h [B][m] float32 of the last decode step (0 for pruned channels is NOT guaranteed: only retained and
@@ -214,6 +224,19 @@ int pop_layer_set_shared_batch_mask(pop_layer_t *layer, int on);
  * 1 = the fused single-sequence kernel, 2 = the batch-general kernels.  If workgroups != NULL it receives the
  * fused kernel's grid size for the current partition (0 when the fused kernel does not apply). */
 int pop_layer_step_kind(pop_layer_t *layer, int *workgroups);
+
+/* ---- measurement aids: bare reads of device memory (they compute nothing of the method) ----
+ * The decode step (Sec. 3.3 "Decoding Stage", Sec. 3.4) is bound by the bytes it must stream; these two calls request
+ * such bytes and nothing else, so that timing them (events on `stream`) gives the time the memory system itself needs:
+ * the yardstick next to the published peak bandwidth.  sink: dev, one unsigned int the kernels may OR a bit into.
+ *   pop_probe_read       contiguous read of `bytes` (rounded down to 16) of buf (dev, 16-byte aligned).
+ *   pop_probe_step_read  the weight rows one decode step of the layer's current partition reads: gate and up rows of
+ *                        all retained and candidate channels, down rows of the retained channels and of the first k
+ *                        candidates (standing in for the selected ones).
+ * workgroups: grid size (512 threads each).  Errors: NULL / misaligned pointers -> POP_EINVAL; no partition ->
+ * POP_ESTATE; sizes out of range -> POP_ESHAPE. */
+int pop_probe_read(const void *buf, size_t bytes, int workgroups, unsigned int *sink, void *stream);
+int pop_probe_step_read(pop_layer_t *layer, int k, int workgroups, unsigned int *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -29,6 +29,18 @@ def build(force: bool = False) -> str:
 
 _lib = None
 
+_TIMED_LIB = os.path.join(_HERE, "libpop_oracle_timed.so")
+_TIMED_FLAGS = ["-O3", "-march=native", "-std=c11", "-fopenmp"]
+
+
+def use_timed_build():
+    """Switch this process to a build of the same source with -O3 -march=native (the benchmark's timed baseline leg;
+    compiled on the machine it runs on).  Returns the flags."""
+    global _lib
+    subprocess.check_call(["gcc", *_TIMED_FLAGS, "-fPIC", "-shared", "-o", _TIMED_LIB, _SRC, "-lm"])
+    _lib = C.CDLL(_TIMED_LIB)
+    return list(_TIMED_FLAGS)
+
 
 def lib():
     global _lib

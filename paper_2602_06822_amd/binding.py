@@ -47,6 +47,9 @@ _SIGS = {
     "pop_partition_top_from_scores": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pop_topk_from_scores": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp]),
     "pop_importance_reduce": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
+    "pop_layer_reserve_prompt": (_i, [_vp, _i, _vp]),
+    "pop_probe_read": (_i, [_vp, C.c_size_t, _i, _vp, _vp]),
+    "pop_probe_step_read": (_i, [_vp, _i, _i, _vp, _vp]),
     "pop_layer_get_norms": (_i, [_vp, _vp, _vp]),
     "pop_layer_get_hidden": (_i, [_vp, _vp, _i, _vp]),
     "pop_layer_sync_status": (_i, [_vp, _vp]),
@@ -196,6 +199,18 @@ def pop_topk_from_scores(cand_scores, cand_idx, n_cand, k, region, m, mask=None,
 def pop_importance_reduce(h, hdtype, T, m, nrm, scores, stream=None):
     _check(_lib.pop_importance_reduce(_ptr(h), hdtype, T, m, _ptr(nrm), _ptr(scores), _stream(stream)),
            "pop_importance_reduce")
+
+
+def pop_layer_reserve_prompt(layer, T: int, stream=None):
+    _check(_lib.pop_layer_reserve_prompt(layer, T, _stream(stream)), "pop_layer_reserve_prompt")
+
+
+def pop_probe_read(buf, nbytes: int, workgroups: int, sink, stream=None):
+    _check(_lib.pop_probe_read(_ptr(buf), nbytes, workgroups, _ptr(sink), _stream(stream)), "pop_probe_read")
+
+
+def pop_probe_step_read(layer, k: int, workgroups: int, sink, stream=None):
+    _check(_lib.pop_probe_step_read(layer, k, workgroups, _ptr(sink), _stream(stream)), "pop_probe_step_read")
 
 
 def pop_layer_get_norms(layer, nrm, stream=None):

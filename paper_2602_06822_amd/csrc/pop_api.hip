@@ -1,6 +1,7 @@
 // C ABI of the POP pruned-FFN library: argument validation, layer state and kernel sequencing.
 // Every step of the path runs in the HIP kernels of the sibling files; nothing here computes on the host
 // except the integer region counts.
+#include <stddef.h>
 #include <stdint.h>
 #include <math.h>
 #include <stdio.h>
@@ -152,22 +153,29 @@ int grow(void **p, size_t *cap, size_t need, size_t esize)
 
 // Scratch of the prompt-sized forward pass for T tokens: compact H, split partials, the byte mask; with keep_all
 // also H of all channels.  Returns the row stride of the H buffers and the number of contraction splits.
-int ffn_scratch(pop_layer *L, int T, bool keep_all, int *ldh, int *n_split)
+int ffn_scratch(pop_layer *L, int T, bool keep_all, int *ldh, int *n_split, hipStream_t s, bool shorter_too = false)
 {
-    // rows are whole 64-channel k-steps long, and compact H starts out as zeros: the direct-load GEMM reads the columns
-    // between a list's end and the end of its last k-step (times rows of zeros, so they only have to be finite)
+    // rows are whole 64-channel k-steps long: the direct-load GEMM reads the columns between a list's end and the end
+    // of its last k-step (times rows of zeros, so they only have to be finite; every writer of compact H zeroes them).
+    // New buffers are cleared by a kernel on the caller's stream, ahead of the kernels that read them.
     *ldh = (L->m + 63) / 64 * 64;
     *n_split = down_gemm_splits(T, L->d, L->n_cu);
     const size_t hc_before = L->ffn_hc_cap;
     int rc = grow((void **)&L->ffn_hc, &L->ffn_hc_cap, (size_t)T * *ldh, sizeof(uint16_t));
     if (rc == POP_OK && L->ffn_hc_cap != hc_before)
-        POP_HIP(hipMemset(L->ffn_hc, 0, L->ffn_hc_cap * sizeof(uint16_t)));
+        POP_HIP(launch_fill_int((int *)L->ffn_hc, (int)(L->ffn_hc_cap / 2), 0, s));
     if (rc == POP_OK && !L->zero_row) {
         if (!dev_alloc((void **)&L->zero_row, 256)) return POP_ENOMEM;
-        POP_HIP(hipMemset(L->zero_row, 0, 256));
+        POP_HIP(launch_fill_int((int *)L->zero_row, 64, 0, s));
     }
-    if (rc == POP_OK && *n_split > 1)
-        rc = grow((void **)&L->ffn_part, &L->ffn_part_cap, (size_t)*n_split * T * L->d, sizeof(float));
+    size_t part_rows = *n_split > 1 ? (size_t)*n_split * T : 0;
+    if (shorter_too)  // a shorter prompt is split more ways: room for every prompt length up to T
+        for (int t = 1; t < T; ++t) {
+            const size_t r = (size_t)down_gemm_splits(t, L->d, L->n_cu) * t;
+            if (r > part_rows) part_rows = r;
+        }
+    if (rc == POP_OK && part_rows)
+        rc = grow((void **)&L->ffn_part, &L->ffn_part_cap, part_rows * L->d, sizeof(float));
     if (rc == POP_OK && keep_all) rc = grow((void **)&L->ffn_hall, &L->ffn_hall_cap, (size_t)T * *ldh, sizeof(uint16_t));
     if (rc == POP_OK && !L->ffn_any && !dev_alloc((void **)&L->ffn_any, ((size_t)L->m + 3) / 4 * 4))
         rc = POP_ENOMEM;
@@ -181,13 +189,13 @@ int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mas
 {
     const int m = L->m, d = L->d;
     int ldh, n_split;
-    { int rc = ffn_scratch(L, T, false, &ldh, &n_split); if (rc != POP_OK) return rc; }
+    { int rc = ffn_scratch(L, T, false, &ldh, &n_split, s); if (rc != POP_OK) return rc; }
     const unsigned char *tmask = nullptr;
     if (mask_rows == 1) {
-        POP_HIP(launch_mask_to_list(mask, 1, m, L->ulist, L->n_ulist, s));
+        POP_HIP(launch_mask_to_list(mask, 1, m, L->ulist, L->n_ulist, s, L->ffn_hc, ldh, T));
     } else {
         POP_HIP(launch_mask_any(mask, T, m, L->ffn_any, s));
-        POP_HIP(launch_mask_to_list(L->ffn_any, 1, m, L->ulist, L->n_ulist, s));
+        POP_HIP(launch_mask_to_list(L->ffn_any, 1, m, L->ulist, L->n_ulist, s, L->ffn_hc, ldh, T));
         tmask = mask;
     }
     POP_HIP(launch_gateup_list_bf16(L->w, d, m, x, T, L->ulist, L->n_ulist, tmask, L->ffn_hc, ldh, L->n_cu, s));
@@ -200,7 +208,7 @@ int pruned_ffn_mfma(pop_layer *L, const void *x, int T, const unsigned char *mas
 // n_top >= 0: the same launch also leaves the n_top best channels as an ascending list with its length in top_list
 // and, with top_mask, as a byte mask in ffn_any; compact: a column gather that the state launch takes along.
 int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, unsigned char *region, int *ret_idx,
-                     int *cand_idx, hipStream_t s, int n_top = -1, bool top_mask = true,
+                     int *cand_idx, hipStream_t s, bool scores_ready, int n_top = -1, bool top_mask = true,
                      const CompactJob *compact = nullptr)
 {
     const int m = L->m;
@@ -209,8 +217,8 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     // partition (retained bytes of every mask row, retained prefix of every active list and of the union list, the
     // candidate-then-retained list) and zeroes the fused kernel's selection words
     PartitionExtra ex;
-    const bool from_partials = !L->input_side && partition_takes_partials(m);
-    if (!L->input_side && !from_partials)
+    const bool from_partials = !scores_ready && partition_takes_partials(m);
+    if (!scores_ready && !from_partials)
         POP_HIP(launch_scores_from_partials(L->s2_part, prefill_rows_used(T, L->is_bf16, m, L->n_cu), m, L->nrm, L->scores, s));
     if (from_partials) {
         ex.s2_part = L->s2_part, ex.n_tiles = prefill_rows_used(T, L->is_bf16, m, L->n_cu), ex.nrm = L->nrm;
@@ -444,29 +452,34 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
 int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n_cand, float *scores,
                           unsigned char *region, int *ret_idx, int *cand_idx, void *stream)
 {
-    if (!L || !x || !aligned16(x)) return POP_EINVAL;
-    if (T < 1 || T > L->max_tokens) return POP_ESHAPE;
+    if (!L) return POP_EINVAL;
+    if (T < 0 || T > L->max_tokens) return POP_ESHAPE;
+    if (T > 0 && (!x || !aligned16(x))) return POP_EINVAL;
     if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
     hipStream_t s = as_stream(stream);
     const int m = L->m;
     L->has_partition = false;
     L->has_step = false;
-    if (L->input_side) {
+    if (T == 0) {
+        // no tokens: every importance is zero under either reading, and the order falls back on the channel index
+        POP_HIP(launch_fill_int((int *)L->scores, m, 0, s));
+    } else if (L->input_side) {
         POP_HIP(launch_input_norms(x, L->is_bf16, T, L->d, L->in_part, L->in_s2, s));
         POP_HIP(launch_input_side_scores(L->w, L->is_bf16, L->d, L->in_s2, 1, nullptr, m, L->scores, m, s));
     } else {
         POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s));
     }
-    return finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s);
+    return finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, T == 0 || L->input_side);
 }
 
 int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_cand, int k0, void *y, pop_dtype_t ydtype,
                         float *scores, unsigned char *region, int *ret_idx, int *cand_idx, unsigned char *mask,
                         void *stream)
 {
-    if (!L || !x || !y || !aligned16(x) || !aligned16(y)) return POP_EINVAL;
+    if (!L) return POP_EINVAL;
+    if (T < 0 || T > L->max_tokens) return POP_ESHAPE;
+    if (T > 0 && (!x || !y || !aligned16(x) || !aligned16(y))) return POP_EINVAL;
     if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
-    if (T < 1 || T > L->max_tokens) return POP_ESHAPE;
     if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
     if (k0 < 0 || k0 > n_cand) return POP_ESHAPE;
     hipStream_t s = as_stream(stream);
@@ -478,12 +491,14 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     L->has_step = false;
     int ldh = 0, n_split = 1;
     if (keep) {
-        int rc = ffn_scratch(L, T, true, &ldh, &n_split);
+        int rc = ffn_scratch(L, T, true, &ldh, &n_split, s);
         if (rc != POP_OK) return rc;
         POP_HIP(launch_prefill_gateup_keep_bf16(L->w, d, m, x, T, L->s2_part, L->ffn_hall, ldh, L->n_cu, s));
     } else {
         if (!L->ffn_any && !dev_alloc((void **)&L->ffn_any, ((size_t)m + 3) / 4 * 4)) return POP_ENOMEM;
-        if (L->input_side) {
+        if (T == 0) {
+            POP_HIP(launch_fill_int((int *)L->scores, m, 0, s));  // no tokens: all importances zero
+        } else if (L->input_side) {
             POP_HIP(launch_input_norms(x, L->is_bf16, T, d, L->in_part, L->in_s2, s));
             POP_HIP(launch_input_side_scores(L->w, L->is_bf16, d, L->in_s2, 1, nullptr, m, L->scores, m, s));
         } else {
@@ -500,9 +515,14 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
         gather.h_all = L->ffn_hall, gather.ldh = ldh, gather.T = T, gather.list = L->top_list;
         gather.n_list = L->top_list + m, gather.hc = L->ffn_hc, gather.ldhc = ldh;
     }
-    { int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, n_ret + k0, mask || !keep, keep ? &gather : nullptr); if (rc != POP_OK) return rc; }
+    {
+        int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, T == 0 || L->input_side,
+                                  n_ret + k0, mask || !keep, keep ? &gather : nullptr);
+        if (rc != POP_OK) return rc;
+    }
     unsigned char *pm = L->ffn_any;
     if (mask) POP_HIP(hipMemcpyAsync(mask, pm, (size_t)m, hipMemcpyDeviceToDevice, s));
+    if (T == 0) return POP_OK;  // no token rows to produce
     if (keep) {
         POP_HIP(launch_down_gemm_bf16(L->w, d, L->top_list, L->top_list + m, L->ffn_hc, ldh, T, n_split, L->ffn_part, y,
                                       ydtype == POP_BF16, s, L->zero_row));
@@ -700,6 +720,36 @@ int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const
     if (hdtype != POP_F32 && hdtype != POP_BF16) return POP_EINVAL;
     if (T < 1 || m < 1) return POP_ESHAPE;
     POP_HIP(launch_importance_reduce(h, hdtype == POP_BF16, T, m, nrm, scores, as_stream(stream)));
+    return POP_OK;
+}
+
+int pop_layer_reserve_prompt(pop_layer_t *L, int T, void *stream)
+{
+    if (!L) return POP_EINVAL;
+    if (T < 1 || T > L->max_tokens) return POP_ESHAPE;
+    if (!L->is_bf16 || T < kFfnMfmaMinTokens) return POP_OK;  // those forward passes use the layer's fixed scratch
+    int ldh = 0, n_split = 1;
+    { int rc = ffn_scratch(L, T, true, &ldh, &n_split, as_stream(stream), true); if (rc != POP_OK) return rc; }
+    if (!L->top_list && !dev_alloc((void **)&L->top_list, ((size_t)L->m + 1) * sizeof(int))) return POP_ENOMEM;
+    return POP_OK;
+}
+
+int pop_probe_read(const void *buf, size_t bytes, int workgroups, unsigned int *sink, void *stream)
+{
+    if (!buf || !sink || !aligned16(buf)) return POP_EINVAL;
+    if (bytes < 16 || workgroups < 1 || workgroups > 65535) return POP_ESHAPE;
+    POP_HIP(launch_probe_read(buf, bytes, workgroups, sink, as_stream(stream)));
+    return POP_OK;
+}
+
+int pop_probe_step_read(pop_layer_t *L, int k, int workgroups, unsigned int *sink, void *stream)
+{
+    if (!L || !sink) return POP_EINVAL;
+    if (!L->has_partition) return POP_ESTATE;
+    if (k < 0 || k > L->n_cand || workgroups < 1 || workgroups > 65535) return POP_ESHAPE;
+    if (L->n_ret + L->n_cand == 0) return POP_OK;
+    POP_HIP(launch_probe_step_read(L->w, L->d / (L->is_bf16 ? 8 : 4), L->rc_idx, L->n_ret + L->n_cand, L->ret_idx,
+                                   L->n_ret, L->cand_idx, k, workgroups, sink, as_stream(stream)));
     return POP_OK;
 }
 

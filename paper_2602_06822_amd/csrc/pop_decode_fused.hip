@@ -140,7 +140,6 @@ __device__ __forceinline__ float wave_total(float v)
     const float r = dpp_row_sum(v);
     return (lane_value(r, 0) + lane_value(r, 16)) + (lane_value(r, 32) + lane_value(r, 48));
 }
-__device__ __forceinline__ double wave_total(double v) { return wave_sum(v); }
 
 // 16-byte write-through store (device scope), p 16-byte aligned.  Not tracked by the compiler's wait counting:
 // follow with an explicit wait before relying on it.
@@ -164,7 +163,7 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     __shared__ SelShared sh;
     __shared__ int s_flag;
     __shared__ int mb_bits[2];  // thread 0 -> everyone, handed over at the round's barrier
-    __shared__ acc_t part[2][2 * kRB + kXL][kSelMaxWaves];
+    __shared__ double part[2][2 * kRB + kXL][kSelMaxWaves];  // wave partials of the dot products, summed in double
     __shared__ int j_s[(kMaxStatic + 1) * kRB];                     // statically dealt retained channels
     __shared__ int j_a[32];                                         // this workgroup's candidates, by slot
     __shared__ float h_a[32];                                       // their hidden activations
@@ -349,9 +348,11 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
         make_desc(dn2, i + 2);
 
         // wave partials -> LDS -> totals in every thread (one barrier)
+        // (a thread's one or two vectors of products are summed in the row's accumulator type; across lanes and
+        // waves the sums run in double, so the tree adds no float32 rounding at the magnitude of the full sum)
 #pragma unroll
         for (int t = 0; t < kRB; ++t) {
-            const acc_t gt = wave_total(ag[t]), ut = wave_total(au[t]);
+            const double gt = wave_total((double)ag[t]), ut = wave_total((double)au[t]);
             if (lane == 0) {
                 part[par][2 * t][wave] = gt;
                 part[par][2 * t + 1][wave] = ut;
@@ -360,37 +361,27 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
         if (xkind == 1) {
 #pragma unroll
             for (int a = 0; a < kXL; ++a) {
-                const acc_t xt = wave_total(ax[a]);
+                const double xt = wave_total((double)ax[a]);
                 if (lane == 0) part[par][2 * kRB + a][wave] = xt;
             }
         }
         __syncthreads();
         float hv[kRB], hx[2] = {0.f, 0.f};
-        if constexpr (sizeof(acc_t) == 4) {
-            static_assert(2 * kRB * kSelMaxWaves == kWave && kXL * kSelMaxWaves == kWave, "one LDS word per lane");
-            // lane l holds value l/16 of wave l%16; a DPP row sum adds the waves in a fixed tree order
-            const float tot = dpp_row_sum((&part[par][0][0])[lane]);
+        {
+            static_assert(2 * kRB * kSelMaxWaves == kWave && kXL * kSelMaxWaves == kWave, "one LDS value per lane");
+            // lane l holds value l/16 of wave l%16 (unused waves' slots stay zero); a DPP row sum adds the waves in a
+            // fixed tree order
+            const double tot = dpp_row_sum((&part[par][0][0])[lane]);
 #pragma unroll
             for (int t = 0; t < kRB; ++t)
-                hv[t] = dc.jb[t] >= 0 ? silu_mul(lane_value(tot, 32 * t), lane_value(tot, 32 * t + 16)) : 0.f;
+                hv[t] = dc.jb[t] >= 0 ? silu_mul((float)lane_value(tot, 32 * t), (float)lane_value(tot, 32 * t + 16)) : 0.f;
             if (xkind == 1) {
-                const float tx = dpp_row_sum((&part[par][2 * kRB][0])[lane]);
+                const double tx = dpp_row_sum((&part[par][2 * kRB][0])[lane]);
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
-                    hx[a] = dc.xrow[2 * a] >= 0 ? silu_mul(lane_value(tx, 32 * a), lane_value(tx, 32 * a + 16)) : 0.f;
-            }
-        } else {
-            auto total = [&](int v) {
-                acc_t sum = 0;
-                for (int wv = 0; wv < nw; ++wv) sum += part[par][v][wv];
-                return (float)sum;
-            };
-#pragma unroll
-            for (int t = 0; t < kRB; ++t) hv[t] = dc.jb[t] >= 0 ? silu_mul(total(2 * t), total(2 * t + 1)) : 0.f;
-            if (xkind == 1) {
-#pragma unroll
-                for (int a = 0; a < 2; ++a)
-                    hx[a] = dc.xrow[2 * a] >= 0 ? silu_mul(total(2 * kRB + 2 * a), total(2 * kRB + 2 * a + 1)) : 0.f;
+                    hx[a] = dc.xrow[2 * a] >= 0
+                                ? silu_mul((float)lane_value(tx, 32 * a), (float)lane_value(tx, 32 * a + 16))
+                                : 0.f;
             }
         }
         if (tid == 0) {

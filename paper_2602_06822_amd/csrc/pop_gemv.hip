@@ -32,9 +32,12 @@ __device__ __forceinline__ void gateup_row(const typename V::vec_t *__restrict__
     const int nvec_full = nvec / group * group;
     const vec_t *g = w + (size_t)j * 3 * nvec;
     const vec_t *u = g + nvec;
-    typename V::acc_t ag[B], au[B];
+    // a 16-byte vector's products are summed in the row's accumulator type (float32 for bf16 rows: eight exact
+    // products), the vectors of a lane and then the lanes in double: a long float32 chain would round every add at the
+    // magnitude of the largest product met so far
+    double ag[B], au[B];
 #pragma unroll
-    for (int b = 0; b < B; ++b) ag[b] = au[b] = 0;
+    for (int b = 0; b < B; ++b) ag[b] = au[b] = 0.0;
 
     for (int c0 = 0; c0 < nvec_full; c0 += group) {
         vec_t wg[kGuUnroll], wu[kGuUnroll];
@@ -48,8 +51,8 @@ __device__ __forceinline__ void gateup_row(const typename V::vec_t *__restrict__
 #pragma unroll
             for (int b = 0; b < B; ++b) {
                 vec_t xv = xs[b * nvec + c0 + q * kWave + lane];
-                ag[b] = V::dot(wg[q], xv, ag[b]);
-                au[b] = V::dot(wu[q], xv, au[b]);
+                ag[b] += (double)V::dot(wg[q], xv, (typename V::acc_t)0);
+                au[b] += (double)V::dot(wu[q], xv, (typename V::acc_t)0);
             }
         }
     }
@@ -58,13 +61,13 @@ __device__ __forceinline__ void gateup_row(const typename V::vec_t *__restrict__
 #pragma unroll
         for (int b = 0; b < B; ++b) {
             vec_t xv = xs[b * nvec + c];
-            ag[b] = V::dot(wg, xv, ag[b]);
-            au[b] = V::dot(wu, xv, au[b]);
+            ag[b] += (double)V::dot(wg, xv, (typename V::acc_t)0);
+            au[b] += (double)V::dot(wu, xv, (typename V::acc_t)0);
         }
     }
 #pragma unroll
     for (int b = 0; b < B; ++b) {
-        float gs = (float)wave_sum(ag[b]), us = (float)wave_sum(au[b]);
+        float gs = (float)wave_total(ag[b]), us = (float)wave_total(au[b]);
         if (lane == 0) {
             float hv = silu_mul(gs, us);
             h[(size_t)b * m + j] = hv;

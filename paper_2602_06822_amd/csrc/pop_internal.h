@@ -136,9 +136,15 @@ __device__ __forceinline__ void compact_hidden_block(const CompactJob &job, int 
 {
     const int a = *job.n_list;
     const int c = (bx * 256 + (int)threadIdx.x) * 2;  // a thread owns two adjacent positions (one 32-bit store)
-    if (c >= a) return;
-    const int j0 = job.list[c], j1 = c + 1 < a ? job.list[c + 1] : -1;
     const int t0 = by * kCompactRows, t1 = min(job.T, t0 + kCompactRows);
+    if (c >= a) {
+        // the columns between the list's end and the end of its last 64-channel k-step are read by the direct-load
+        // GEMM (against rows of zeros): they must not keep what an earlier, longer list left there
+        if (c < min((a + 63) / 64 * 64, job.ldhc))
+            for (int t = t0; t < t1; ++t) *reinterpret_cast<uint32_t *>(job.hc + (size_t)t * job.ldhc + c) = 0u;
+        return;
+    }
+    const int j0 = job.list[c], j1 = c + 1 < a ? job.list[c + 1] : -1;
     for (int t = t0; t < t1; ++t) {
         const uint16_t *row = job.h_all + (size_t)t * job.ldh;
         const uint32_t v = (uint32_t)row[j0] | (j1 >= 0 ? (uint32_t)row[j1] << 16 : 0u);
@@ -150,8 +156,11 @@ hipError_t launch_step_state_init(const unsigned char *region, int m, const int 
                                   const int *cand_idx = nullptr, int n_cand = 0, int *rc_idx = nullptr,
                                   int *ulist = nullptr, const StridedClear *clear = nullptr,
                                   const CompactJob *compact = nullptr);
-// mask rows -> ascending list of channels active in any row.
-hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s);
+// mask rows -> ascending list of channels active in any row.  With pad_hc given ([pad_T][pad_ld] bf16, pad_ld a
+// multiple of 64) the launch also zeroes its columns from the list's length up to the next multiple of 64 (what the
+// direct-load GEMM reads beyond a compact H's last column).
+hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s,
+                               uint16_t *pad_hc = nullptr, int pad_ld = 0, int pad_T = 0);
 
 // ---- decode GEMVs (pop_gemv.hip) ----
 // h[b][j] = silu(x_b . gate_j) * (x_b . up_j) for j in rows[0..n_rows); if cscore != null, rows [0, n_score)
@@ -224,6 +233,12 @@ hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *
                               const int *selbits, const int *cand_idx, int n_cand, const float *h, const void *w,
                               int m, int is_bf16, void *y, int y_bf16, hipStream_t s);
 hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s);
+
+// ---- measurement aids (pop_probe.hip): bare reads, nothing of the method ----
+hipError_t launch_probe_read(const void *buf, size_t bytes, int workgroups, unsigned int *sink, hipStream_t s);
+hipError_t launch_probe_step_read(const void *w, int nvec, const int *gu_list, int n_gu, const int *dn_ret,
+                                  int n_dn_ret, const int *dn_sel, int n_dn_sel, int workgroups, unsigned int *sink,
+                                  hipStream_t s);
 
 // ---- prefill (pop_prefill.hip) ----
 // s2_part[tile][j] = sum over the tile's tokens of H[t][j]^2, one row per token tile.

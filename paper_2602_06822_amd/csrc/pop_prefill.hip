@@ -553,20 +553,22 @@ __global__ __launch_bounds__(256) void importance_reduce_kernel(const void *__re
                                                                 const float *__restrict__ nrm,
                                                                 float *__restrict__ scores)
 {
-    __shared__ float part[4][kWave];
+    // sums of squares in double: a float32 running sum over a long prompt loses more than the 1e-5 the scores are
+    // held to (the kernel is bound by the loads of h, not by these adds)
+    __shared__ double part[4][kWave];
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const int j = blockIdx.x * kWave + lane;
-    float acc = 0.f;
+    double acc = 0.0;
     if (j < m)
         for (int t = wave; t < T; t += 4) {
-            float v = BF16 ? __uint_as_float(((uint32_t)((const uint16_t *)h)[(size_t)t * m + j]) << 16)
-                           : ((const float *)h)[(size_t)t * m + j];
-            acc = fmaf(v, v, acc);
+            const float v = BF16 ? __uint_as_float(((uint32_t)((const uint16_t *)h)[(size_t)t * m + j]) << 16)
+                                 : ((const float *)h)[(size_t)t * m + j];
+            acc = fma((double)v, (double)v, acc);
         }
     part[wave][lane] = acc;
     __syncthreads();
     if (wave == 0 && j < m) {
-        double tot = (double)part[0][lane] + (double)part[1][lane] + (double)part[2][lane] + (double)part[3][lane];
+        const double tot = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
         scores[j] = (float)((double)nrm[j] * sqrt(tot));
     }
 }

@@ -312,7 +312,8 @@ hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s)
 // ---------------------------------------------------------------- list compaction
 // list = ascending channels j with mask[r][j] != 0 for some row r < rows.
 __global__ __launch_bounds__(1024) void mask_to_list_kernel(const unsigned char *__restrict__ mask, int rows, int m,
-                                                            int *__restrict__ list, int *__restrict__ n_list)
+                                                            int *__restrict__ list, int *__restrict__ n_list,
+                                                            uint16_t *__restrict__ pad_hc, int pad_ld, int pad_T)
 {
     __shared__ SelShared sh;
     int E = (m + blockDim.x - 1) / blockDim.x;
@@ -331,11 +332,17 @@ __global__ __launch_bounds__(1024) void mask_to_list_kernel(const unsigned char 
         if (any) list[p++] = j;
     }
     if (threadIdx.x == 0) *n_list = tot[0];
+    if (pad_hc) {
+        const int a = tot[0], a_end = min((a + 63) / 64 * 64, pad_ld), w = a_end - a;
+        for (int e = threadIdx.x; e < w * pad_T; e += blockDim.x) pad_hc[(size_t)(e / w) * pad_ld + a + e % w] = 0;
+    }
 }
 
-hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s)
+hipError_t launch_mask_to_list(const unsigned char *mask, int rows, int m, int *list, int *n_list, hipStream_t s,
+                               uint16_t *pad_hc, int pad_ld, int pad_T)
 {
-    hipLaunchKernelGGL(mask_to_list_kernel, dim3(1), dim3(1024), 0, s, mask, rows, m, list, n_list);
+    hipLaunchKernelGGL(mask_to_list_kernel, dim3(1), dim3(1024), 0, s, mask, rows, m, list, n_list, pad_hc, pad_ld,
+                       pad_T);
     return hipGetLastError();
 }
 

@@ -57,6 +57,37 @@ struct VecF32 {
     }
 };
 
+// ---- cross-lane sums in double (DPP moves on the two halves, no LDS).  The partial dot products of a bf16 row are
+// float32 values whose sum can cancel; adding them up in double keeps the rounding of the cross-lane tree (a dozen
+// levels at the magnitude of the full sum) out of h, so that only the few in-lane float32 adds remain.
+template <int kCtrl>
+__device__ __forceinline__ double dpp_move(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), kCtrl, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), kCtrl, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+// Sum over the 16 lanes of each DPP row, result in every lane of the row.
+__device__ __forceinline__ double dpp_row_sum(double v)
+{
+    v += dpp_move<0xB1>(v);   // quad_perm 1,0,3,2
+    v += dpp_move<0x4E>(v);   // quad_perm 2,3,0,1
+    v += dpp_move<0x141>(v);  // row_half_mirror
+    v += dpp_move<0x140>(v);  // row_mirror
+    return v;
+}
+__device__ __forceinline__ double lane_value(double v, int lane)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+// Sum over the 64 lanes of the wave, same value in every lane (fixed order).
+__device__ __forceinline__ double wave_total(double v)
+{
+    const double r = dpp_row_sum(v);
+    return (lane_value(r, 0) + lane_value(r, 16)) + (lane_value(r, 32) + lane_value(r, 48));
+}
+
 // Dot products of one channel's gate and up rows with x (staged in LDS as vectors), lanes striding the row.
 // Returns per-lane partial sums; the caller reduces across the wave.
 template <class V, int U>

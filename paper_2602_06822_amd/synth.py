@@ -113,6 +113,14 @@ def make_layer(cfg: LayerConfig, layer_id: int = 0) -> Layer:
                  w("w_down", (cfg.d, cfg.m)), outl)
 
 
+def make_layers(cfg: LayerConfig, layer_ids, workers: int = 8):
+    """Several layers of one shape, drawn in parallel threads (each tensor has its own counter-based stream, so
+    the result does not depend on the order or the number of workers)."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=max(1, workers)) as ex:
+        return list(ex.map(lambda i: make_layer(cfg, i), layer_ids))
+
+
 def make_activations(layer: Layer, T: int, tag: str, layer_id: int = 0) -> np.ndarray:
     """X[T][d] in the layer's storage dtype; `tag` names the tensor ("prompt", "decode", ...)."""
     cfg = layer.cfg

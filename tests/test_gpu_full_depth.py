@@ -1,0 +1,216 @@
+"""GPU parity at full size and full depth: the layer stacks of the benchmark configurations, the other reading of the
+importance and the decode strategies of the ablation, each at the shape its timing is quoted on.
+
+Same bars as test_gpu_parity.py (selections byte-identical on identical float32 scores, scores 1e-5, outputs 2e-2 of
+max|y| for bf16 layers).  Prefill scores are checked on a sample of channels that always holds the first and the
+last channels (last channel chunk of the contraction) and the channels on both sides of the two region boundaries;
+the prefill sums run over every token, so every token tile takes part.  Decode steps are checked completely.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_06822_amd import synth
+
+from gpu_util import GpuLayer, bf16_out_to_f64, dev, host, max_abs_rel, score_rel_err
+from test_gpu_parity import DECODE_FLOOR, SCORE_TOL, Y_TOL, _check_decode, pop  # noqa: F401  (pop: fixture)
+
+pytestmark = pytest.mark.gpu
+
+F32, BF16 = synth.F32, synth.BF16
+
+
+def _sample_channels(tag, m, scores, n_ret, n_cand, n):
+    """n seeded channels plus the first two, the last two and the channels next to the region boundaries."""
+    order = np.lexsort((np.arange(m), -scores.astype(np.float64)))  # score descending, channel ascending
+    forced = [0, 1, m - 2, m - 1]
+    for rank in (n_ret - 1, n_ret, n_ret + n_cand - 1, n_ret + n_cand):
+        if 0 <= rank < m:
+            forced.append(int(order[rank]))
+    drawn = synth.rng("full_depth_sample", tag).choice(m, size=n, replace=False)
+    return np.unique(np.concatenate([drawn, np.asarray(forced)])).astype(np.int32)
+
+
+def _prefill_checked(oracle, G, L, x, n_ret, n_cand, tag, n_sample=12):
+    """Prefill partition on the device: sampled scores against the oracle, the partition on all channels."""
+    scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+    r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+    assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1), tag
+    sample = _sample_channels(tag, L.cfg.m, scores, n_ret, n_cand, n_sample)
+    H = oracle.hidden(x, L.w_gate, L.w_up, L.cfg.dtype, chan=sample)
+    s_ref = oracle.importance(L.w_down, L.cfg.dtype, H, chan=sample)[sample]
+    err = score_rel_err(scores[sample], s_ref, eps=1e-6)
+    assert err <= SCORE_TOL, f"{tag}: prefill score error {err:.3e}"
+    return scores, region, ret, cand
+
+
+@pytest.mark.timeout(900)
+def test_config3_stack_32_layers_prompt_2048(pop, oracle):
+    """The 32-layer stack of Llama-2-7B-shaped layers as the configuration states it: independent weights and inputs
+    per layer, 2048-token prompts, one stream, four decode tokens through all 32 layers.  Every layer's step is
+    checked against the oracle in the two-call form; then the same tokens run as one captured graph of 32
+    single-launch steps, replayed per token, and every layer's replayed mask, scores and output are checked again."""
+    cfg, n_layers, T, steps, r = synth.CFG3, 32, 2048, 4, 0.35
+    d, m = cfg.d, cfg.m
+    n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r, 0.10)
+    host_layers = synth.make_layers(cfg, range(n_layers), workers=16)
+    stack = []
+    try:
+        for li, L in enumerate(host_layers):
+            G = GpuLayer(pop, L, max_tokens=T, max_batch=1)
+            stack.append(G)
+            x = synth.make_activations(L, T, "prompt", li)
+            _, region, _, cand = _prefill_checked(oracle, G, L, x, n_ret, n_cand, f"cfg3_layer{li}")
+            G.part = (region, cand)
+            print(f"cfg3 layer {li}: prefill ok", flush=True)
+        assert len({G.part[0].tobytes() for G in stack}) == n_layers  # independent partitions
+        xts = [synth.make_activations(L, steps, "decode", li) for li, L in enumerate(host_layers)]
+        eager = [[None] * n_layers for _ in range(steps)]
+        for t in range(steps):
+            for li, (L, G) in enumerate(zip(host_layers, stack)):
+                eager[t][li] = _check_decode(oracle, G, L, G.part[0], G.part[1], xts[li][t:t + 1], k)
+            print(f"cfg3 token {t}: 32 layers ok (two calls)", flush=True)
+        # one graph of 32 single-launch steps
+        side = torch.cuda.Stream()
+        x_in = [torch.zeros(d, dtype=torch.int16, device="cuda") for _ in stack]
+        y_g = [torch.zeros(d, dtype=torch.int16, device="cuda") for _ in stack]
+        cs_g = [torch.zeros(n_cand, dtype=torch.float32, device="cuda") for _ in stack]
+        mk_g = [torch.zeros(m, dtype=torch.uint8, device="cuda") for _ in stack]
+        for G in stack:
+            pop.pop_layer_set_single_launch(G.handle, True)
+        with torch.cuda.stream(side):
+            for li, G in enumerate(stack):  # the same calls eagerly first
+                pop.pop_decode_step(G.handle, x_in[li], 1, [k], y_g[li], BF16, cs_g[li], mk_g[li], stream=side)
+            side.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                s = torch.cuda.current_stream()
+                for li, G in enumerate(stack):
+                    pop.pop_decode_step(G.handle, x_in[li], 1, [k], y_g[li], BF16, cs_g[li], mk_g[li], stream=s)
+            for t in range(steps):
+                for li in range(n_layers):
+                    x_in[li].copy_(dev(xts[li][t:t + 1]).view(-1))
+                    y_g[li].fill_(777)
+                g.replay()
+                torch.cuda.synchronize()
+                for li, G in enumerate(stack):
+                    ref = eager[t][li]
+                    assert np.array_equal(host(mk_g[li]), ref["mask"][0]), (t, li)
+                    assert np.array_equal(host(cs_g[li]), ref["cscore"][0]), (t, li)
+                    y = bf16_out_to_f64(y_g[li])
+                    assert max_abs_rel(y, ref["y_ref"][0]) <= Y_TOL[BF16], (t, li)
+                    assert max_abs_rel(y, ref["y"][0]) <= 1e-2, (t, li)
+                    pop.pop_layer_sync_status(G.handle)
+                print(f"cfg3 token {t}: 32 layers ok (graph replay)", flush=True)
+        del g
+    finally:
+        for G in stack:
+            G.close()
+
+
+@pytest.mark.timeout(900)
+def test_config4_stack_13b_batched(pop, oracle):
+    """Eight of the 40 Llama-2-13B-shaped layers (spread over the stack), 1024-token prompts, decode at B = 1, 4, 8
+    with a different k per sequence, two steps each on one stream; and the one-mask-per-batch mode at this size."""
+    cfg, T, r = synth.CFG4, 1024, 0.50
+    m = cfg.m
+    ids = [0, 5, 11, 17, 23, 29, 34, 39]
+    n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r, 0.10)
+    host_layers = synth.make_layers(cfg, ids, workers=8)
+    stack = []
+    try:
+        for L, li in zip(host_layers, ids):
+            G = GpuLayer(pop, L, max_tokens=T, max_batch=8)
+            stack.append(G)
+            x = synth.make_activations(L, T, "prompt", li)
+            _, region, _, cand = _prefill_checked(oracle, G, L, x, n_ret, n_cand, f"cfg4_layer{li}")
+            G.part = (region, cand)
+        assert len({G.part[0].tobytes() for G in stack}) == len(ids)
+        for step in range(2):
+            for B in (1, 4, 8):
+                ks = [k] * B if B == 1 else [max(0, min(n_cand, k + 7 * b - 11)) for b in range(B)]
+                for L, li, G in zip(host_layers, ids, stack):
+                    xt = synth.make_activations(L, 2 * B, f"decode_b{B}", li)[step * B:(step + 1) * B]
+                    _check_decode(oracle, G, L, G.part[0], G.part[1], xt, ks)
+                print(f"cfg4 step {step} B={B}: {len(ids)} layers ok", flush=True)
+        # one mask for the batch (Eq. 3's activation norm over the step's sequences) on two of the layers
+        B = 8
+        for L, li, G in list(zip(host_layers, ids, stack))[:2]:
+            region, cand = G.part
+            xt = synth.make_activations(L, B, "decode_shared", li)
+            pop.pop_layer_set_shared_batch_mask(G.handle, True)
+            out = G.decode(xt, k)
+            pop.pop_layer_set_shared_batch_mask(G.handle, False)
+            H = oracle.hidden(xt, L.w_gate, L.w_up, BF16)
+            s_ref = oracle.importance(L.w_down, BF16, H)[cand]
+            mask1, _, act1 = oracle.select(region, out["cscore"][0], cand, k)
+            rc = region != 2
+            for b in range(B):
+                assert score_rel_err(out["cscore"][b], s_ref, eps=DECODE_FLOOR[BF16]) <= SCORE_TOL
+                assert np.array_equal(out["cscore"][b], out["cscore"][0])
+                assert score_rel_err(out["h"][b][rc], H[b][rc], eps=DECODE_FLOOR[BF16]) <= SCORE_TOL
+                assert np.array_equal(out["mask"][b], mask1)
+                assert np.array_equal(out["active_idx"][b][:n_ret + k], act1)
+                y_ref = oracle.down(H[b:b + 1], L.w_down, BF16, mask1)[0]
+                assert max_abs_rel(out["y"][b], y_ref) <= Y_TOL[BF16]
+            print(f"cfg4 layer {li}: shared batch mask ok", flush=True)
+    finally:
+        for G in stack:
+            G.close()
+
+
+@pytest.mark.timeout(600)
+def test_input_side_importance_full_size(pop, oracle):
+    """The input-side reading of Eq. 1-2 on the Llama-2-7B-shaped layer: prefill scores on a sample of channels, the
+    partition on all of them, complete decode steps at B = 1 and B = 4 (selection first, then the forward pass over
+    retained and selected channels)."""
+    cfg, T, r = synth.CFG2, 512, 0.35
+    m = cfg.m
+    L = synth.make_layer(cfg, layer_id=0)
+    x = synth.make_activations(L, T, "prompt")
+    n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r, 0.10)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=4) as G:
+        pop.pop_layer_set_importance(G.handle, pop.POP_IMPORTANCE_INPUT_SIDE)
+        scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+        r1, ret1, cand1 = oracle.partition(scores, n_ret, n_cand)
+        assert np.array_equal(region, r1) and np.array_equal(ret, ret1) and np.array_equal(cand, cand1)
+        sample = _sample_channels("input_side_full", m, scores, n_ret, n_cand, 40)
+        s_ref = oracle.importance_input_side(x, L.w_gate, L.w_up, BF16, chan=sample)[sample]
+        assert score_rel_err(scores[sample], s_ref, eps=1e-6) <= SCORE_TOL
+        xt = synth.make_activations(L, 4, "decode_input_side")
+        for xb, ks in ((xt[:1], [k]), (xt, [k, 0, n_cand, k - 3]), (xt[1:2], [k])):
+            for one_call in (False, True):
+                out = G.decode(xb, ks, one_call=one_call)
+                for b in range(xb.shape[0]):
+                    c_ref = oracle.importance_input_side(xb[b:b + 1], L.w_gate, L.w_up, BF16, chan=cand)[cand]
+                    assert score_rel_err(out["cscore"][b], c_ref, eps=1e-6) <= SCORE_TOL
+                    mask1, _, act1 = oracle.select(region, out["cscore"][b], cand, ks[b])
+                    assert np.array_equal(out["mask"][b], mask1)
+                    assert out["n_active"][b] == n_ret + ks[b]
+                    assert np.array_equal(out["active_idx"][b][:n_ret + ks[b]], act1)
+                    active = np.flatnonzero(mask1).astype(np.int32)
+                    H = oracle.hidden(xb[b:b + 1], L.w_gate, L.w_up, BF16, chan=active)
+                    assert score_rel_err(out["h"][b][active], H[0][active], eps=DECODE_FLOOR[BF16]) <= SCORE_TOL
+                    y_ref = oracle.down(H, L.w_down, BF16, mask1)[0]
+                    assert max_abs_rel(out["y"][b], y_ref) <= Y_TOL[BF16]
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("strategy,gamma", [("STATIC_MASK", 0.0), ("RESCORE_ALL", 0.0), ("POP", 0.05), ("POP", 0.20)])
+def test_decode_strategies_full_size(pop, oracle, strategy, gamma):
+    """The decode strategies of the paper's ablation (trade-off table) at the Llama-2-7B shape, r = 0.35: the static
+    prefill mask (no candidates), re-scoring every channel at each step (every channel a candidate) and candidate
+    bands of 5 % and 20 %: partition on all channels, complete decode steps."""
+    cfg, T, r = synth.CFG2, 512, 0.35
+    m = cfg.m
+    L = synth.make_layer(cfg, layer_id=0)
+    x = synth.make_activations(L, T, "prompt")
+    n_ret, n_cand, k = pop.pop_strategy_counts(getattr(pop, "POP_STRATEGY_" + strategy), m, r, gamma)
+    assert n_ret + k == int(np.floor((1 - r) * m + 0.5))
+    xt = synth.make_activations(L, 3, "decode_strategy")
+    with GpuLayer(pop, L, max_tokens=T, max_batch=2) as G:
+        _, region, _, cand = _prefill_checked(oracle, G, L, x, n_ret, n_cand, f"strategy_{strategy}_{gamma}")
+        for t in range(2):
+            out = _check_decode(oracle, G, L, region, cand, xt[t:t + 1], k)
+            assert int(out["mask"].sum()) == n_ret + k
+        _check_decode(oracle, G, L, region, cand, xt[1:3], [k, max(k - 5, 0)])

@@ -145,6 +145,7 @@ def _check_decode(oracle, G, L, region, cand, x_t, ks, ydtype=None):
     ks = [ks] * B if isinstance(ks, int) else ks
     n_ret = int((region == 0).sum())
     rc = region != 2
+    out["y_ref"] = []
     for b in range(B):
         ref = oracle.decode(x_t[b], L.w_gate, L.w_up, L.w_down, dtype, region, cand, ks[b], want_y=False)
         herr = score_rel_err(out["h"][b][rc], ref["h"][rc], eps=DECODE_FLOOR[dtype])
@@ -160,6 +161,7 @@ def _check_decode(oracle, G, L, region, cand, x_t, ks, ydtype=None):
         y_ref = oracle.down(ref["h"].reshape(1, -1), L.w_down, dtype, mask1)[0]
         yerr = max_abs_rel(out["y"][b], y_ref)
         assert yerr <= Y_TOL[dtype], f"y error {yerr:.3e}"
+        out["y_ref"].append(y_ref)
     # the whole step in one call: same selection, scores and h bit for bit.  Its default form issues the same
     # launches (y bit for bit); the single-launch form sums y in another (fixed) order
     for form in (True, "single_launch"):
@@ -557,6 +559,76 @@ def test_importance_reduce_standalone(pop, oracle):
     assert score_rel_err(host(out), refb, eps=1e-9) <= SCORE_TOL
 
 
+def test_importance_reduce_long_prompt_with_outliers(pop, oracle):
+    """2048 tokens with a few columns a thousand times larger than the rest and a few tokens that dominate their
+    column: the column sums must keep the 1e-5 of the scores (a float32 running sum would not)."""
+    T, m = 2048, 1536
+    g = synth.rng("impred_long")
+    H = g.standard_normal((T, m), dtype=np.float32)
+    H[:, ::97] *= np.float32(1000.0)
+    H[5, ::13] *= np.float32(300.0)
+    nrm = np.abs(g.standard_normal(m, dtype=np.float32)) + np.float32(0.1)
+    out = torch.empty(m, dtype=torch.float32, device="cuda")
+    ref = oracle.importance(nrm.reshape(1, m), F32, H.astype(np.float64))
+    pop.pop_importance_reduce(dev(H), F32, T, m, dev(nrm), out)
+    assert score_rel_err(host(out), ref, eps=1e-9) <= SCORE_TOL
+    Hb = synth.f32_to_bf16_bits(H)
+    refb = oracle.importance(nrm.reshape(1, m), F32, synth.storage_to_f64(Hb, BF16))
+    pop.pop_importance_reduce(dev(Hb), BF16, T, m, dev(nrm), out)
+    assert score_rel_err(host(out), refb, eps=1e-9) <= SCORE_TOL
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_prefill_without_tokens(pop, oracle, dtype):
+    """T = 0 (an expert no prompt token was routed to): all scores zero, so the one total order falls back on the
+    channel index: the first n_ret channels are retained, the next n_cand are candidates; decode steps then run on
+    that partition as on any other.  The forward-pass form gives the same partition and the index-order mask."""
+    d, m = (264, 301) if dtype == BF16 else (260, 301)
+    L = synth.make_layer(synth.small_config("no_tokens", d, m, dtype))
+    xt = synth.make_activations(L, 2, "decode")
+    n_ret, n_cand, k = 120, 80, 33
+    with GpuLayer(pop, L, max_tokens=8, max_batch=2) as G:
+        scores, region, ret, cand = G.prefill(np.zeros((0, d), xt.dtype), n_ret, n_cand)
+        assert not scores.any()
+        r0, ret0, cand0 = oracle.partition(np.zeros(m, np.float32), n_ret, n_cand)
+        assert np.array_equal(region, r0) and np.array_equal(ret, ret0) and np.array_equal(cand, cand0)
+        assert np.array_equal(ret, np.arange(n_ret)) and np.array_equal(cand, n_ret + np.arange(n_cand))
+        _check_decode(oracle, G, L, region, cand, xt[:1], k)
+        _check_decode(oracle, G, L, region, cand, xt, [k, 0])
+        sc2, region2, _, _, mask, _ = G.prefill_forward(np.zeros((0, d), xt.dtype), n_ret, n_cand, k)
+        assert not sc2.any() and np.array_equal(region2, region)
+        assert np.array_equal(mask, (np.arange(m) < n_ret + k).astype(np.uint8))
+
+
+def test_forward_pass_scratch_poisoned_and_side_stream(pop, oracle):
+    """The prompt-sized forward pass on a non-blocking side stream (scratch reserved ahead, so the calls only enqueue),
+    and a short channel list right after a call whose compact H holds non-finite values: the columns the GEMM reads
+    beyond the short list's end must not keep them."""
+    d, m, T = 256, 2000, 96
+    L = synth.make_layer(synth.small_config("ffn_poison", d, m, BF16))
+    x = synth.make_activations(L, T, "tokens")
+    xbad = x.copy()
+    xbad[:, ::3] = 0x7F80  # +inf in bf16: H of every channel becomes non-finite
+    g = synth.rng("ffn_poison_masks")
+    side = torch.cuda.Stream()
+    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+        with torch.cuda.stream(side):
+            pop.pop_layer_reserve_prompt(G.handle, T, stream=side)
+            G.ffn(xbad, np.ones(m, np.uint8), F32)  # fills compact H with inf / nan over all 2000 columns
+            for a in (65, 1, 130, 1999):
+                mask = np.zeros(m, np.uint8)
+                mask[g.choice(m, size=a, replace=False)] = 1
+                y = G.ffn(x, mask, F32)
+                y_ref = oracle.pruned_ffn(x, L.w_gate, L.w_up, L.w_down, BF16, mask)
+                assert np.isfinite(y).all(), a
+                assert max_abs_rel(y, y_ref) <= FFN_MFMA_TOL_F32, a
+            # the one-call prefilling stage on the same stream, after a poisoned one
+            n_ret, n_cand, k0 = 900, 300, 77
+            G.prefill_forward(xbad, n_ret, n_cand, k0, F32)
+            _check_prefill_forward(oracle, G, L, x, n_ret, n_cand, k0, F32, FFN_MFMA_TOL_F32)
+            side.synchronize()
+
+
 def test_single_launch_step_replays_from_a_graph(pop):
     """The single-launch step keeps no per-launch state on the host: a captured launch is replayed several times,
     with eager steps in between, and every replay must reproduce the eager result bit for bit."""
@@ -654,7 +726,9 @@ def test_error_paths(pop):
         assert status(pop.pop_decode_mask, G.handle, x, 1, 1) == pop.POP_ESTATE
         assert status(pop.pop_pruned_ffn, G.handle, None, 1, None, 0, y, F32) == pop.POP_ESTATE
         assert status(pop.pop_prefill_partition, G.handle, x, 9, 10, 10) == pop.POP_ESHAPE
-        assert status(pop.pop_prefill_partition, G.handle, x, 0, 10, 10) == pop.POP_ESHAPE
+        assert status(pop.pop_prefill_partition, G.handle, x, -1, 10, 10) == pop.POP_ESHAPE
+        assert status(pop.pop_layer_reserve_prompt, G.handle, 9) == pop.POP_ESHAPE
+        assert status(pop.pop_layer_reserve_prompt, None, 4) == pop.POP_EINVAL
         assert status(pop.pop_prefill_partition, G.handle, x, 8, 30, 11) == pop.POP_ESHAPE
         assert status(pop.pop_prefill_partition, G.handle, x, 8, -1, 11) == pop.POP_ESHAPE
         assert status(pop.pop_prefill_partition, G.handle, None, 8, 10, 10) == pop.POP_EINVAL
@@ -795,7 +869,11 @@ def _moe_case(pop, oracle, cfg, n_experts, T, steps, r, n_sample, f_cand=0.10):
             G = GpuLayer(pop, L, max_tokens=max(len(tok), 1), max_batch=1)
             layers.append(G)
             if len(tok) == 0:  # an expert nobody was routed to: all-zero scores, partition by channel order
-                pytest.skip("synthetic routing left an expert without tokens")
+                scores, region, ret, cand = G.prefill(np.zeros((0, d), x.dtype), n_ret, n_cand)
+                assert not scores.any()
+                assert np.array_equal(ret, np.arange(n_ret)) and np.array_equal(cand, n_ret + np.arange(n_cand))
+                parts.append((region, cand))
+                continue
             xe = np.ascontiguousarray(x[tok])
             scores, region, ret, cand = G.prefill(xe, n_ret, n_cand)
             sample = np.sort(synth.rng("moe_sample", e).choice(m, size=n_sample, replace=False)).astype(np.int32)
