@@ -179,7 +179,9 @@ int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_ca
                          const unsigned char *region, int m, unsigned char *mask, int *sel_idx, void *stream);
 
 /* Column-wise importance reduction alone (Eq. 3): h dev [T][m] (float32 or bf16), nrm dev [m] float32,
- * scores[j] = nrm[j] * sqrt(sum_t h[t][j]^2). */
+ * scores[j] = nrm[j] * sqrt(sum_t h[t][j]^2).  The tokens are summed in chunks; the per-chunk partial sums
+ * (at most 32 x m doubles) live in scratch that this call allocates and frees on `stream` (hipMallocAsync).
+ * Errors: NULL pointers, bad dtype -> POP_EINVAL; T < 1 or m < 1 -> POP_ESHAPE; no memory -> POP_ENOMEM. */
 int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const float *nrm,
                           float *scores, void *stream);
 

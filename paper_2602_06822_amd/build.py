@@ -13,7 +13,7 @@ OUT = os.path.join(PKG, "libpop_hip.so")
 OBJ_DIR = os.path.join(ROOT, "_build")
 
 SOURCES = ["pop_api.hip", "pop_setup.hip", "pop_select.hip", "pop_gemv.hip", "pop_decode_fused.hip",
-           "pop_prefill.hip", "pop_down_gemm.hip", "pop_input_side.hip", "pop_probe.hip"]
+           "pop_prefill.hip", "pop_down_gemm.hip", "pop_input_side.hip", "pop_probe.hip", "pop_importance.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -719,7 +719,18 @@ int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const
     if (!h || !nrm || !scores) return POP_EINVAL;
     if (hdtype != POP_F32 && hdtype != POP_BF16) return POP_EINVAL;
     if (T < 1 || m < 1) return POP_ESHAPE;
-    POP_HIP(launch_importance_reduce(h, hdtype == POP_BF16, T, m, nrm, scores, as_stream(stream)));
+    // the per-chunk partial sums live in stream-ordered scratch: allocated and freed on the caller's stream
+    hipStream_t s = as_stream(stream);
+    void *scratch = nullptr;
+    hipError_t e = hipMallocAsync(&scratch, importance_reduce_scratch_bytes(T, m), s);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? POP_ENOMEM : hip_fail(e, "hipMallocAsync");
+    }
+    e = launch_importance_reduce(h, hdtype == POP_BF16, T, m, nrm, scores, scratch, s);
+    const hipError_t ef = hipFreeAsync(scratch, s);
+    if (e != hipSuccess) return hip_fail(e, "importance reduction");
+    if (ef != hipSuccess) return hip_fail(ef, "hipFreeAsync");
     return POP_OK;
 }
 

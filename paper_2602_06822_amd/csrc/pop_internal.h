@@ -2,6 +2,7 @@
 // Each .hip file defines its kernels and a host launcher; pop_api.hip holds the C ABI.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 #include <stdint.h>
 
 #include "pop.h"
@@ -278,8 +279,10 @@ hipError_t launch_mask_any(const unsigned char *mask, int rows, int m, unsigned 
 // scores[j] = nrm[j] * sqrt(sum_tile s2_part[tile][j])
 hipError_t launch_scores_from_partials(const float *s2_part, int n_tiles, int m, const float *nrm, float *scores,
                                        hipStream_t s);
-// stand-alone column reduction of a materialised H[T][m]
+// stand-alone column reduction of a materialised H[T][m] (pop_importance.hip); scratch: device memory of
+// importance_reduce_scratch_bytes(T, m) bytes, 8-byte aligned, for the per-chunk partial sums
+size_t importance_reduce_scratch_bytes(int T, int m);
 hipError_t launch_importance_reduce(const void *h, int is_bf16, int T, int m, const float *nrm, float *scores,
-                                    hipStream_t s);
+                                    void *scratch, hipStream_t s);
 
 }  // namespace pop

@@ -546,42 +546,4 @@ hipError_t launch_scores_from_partials(const float *s2_part, int n_tiles, int m,
     return hipGetLastError();
 }
 
-// Stand-alone column reduction of a materialised H[T][m]: a workgroup owns 64 channels; its 4 waves stride the
-// tokens (coalesced rows of 64 channels), then combine through LDS in wave order.
-template <bool BF16>
-__global__ __launch_bounds__(256) void importance_reduce_kernel(const void *__restrict__ h, int T, int m,
-                                                                const float *__restrict__ nrm,
-                                                                float *__restrict__ scores)
-{
-    // sums of squares in double: a float32 running sum over a long prompt loses more than the 1e-5 the scores are
-    // held to (the kernel is bound by the loads of h, not by these adds)
-    __shared__ double part[4][kWave];
-    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    const int j = blockIdx.x * kWave + lane;
-    double acc = 0.0;
-    if (j < m)
-        for (int t = wave; t < T; t += 4) {
-            const float v = BF16 ? __uint_as_float(((uint32_t)((const uint16_t *)h)[(size_t)t * m + j]) << 16)
-                                 : ((const float *)h)[(size_t)t * m + j];
-            acc = fma((double)v, (double)v, acc);
-        }
-    part[wave][lane] = acc;
-    __syncthreads();
-    if (wave == 0 && j < m) {
-        const double tot = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
-        scores[j] = (float)((double)nrm[j] * sqrt(tot));
-    }
-}
-
-hipError_t launch_importance_reduce(const void *h, int is_bf16, int T, int m, const float *nrm, float *scores,
-                                    hipStream_t s)
-{
-    dim3 grid((m + kWave - 1) / kWave);
-    if (is_bf16)
-        hipLaunchKernelGGL(importance_reduce_kernel<true>, grid, dim3(256), 0, s, h, T, m, nrm, scores);
-    else
-        hipLaunchKernelGGL(importance_reduce_kernel<false>, grid, dim3(256), 0, s, h, T, m, nrm, scores);
-    return hipGetLastError();
-}
-
 }  // namespace pop
