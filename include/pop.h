@@ -191,6 +191,15 @@ int pop_importance_reduce(const void *h, pop_dtype_t hdtype, int T, int m, const
  * Errors: T < 1 or T > max_tokens -> POP_ESHAPE; allocation failure -> POP_ENOMEM. */
 int pop_layer_reserve_prompt(pop_layer_t *layer, int T, void *stream);
 
+/* pop_importance_reduce for callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the same kernels, arguments, results (bit for bit) and errors, but the per-chunk partial
+ * sums live in a static device array of 8 MiB that every GPU the library runs on holds until the process ends; the
+ * call allocates and frees nothing.  Limit: m <= 32768 channels, else POP_EUNSUPPORTED (use pop_importance_reduce).
+ * All calls on one GPU share that array: calls that overlap in time on one GPU (different streams) race; calls on one
+ * stream are ordered and safe.  A failing HIP call gives POP_EHIP (no text is recorded for pop_last_hip_error). */
+int pop_importance_reduce_static(const void *h, pop_dtype_t hdtype, int T, int m, const float *nrm,
+                                 float *scores, void *stream);
+
 /* Read-only views of layer state, for tests and callers that build on the partition.
  * Copies are enqueued on `stream`; outputs dev, any may be NULL: nrm [m] float32 (n_j of Eq. 3),
  * h [B][m] float32 of the last decode step (0 for pruned channels is NOT guaranteed: only retained and

@@ -47,6 +47,7 @@ _SIGS = {
     "pop_partition_top_from_scores": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "pop_topk_from_scores": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp]),
     "pop_importance_reduce": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
+    "pop_importance_reduce_static": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "pop_layer_reserve_prompt": (_i, [_vp, _i, _vp]),
     "pop_probe_read": (_i, [_vp, C.c_size_t, _i, _vp, _vp]),
     "pop_probe_step_read": (_i, [_vp, _i, _i, _vp, _vp]),
@@ -199,6 +200,11 @@ def pop_topk_from_scores(cand_scores, cand_idx, n_cand, k, region, m, mask=None,
 def pop_importance_reduce(h, hdtype, T, m, nrm, scores, stream=None):
     _check(_lib.pop_importance_reduce(_ptr(h), hdtype, T, m, _ptr(nrm), _ptr(scores), _stream(stream)),
            "pop_importance_reduce")
+
+
+def pop_importance_reduce_static(h, hdtype, T, m, nrm, scores, stream=None):
+    _check(_lib.pop_importance_reduce_static(_ptr(h), hdtype, T, m, _ptr(nrm), _ptr(scores), _stream(stream)),
+           "pop_importance_reduce_static")
 
 
 def pop_layer_reserve_prompt(layer, T: int, stream=None):

@@ -115,3 +115,58 @@ hipError_t launch_importance_reduce(const void *h, int is_bf16, int T, int m, co
 }
 
 }  // namespace pop
+
+// ---------------------------------------------------------------- the variant that allocates nothing
+// Scratch of the variant below: a file-scope device array (every GPU the library runs on holds its own copy until
+// the process ends).  Host code never passes the array's name to a kernel: the name is a host-side stand-in, not a
+// device address.  Its device address is looked up once per device and used from then on.
+namespace {
+
+constexpr int kStaticMaxChannels = 32768;  // largest m of the allocation-free variant
+constexpr size_t kStaticScratchBytes = (size_t)pop::kIrMaxChunks * kStaticMaxChannels * sizeof(double);  // 8 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};  // device address of `scratch` on each device, once looked up
+
+// Device address of the static scratch on the current device (looked up at the first call on that device).
+hipError_t static_scratch(void **ptr)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+}  // namespace
+
+extern "C" int pop_importance_reduce_static(const void *h, pop_dtype_t hdtype, int T, int m, const float *nrm,
+                                            float *scores, void *stream)
+{
+    if (!h || !nrm || !scores) return POP_EINVAL;
+    if (hdtype != POP_F32 && hdtype != POP_BF16) return POP_EINVAL;
+    if (T < 1 || m < 1) return POP_ESHAPE;
+    if (m > kStaticMaxChannels || pop::importance_reduce_scratch_bytes(T, m) > kStaticScratchBytes)
+        return POP_EUNSUPPORTED;  // beyond the static scratch: use pop_importance_reduce
+    void *ptr = nullptr;
+    if (static_scratch(&ptr) != hipSuccess) {
+        (void)hipGetLastError();
+        return POP_EHIP;
+    }
+    // stage 1 writes every partial sum that stage 2 reads, so nothing in the array has to start at zero
+    const hipError_t e = pop::launch_importance_reduce(h, hdtype == POP_BF16, T, m, nrm, scores, ptr,
+                                                       reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return POP_EHIP;
+    return POP_OK;
+}
