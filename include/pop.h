@@ -144,16 +144,14 @@ int pop_pruned_ffn(pop_layer_t *layer, const void *x, int T, const unsigned char
 
 /* Whole decode step in one call (Sec. 3.3 "Decoding Stage", Sec. 3.4: pass 1 over retained and candidate
  * channels, candidate re-scoring, per-token selection, then the output over retained and selected channels):
- * the same results as pop_decode_mask followed by pop_pruned_ffn(mask = NULL), with y: dev [B][d] of dtype ydtype
- * and the other outputs as in pop_decode_mask (each may be NULL).
- * By default it issues exactly those two calls' launches.  With pop_layer_set_single_launch(layer, 1) (or the
- * environment variable POP_SINGLE_LAUNCH=1 at layer creation) a B == 1 step is a single kernel launch, whose
- * workgroups wait for each other at the end and then sum their partial outputs themselves; it keeps no host-side
- * state per launch, so a captured launch can be replayed.  That wait is bounded: if it (or the wait for the
- * selection) expires, y is not written and pop_layer_sync_status reports POP_EDEVICE; repeat the step in the
- * default form, which never depends on such a wait for its result.  The single launch sums y in another (also
- * fixed) order, so the two forms agree to float32 rounding, not bit for bit.  Measured on MI355X the two forms
- * take the same time to within 3 %.
+ * the same results, bit for bit, as pop_decode_mask followed by pop_pruned_ffn(mask = NULL), with y: dev [B][d] of
+ * dtype ydtype and the other outputs as in pop_decode_mask (each may be NULL).
+ * It issues exactly those two calls' launches.  A B == 1 step on a shape the fused single-sequence kernel takes is
+ * two launches: that kernel, whose workgroups hand each other the candidates' h and the selection inside the launch,
+ * and a small kernel that sums their partial outputs.  Neither keeps host-side state per launch, so captured
+ * launches can be replayed.  The waits inside the fused launch are bounded (pop_layer_set_wait_limit): if one gives
+ * up, the step's results are invalid, pop_layer_sync_status reports POP_EDEVICE, every kernel still exits and the
+ * next step is unaffected.
  * Errors: as pop_decode_mask; y == NULL or bad ydtype -> POP_EINVAL. */
 int pop_decode_step(pop_layer_t *layer, const void *x_t, int B, const int *k, void *y, pop_dtype_t ydtype,
                     float *cand_scores, unsigned char *mask, int *active_idx, int *n_active, void *stream);
@@ -205,13 +203,17 @@ int pop_importance_reduce_static(const void *h, pop_dtype_t hdtype, int T, int m
  * h [B][m] float32 of the last decode step (0 for pruned channels is NOT guaranteed: only retained and
  * candidate entries are defined). */
 int pop_layer_get_norms(pop_layer_t *layer, float *nrm, void *stream);
-/* Synchronises `stream`, then reports whether any decode step on this layer since the last prefill hit the
- * bound of an in-kernel wait (the fused decode kernel waits, with a bound, for its own selection stage):
- * POP_OK, or POP_EDEVICE.  Every kernel exits either way; this call is how a caller finds out. */
+/* Synchronises `stream`, then reports whether any decode step on this layer since the last report (or the last
+ * prefill) hit the bound of an in-kernel wait: POP_OK, or POP_EDEVICE (the results of such a step are invalid; repeat
+ * it).  The record is cleared by the report.  Every kernel exits either way; this call is how a caller finds out. */
 int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
-/* Host only.  See pop_decode_step. */
-int pop_layer_set_single_launch(pop_layer_t *layer, int on);
+/* Host only.  How many times a bounded in-kernel wait of the fused single-sequence decode step (Sec. 3.4: its
+ * workgroups hand each other the candidates' h and the selection) looks for what it waits for before it gives
+ * up (default 65536: a fraction of a second).  A wait that gives up flags the step (pop_layer_sync_status:
+ * POP_EDEVICE); every kernel still exits, and the next step is unaffected.  0 makes every wait give up at once unless
+ * the data is already there: a testing knob.  Errors: NULL layer or looks < 0 -> POP_EINVAL. */
+int pop_layer_set_wait_limit(pop_layer_t *layer, int looks);
 /* Host only.  Which reading of Sec. 3.1 defines channel importance on this layer (the paper's equations admit two):
  *   POP_IMPORTANCE_OUTPUT_SIDE (default)  the down projection and the intermediate activations, as at the top of
  *       this file; the decode step scores candidates from h (Sec. 3.4's two-step decoding).
@@ -231,9 +233,9 @@ int pop_layer_set_importance(pop_layer_t *layer, int reading);
  * batch: all k[b] must be equal (else POP_ESHAPE), every row of cand_scores, mask and active_idx comes out the
  * same.  B == 1 is unaffected.  Invalidates a cached decode step. */
 int pop_layer_set_shared_batch_mask(pop_layer_t *layer, int on);
-/* Host only.  Which implementation the last successful pop_decode_mask on this layer used: 0 = none yet,
- * 1 = the fused single-sequence kernel, 2 = the batch-general kernels.  If workgroups != NULL it receives the
- * fused kernel's grid size for the current partition (0 when the fused kernel does not apply). */
+/* Host only.  Which implementation the last successful decode step on this layer used: 0 = none yet,
+ * 1 = the fused single-sequence kernel, 2 = the batch-general kernels.  If workgroups != NULL it
+ * receives the fused kernel's grid size for the current partition (0 when the fused kernel does not apply). */
 int pop_layer_step_kind(pop_layer_t *layer, int *workgroups);
 
 /* ---- measurement aids: bare reads of device memory (they compute nothing of the method) ----

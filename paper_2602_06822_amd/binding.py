@@ -55,7 +55,7 @@ _SIGS = {
     "pop_layer_get_hidden": (_i, [_vp, _vp, _i, _vp]),
     "pop_layer_sync_status": (_i, [_vp, _vp]),
     "pop_layer_step_kind": (_i, [_vp, _ip]),
-    "pop_layer_set_single_launch": (_i, [_vp, _i]),
+    "pop_layer_set_wait_limit": (_i, [_vp, _i]),
     "pop_layer_set_shared_batch_mask": (_i, [_vp, _i]),
     "pop_layer_set_importance": (_i, [_vp, _i]),
 }
@@ -231,8 +231,8 @@ def pop_layer_sync_status(layer, stream=None):
     _check(_lib.pop_layer_sync_status(layer, _stream(stream)), "pop_layer_sync_status")
 
 
-def pop_layer_set_single_launch(layer, on: bool):
-    _check(_lib.pop_layer_set_single_launch(layer, 1 if on else 0), "pop_layer_set_single_launch")
+def pop_layer_set_wait_limit(layer, looks: int):
+    _check(_lib.pop_layer_set_wait_limit(layer, looks), "pop_layer_set_wait_limit")
 
 
 POP_IMPORTANCE_OUTPUT_SIDE, POP_IMPORTANCE_INPUT_SIDE = 0, 1

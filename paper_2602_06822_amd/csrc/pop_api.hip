@@ -46,7 +46,6 @@ struct pop_layer {
     void *w = nullptr;     // [m][3][d]: gate row, up row, down column of each channel
     float *nrm = nullptr;  // [m]
     int n_cu = 0, wg_target = 0;
-    bool single_launch = false;  // pop_decode_step at B = 1: sum the partial outputs inside the fused kernel
     bool shared_mask = false;    // B > 1: one selection for the batch from scores aggregated over its sequences
     bool input_side = false;     // importance from the first projections and the FFN input (pop_layer_set_importance)
     float *in_s2 = nullptr;      // [max_batch][d]: squared input norms (input-side importance)
@@ -67,8 +66,11 @@ struct pop_layer {
     bool fused_ok = false;             // the fused kernel supports this partition
     FusedPlan plan = {};
     int *sync = nullptr;               // [8]
-    int *deferred = nullptr;           // [fused_max_workgroups]
-    int *selbits = nullptr;            // [fused_max_workgroups]
+    // what the fused kernel's workgroups hand to each other: 64-bit words {value, epoch}
+    unsigned long long *hc = nullptr;     // [m] a candidate's h, by candidate position
+    unsigned long long *selw = nullptr;   // per-workgroup selection words
+    int *fctr = nullptr;                  // [16]: [0] epoch, [1] finished workgroups, [2] sticky error flag
+    int spin_limit = 1 << 16;             // looks a bounded in-kernel wait takes before it gives up
     BatchK step_k = {};
     float *h = nullptr;                // [max_batch][m]
     float *cscore = nullptr;           // [max_batch][m]
@@ -215,7 +217,7 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     // the partition launch also forms the scores from the contraction's partial rows (the input-side scores are
     // already in place) and clears the step counters; one more launch writes everything that is constant per
     // partition (retained bytes of every mask row, retained prefix of every active list and of the union list, the
-    // candidate-then-retained list) and zeroes the fused kernel's selection words
+    // candidate-then-retained list)
     PartitionExtra ex;
     const bool from_partials = !scores_ready && partition_takes_partials(m);
     if (!scores_ready && !from_partials)
@@ -230,9 +232,8 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
         ex.top_mask = top_mask ? L->ffn_any : nullptr;
     }
     POP_HIP(launch_partition(L->scores, m, n_ret, n_cand, L->region, L->ret_idx, L->cand_idx, s, &ex));
-    const StridedClear clr = fused_selbits_clear(L->selbits);
     POP_HIP(launch_step_state_init(L->region, m, L->ret_idx, n_ret, L->max_batch, m, L->mask, L->active_idx, s,
-                                   L->cand_idx, n_cand, L->rc_idx, L->ulist, &clr, compact));
+                                   L->cand_idx, n_cand, L->rc_idx, L->ulist, nullptr, compact));
     L->ulist_prefix_ok = true;
     L->n_ret = n_ret;
     L->n_cand = n_cand;
@@ -267,10 +268,11 @@ FusedParams fused_params(pop_layer *L, const void *x_t, int k)
     p.mask = L->mask;
     p.active_idx = L->active_idx;
     p.n_active = L->n_active;
+    p.hc = L->hc;
+    p.selw = L->selw;
     p.partial = L->partial;
-    p.sync = L->sync;
-    p.deferred = L->deferred;
-    p.selbits = L->selbits;
+    p.ctr = L->fctr;
+    p.spin_limit = L->spin_limit;
 #ifdef POP_TRACE
     p.trace = g_trace;
 #endif
@@ -356,7 +358,7 @@ int pop_layer_destroy(pop_layer_t *L)
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
                     L->h,      L->cscore, L->mask, L->selflag, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
-                    L->sync,   L->deferred, L->selbits, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part, L->top_list, L->zero_row};
+                    L->sync,   L->hc, L->selw, L->fctr, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part, L->top_list, L->zero_row};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -400,7 +402,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         if (v >= 2 && v <= fused_max_workgroups()) L->wg_target = v;
     }
     if (L->wg_target > fused_max_workgroups()) L->wg_target = fused_max_workgroups();
-    if (const char *e = getenv("POP_SINGLE_LAUNCH")) L->single_launch = atoi(e) != 0;
+    if (const char *e = getenv("POP_WAIT_LIMIT")) L->spin_limit = atoi(e) < 0 ? 0 : atoi(e);  // (tuning, tests)
 
     const size_t mm = (size_t)m, B = (size_t)max_batch;
     struct Req { void **p; size_t bytes; };
@@ -424,8 +426,9 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         {(void **)&L->partial, ((size_t)L->n_slabs * B > (size_t)fused_max_workgroups() ? (size_t)L->n_slabs * B
                                                                                         : (size_t)fused_max_workgroups()) * d * 4},
         {(void **)&L->sync, 64},
-        {(void **)&L->deferred, (size_t)fused_max_workgroups() * 4},
-        {(void **)&L->selbits, (size_t)fused_selbits_ints() * 4},
+        {(void **)&L->hc, mm * 8},
+        {(void **)&L->selw, fused_selw_words() * 8},
+        {(void **)&L->fctr, 64},
     };
     for (const Req &r : reqs) {
         hipError_t e = hipMalloc(r.p, r.bytes);
@@ -438,8 +441,12 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     hipStream_t s = as_stream(stream);
     hipError_t e = launch_repack(w_gate, w_up, w_down, d, m, esize, L->w, L->nrm, is_bf16, s);
     if (e == hipSuccess) e = launch_fill_int(L->sync, 16, 0, s);
-    if (e == hipSuccess) e = launch_fill_int(L->deferred, fused_max_workgroups(), 0, s);
-    if (e == hipSuccess) e = launch_fill_int(L->selbits, fused_selbits_ints(), 0, s);
+    // the words the fused kernel's workgroups exchange start out with epoch 0, the counter at 1: nothing stale can
+    // ever look valid
+    if (e == hipSuccess) e = hipMemsetAsync(L->hc, 0, mm * 8, s);
+    if (e == hipSuccess) e = hipMemsetAsync(L->selw, 0, fused_selw_words() * 8, s);
+    if (e == hipSuccess) e = launch_fill_int(L->fctr, 16, 0, s);
+    if (e == hipSuccess) e = launch_fill_int(L->fctr, 1, 1, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
         pop_layer_destroy(L);
@@ -617,24 +624,11 @@ int pop_decode_step(pop_layer_t *L, const void *x_t, int B, const int *k, void *
     if (B < 1 || B > L->max_batch) return POP_ESHAPE;
     for (int b = 0; b < B; ++b)
         if (k[b] < 0 || k[b] > L->n_cand) return POP_ESHAPE;
-    if (!(B == 1 && L->fused_ok && L->single_launch)) {
-        int rc = pop_decode_mask(L, x_t, B, k, cand_scores, mask, active_idx, n_active, stream);
-        if (rc != POP_OK) return rc;
-        return pop_pruned_ffn(L, nullptr, B, nullptr, 0, y, ydtype, stream);
-    }
-    hipStream_t s = as_stream(stream);
-    L->has_step = false;
-    FusedParams p = fused_params(L, x_t, k[0]);
-    p.y = y;
-    p.y_bf16 = ydtype == POP_BF16;
-    POP_HIP(launch_decode_fused(L->plan, L->is_bf16, p, s));
-    L->step_fused = true;
-    { int rc = copy_step_outputs(L, B, cand_scores, mask, active_idx, n_active, s); if (rc != POP_OK) return rc; }
-    L->step_B = 1;
-    L->step_k = BatchK{};
-    L->step_k.k[0] = k[0];
-    L->has_step = true;
-    return POP_OK;
+    // the launches of the two calls (a single-sequence step on a shape the fused kernel takes: that kernel, then the
+    // small kernel that sums its workgroups' partial outputs)
+    int rc = pop_decode_mask(L, x_t, B, k, cand_scores, mask, active_idx, n_active, stream);
+    if (rc != POP_OK) return rc;
+    return pop_pruned_ffn(L, nullptr, B, nullptr, 0, y, ydtype, stream);
 }
 
 int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *mask, int mask_rows, void *y,
@@ -648,8 +642,7 @@ int pop_pruned_ffn(pop_layer_t *L, const void *x, int T, const unsigned char *ma
         if (!L->has_step) return POP_ESTATE;
         if (T != L->step_B) return POP_ESHAPE;
         if (L->step_fused)
-            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, L->deferred, L->sync, L->selbits, L->cand_idx,
-                                       L->n_cand, L->h, L->w, m, L->is_bf16, y, y_bf16, s));
+            POP_HIP(launch_decode_tail(L->partial, L->plan.n_wg, d, y, y_bf16, s));
         else if (T == 1)
             POP_HIP(launch_down(L->w, L->is_bf16, d, m, L->active_idx, nullptr, L->n_ret + L->step_k.k[0], L->h,
                                 nullptr, 0, 1, L->partial, L->n_slabs, y, y_bf16, s));
@@ -778,10 +771,13 @@ void pop_trace_set_buffer(void *dev_ptr) { g_trace = (unsigned long long *)dev_p
 int pop_layer_sync_status(pop_layer_t *L, void *stream)
 {
     if (!L) return POP_EINVAL;
-    int flag = 0;
+    int flag = 0, flag_fused = 0;
     POP_HIP(hipMemcpyAsync(&flag, L->sync + 2, 4, hipMemcpyDeviceToHost, as_stream(stream)));
+    POP_HIP(hipMemcpyAsync(&flag_fused, L->fctr + 2, 4, hipMemcpyDeviceToHost, as_stream(stream)));
     POP_HIP(hipStreamSynchronize(as_stream(stream)));
-    return flag ? POP_EDEVICE : POP_OK;
+    if (flag) POP_HIP(launch_fill_int(L->sync + 2, 1, 0, as_stream(stream)));  // reported once
+    if (flag_fused) POP_HIP(launch_fill_int(L->fctr + 2, 1, 0, as_stream(stream)));
+    return (flag || flag_fused) ? POP_EDEVICE : POP_OK;
 }
 
 int pop_layer_set_importance(pop_layer_t *L, int reading)
@@ -809,10 +805,10 @@ int pop_layer_set_shared_batch_mask(pop_layer_t *L, int on)
     return POP_OK;
 }
 
-int pop_layer_set_single_launch(pop_layer_t *L, int on)
+int pop_layer_set_wait_limit(pop_layer_t *L, int looks)
 {
-    if (!L) return POP_EINVAL;
-    L->single_launch = on != 0;
+    if (!L || looks < 0) return POP_EINVAL;
+    L->spin_limit = looks;
     return POP_OK;
 }
 

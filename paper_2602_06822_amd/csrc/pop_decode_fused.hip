@@ -22,20 +22,27 @@
 // keep their latency out of the stream, and with that much claimed-ahead work the finishing times did not even
 // out; it measured 3 % slower.)
 //
-//   select   workgroup 0 owns no retained rows.  It waits until all workgroups have published their candidate
-//            results (bounded spin on a counter; nobody waits for anything before that point), runs the top-k
-//            selection and hands every workgroup one word: a valid bit plus one bit per candidate slot of that
-//            workgroup that was selected.  Mask and active list for the caller are written afterwards.
+//   select   workgroup 0 owns no retained rows.  It collects every candidate's h (bounded wait; nobody waits for
+//            anything before that point), forms the step scores, runs the top-k selection and hands every workgroup
+//            one word: one bit per candidate slot of that workgroup that was selected.  Mask and active list for the
+//            caller are written afterwards.
 //   poll     a worker looks at its word once per round without ever stalling on it (thread 0 passes the value
 //            loaded in the previous round to the others through LDS, at the round's barrier); if the word has not
-//            arrived when the retained rounds are done the workgroup waits, bounded.  If the bound is ever hit,
-//            the workgroup marks its share as deferred (and raises sync[3]) and the tail kernel adds it, so every
-//            wave still exits.
-//   tail     a second small kernel sums the per-workgroup partials in workgroup order (plus deferred shares)
-//            and writes y; or, in the single-launch form, the workgroups do it themselves behind a bounded barrier.
+//            arrived when the retained rounds are done the workgroup waits, bounded.
+//   output   every workgroup leaves its partial y as one row; a second small kernel (decode_tail_kernel) sums the
+//            rows in workgroup order and writes y.
+//
+// Hand-overs carry their own validity.  Everything one workgroup hands to another inside the launch (a candidate's
+// h, a selection word) is a 64-bit word {value, epoch} written with one write-through store and read
+// with one device-coherent load; the epoch is a device-resident counter that the last workgroup of a launch
+// increments.  A reader that finds another epoch sees "not there yet" and looks again.  There are no counters or
+// flags to clear or re-arm, words of an earlier step (or of a step that gave up) can never be taken for valid, and
+// a captured launch can be replayed.
 //
 // Waiting is safe because the launch is sized to be co-resident (host checks the occupancy) and every wait is
-// bounded; nothing spins without an exit.
+// bounded; nothing spins without an exit.  A wait that expires raises the sticky error flag (the step's results
+// are then invalid) and changes nothing else: every workgroup still reaches the end, and the next launch starts
+// from a new epoch.
 #include <limits.h>
 #include <type_traits>
 #include <stdlib.h>
@@ -149,11 +156,19 @@ __device__ __forceinline__ void coherent_store4(float *p, float4 v)
     const f4 t = {v.x, v.y, v.z, v.w};
     asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(t) : "memory");
 }
-constexpr int kStage = 4096;  // floats of a partial output row staged in LDS at a time
 
-constexpr int kBitsStride = 1024;    // ints between the selection words of two workgroups
-constexpr int kGoWord = 64;          // offset of a workgroup's end-of-step "go" word from its selection word
-constexpr int kBitsValid = 1 << 31;  // set in a selection word once the selection of this step is known
+constexpr int kSelStride = 16;       // 64-bit words between the selection words of two workgroups (128 bytes)
+constexpr int kBitsValid = 1 << 31;  // set, next to the slot bits, in the copy of a selection word that thread 0
+                                     // hands to its workgroup once the word carries the step's epoch
+
+__device__ __forceinline__ unsigned long long tagged(uint32_t value, int epoch)
+{
+    return ((unsigned long long)(uint32_t)epoch << 32) | value;
+}
+__device__ __forceinline__ void coherent_store(unsigned long long *p, unsigned long long v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 template <class V, int PER, int MAXB>
 __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 {
@@ -163,29 +178,25 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     __shared__ SelShared sh;
     __shared__ int s_flag;
     __shared__ int mb_bits[2];  // thread 0 -> everyone, handed over at the round's barrier
-    __shared__ double part[2][2 * kRB + kXL][kSelMaxWaves];  // wave partials of the dot products, summed in double
+    // wave partials of the dot products, summed in double: [parity][group: retained, extras][value][wave][row of 16 lanes]
+    __shared__ __attribute__((aligned(32))) double part[2][2][4][kSelMaxWaves][4];
     __shared__ int j_s[(kMaxStatic + 1) * kRB];                     // statically dealt retained channels
     __shared__ int j_a[32];                                         // this workgroup's candidates, by slot
     __shared__ float h_a[32];                                       // their hidden activations
     __shared__ int j_st[kKeep * kRB];                               // retained channels processed since the last flush
     __shared__ float h_st[kKeep * kRB];                             // and their hidden activations
-    __shared__ __attribute__((aligned(16))) float y_stage[kStage];  // single-launch step: partial row on its way out
     __shared__ int wg_bits[1024];                                   // selector only: selected candidate slots per workgroup
 
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int nw = blockDim.x / kWave;
     const int b = blockIdx.x, n_wg = gridDim.x, n_workers = n_wg - 1, wb = b - 1;
     const int nvec = p.nvec;
     const vec_t *w = reinterpret_cast<const vec_t *>(p.w);
-    int *const my_word = p.selbits + (size_t)b * kBitsStride;
+    unsigned long long *const my_word = p.selw + (size_t)b * kSelStride;
+    const int epoch = coherent_load(&p.ctr[0]);  // the tag of everything handed over in this step
+    const int limit = p.spin_limit;
 
     POP_STAMP(0);
-    // end-of-step "go" word of this workgroup: all go words hold the same value between launches, and change once,
-    // together, when the last workgroup of a single-launch step has delivered its partial output row
-    int *const go = my_word + kGoWord;
-    const int go_before = p.y ? coherent_load(go) : 0;
-    if (b == 0 && tid == 0) coherent_store(&p.sync[3], 0);  // "some workgroup deferred its share" flag of this step
     int col[PER];
     bool ok[PER];
     vec_t xv[PER];
@@ -195,7 +206,7 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
         ok[q] = col[q] < nvec;
         xv[q] = ok[q] ? reinterpret_cast<const vec_t *>(p.x)[col[q]] : V::zero();
     }
-    for (int i = tid; i < 2 * (2 * kRB + kXL) * kSelMaxWaves; i += blockDim.x) (&part[0][0][0])[i] = 0;
+    for (int i = tid; i < 2 * 2 * 4 * kSelMaxWaves * 4; i += blockDim.x) (&part[0][0][0][0][0])[i] = 0;
 
     // ---- this workgroup's share
     // candidates: slot s of workgroup b is candidate s * n_wg + b
@@ -224,10 +235,8 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     int rem_d = 0;              // selected slots whose down rows are still to be added (valid once bits_known)
     bool bits_known = false;    // the selection word of this step has been seen
     int n_st = 0;               // rounds staged in j_st / h_st
-    int a_pub = n_aslots == 0 ? -2 : -1;  // round after which the candidate results were stored (-1: not yet)
-    bool arrived = false;       // the arrival has been signalled to the selector
     // thread 0 only: results of the polls of the selection word issued in the previous two rounds (by parity)
-    int poll_ret[2] = {0, 0};
+    unsigned long long poll_ret[2] = {0, 0};
 
     // Descriptor of round r.  Called once per round, in order.
     auto make_desc = [&](RoundDesc &ds, int r) {
@@ -290,7 +299,7 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     // nothing stands between the arrival of one round and the request for the next); the descriptor of round i + 2
     // is prepared into dn2 while that request is in flight.
     auto step = [&](RoundBuf<V, PER> &cur, const RoundDesc &dc, RoundBuf<V, PER> &nxt, const RoundDesc &dn1,
-                    RoundDesc &dn2, int i, float nrm_mine, auto parity) {
+                    RoundDesc &dn2, int i, auto parity) {
         constexpr int par = decltype(parity)::value;  // i & 1
         const int xkind = dc.xkind();
         acc_t ag[kRB], au[kRB], ax[kXL];
@@ -314,24 +323,16 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
             for (int q = 0; q < PER; ++q) ax[a] = V::dot(cur.xl[a][q], xv[q], ax[a]);
         }
         asm volatile("" ::: "memory");  // everything below stays behind the uses of this round's gate/up rows
-        // Candidate results stored in the previous round: the explicit wait below finds them acknowledged.
-        if (!arrived && a_pub != -1 && i >= a_pub + 1) {
-            if (wave == 0) {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // only requests of the previous round are outstanding here
-                if (tid == 0 && b != 0) atomicAdd(&p.sync[0], 1);
-            }
-            arrived = true;
-            POP_STAMP(1);
-        }
         load_round<V, PER>(nxt, dn1, w, nvec, col, ok);  // an empty round requests the dummy vector only
         asm volatile("" ::: "memory");
         if (tid == 0) {
             // The poll thread 0 issued two rounds ago has had two rounds to arrive: hand it to the others at this
             // round's barrier.  Then poll the selection word again (zero until the selector has written it),
             // straight into the register it is read from two rounds later.
-            mb_bits[par] = poll_ret[par];
+            const bool here = (int)(poll_ret[par] >> 32) == epoch;
+            mb_bits[par] = here ? ((int)(uint32_t)poll_ret[par] | kBitsValid) : 0;
 #ifdef POP_TRACE
-            if ((poll_ret[par] & kBitsValid) && p.trace && p.trace[(size_t)blockIdx.x * 8 + 5] == 0) POP_STAMP(5);
+            if (here && p.trace && p.trace[(size_t)blockIdx.x * 8 + 5] == 0) POP_STAMP(5);
 #endif
             poll_ret[par] = coherent_load(my_word);
         }
@@ -349,34 +350,33 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 
         // wave partials -> LDS -> totals in every thread (one barrier)
         // (a thread's one or two vectors of products are summed in the row's accumulator type; across lanes and
-        // waves the sums run in double, so the tree adds no float32 rounding at the magnitude of the full sum)
-#pragma unroll
-        for (int t = 0; t < kRB; ++t) {
-            const double gt = wave_total((double)ag[t]), ut = wave_total((double)au[t]);
-            if (lane == 0) {
-                part[par][2 * t][wave] = gt;
-                part[par][2 * t + 1][wave] = ut;
-            }
-        }
-        if (xkind == 1) {
-#pragma unroll
-            for (int a = 0; a < kXL; ++a) {
-                const double xt = wave_total((double)ax[a]);
-                if (lane == 0) part[par][2 * kRB + a][wave] = xt;
+        // waves the sums run in double, so the tree adds no float32 rounding at the magnitude of the full sum).  Each
+        // group of four values goes through halving exchanges inside the 16-lane rows; the four row sums of each wave
+        // meet the other waves' in LDS: one barrier per round
+        static_assert(kRB == 2 && kXL == 4, "two groups of four values: gate/up of two retained channels, four extra rows");
+        {
+            const double a4[4] = {(double)ag[0], (double)au[0], (double)ag[1], (double)au[1]};
+            const double z = butterfly4_row_sum(a4, lane);
+            if (lane % 16 < 4) part[par][0][butterfly_value_id(lane)][wave][lane / 16] = z;
+            if (xkind == 1) {
+                const double x4[4] = {(double)ax[0], (double)ax[1], (double)ax[2], (double)ax[3]};
+                const double zx = butterfly4_row_sum(x4, lane);
+                if (lane % 16 < 4) part[par][1][butterfly_value_id(lane)][wave][lane / 16] = zx;
             }
         }
         __syncthreads();
         float hv[kRB], hx[2] = {0.f, 0.f};
         {
-            static_assert(2 * kRB * kSelMaxWaves == kWave && kXL * kSelMaxWaves == kWave, "one LDS value per lane");
-            // lane l holds value l/16 of wave l%16 (unused waves' slots stay zero); a DPP row sum adds the waves in a
-            // fixed tree order
-            const double tot = dpp_row_sum((&part[par][0][0])[lane]);
+            // lane l: value l / 16 of wave l % 16 (unused waves' slots stay zero): its four row sums, then a row sum
+            // over the 16 lanes adds the waves in a fixed tree order
+            const double4 q4 = *reinterpret_cast<const double4 *>(&part[par][0][lane / 16][lane % 16][0]);
+            const double tot = dpp_row_sum((q4.x + q4.y) + (q4.z + q4.w));
 #pragma unroll
             for (int t = 0; t < kRB; ++t)
                 hv[t] = dc.jb[t] >= 0 ? silu_mul((float)lane_value(tot, 32 * t), (float)lane_value(tot, 32 * t + 16)) : 0.f;
             if (xkind == 1) {
-                const double tx = dpp_row_sum((&part[par][2 * kRB][0])[lane]);
+                const double4 x4 = *reinterpret_cast<const double4 *>(&part[par][1][lane / 16][lane % 16][0]);
+                const double tx = dpp_row_sum((x4.x + x4.y) + (x4.z + x4.w));
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
                     hx[a] = dc.xrow[2 * a] >= 0
@@ -413,16 +413,15 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
             }
         }
         if (dc.last_a()) {
-            // Publish this workgroup's candidate results: write-through stores, visible device-wide once
-            // acknowledged, so the hand-over needs no cache write-back.  h_a was written by thread 0 of this same
-            // wave, and a wave's LDS operations execute in order.
+            // Publish this workgroup's candidate results: one tagged word each, written through, so the hand-over
+            // needs no cache write-back, no acknowledgement and no counter.  h_a was written by thread 0 of this
+            // same wave, and a wave's LDS operations execute in order.
             if (wave == 0 && lane < n_aslots) {
-                const int j = j_a[lane];
                 const float hvv = h_a[lane];
-                coherent_store(&p.h[j], hvv);
-                coherent_store(&p.cscore[lane * n_wg + b], nrm_mine * fabsf(hvv));
+                coherent_store(&p.hc[lane * n_wg + b], tagged(__float_as_uint(hvv), epoch));
+                p.h[j_a[lane]] = hvv;
             }
-            a_pub = i;
+            POP_STAMP(1);
         }
         if (n_st == kKeep) flush_hidden();
     };
@@ -435,33 +434,21 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     RoundDesc d0, d1, d2;           // descriptors of the round being reduced, the one in flight, the one after
     make_desc(d0, 0);
     load_round<V, PER>(buf_a, d0, w, nvec, col, ok);
-    // weight factor n_j of this lane's candidate slot (wave 0), requested behind the first round's rows
-    const float nrm_mine = p.nrm[max(j_a[tid < 32 ? tid : 0], 0)];
-    asm volatile("" ::"v"(nrm_mine));  // waited for here, once, next to the first round's rows
     make_desc(d1, 1);
     int i = 0;
     // a round without work can still be followed by one with work (selected rows, once the selection is known)
     while (d0.work || d1.work) {
-        step(buf_a, d0, buf_b, d1, d2, i, nrm_mine, std::integral_constant<int, 0>{});
+        step(buf_a, d0, buf_b, d1, d2, i, std::integral_constant<int, 0>{});
         ++i;
         d0 = d1;
         d1 = d2;
         if (!(d0.work || d1.work)) break;
-        step(buf_b, d0, buf_a, d1, d2, i, nrm_mine, std::integral_constant<int, 1>{});
+        step(buf_b, d0, buf_a, d1, d2, i, std::integral_constant<int, 1>{});
         ++i;
         d0 = d1;
         d1 = d2;
     }
     POP_STAMP(2);
-    if (!arrived) {
-        // fewer than two rounds followed the last candidate round
-        if (wave == 0) {
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            if (tid == 0 && b != 0) atomicAdd(&p.sync[0], 1);
-        }
-        arrived = true;
-        POP_STAMP(1);
-    }
 
     // Adds the down rows of the selected slots in rem_d (this workgroup's own candidates; h still in LDS).
     auto drain_selected = [&]() {
@@ -502,28 +489,14 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
             for (int e = 0; e < 8; ++e) acc[q][e] += acc_sel[q][e];
     };
 
+    // This workgroup's partial y: one row of float32, summed with the others' by decode_tail_kernel.  (Summing the
+    // rows inside this launch was built twice - behind an arrival counter, and with every element a tagged word that
+    // the readers wait for - and measured no faster than the second launch: after the slowest workgroup's last store
+    // either form needs the store to become visible, a look that finds it and a trip for the rows, while the launch
+    // boundary is one kernel start plus one trip.)  The last workgroup to get here starts the next epoch: everybody
+    // has stopped looking at this one's words.
     auto store_partial = [&]() __attribute__((always_inline)) {
         float *dst = p.partial + (size_t)b * p.d;
-        if (p.y) {
-            // single-launch step: other workgroups read these rows in this launch, so write them through; staged
-            // in LDS first so that each store instruction covers whole contiguous lines (a write-through store of
-            // a few bytes per lane is one memory transaction per lane)
-            for (int c0 = 0; c0 < p.d; c0 += kStage) {
-#pragma unroll
-                for (int q = 0; q < PER; ++q) {
-                    const int o = col[q] * E - c0;
-                    if (ok[q] && o >= 0 && o < kStage)
-#pragma unroll
-                        for (int e = 0; e < E; ++e) y_stage[o + e] = acc[q][e];
-                }
-                __syncthreads();
-                const int n = min(kStage, p.d - c0);
-                for (int v = tid * 4; v < n; v += blockDim.x * 4)
-                    coherent_store4(dst + c0 + v, *reinterpret_cast<const float4 *>(&y_stage[v]));
-                __syncthreads();
-            }
-            return;
-        }
 #pragma unroll
         for (int q = 0; q < PER; ++q)
             if (ok[q]) {
@@ -532,165 +505,113 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                     *reinterpret_cast<float4 *>(dst + (size_t)col[q] * E + e) =
                         make_float4(acc[q][e], acc[q][e + 1], acc[q][e + 2], acc[q][e + 3]);
             }
-    };
-    // Single-launch step: once every workgroup's partial row is acknowledged device-wide (write-through stores,
-    // counter wait, barrier, then one arrival per workgroup), each workgroup sums a slice of the d outputs over
-    // all rows in a fixed order: 16 lanes take 16 adjacent outputs, the block's blockDim/16 lane groups take the
-    // rows round robin, then a fixed tree over the groups.  The wait is bounded like the others; if it expires
-    // the sticky error flag is raised and y is left unwritten.
-    auto final_reduce = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        // Arrival counter + one "go" word per workgroup (each in its own 4 KiB, next to its selection word): the
-        // last workgroup to arrive rewinds the counter and changes all the go words, and every workgroup polls
-        // only its own.  Hundreds of workgroups polling the one counter would queue up at a single memory
-        // channel, in front of the last arrivals.  Nothing here depends on host-side state, so a captured launch
-        // can be replayed.
-        if (tid == 0) s_flag = atomicAdd(&p.sync[6], 1) == n_wg - 1 ? 1 : 0;
-        __syncthreads();
-        if (s_flag) {
-            if (tid == 0) coherent_store(&p.sync[6], 0);
-            for (int q = tid; q < n_wg; q += blockDim.x)
-                coherent_store(p.selbits + (size_t)q * kBitsStride + kGoWord, go_before + 1);
-        }
-        __syncthreads();
-        if (tid == 0) {
-            bool all_in = false;
-            for (int it = 0; !all_in && it < kSpinLimit; ++it) {
-                all_in = coherent_load(go) != go_before;
-                if (!all_in) __builtin_amdgcn_s_sleep(2);
-            }
-            if (!all_in) p.sync[2] = 1;
-            s_flag = all_in ? 1 : 0;
-        }
-        __syncthreads();
-        POP_STAMP(5);
-        if (!s_flag) return;
-        const bool whole = coherent_load(&p.sync[3]) == 0;  // some workgroup gave up waiting for the selection: y would miss its share
-        float *red = reinterpret_cast<float *>(&sh.hist[0]);  // [waves][16]
-        const int cpw = (p.d + n_wg - 1) / n_wg;
-        const int c_lo = min(p.d, b * cpw), c_hi = min(p.d, c_lo + cpw);
-        const int cc = tid % 16, g = tid / 16, ng = blockDim.x / 16;
-        for (int c0 = c_lo; c0 < c_hi; c0 += 16) {
-            const int c = c0 + cc;
-            const bool in = c < c_hi;
-            const float *src = p.partial + (in ? c : c_lo);
-            float s = 0.f;
-            int r = g;
-            for (; r + 15 * ng < n_wg; r += 16 * ng) {  // all of a 256-row grid in one batch of independent loads
-                float v[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u)
-                    v[u] = __hip_atomic_load(src + (size_t)(r + u * ng) * p.d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-                for (int u = 0; u < 16; ++u) s += v[u];
-            }
-            for (; r < n_wg; r += ng)
-                s += __hip_atomic_load(src + (size_t)r * p.d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            s += __shfl_xor(s, 16, kWave);
-            s += __shfl_xor(s, 32, kWave);
-            if (lane < 16) red[wave * 16 + lane] = s;
-            __syncthreads();
-            if (tid < 16 && in && whole) {
-                float v = 0.f;
-                for (int wv = 0; wv < nw; ++wv) v += red[wv * 16 + tid];
-                if (p.y_bf16)
-                    reinterpret_cast<uint16_t *>(p.y)[c] = f32_to_bf16(v);
-                else
-                    reinterpret_cast<float *>(p.y)[c] = v;
-            }
-            __syncthreads();
+        if (tid == 0 && atomicAdd(&p.ctr[1], 1) == n_wg - 1) {
+            coherent_store(&p.ctr[1], 0);
+            coherent_store(&p.ctr[0], epoch + 1);
         }
     };
 
     if (b == 0) {
-        // ---- select (workgroup 0 only): wait for every other workgroup's candidate results, then top-k
-        if (tid == 0) {
-            bool ok_a = spin_until(&p.sync[0], n_workers);
-            if (!ok_a) p.sync[2] = 1;
-            coherent_store(&p.sync[0], 0);  // all arrivals are in
-            s_flag = ok_a ? 1 : 0;
-        }
+        // ---- select (workgroup 0 only): collect every candidate's h (tagged words; bounded wait), form the step
+        // scores I_j(t) = n_j |h_j| (Eq. 3 with one token), then top-k
         for (int q = tid; q < n_wg; q += blockDim.x) wg_bits[q] = 0;
+        const int n_cand = p.n_cand;
+        const bool in_lds = n_cand <= kSelLdsKeys;
+        bool got_all = true;
+        for (int base = 0; base < n_cand; base += 4 * blockDim.x) {
+            unsigned long long v[4];
+            int c[4], j[4];
+            float nr[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                c[u] = base + u * blockDim.x + tid;
+                j[u] = c[u] < n_cand ? p.cand_idx[c[u]] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) nr[u] = p.nrm[j[u]];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) v[u] = c[u] < n_cand ? coherent_load(&p.hc[c[u]]) : tagged(0, epoch);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                for (int it = 0; (int)(v[u] >> 32) != epoch && it < limit; ++it) {
+                    __builtin_amdgcn_s_sleep(2);
+                    v[u] = coherent_load(&p.hc[c[u]]);
+                }
+                if ((int)(v[u] >> 32) != epoch) got_all = false;
+                if (c[u] < n_cand) {
+                    const float sc = nr[u] * fabsf(__uint_as_float((uint32_t)v[u]));
+                    if (in_lds) {
+                        sh.keys[c[u]] = score_key(sc);
+                        p.cscore[c[u]] = sc;
+                    } else {
+                        coherent_store(&p.cscore[c[u]], sc);  // read back below by other threads of this workgroup
+                    }
+                }
+            }
+        }
+        if (!got_all) p.ctr[2] = 1;
+        if (!in_lds) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         POP_STAMP(3);
-        if (s_flag) {
-            block_select_candidates<true>(
-                p.cscore, p.cand_idx, p.n_cand, p.k, p.mask, p.active_idx + p.n_ret, sh,
-                [&](int c) { atomicOr(&wg_bits[c % n_wg], 1 << (c / n_wg)); },  // candidate c is slot c / n_wg of workgroup c % n_wg
-                [&]() {  // publish the per-workgroup slot masks first: they are all the other workgroups wait for
-                    __syncthreads();
-                    for (int q = 1 + tid; q < n_wg && q < p.n_cand; q += blockDim.x)
-                        coherent_store(&p.selbits[(size_t)q * kBitsStride], wg_bits[q] | kBitsValid);
-                }
+        block_select_candidates<true>(
+            p.cscore, p.cand_idx, p.n_cand, p.k, p.mask, p.active_idx + p.n_ret, sh,
+            [&](int c) { atomicOr(&wg_bits[c % n_wg], 1 << (c / n_wg)); },  // candidate c is slot c / n_wg of workgroup c % n_wg
+            [&]() {  // publish the per-workgroup slot masks first: they are all the other workgroups wait for
+                __syncthreads();
+                for (int q = 1 + tid; q < n_wg && q < p.n_cand; q += blockDim.x)
+                    coherent_store(&p.selw[(size_t)q * kSelStride], tagged((uint32_t)wg_bits[q], epoch));
+            },
 #ifdef POP_TRACE
-                , p.trace ? p.trace + 1023 * 8 : nullptr
+            p.trace ? p.trace + 1023 * 8 : nullptr,
+#else
+            nullptr,
 #endif
-                );
-            if (tid == 0 && p.n_active) *p.n_active = p.n_ret + p.k;
-            POP_STAMP(4);
-            bits_known = true;
-            rem_d = wg_bits[0];
-            drain_selected();
-        }
+            nullptr, 1, in_lds);
+        if (tid == 0 && p.n_active) *p.n_active = p.n_ret + p.k;
+        POP_STAMP(4);
+        bits_known = true;
+        rem_d = wg_bits[0];
+        drain_selected();
         store_partial();
-        if (p.y) final_reduce();
         POP_STAMP(6);
         return;
     }
 
     // ---- selected candidates of this worker that did not ride along with the retained rounds
-    bool d_ok = true;
     if (n_aslots > 0) {
         if (!bits_known) {
             // normally the word arrived during the retained rounds; else wait (bounded)
             if (tid == 0) {
-                int v = 0;
-                for (int it = 0; v >= 0 && it < kSpinLimit; ++it) {
+                unsigned long long v = coherent_load(my_word);
+                for (int it = 0; (int)(v >> 32) != epoch && it < limit; ++it) {
+                    __builtin_amdgcn_s_sleep(2);
                     v = coherent_load(my_word);
-                    if (v >= 0) __builtin_amdgcn_s_sleep(2);
                 }
-                s_flag = v;
+                const bool here = (int)(v >> 32) == epoch;
+                if (!here) p.ctr[2] = 1;  // the step is flagged invalid; it goes on without this workgroup's selection
+                s_flag = here ? (int)(uint32_t)v : 0;
             }
             __syncthreads();
-            const int v = s_flag;
-            d_ok = v < 0;  // kBitsValid is the sign bit
-            if (d_ok) {
-                bits_known = true;
-                rem_d = v & ~kBitsValid;
-            }
+            bits_known = true;
+            rem_d = s_flag;
         }
         POP_STAMP(3);
-        if (d_ok) drain_selected();
     }
+    drain_selected();
     POP_STAMP(4);
-    store_partial();
-    if (tid == 0) {
-        p.deferred[b] = d_ok ? 0 : 1;
-        if (d_ok) {
-            if (n_aslots > 0) coherent_store(my_word, 0);  // rearmed for the next launch
-        } else {
-            p.sync[2] = 1;
-            coherent_store(&p.sync[3], 1);
-        }
-    }
     __syncthreads();
     for (int e = tid; e < n_st * kRB; e += blockDim.x)
         if (j_st[e] >= 0) p.h[j_st[e]] = h_st[e];
-    if (p.y) final_reduce();
+    store_partial();
     POP_STAMP(6);
 }
 
-// y[o] = sum over workgroups (in order) of partial[b][o], plus shares a workgroup deferred.  A workgroup owns 64
-// outputs; its 16 waves each sum a contiguous sixteenth of the partial rows (independent loads, fixed order)
-// and wave 0 combines them in wave order, so y does not depend on scheduling.
+// y[o] = sum over workgroups (in order) of partial[b][o].  A workgroup owns 64 outputs; its 16 waves each sum a
+// contiguous sixteenth of the partial rows (independent loads, fixed order) and wave 0 combines them in wave order,
+// so y does not depend on scheduling.
 constexpr int kTailWaves = 16;
 __global__ __launch_bounds__(1024) void decode_tail_kernel(const float *__restrict__ partial, int n_wg, int d,
-                                                           const int *__restrict__ deferred, const int *sync,
-                                                           const int *__restrict__ selbits,
-                                                           const int *__restrict__ cand_idx, int n_cand,
-                                                           const float *__restrict__ h, const void *__restrict__ w,
-                                                           int m, int is_bf16, void *__restrict__ y, int y_bf16)
+                                                           void *__restrict__ y, int y_bf16)
 {
     __shared__ float part[kTailWaves][kWave];
     const int lane = threadIdx.x % kWave, q = threadIdx.x / kWave;
@@ -715,24 +636,6 @@ __global__ __launch_bounds__(1024) void decode_tail_kernel(const float *__restri
         float v = 0.f;
 #pragma unroll
         for (int u = 0; u < kTailWaves; ++u) v += part[u][lane];
-        const bool any_deferred = sync[3] != 0;  // set only when some workgroup gave up waiting in this step
-        for (int b = 1; any_deferred && b < n_wg; ++b) {
-            if (!deferred[b]) continue;
-            // the workgroup's deferred share: its own candidate slots that the selection kept
-            const int bits = selbits[(size_t)b * kBitsStride];
-            if (bits >= 0) continue;  // the selection never ran: the step is flagged invalid
-            for (int e = 0; e < kMaxASlots; ++e) {
-                if (!((bits >> e) & 1)) continue;
-                const int c = e * n_wg + b;
-                if (c >= n_cand) continue;
-                const int j = cand_idx[c];
-                if (j < 0 || j >= m) continue;
-                const size_t idx = ((size_t)j * 3 + 2) * d + o;
-                const float wv = is_bf16 ? __uint_as_float(((uint32_t)((const uint16_t *)w)[idx]) << 16)
-                                         : ((const float *)w)[idx];
-                v = fmaf(h[j], wv, v);
-            }
-        }
         if (y_bf16)
             ((uint16_t *)y)[o] = f32_to_bf16(v);
         else
@@ -790,17 +693,7 @@ struct FusedLaunchFn {
 };
 
 int fused_max_workgroups() { return 1024; }
-int fused_selbits_ints() { return 1024 * kBitsStride; }
-
-// The words of the selection-word buffer that the kernels use (the selection word and the "go" word of every
-// workgroup slot), not the padding that keeps them in separate cache lines.
-StridedClear fused_selbits_clear(int *selbits)
-{
-    static_assert(kGoWord < 128, "both words of a slot lie in its first 128 ints");
-    StridedClear c;
-    c.p = selbits, c.n = 1024, c.stride = kBitsStride, c.words = 128;
-    return c;
-}
+size_t fused_selw_words() { return (size_t)1024 * kSelStride; }
 
 // Chooses the launch shape; false when the fused kernel does not support this shape.
 bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl)
@@ -841,12 +734,10 @@ hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p,
     return fused_dispatch(is_bf16, pl.per, pl.block, FusedLaunchFn{pl, p, s});
 }
 
-hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync,
-                              const int *selbits, const int *cand_idx, int n_cand, const float *h, const void *w,
-                              int m, int is_bf16, void *y, int y_bf16, hipStream_t s)
+hipError_t launch_decode_tail(const float *partial, int n_wg, int d, void *y, int y_bf16, hipStream_t s)
 {
-    hipLaunchKernelGGL(decode_tail_kernel, dim3((d + kWave - 1) / kWave), dim3(kTailWaves * kWave), 0, s, partial, n_wg, d, deferred,
-                       sync, selbits, cand_idx, n_cand, h, w, m, is_bf16, y, y_bf16);
+    hipLaunchKernelGGL(decode_tail_kernel, dim3((d + kWave - 1) / kWave), dim3(kTailWaves * kWave), 0, s, partial, n_wg, d,
+                       y, y_bf16);
     return hipGetLastError();
 }
 

@@ -197,24 +197,20 @@ struct FusedParams {
     const int *cand_idx;
     int n_cand, k;
     const float *nrm;
-    float *h;                // [m]
-    float *cscore;           // [n_cand]
-    unsigned char *mask;     // [m]
-    int *active_idx;         // [>= n_ret + k]
-    int *n_active;           // [1]
-    float *partial;          // [n_wg][d]
-    int *sync;               // [0] arrivals of candidate results, [2] sticky error flag, [3] some workgroup deferred
-                             // its share in this step, [6] end-of-step arrivals (single-launch step only),
-                             // [8] arrivals of the batched top-k.  All counters are back at zero when a kernel ends.
-    int n_static;            // retained rounds per worker
-    int *selbits;            // [n_wg] per-workgroup selection word (valid bit + selected candidate slots);
-                             // each workgroup clears its own word after use, so a launch can be replayed
+    float *h;                   // [m]
+    float *cscore;              // [n_cand]
+    unsigned char *mask;        // [m]
+    int *active_idx;            // [>= n_ret + k]
+    int *n_active;              // [1]
+    // what the workgroups hand to each other: 64-bit words {value, epoch}
+    unsigned long long *hc;     // [n_cand] a candidate's h, by candidate position
+    unsigned long long *selw;   // [n_wg] per-workgroup selection word (selected candidate slots), 128 bytes apart
+    float *partial;             // [n_wg][d] partial output rows (summed by decode_tail_kernel)
+    int *ctr;                   // [0] epoch (>= 1), [1] workgroups that finished (back at zero when the kernel ends),
+                                // [2] sticky error flag: a bounded wait gave up
+    int spin_limit;             // looks a bounded wait takes before it gives up
+    int n_static;               // retained rounds per worker
     unsigned long long *trace;  // profiling builds only: 8 timestamps per workgroup, else null
-    int *deferred;           // [n_wg]
-    // single-launch step: when y is non-null the kernel also sums the partial rows itself, behind a grid-wide
-    // arrival counter (sync[6], back at zero when the kernel ends)
-    void *y;                 // [d] float32 or bf16, or null: the partial rows are summed by decode_tail_kernel
-    int y_bf16;
 };
 
 struct FusedPlan {
@@ -222,17 +218,13 @@ struct FusedPlan {
     int n_static;  // retained rounds per worker
 };
 int fused_max_workgroups();
-int fused_selbits_ints();  // size of the selection-word buffer (one word per workgroup, spaced apart)
-// The words of that buffer that are in use (the rest is padding between cache lines), as a clearing job.
-StridedClear fused_selbits_clear(int *selbits);
+size_t fused_selw_words();  // 64-bit words of the selection-word buffer (one per workgroup, spaced apart)
 // Launch shape for (d, dtype, region sizes); false when the fused kernel does not support the shape.
 bool fused_plan(int d, int is_bf16, int n_ret, int n_cand, int wg_target, FusedPlan *pl);
 // Largest grid of this shape that is co-resident on n_cu compute units.
 hipError_t fused_resident_limit(int is_bf16, const FusedPlan &pl, int n_cu, int *max_wg);
 hipError_t launch_decode_fused(const FusedPlan &pl, int is_bf16, FusedParams &p, hipStream_t s);
-hipError_t launch_decode_tail(const float *partial, int n_wg, int d, const int *deferred, const int *sync,
-                              const int *selbits, const int *cand_idx, int n_cand, const float *h, const void *w,
-                              int m, int is_bf16, void *y, int y_bf16, hipStream_t s);
+hipError_t launch_decode_tail(const float *partial, int n_wg, int d, void *y, int y_bf16, hipStream_t s);
 hipError_t launch_fill_int(int *p, int n, int value, hipStream_t s);
 
 // ---- measurement aids (pop_probe.hip): bare reads, nothing of the method ----

@@ -355,15 +355,17 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
                                                         AfterSelected after_selected = AfterSelected(),
                                                         unsigned long long *tr = nullptr,
                                                         unsigned char *__restrict__ selpos = nullptr,
-                                                        int selpos_stride = 1)
+                                                        int selpos_stride = 1, bool keys_ready = false)
 {
 #define SEL_STAMP(k) do { if (tr && threadIdx.x == 0) tr[k] = wall_clock64(); } while (0)
     SEL_STAMP(0);
     auto score = [&](int i) -> float {
         return kCoherentScores ? __hip_atomic_load(&cs[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : cs[i];
     };
+    // keys_ready: the caller has put score_key(score) of every candidate into sh.keys (n_cand <= kSelLdsKeys) and
+    // synchronised the block
     const bool in_lds = n_cand <= kSelLdsKeys;
-    if (in_lds) {
+    if (in_lds && !keys_ready) {
         // eight independent loads in flight per thread: under a streaming load a trip to memory takes microseconds
         for (int base = 0; base < n_cand; base += 8 * blockDim.x) {
             float v[8];

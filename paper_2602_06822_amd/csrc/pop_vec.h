@@ -88,6 +88,26 @@ __device__ __forceinline__ double wave_total(double v)
     return (lane_value(r, 0) + lane_value(r, 16)) + (lane_value(r, 32) + lane_value(r, 48));
 }
 
+// Four values per lane -> in every lane the sum over its row of 16 lanes of ONE of them: value id
+// butterfly_value_id(lane).  Halving exchanges (each level sends half of what is left): 7 cross-lane moves of a
+// double instead of 16, so that summing in double costs no more than the plain float32 row sums it replaces.
+__device__ __forceinline__ double butterfly4_row_sum(const double (&v)[4], int lane)
+{
+    const bool o1 = lane & 1, o2 = lane & 2;
+    double w[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const double send = o1 ? v[j] : v[j + 2], keep = o1 ? v[j + 2] : v[j];
+        w[j] = keep + dpp_move<0xB1>(send);  // partner lane ^ 1
+    }
+    const double send = o2 ? w[0] : w[1], keep = o2 ? w[1] : w[0];
+    double z = keep + dpp_move<0x4E>(send);  // partner lane ^ 2
+    z += dpp_move<0x124>(z);                 // row_ror:4
+    z += dpp_move<0x128>(z);                 // row_ror:8
+    return z;
+}
+__device__ __forceinline__ int butterfly_value_id(int lane) { return ((lane & 1) << 1) | ((lane >> 1) & 1); }
+
 // Dot products of one channel's gate and up rows with x (staged in LDS as vectors), lanes striding the row.
 // Returns per-lane partial sums; the caller reduces across the wave.
 template <class V, int U>

@@ -81,8 +81,7 @@ class GpuLayer:
 
     def decode(self, x_t: np.ndarray, k, ydtype=None, one_call=False):
         """x_t: [B][d] storage.  Returns dict of host arrays (cscore, mask, active_idx, n_active, h, y).
-        one_call: use pop_decode_step instead of pop_decode_mask + pop_pruned_ffn (True: its default form;
-        "single_launch": its single-launch form)."""
+        one_call: use pop_decode_step instead of pop_decode_mask + pop_pruned_ffn."""
         B = x_t.shape[0]
         ks = [k] * B if isinstance(k, int) else list(k)
         n_ret, n_cand, m, d = self.n_ret, self.n_cand, self.m, self.d
@@ -93,7 +92,6 @@ class GpuLayer:
         ydtype = self.dtype if ydtype is None else ydtype
         y = torch.full((B, d), 12345, dtype=torch.float32 if ydtype == synth.F32 else torch.int16, device="cuda")
         if one_call:
-            self.pop.pop_layer_set_single_launch(self.handle, one_call == "single_launch")
             self.pop.pop_decode_step(self.handle, dev(x_t), B, ks, y, ydtype, cs if n_cand else None, mask,
                                      act if n_ret + n_cand else None, na)
         else:
