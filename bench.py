@@ -124,7 +124,7 @@ def run(args):
             for li in range(len(layers)):
                 a_mask, a_ffn, a_step = decode[li][t]
                 if single:
-                    # the whole step as one kernel launch (pop_decode_step in its single-launch form)
+                    # the whole step in one call (pop_decode_step: the same launches as the two calls)
                     check(lib.pop_decode_step(*a_step))
                 elif probe is not None and (t * len(layers) + li) % probe["every"] == 0:
                     e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
@@ -212,11 +212,9 @@ def run(args):
         layers = layers[:1]
         warm = timed(r_main, max(1, args.steps // 2), 1)["decode_us_per_token"]
         layers = keep
-    # the same step as a single kernel launch that also sums the partial outputs, for comparison
+    # the same step through the one-call entry point (pop_decode_step), for comparison
     single = None
     if not args.quick:
-        for L in layers:
-            pop.pop_layer_set_single_launch(L.handle, True)
         single = timed(r_main, max(1, args.steps // 2), 1, single=True)["decode_us_per_token"]
 
     # the prefilling stage with its output (pop_prefill_forward: contraction that keeps H, partition, prefill mask,
@@ -245,7 +243,7 @@ def run(args):
         del yp
 
     # configs[2]: a 32-layer stack of this layer shape, one token through all layers (each layer its own weights,
-    # partition and input), as eager calls and as one captured HIP graph of 32 single-launch steps
+    # partition and input), as eager calls and as one captured HIP graph of the 32 steps
     stack = None
     if not args.quick:
         stack = time_layer_stack(pop, synth, lib, layers, counts(r_main), 32)
@@ -303,8 +301,6 @@ def run(args):
         del bufs
         return out
 
-    for L in layers:
-        pop.pop_layer_set_single_launch(L.handle, False)
     fused_us = kernel_only("mask")
     tail_us = kernel_only("ffn")
     reads = read_legs()
@@ -416,7 +412,7 @@ def run(args):
         "frac_of_peak_active_bytes": round(bm["active"] / us / 1e3 / HBM_PEAK_GBS, 4),
         "warm_us_per_token": None if warm is None else round(warm, 3),
         "other_sparsities": extra,
-        "single_launch_step_us_per_token": None if single is None else round(single, 3),
+        "one_call_step_us_per_token": None if single is None else round(single, 3),
         "ablation_r0.35": ablation,
         "other_shapes": other_configs,
         "roofline": roofline,
@@ -428,7 +424,7 @@ def run(args):
 def time_layer_stack(pop, synth, lib, bench_layers, cnt, n_layers):
     """One decode token through n_layers independent layers of the benchmark shape (device copies of the bench
     layers' weights, each with its own partition and its own inputs): per-token time of the eager call sequence
-    (two launches per layer), of the single-launch steps, and of one captured graph of the single-launch steps."""
+    (two calls per layer), of the one-call steps, and of one captured graph of the one-call steps."""
     n_ret, n_cand, k = cnt
     cfg = bench_layers[0].host_layer.cfg
     d = cfg.d
@@ -472,10 +468,8 @@ def time_layer_stack(pop, synth, lib, bench_layers, cnt, n_layers):
 
     with torch.cuda.stream(side):
         sp = C.c_void_p(side.cuda_stream)
-        out["eager_two_launch_us_per_token"] = round(timeit(lambda: token(sp, False)), 1)
-        for h in hs:
-            pop.pop_layer_set_single_launch(h, True)
-        out["eager_single_launch_us_per_token"] = round(timeit(lambda: token(sp, True)), 1)
+        out["eager_two_calls_us_per_token"] = round(timeit(lambda: token(sp, False)), 1)
+        out["eager_one_call_us_per_token"] = round(timeit(lambda: token(sp, True)), 1)
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=side):
             token(C.c_void_p(torch.cuda.current_stream().cuda_stream), True)

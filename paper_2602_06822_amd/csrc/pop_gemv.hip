@@ -28,31 +28,34 @@ __device__ __forceinline__ void gateup_row(const typename V::vec_t *__restrict__
                                            int n_score)
 {
     typedef typename V::vec_t vec_t;
-    const int group = kWave * kGuUnroll;
+    // (many sequences: fewer row vectors in flight per lane, so that the sequences' accumulators stay in registers)
+    constexpr int U = B >= 5 ? kGuUnroll / 2 : kGuUnroll;
+    const int group = kWave * U;
     const int nvec_full = nvec / group * group;
     const vec_t *g = w + (size_t)j * 3 * nvec;
     const vec_t *u = g + nvec;
-    // a 16-byte vector's products are summed in the row's accumulator type (float32 for bf16 rows: eight exact
-    // products), the vectors of a lane and then the lanes in double: a long float32 chain would round every add at the
-    // magnitude of the largest product met so far
+    // Two 16-byte vectors' products (sixteen exact products for bf16 rows) are summed in the row's accumulator type,
+    // the pairs of a lane and then the lanes in double: a long float32 chain would round every add at the magnitude
+    // of the largest product met so far, and so would a float32 tree over the lanes.
+    static_assert(U % 2 == 0, "vectors are taken in pairs");
     double ag[B], au[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) ag[b] = au[b] = 0.0;
 
     for (int c0 = 0; c0 < nvec_full; c0 += group) {
-        vec_t wg[kGuUnroll], wu[kGuUnroll];
+        vec_t wg[U], wu[U];
 #pragma unroll
-        for (int q = 0; q < kGuUnroll; ++q) {
+        for (int q = 0; q < U; ++q) {
             wg[q] = g[c0 + q * kWave + lane];
             wu[q] = u[c0 + q * kWave + lane];
         }
 #pragma unroll
-        for (int q = 0; q < kGuUnroll; ++q) {
+        for (int q = 0; q < U; q += 2) {
 #pragma unroll
             for (int b = 0; b < B; ++b) {
-                vec_t xv = xs[b * nvec + c0 + q * kWave + lane];
-                ag[b] += (double)V::dot(wg[q], xv, (typename V::acc_t)0);
-                au[b] += (double)V::dot(wu[q], xv, (typename V::acc_t)0);
+                const vec_t x0 = xs[b * nvec + c0 + q * kWave + lane], x1 = xs[b * nvec + c0 + (q + 1) * kWave + lane];
+                ag[b] += (double)V::dot(wg[q + 1], x1, V::dot(wg[q], x0, (typename V::acc_t)0));
+                au[b] += (double)V::dot(wu[q + 1], x1, V::dot(wu[q], x0, (typename V::acc_t)0));
             }
         }
     }
@@ -65,11 +68,19 @@ __device__ __forceinline__ void gateup_row(const typename V::vec_t *__restrict__
             au[b] += (double)V::dot(wu, xv, (typename V::acc_t)0);
         }
     }
+    // Lanes: four values at a time (gate and up sums of two sequences) through halving exchanges inside the rows of
+    // 16 lanes, then across the four rows; lanes 0 and 1 end up with the gate sums of the two sequences and fetch
+    // the matching up sums from lanes 2 and 3.
 #pragma unroll
-    for (int b = 0; b < B; ++b) {
-        float gs = (float)wave_total(ag[b]), us = (float)wave_total(au[b]);
-        if (lane == 0) {
-            float hv = silu_mul(gs, us);
+    for (int b0 = 0; b0 < B; b0 += 2) {
+        const double v4[4] = {ag[b0], au[b0], b0 + 1 < B ? ag[b0 + 1] : 0.0, b0 + 1 < B ? au[b0 + 1] : 0.0};
+        double z = butterfly4_row_sum(v4, lane);
+        z += __shfl_xor(z, 16, kWave);
+        z += __shfl_xor(z, 32, kWave);
+        const double zu = dpp_move<0x4E>(z);  // quad_perm 2,3,0,1
+        const int b = b0 + lane;
+        if (lane < 2 && b < B) {
+            const float hv = silu_mul((float)z, (float)zu);
             h[(size_t)b * m + j] = hv;
             if (p < n_score) {
                 const float sc = nrm[j] * fabsf(hv);
