@@ -91,6 +91,13 @@ def run(args):
         n_ret, n_cand, _ = pop.pop_region_counts(m, f_ret, f_cand)
         return n_ret, n_cand, pop.pop_k_for_ratio(m, r, n_ret, n_cand)
 
+    if args.stack_only:
+        # only the 32-layer stack (for a kernel trace of the eager call sequences against the captured graph)
+        print(json.dumps({"stack_of_32_layers": time_layer_stack(pop, synth, lib, layers, counts(0.35), 32)}))
+        for L in layers:
+            L.close()
+        return
+
     def make_calls(r):
         n_ret, n_cand, k = r if isinstance(r, tuple) else counts(r)  # explicit region sizes, or a sparsity
         karr = (C.c_int * 1)(k)
@@ -612,6 +619,8 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 256 MiB device copies")
     ap.add_argument("--other-shapes-only", action="store_true",
                     help="run only the 13B-shaped (B = 1, 4, 8) and Mixtral-expert timings")
+    ap.add_argument("--stack-only", action="store_true",
+                    help="run only the 32-layer stack: eager two-call steps, eager one-call steps, captured graph")
     ap.add_argument("--forward", action="store_true", help="with --quick: keep the prefill-forward section")
     ap.add_argument("--quick", action="store_true", help="main line only: skip other sparsities and the warm figure")
     args = ap.parse_args()

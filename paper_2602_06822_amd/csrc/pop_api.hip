@@ -55,6 +55,7 @@ struct pop_layer {
     int n_ret = 0, n_cand = 0;
     float *scores = nullptr;           // [m]
     float *s2_part = nullptr;          // [tiles][m]
+    int *pf_ctr = nullptr;             // [m] arrival counters of the prefill kernel's channel chunks (zero at rest)
     int tiles_cap = 0;
     unsigned char *region = nullptr;   // [m]
     int *ret_idx = nullptr;            // [m]
@@ -358,7 +359,7 @@ int pop_layer_destroy(pop_layer_t *L)
     if (!L) return POP_EINVAL;
     void *ptrs[] = {L->w,      L->nrm, L->scores, L->s2_part, L->region,     L->ret_idx,  L->cand_idx, L->rc_idx,
                     L->h,      L->cscore, L->mask, L->selflag, L->active_idx, L->n_active, L->ulist, L->n_ulist,  L->partial,
-                    L->sync,   L->hc, L->selw, L->fctr, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part, L->top_list, L->zero_row};
+                    L->sync,   L->hc, L->selw, L->fctr, L->pf_ctr, L->ffn_hc, L->ffn_part, L->ffn_any, L->ffn_hall, L->in_s2, L->in_part, L->top_list, L->zero_row};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     delete L;
@@ -429,6 +430,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
         {(void **)&L->hc, mm * 8},
         {(void **)&L->selw, fused_selw_words() * 8},
         {(void **)&L->fctr, 64},
+        {(void **)&L->pf_ctr, mm * 4},
     };
     for (const Req &r : reqs) {
         hipError_t e = hipMalloc(r.p, r.bytes);
@@ -446,6 +448,7 @@ int pop_layer_create(pop_layer_t **out, int d, int m, pop_dtype_t wdtype, const 
     if (e == hipSuccess) e = hipMemsetAsync(L->hc, 0, mm * 8, s);
     if (e == hipSuccess) e = hipMemsetAsync(L->selw, 0, fused_selw_words() * 8, s);
     if (e == hipSuccess) e = launch_fill_int(L->fctr, 16, 0, s);
+    if (e == hipSuccess) e = launch_fill_int(L->pf_ctr, m, 0, s);
     if (e == hipSuccess) e = launch_fill_int(L->fctr, 1, 1, s);
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) {
@@ -474,9 +477,11 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
         POP_HIP(launch_input_norms(x, L->is_bf16, T, L->d, L->in_part, L->in_s2, s));
         POP_HIP(launch_input_side_scores(L->w, L->is_bf16, L->d, L->in_s2, 1, nullptr, m, L->scores, m, s));
     } else {
-        POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s));
+        const PrefillScores fin{L->pf_ctr, L->nrm, L->scores};
+        POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s, &fin));
     }
-    return finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, T == 0 || L->input_side);
+    return finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s,
+                            T == 0 || L->input_side || prefill_forms_scores(L->is_bf16));
 }
 
 int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_cand, int k0, void *y, pop_dtype_t ydtype,
@@ -500,7 +505,8 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     if (keep) {
         int rc = ffn_scratch(L, T, true, &ldh, &n_split, s);
         if (rc != POP_OK) return rc;
-        POP_HIP(launch_prefill_gateup_keep_bf16(L->w, d, m, x, T, L->s2_part, L->ffn_hall, ldh, L->n_cu, s));
+        const PrefillScores fin{L->pf_ctr, L->nrm, L->scores};
+        POP_HIP(launch_prefill_gateup_keep_bf16(L->w, d, m, x, T, L->s2_part, L->ffn_hall, ldh, L->n_cu, s, &fin));
     } else {
         if (!L->ffn_any && !dev_alloc((void **)&L->ffn_any, ((size_t)m + 3) / 4 * 4)) return POP_ENOMEM;
         if (T == 0) {
@@ -509,7 +515,8 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
             POP_HIP(launch_input_norms(x, L->is_bf16, T, d, L->in_part, L->in_s2, s));
             POP_HIP(launch_input_side_scores(L->w, L->is_bf16, d, L->in_s2, 1, nullptr, m, L->scores, m, s));
         } else {
-            POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, d, m, x, T, L->s2_part, L->n_cu, s));
+            const PrefillScores fin{L->pf_ctr, L->nrm, L->scores};
+            POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, d, m, x, T, L->s2_part, L->n_cu, s, &fin));
         }
     }
     // prefill mask: retained channels plus the best k0 candidates by prefill score, i.e. the n_ret + k0 best channels
@@ -523,8 +530,8 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
         gather.n_list = L->top_list + m, gather.hc = L->ffn_hc, gather.ldhc = ldh;
     }
     {
-        int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s, T == 0 || L->input_side,
-                                  n_ret + k0, mask || !keep, keep ? &gather : nullptr);
+        int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s,
+                                  T == 0 || L->input_side || prefill_forms_scores(L->is_bf16), n_ret + k0, mask || !keep, keep ? &gather : nullptr);
         if (rc != POP_OK) return rc;
     }
     unsigned char *pm = L->ffn_any;

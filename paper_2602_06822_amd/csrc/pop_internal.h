@@ -62,6 +62,10 @@ __device__ __forceinline__ void coherent_store(unsigned char *p, unsigned char v
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ __forceinline__ float coherent_load(const float *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ __forceinline__ unsigned long long coherent_load(const unsigned long long *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -237,8 +241,17 @@ hipError_t launch_probe_step_read(const void *w, int nvec, const int *gu_list, i
 // s2_part[tile][j] = sum over the tile's tokens of H[t][j]^2, one row per token tile.
 int prefill_num_tiles(int T, int is_bf16);  // upper bound on the rows used, for sizing s2_part
 int prefill_rows_used(int T, int is_bf16, int m, int n_cu);  // rows the launch below writes for this T
+// With `fin`, bf16 layers (prefill_forms_scores) also leave scores[j] = nrm[j] * sqrt(sum over the token tiles, in tile
+// order and in double, of s2_part[tile][j]) (Eq. 3): the token tile of a channel chunk that finishes last does the sum.
+// chunk_ctr: one int per channel chunk (m of them suffice), zero before the launch and zero again after it.
+struct PrefillScores {
+    int *chunk_ctr;
+    const float *nrm;
+    float *scores;
+};
+bool prefill_forms_scores(int is_bf16);
 hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
-                                 int n_cu, hipStream_t s);
+                                 int n_cu, hipStream_t s, const PrefillScores *fin = nullptr);
 // bf16 layers: gate/up over the channels of a device-resident list (n_list: its length, on the device);
 // hc[t][c] = bf16(H[t][list[c]]), times tmask[t][list[c]] if tmask ([T][m]) is given.  ldh % 8 == 0.
 hipError_t launch_gateup_list_bf16(const void *w, int d, int m, const void *x, int T, const int *list, const int *n_list,
@@ -254,7 +267,8 @@ hipError_t launch_down_gemm_bf16(const void *w, int d, const int *list, const in
 // bf16 layers: the prefill contraction (s2_part as in launch_prefill_gateup) that also keeps H:
 // h_all[t][j] = bf16(H[t][j]), row stride ldh.
 hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const void *x, int T, float *s2_part,
-                                           uint16_t *h_all, int ldh, int n_cu, hipStream_t s);
+                                           uint16_t *h_all, int ldh, int n_cu, hipStream_t s,
+                                           const PrefillScores *fin = nullptr);
 // ---- input-side importance (pop_input_side.hip) ----
 int input_side_groups(int T);  // row groups of a T-token prompt (sizes part below: [groups][d] doubles)
 // s2[k] = sum_t x[t][k]^2 over the T rows (fixed summation order)

@@ -115,6 +115,11 @@ struct PfStore {
     int ldh;
     const unsigned char *tmask; // per-token masks [T][m], or null
     int n_cu;
+    // scores formed in the same launch (modes 0 and 2; null = leave that to the caller): the token tile of a
+    // channel chunk that finishes last sums the chunk's partial rows
+    int *fin_ctr = nullptr;     // one arrival counter per channel chunk; zero between launches
+    const float *nrm = nullptr; // [m]
+    float *scores = nullptr;    // [m]
 };
 
 // kMode 0: scores only (s2_part).  1: channels from st.list, H stored compact (no s2_part).  2: all m channels,
@@ -294,7 +299,9 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
     // epilogue: lane holds 16 * MT token rows of column (lane % 32) of each fragment.  Register-staged path: rows of
     // padded tokens and columns of padded channels are exactly 0.  Direct path: they hold products of the rows their
     // loads were pointed at; padded tokens are left out of the sums below, padded channels are never written.
-    if (kStore) {
+    // H of the tile (modes 1 and 2), written after the partial sums have gone out: the tile's arrival is counted once
+    // its partial row is acknowledged, and that wait should not take in the much larger H.
+    auto store_h = [&]() {
         // register v of a fragment is token row (v / 4) * 8 + (lane / 32) * 4 + v % 4, column lane % 32
         const int col = lane % 32;
         const int c01 = wn * WC + col, c2 = wn * WC + 32 + col;
@@ -325,7 +332,10 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
                     }
                 }
             }
-        if (kList) return;
+    };
+    if (kList) {
+        store_h();
+        return;
     }
     float ss01 = 0.f, ss2 = 0.f;
     const int t_left = T - (t0 + wm * (BM / TW) + (lane / 32) * 4);  // this lane's rows below t_left are tokens
@@ -353,8 +363,32 @@ __global__ __launch_bounds__(NW * 64) void prefill_bf16_kernel(const uint16_t *_
         float tot = 0.f;
 #pragma unroll
         for (int q = 0; q < TW; ++q) tot += colsum[q][tid];
-        s2_part[(size_t)ttile * m + c0 + tid] = tot;
+        if (st.fin_ctr)
+            coherent_store(&s2_part[(size_t)ttile * m + c0 + tid], tot);
+        else
+            s2_part[(size_t)ttile * m + c0 + tid] = tot;
     }
+    if (st.fin_ctr) {
+        // Scores of this chunk's channels (Eq. 3): I_j = n_j * sqrt(sum over the token tiles, in tile order and in
+        // double, of the partial sums).  The partial rows are written through and read with device-coherent loads;
+        // a tile counts itself in once its own row has been acknowledged, and the tile that completes the count does
+        // the sum and puts the counter back to zero for the next launch.  Nobody waits for anybody.
+        __shared__ int fin_last;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            const bool last = atomicAdd(&st.fin_ctr[ctile], 1) == n_ttiles - 1;
+            if (last) coherent_store(&st.fin_ctr[ctile], 0);
+            fin_last = last;
+        }
+        __syncthreads();
+        if (fin_last && tid < cn) {
+            double acc = 0.0;
+            for (int t = 0; t < n_ttiles; ++t) acc += (double)coherent_load(&s2_part[(size_t)t * m + c0 + tid]);
+            st.scores[c0 + tid] = (float)((double)st.nrm[c0 + tid] * sqrt(acc));
+        }
+    }
+    if (kStore) store_h();
 }
 
 // float32: 64 tokens x 32 channels per workgroup; thread (tx = channel, ty = group of 8 tokens).
@@ -484,16 +518,23 @@ static hipError_t launch_pf_bf16_all(const void *w, int d, int m, const void *x,
 
 // bf16 only: the prefill contraction that also keeps H, h_all[t][j] = bf16(H[t][j]) with row stride ldh.
 hipError_t launch_prefill_gateup_keep_bf16(const void *w, int d, int m, const void *x, int T, float *s2_part,
-                                           uint16_t *h_all, int ldh, int n_cu, hipStream_t s)
+                                           uint16_t *h_all, int ldh, int n_cu, hipStream_t s, const PrefillScores *fin)
 {
     PfStore st{nullptr, nullptr, h_all, ldh, nullptr, n_cu};
+    if (fin) st.fin_ctr = fin->chunk_ctr, st.nrm = fin->nrm, st.scores = fin->scores;
     return launch_pf_bf16_all<2>(w, d, m, x, T, s2_part, n_cu, st, s);
 }
 
+bool prefill_forms_scores(int is_bf16) { return is_bf16 != 0; }
+
 hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
-                                 int n_cu, hipStream_t s)
+                                 int n_cu, hipStream_t s, const PrefillScores *fin)
 {
-    if (is_bf16) return launch_pf_bf16_all<0>(w, d, m, x, T, s2_part, n_cu, PfStore{}, s);
+    if (is_bf16) {
+        PfStore st{};
+        if (fin) st.fin_ctr = fin->chunk_ctr, st.nrm = fin->nrm, st.scores = fin->scores;
+        return launch_pf_bf16_all<0>(w, d, m, x, T, s2_part, n_cu, st, s);
+    }
     dim3 grid((m + kPf32BC - 1) / kPf32BC, (T + kPf32BM - 1) / kPf32BM);
     hipLaunchKernelGGL(prefill_f32_kernel, grid, dim3(256), 0, s, (const float *)w, (const float *)x, T, d, m, s2_part);
     return hipGetLastError();

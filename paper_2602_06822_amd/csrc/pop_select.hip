@@ -111,15 +111,16 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
             }
         }
     } else if (in_lds) {
-        for (int base = 0; base < m; base += 8 * blockDim.x) {
-            float v[8];
+        constexpr int kLoads = 12;  // scores requested together per thread (11008 channels: one pass)
+        for (int base = 0; base < m; base += kLoads * blockDim.x) {
+            float v[kLoads];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kLoads; ++u) {
                 const int i = base + u * blockDim.x + threadIdx.x;
                 v[u] = scores[i < m ? i : 0];
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kLoads; ++u) {
                 const int i = base + u * blockDim.x + threadIdx.x;
                 if (i < m) {
                     const uint32_t k = score_key(v[u]);
