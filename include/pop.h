@@ -220,10 +220,11 @@ int pop_layer_set_wait_limit(pop_layer_t *layer, int looks);
  *   POP_IMPORTANCE_INPUT_SIDE             Eq. 1-2 literally on the first projections and the FFN input:
  *       I_j = || [W_gate[j,:], W_up[j,:]] * s ||_2,  s_k = sqrt(sum over tokens of x[t][k]^2)  (a channel is removed
  *       from both matrices, so its weights are both rows); at a decode step s_k = |x_k|, per sequence.  Prefill
- *       then needs no contraction (one pass over the gate and up rows), and a decode step selects first and runs
- *       the forward pass over retained and selected channels only: h of an unselected candidate is not computed,
- *       and pop_layer_get_hidden is defined on active channels only.  The step runs as separate launches (no fused
- *       kernel); the shared batch mask is not available (POP_EUNSUPPORTED).
+ *       then needs no contraction (one pass over the gate and up rows).  A single-sequence decode step runs in the
+ *       fused kernel, which forms a candidate's score from the same two rows it reads for h; a step with B > 1
+ *       selects first and runs the forward pass over retained and selected channels only, as separate launches: h
+ *       of an unselected candidate is then not computed, so pop_layer_get_hidden is defined on active channels
+ *       only under this reading.  The shared batch mask is not available (POP_EUNSUPPORTED).
  * Changing the reading discards the layer's partition (prefill again).  Errors: unknown value -> POP_EINVAL. */
 enum { POP_IMPORTANCE_OUTPUT_SIDE = 0, POP_IMPORTANCE_INPUT_SIDE = 1 };
 int pop_layer_set_importance(pop_layer_t *layer, int reading);

@@ -239,7 +239,6 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
     L->n_ret = n_ret;
     L->n_cand = n_cand;
     { int rc = plan_fused_step(L); if (rc != POP_OK) return rc; }
-    if (L->input_side) L->fused_ok = false;  // the fused kernel scores candidates from h
     if (scores) POP_HIP(hipMemcpyAsync(scores, L->scores, (size_t)m * 4, hipMemcpyDeviceToDevice, s));
     if (region) POP_HIP(hipMemcpyAsync(region, L->region, (size_t)m, hipMemcpyDeviceToDevice, s));
     if (ret_idx && n_ret) POP_HIP(hipMemcpyAsync(ret_idx, L->ret_idx, (size_t)n_ret * 4, hipMemcpyDeviceToDevice, s));
@@ -274,6 +273,7 @@ FusedParams fused_params(pop_layer *L, const void *x_t, int k)
     p.partial = L->partial;
     p.ctr = L->fctr;
     p.spin_limit = L->spin_limit;
+    p.input_side = L->input_side ? 1 : 0;
 #ifdef POP_TRACE
     p.trace = g_trace;
 #endif
@@ -571,8 +571,9 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
             L->ulist_prefix_ok = true;
         }
         if (L->input_side) {
-            // candidates are scored from their gate and up rows and |x_t| alone, so the selection comes first and
-            // the forward pass runs over retained and selected channels only
+            // (a single sequence on a shape the fused kernel takes went there: it scores the candidates from the same
+            // rows it reads for h.)  Here candidates are scored from their gate and up rows and |x_t| alone, so the
+            // selection comes first and the forward pass runs over retained and selected channels only
             if (B > 1 && L->shared_mask) return POP_EUNSUPPORTED;
             POP_HIP(launch_input_squares(x_t, L->is_bf16, B, L->d, L->in_s2, s));
             POP_HIP(launch_input_side_scores(L->w, L->is_bf16, L->d, L->in_s2, B, L->cand_idx, n_cand, L->cscore, m, s));

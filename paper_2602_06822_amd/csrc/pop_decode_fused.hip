@@ -169,6 +169,31 @@ __device__ __forceinline__ void coherent_store(unsigned long long *p, unsigned l
 {
     __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// sum over the vector's elements of (g_e^2 + u_e^2) * x_e^2, added to acc: a candidate's importance under the
+// input-side reading of Eq. 1-2 with one token (all terms are positive: no cancellation)
+__device__ __forceinline__ float sq_dot(const uint4 &g, const uint4 &u, const uint4 &x, float acc)
+{
+    const uint32_t gw[4] = {g.x, g.y, g.z, g.w}, uw[4] = {u.x, u.y, u.z, u.w}, xw[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float xl = bf16_lo(xw[e]), xh = bf16_hi(xw[e]);
+        const float gl = bf16_lo(gw[e]), gh = bf16_hi(gw[e]), ul = bf16_lo(uw[e]), uh = bf16_hi(uw[e]);
+        acc = fmaf(fmaf(gl, gl, ul * ul), xl * xl, acc);
+        acc = fmaf(fmaf(gh, gh, uh * uh), xh * xh, acc);
+    }
+    return acc;
+}
+__device__ __forceinline__ double sq_dot(const float4 &g, const float4 &u, const float4 &x, double acc)
+{
+    const float gv[4] = {g.x, g.y, g.z, g.w}, uv[4] = {u.x, u.y, u.z, u.w}, xs[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const double gg = (double)gv[e], uu = (double)uv[e], xx = (double)xs[e];
+        acc = fma(fma(gg, gg, uu * uu), xx * xx, acc);
+    }
+    return acc;
+}
+
 template <class V, int PER, int MAXB>
 __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 {
@@ -179,10 +204,12 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     __shared__ int s_flag;
     __shared__ int mb_bits[2];  // thread 0 -> everyone, handed over at the round's barrier
     // wave partials of the dot products, summed in double: [parity][group: retained, extras][value][wave][row of 16 lanes]
-    __shared__ __attribute__((aligned(32))) double part[2][2][4][kSelMaxWaves][4];
+    // (third group: the candidates' input-side importance sums, when that reading is on)
+    __shared__ __attribute__((aligned(32))) double part[2][3][4][kSelMaxWaves][4];
     __shared__ int j_s[(kMaxStatic + 1) * kRB];                     // statically dealt retained channels
     __shared__ int j_a[32];                                         // this workgroup's candidates, by slot
     __shared__ float h_a[32];                                       // their hidden activations
+    __shared__ float q_a[32];                                       // their step scores (input-side reading only)
     __shared__ int j_st[kKeep * kRB];                               // retained channels processed since the last flush
     __shared__ float h_st[kKeep * kRB];                             // and their hidden activations
     __shared__ int wg_bits[1024];                                   // selector only: selected candidate slots per workgroup
@@ -195,6 +222,7 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     unsigned long long *const my_word = p.selw + (size_t)b * kSelStride;
     const int epoch = coherent_load(&p.ctr[0]);  // the tag of everything handed over in this step
     const int limit = p.spin_limit;
+    const bool input_side = p.input_side != 0;
 
     POP_STAMP(0);
     int col[PER];
@@ -206,7 +234,7 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
         ok[q] = col[q] < nvec;
         xv[q] = ok[q] ? reinterpret_cast<const vec_t *>(p.x)[col[q]] : V::zero();
     }
-    for (int i = tid; i < 2 * 2 * 4 * kSelMaxWaves * 4; i += blockDim.x) (&part[0][0][0][0][0])[i] = 0;
+    for (int i = tid; i < 2 * 3 * 4 * kSelMaxWaves * 4; i += blockDim.x) (&part[0][0][0][0][0])[i] = 0;
 
     // ---- this workgroup's share
     // candidates: slot s of workgroup b is candidate s * n_wg + b
@@ -322,6 +350,14 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 #pragma unroll
             for (int q = 0; q < PER; ++q) ax[a] = V::dot(cur.xl[a][q], xv[q], ax[a]);
         }
+        // input-side reading: a candidate's step score comes from the same two rows, sum (g^2 + u^2) x_t^2
+        acc_t aq[2] = {0, 0};
+        if (input_side && xkind == 1) {
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int q = 0; q < PER; ++q) aq[a] = sq_dot(cur.xl[2 * a][q], cur.xl[2 * a + 1][q], xv[q], aq[a]);
+        }
         asm volatile("" ::: "memory");  // everything below stays behind the uses of this round's gate/up rows
         load_round<V, PER>(nxt, dn1, w, nvec, col, ok);  // an empty round requests the dummy vector only
         asm volatile("" ::: "memory");
@@ -362,10 +398,15 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                 const double x4[4] = {(double)ax[0], (double)ax[1], (double)ax[2], (double)ax[3]};
                 const double zx = butterfly4_row_sum(x4, lane);
                 if (lane % 16 < 4) part[par][1][butterfly_value_id(lane)][wave][lane / 16] = zx;
+                if (input_side) {
+                    const double q4[4] = {(double)aq[0], (double)aq[1], 0.0, 0.0};
+                    const double zq = butterfly4_row_sum(q4, lane);
+                    if (lane % 16 < 4) part[par][2][butterfly_value_id(lane)][wave][lane / 16] = zq;
+                }
             }
         }
         __syncthreads();
-        float hv[kRB], hx[2] = {0.f, 0.f};
+        float hv[kRB], hx[2] = {0.f, 0.f}, sx[2] = {0.f, 0.f};
         {
             // lane l: value l / 16 of wave l % 16 (unused waves' slots stay zero): its four row sums, then a row sum
             // over the 16 lanes adds the waves in a fixed tree order
@@ -382,6 +423,12 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                     hx[a] = dc.xrow[2 * a] >= 0
                                 ? silu_mul((float)lane_value(tx, 32 * a), (float)lane_value(tx, 32 * a + 16))
                                 : 0.f;
+                if (input_side) {
+                    const double4 s4 = *reinterpret_cast<const double4 *>(&part[par][2][lane / 16][lane % 16][0]);
+                    const double ts = dpp_row_sum((s4.x + s4.y) + (s4.z + s4.w));
+#pragma unroll
+                    for (int a = 0; a < 2; ++a) sx[a] = sqrtf((float)lane_value(ts, 16 * a));
+                }
             }
         }
         if (tid == 0) {
@@ -395,7 +442,10 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
             if (xkind == 1) {
 #pragma unroll
                 for (int a = 0; a < 2; ++a)
-                    if (dc.xrow[2 * a] >= 0) h_a[dc.xslot(a)] = hx[a];
+                    if (dc.xrow[2 * a] >= 0) {
+                        h_a[dc.xslot(a)] = hx[a];
+                        q_a[dc.xslot(a)] = sx[a];
+                    }
             }
         }
         if (dc.jb[0] >= 0) ++n_st;
@@ -418,7 +468,8 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
             // same wave, and a wave's LDS operations execute in order.
             if (wave == 0 && lane < n_aslots) {
                 const float hvv = h_a[lane];
-                coherent_store(&p.hc[lane * n_wg + b], tagged(__float_as_uint(hvv), epoch));
+                // (what the selector ranks: h, from which it forms n_j |h_j|, or the input-side score itself)
+                coherent_store(&p.hc[lane * n_wg + b], tagged(__float_as_uint(input_side ? q_a[lane] : hvv), epoch));
                 p.h[j_a[lane]] = hvv;
             }
             POP_STAMP(1);
@@ -539,7 +590,8 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                 }
                 if ((int)(v[u] >> 32) != epoch) got_all = false;
                 if (c[u] < n_cand) {
-                    const float sc = nr[u] * fabsf(__uint_as_float((uint32_t)v[u]));
+                    const float hq = __uint_as_float((uint32_t)v[u]);
+                    const float sc = input_side ? hq : nr[u] * fabsf(hq);
                     if (in_lds) {
                         sh.keys[c[u]] = score_key(sc);
                         p.cscore[c[u]] = sc;

@@ -207,12 +207,13 @@ struct FusedParams {
     int *active_idx;            // [>= n_ret + k]
     int *n_active;              // [1]
     // what the workgroups hand to each other: 64-bit words {value, epoch}
-    unsigned long long *hc;     // [n_cand] a candidate's h, by candidate position
+    unsigned long long *hc;     // [n_cand] a candidate's h (input-side reading: its step score), by candidate position
     unsigned long long *selw;   // [n_wg] per-workgroup selection word (selected candidate slots), 128 bytes apart
     float *partial;             // [n_wg][d] partial output rows (summed by decode_tail_kernel)
     int *ctr;                   // [0] epoch (>= 1), [1] workgroups that finished (back at zero when the kernel ends),
                                 // [2] sticky error flag: a bounded wait gave up
     int spin_limit;             // looks a bounded wait takes before it gives up
+    int input_side;             // candidates are ranked by || [gate_j, up_j] * |x_t| ||_2 instead of n_j |h_j|
     int n_static;               // retained rounds per worker
     unsigned long long *trace;  // profiling builds only: 8 timestamps per workgroup, else null
 };

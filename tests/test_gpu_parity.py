@@ -498,7 +498,9 @@ def test_input_side_importance(pop, oracle, dtype):
         for xb, ks in ((xt[:1], [k]), (xt, [k, 0, n_cand])):
             for one_call in (False, True):
                 out = G.decode(xb, ks, one_call=one_call)
-                assert pop.pop_layer_step_kind(G.handle)[0] == 2
+                # one sequence: the fused kernel (it scores the candidates from the rows it reads for h); else launches
+                kind, wgs = pop.pop_layer_step_kind(G.handle)  # (wgs: 0 where the fused kernel does not take the shape)
+                assert kind == (1 if xb.shape[0] == 1 and wgs > 0 else 2)
                 for b in range(xb.shape[0]):
                     c_ref = oracle.importance_input_side(xb[b:b + 1], L.w_gate, L.w_up, dtype, chan=cand)[cand]
                     assert score_rel_err(out["cscore"][b], c_ref, eps=1e-6) <= SCORE_TOL
