@@ -13,8 +13,11 @@
 //
 // A round carries kRB retained channels (gate, up and down rows: h_j = silu(g_j) u_j, then y += h_j * down_j) and
 // kXL extra rows that ride along:
-//   - first the workgroup's share of the candidate channels, two per round (gate+up only): h_j and the step score
-//     I_j(t) = n_j |h_j| (Eq. 3 with one token) are published to global memory with write-through stores;
+//   - first the workgroup's share of the candidate channels (gate+up only): h_j and the step score
+//     I_j(t) = n_j |h_j| (Eq. 3 with one token) are published to global memory with write-through stores.  The
+//     selection waits for every workgroup's candidates, so they go first: four per round (the retained channels'
+//     gate and up buffers take two of them) while three or more are left, the last one or two next to retained
+//     channels;
 //   - later, once the selection is known, the down rows of those of its own candidates that were selected.
 // Candidates are dealt round-robin to all workgroups, retained rounds round-robin to the workers: the schedule,
 // and with it the summation order of y, is fixed (bit-reproducible output).  (Letting workers draw part of their
@@ -84,12 +87,16 @@ struct RoundDesc {
                     // candidates (xkind 1) or down rows of up to four selected candidates (xkind 2)
     int xmeta;      // bits 0-1 xkind, bit 2 "this round completes the workgroup's candidates",
                     // bits 8+5a .. 12+5a the candidate slot in this workgroup of extra item a
+    int bmeta;      // 0: jb are retained channels.  Bit 0 set: a round of candidates only - jb are two more of the
+                    // workgroup's candidates (gate and up rows, no down row), bits 8+8t .. 15+8t their slots
     uint32_t boff[kRB], xoff[kXL];  // where those rows start in w, in 16-byte vectors (0 for an empty slot):
                                     // worked out with the descriptor, a round before the rows are requested
     bool work;      // the round holds anything at all
     __device__ __forceinline__ int xkind() const { return xmeta & 3; }
     __device__ __forceinline__ bool last_a() const { return (xmeta & 4) != 0; }
     __device__ __forceinline__ int xslot(int a) const { return (xmeta >> (8 + 5 * a)) & 31; }
+    __device__ __forceinline__ bool bcand() const { return (bmeta & 1) != 0; }
+    __device__ __forceinline__ int bslot(int t) const { return (bmeta >> (8 + 8 * t)) & 255; }
 };
 
 // Requests the rows of one round: the extra rows first (only in rounds that have any: a request for a dummy
@@ -124,7 +131,8 @@ __device__ __forceinline__ void load_round(RoundBuf<V, PER> &rb, const RoundDesc
 #pragma unroll
     for (int t = 0; t < kRB; ++t)
 #pragma unroll
-        for (int q = 0; q < PER; ++q) rb.dn[t][q] = w[(ok[q] && ds.jb[t] >= 0) ? idx[t][q] + 2u * (uint32_t)nvec : 0u];
+        for (int q = 0; q < PER; ++q)
+            rb.dn[t][q] = w[(ok[q] && ds.jb[t] >= 0 && !ds.bcand()) ? idx[t][q] + 2u * (uint32_t)nvec : 0u];
 }
 
 // Sum over the 16 lanes of each DPP row, result in every lane of the row (4 cross-lane adds, no LDS).
@@ -263,24 +271,29 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
     int rem_d = 0;              // selected slots whose down rows are still to be added (valid once bits_known)
     bool bits_known = false;    // the selection word of this step has been seen
     int n_st = 0;               // rounds staged in j_st / h_st
-    // thread 0 only: results of the polls of the selection word issued in the previous two rounds (by parity)
-    unsigned long long poll_ret[2] = {0, 0};
+    // thread 0 only: the selection word as polled in the previous round
+    unsigned long long poll_ret = 0;
 
-    // Descriptor of round r.  Called once per round, in order.
-    auto make_desc = [&](RoundDesc &ds, int r) {
+    // Descriptor of the next round.  Called once per round, in order.  While the workgroup has three or more
+    // candidates left, a round holds candidates only, four at a time (two in the extra rows, two in the retained
+    // channels' gate and up buffers): the candidates' results are what the selection waits for, so they go out
+    // first, in rounds that still carry 64 KB.  The last one or two ride along with retained rounds.
+    int ir = 0;  // next retained round of this worker
+    auto make_desc = [&](RoundDesc &ds) {
         bool work = false;
 #pragma unroll
         for (int t = 0; t < kRB; ++t) ds.jb[t] = -1;
-        if (r < n_static) {
-#pragma unroll
-            for (int t = 0; t < kRB; ++t) ds.jb[t] = uniform(j_s[r * kRB + t]);
-            work = ds.jb[0] >= 0;
-        }
-#pragma unroll
-        for (int t = 0; t < kRB; ++t) ds.boff[t] = (uint32_t)max(ds.jb[t], 0) * 3u * (uint32_t)nvec;
+        ds.bmeta = 0;
         ds.xmeta = 0;
 #pragma unroll
         for (int a = 0; a < kXL; ++a) ds.xrow[a] = -1;
+        const bool cand_round = n_aslots - ia >= 3;
+        if (!cand_round && ir < n_static) {
+#pragma unroll
+            for (int t = 0; t < kRB; ++t) ds.jb[t] = uniform(j_s[ir * kRB + t]);
+            work = ds.jb[0] >= 0;
+            ++ir;
+        }
         if (ia < n_aslots) {
             ds.xmeta = 1;
 #pragma unroll
@@ -292,6 +305,16 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                     ds.xrow[2 * a + 1] = j * 3 + 1;
                 }
             ia += 2;
+            if (cand_round) {
+                ds.bmeta = 1;
+#pragma unroll
+                for (int t = 0; t < kRB; ++t)
+                    if (ia + t < n_aslots) {
+                        ds.jb[t] = uniform(j_a[ia + t]);
+                        ds.bmeta |= (ia + t) << (8 + 8 * t);
+                    }
+                ia += 2;
+            }
             if (ia >= n_aslots) ds.xmeta |= 4;
             work = true;
         } else if (bits_known && rem_d && work) {
@@ -308,6 +331,8 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                 }
             work = true;
         }
+#pragma unroll
+        for (int t = 0; t < kRB; ++t) ds.boff[t] = (uint32_t)max(ds.jb[t], 0) * 3u * (uint32_t)nvec;
 #pragma unroll
         for (int a = 0; a < kXL; ++a) ds.xoff[a] = (uint32_t)max(ds.xrow[a], 0) * (uint32_t)nvec;
         ds.work = work;
@@ -351,38 +376,34 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
             for (int q = 0; q < PER; ++q) ax[a] = V::dot(cur.xl[a][q], xv[q], ax[a]);
         }
         // input-side reading: a candidate's step score comes from the same two rows, sum (g^2 + u^2) x_t^2
-        acc_t aq[2] = {0, 0};
+        acc_t aq[4] = {0, 0, 0, 0};
         if (input_side && xkind == 1) {
 #pragma unroll
             for (int a = 0; a < 2; ++a)
 #pragma unroll
                 for (int q = 0; q < PER; ++q) aq[a] = sq_dot(cur.xl[2 * a][q], cur.xl[2 * a + 1][q], xv[q], aq[a]);
+            if (dc.bcand()) {
+#pragma unroll
+                for (int t = 0; t < kRB; ++t)
+#pragma unroll
+                    for (int q = 0; q < PER; ++q) aq[2 + t] = sq_dot(cur.g[t][q], cur.u[t][q], xv[q], aq[2 + t]);
+            }
         }
         asm volatile("" ::: "memory");  // everything below stays behind the uses of this round's gate/up rows
-        load_round<V, PER>(nxt, dn1, w, nvec, col, ok);  // an empty round requests the dummy vector only
-        asm volatile("" ::: "memory");
         if (tid == 0) {
-            // The poll thread 0 issued two rounds ago has had two rounds to arrive: hand it to the others at this
-            // round's barrier.  Then poll the selection word again (zero until the selector has written it),
-            // straight into the register it is read from two rounds later.
-            const bool here = (int)(poll_ret[par] >> 32) == epoch;
-            mb_bits[par] = here ? ((int)(uint32_t)poll_ret[par] | kBitsValid) : 0;
+            // The poll of the selection word that thread 0 issued in the previous round is older than this round's
+            // rows, which have arrived: hand it to the others at this round's barrier.  Then poll again (another
+            // epoch until the selector has written the word), ahead of the next round's requests.
+            const bool here = (int)(poll_ret >> 32) == epoch;
+            mb_bits[par] = here ? ((int)(uint32_t)poll_ret | kBitsValid) : 0;
 #ifdef POP_TRACE
             if (here && p.trace && p.trace[(size_t)blockIdx.x * 8 + 5] == 0) POP_STAMP(5);
 #endif
-            poll_ret[par] = coherent_load(my_word);
+            poll_ret = coherent_load(my_word);
         }
         asm volatile("" ::: "memory");
-        // descriptor of round i + 2, from what thread 0 handed over at the previous barrier
-        if (!bits_known && i >= 1) {
-            const int v = uniform(mb_bits[par ^ 1]);  // handed over at the previous round's barrier
-            if (v & kBitsValid) {
-                bits_known = true;
-                rem_d = v & ~kBitsValid;
-                POP_STAMP(7);
-            }
-        }
-        make_desc(dn2, i + 2);
+        load_round<V, PER>(nxt, dn1, w, nvec, col, ok);  // an empty round requests the dummy vector only
+        asm volatile("" ::: "memory");
 
         // wave partials -> LDS -> totals in every thread (one barrier)
         // (a thread's one or two vectors of products are summed in the row's accumulator type; across lanes and
@@ -399,14 +420,24 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                 const double zx = butterfly4_row_sum(x4, lane);
                 if (lane % 16 < 4) part[par][1][butterfly_value_id(lane)][wave][lane / 16] = zx;
                 if (input_side) {
-                    const double q4[4] = {(double)aq[0], (double)aq[1], 0.0, 0.0};
+                    const double q4[4] = {(double)aq[0], (double)aq[1], (double)aq[2], (double)aq[3]};
                     const double zq = butterfly4_row_sum(q4, lane);
                     if (lane % 16 < 4) part[par][2][butterfly_value_id(lane)][wave][lane / 16] = zq;
                 }
             }
         }
         __syncthreads();
-        float hv[kRB], hx[2] = {0.f, 0.f}, sx[2] = {0.f, 0.f};
+        // descriptor of round i + 2, with what thread 0 handed over at this barrier
+        if (!bits_known) {
+            const int v = uniform(mb_bits[par]);
+            if (v & kBitsValid) {
+                bits_known = true;
+                rem_d = v & ~kBitsValid;
+                POP_STAMP(7);
+            }
+        }
+        make_desc(dn2);
+        float hv[kRB], hx[2] = {0.f, 0.f}, sx[4] = {0.f, 0.f, 0.f, 0.f};
         {
             // lane l: value l / 16 of wave l % 16 (unused waves' slots stay zero): its four row sums, then a row sum
             // over the 16 lanes adds the waves in a fixed tree order
@@ -427,12 +458,20 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                     const double4 s4 = *reinterpret_cast<const double4 *>(&part[par][2][lane / 16][lane % 16][0]);
                     const double ts = dpp_row_sum((s4.x + s4.y) + (s4.z + s4.w));
 #pragma unroll
-                    for (int a = 0; a < 2; ++a) sx[a] = sqrtf((float)lane_value(ts, 16 * a));
+                    for (int a = 0; a < 4; ++a) sx[a] = sqrtf((float)lane_value(ts, 16 * a));
                 }
             }
         }
+        const bool bcand = dc.bcand();
         if (tid == 0) {
-            if (dc.jb[0] >= 0) {
+            if (bcand) {
+#pragma unroll
+                for (int t = 0; t < kRB; ++t)
+                    if (dc.jb[t] >= 0) {
+                        h_a[dc.bslot(t)] = hv[t];
+                        q_a[dc.bslot(t)] = sx[2 + t];
+                    }
+            } else if (dc.jb[0] >= 0) {
 #pragma unroll
                 for (int t = 0; t < kRB; ++t) {
                     j_st[n_st * kRB + t] = dc.jb[t];
@@ -448,11 +487,11 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
                     }
             }
         }
-        if (dc.jb[0] >= 0) ++n_st;
+        if (dc.jb[0] >= 0 && !bcand) ++n_st;
 #pragma unroll
         for (int t = 0; t < kRB; ++t)
 #pragma unroll
-            for (int q = 0; q < PER; ++q) V::axpy(hv[t], cur.dn[t][q], acc[q]);
+            for (int q = 0; q < PER; ++q) V::axpy(bcand ? 0.f : hv[t], cur.dn[t][q], acc[q]);  // (no down row: dummy)
         if (xkind == 2) {
 #pragma unroll
             for (int a = 0; a < kXL; ++a) {
@@ -483,9 +522,9 @@ __global__ __launch_bounds__(MAXB) void decode_fused_kernel(FusedParams p)
 #pragma unroll
         for (int q = 0; q < PER; ++q) buf_a.xl[a][q] = buf_b.xl[a][q] = V::zero();  // read before the first extra rows
     RoundDesc d0, d1, d2;           // descriptors of the round being reduced, the one in flight, the one after
-    make_desc(d0, 0);
+    make_desc(d0);
     load_round<V, PER>(buf_a, d0, w, nvec, col, ok);
-    make_desc(d1, 1);
+    make_desc(d1);
     int i = 0;
     // a round without work can still be followed by one with work (selected rows, once the selection is known)
     while (d0.work || d1.work) {
