@@ -481,7 +481,7 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
         POP_HIP(launch_prefill_gateup(L->w, L->is_bf16, L->d, m, x, T, L->s2_part, L->n_cu, s, &fin));
     }
     return finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s,
-                            T == 0 || L->input_side || prefill_forms_scores(L->is_bf16));
+                            T == 0 || L->input_side || prefill_forms_scores(L->is_bf16, T, m, L->n_cu));
 }
 
 int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_cand, int k0, void *y, pop_dtype_t ydtype,
@@ -531,7 +531,7 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     }
     {
         int rc = finish_partition(L, T, n_ret, n_cand, scores, region, ret_idx, cand_idx, s,
-                                  T == 0 || L->input_side || prefill_forms_scores(L->is_bf16), n_ret + k0, mask || !keep, keep ? &gather : nullptr);
+                                  T == 0 || L->input_side || prefill_forms_scores(L->is_bf16, T, m, L->n_cu), n_ret + k0, mask || !keep, keep ? &gather : nullptr);
         if (rc != POP_OK) return rc;
     }
     unsigned char *pm = L->ffn_any;

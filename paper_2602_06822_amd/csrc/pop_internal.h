@@ -242,7 +242,7 @@ hipError_t launch_probe_step_read(const void *w, int nvec, const int *gu_list, i
 // s2_part[tile][j] = sum over the tile's tokens of H[t][j]^2, one row per token tile.
 int prefill_num_tiles(int T, int is_bf16);  // upper bound on the rows used, for sizing s2_part
 int prefill_rows_used(int T, int is_bf16, int m, int n_cu);  // rows the launch below writes for this T
-// With `fin`, bf16 layers (prefill_forms_scores) also leave scores[j] = nrm[j] * sqrt(sum over the token tiles, in tile
+// With `fin`, launches for which prefill_forms_scores holds (bf16 layers, prompts of one tile per compute unit) also leave scores[j] = nrm[j] * sqrt(sum over the token tiles, in tile
 // order and in double, of s2_part[tile][j]) (Eq. 3): the token tile of a channel chunk that finishes last does the sum.
 // chunk_ctr: one int per channel chunk (m of them suffice), zero before the launch and zero again after it.
 struct PrefillScores {
@@ -250,7 +250,7 @@ struct PrefillScores {
     const float *nrm;
     float *scores;
 };
-bool prefill_forms_scores(int is_bf16);
+bool prefill_forms_scores(int is_bf16, int T, int m, int n_cu);
 hipError_t launch_prefill_gateup(const void *w, int is_bf16, int d, int m, const void *x, int T, float *s2_part,
                                  int n_cu, hipStream_t s, const PrefillScores *fin = nullptr);
 // bf16 layers: gate/up over the channels of a device-resident list (n_list: its length, on the device);
