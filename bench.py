@@ -512,7 +512,7 @@ def time_other_shapes(pop, synth, lib, stream):
         to_dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda()  # noqa: E731
         n_ret, n_cand, _ = pop.pop_region_counts(cfg.m, *region_fractions(r))
         k = pop.pop_k_for_ratio(cfg.m, r, n_ret, n_cand)
-        hs, xds = [], []
+        hs, xds, host_layers = [], [], []
         for i in range(n_layers):
             L = synth.make_layer(cfg, i)
             h = pop.pop_layer_create(cfg.d, cfg.m, pop.POP_BF16, to_dev(L.w_gate), to_dev(L.w_up), to_dev(L.w_down),
@@ -520,7 +520,7 @@ def time_other_shapes(pop, synth, lib, stream):
             pop.pop_prefill_partition(h, to_dev(synth.make_activations(L, T, "prompt", i)), T, n_ret, n_cand)
             hs.append(h)
             xds.append(to_dev(synth.make_activations(L, 64, "decode", i)))
-            del L
+            host_layers.append(L)
         bm = byte_model(cfg.d, n_ret, n_cand, k)
         res = {}
         for B in batches:
@@ -560,7 +560,53 @@ def time_other_shapes(pop, synth, lib, stream):
                                  active_GBps_one_sequence=round(bm["active"] / us / 1e3, 1),
                                  union_channels=union, MB_streamed=round(streamed / 1e6, 2),
                                  streamed_GBps=round(streamed / us / 1e3, 1))
-        for h in hs:
+        # The whole workload the shape stands for, per token: configs[3] is a stack of 40 such layers (each with its
+        # own weights - device copies of the four above -, partition and input), configs[4] a layer of 8 experts of
+        # which every token runs 2 (the router is harness-side; here a seeded draw).
+        n_units = 40 if cfg is synth.CFG4 else 8
+        units = list(hs)
+        for i in range(n_layers, n_units):
+            L = host_layers[i % n_layers]
+            h = pop.pop_layer_create(cfg.d, cfg.m, pop.POP_BF16, to_dev(L.w_gate), to_dev(L.w_up), to_dev(L.w_down),
+                                     T, max(batches))
+            pop.pop_prefill_partition(h, to_dev(synth.make_activations(L, T, "prompt", i)), T, n_ret, n_cand)
+            units.append(h)
+        del host_layers
+
+        def time_tokens(token, reps):
+            token(0)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for t in range(reps):
+                token(t + 1)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) * 1e3 / reps
+
+        def one_step(h, xd, t, B, karr, y):
+            xt = C.c_void_p(xd.data_ptr() + (t % (64 // B)) * B * cfg.d * 2)
+            rc = lib.pop_decode_step(h, xt, B, karr, C.c_void_p(y.data_ptr()), pop.POP_BF16, None, None, None, None, sp)
+            if rc:
+                raise pop.PopError(rc, "bench")
+
+        if cfg is synth.CFG4:
+            stack = {"layers": n_units}
+            for B in batches:
+                y = torch.empty(B * cfg.d, dtype=torch.int16, device="cuda")
+                karr = (C.c_int * B)(*([k] * B))
+                us = time_tokens(lambda t: [one_step(h, xds[i % n_layers], t, B, karr, y) for i, h in enumerate(units)], 6)
+                stack[f"B={B}"] = dict(us_per_step=round(us, 1), us_per_token=round(us / B, 1))
+            res["stack_of_40_layers"] = stack
+        else:
+            y = torch.empty(cfg.d, dtype=torch.int16, device="cuda")
+            karr = (C.c_int * 1)(k)
+            draw = np.random.default_rng(20260206)
+            routes = [draw.choice(n_units, size=2, replace=False) for _ in range(65)]
+            us = time_tokens(lambda t: [one_step(units[e], xds[e % n_layers], t, 1, karr, y) for e in routes[t]], 64)
+            res["moe_layer_8_experts_top2"] = dict(us_per_token=round(us, 2), experts_per_token=2,
+                                                   note="two expert steps per token; router harness-side, not timed")
+        for h in units:
             pop.pop_layer_destroy(h)
         torch.cuda.empty_cache()
         out[name] = dict(d=cfg.d, m=cfg.m, n_ret=n_ret, n_cand=n_cand, k=k, layers_rotated=n_layers, **res)
