@@ -228,6 +228,9 @@ int finish_partition(pop_layer *L, int T, int n_ret, int n_cand, float *scores, 
         ex.scores_out = L->scores;
     }
     ex.sync = L->sync, ex.n_sync = 16;
+#ifdef POP_TRACE
+    ex.trace = g_trace ? g_trace + 1000 * 8 : nullptr;
+#endif
     if (n_top >= 0) {
         ex.n_top = n_top, ex.top_list = L->top_list, ex.top_count = L->top_list + m;
         ex.top_mask = top_mask ? L->ffn_any : nullptr;

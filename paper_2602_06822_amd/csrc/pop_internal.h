@@ -106,6 +106,7 @@ struct PartitionExtra {
     unsigned char *top_mask = nullptr;
     int *top_list = nullptr;
     int *top_count = nullptr;
+    unsigned long long *trace = nullptr;  // profiling builds only: timestamps of the kernel's phases, else null
 };
 bool partition_takes_partials(int m);
 hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,

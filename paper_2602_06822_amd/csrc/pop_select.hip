@@ -69,6 +69,17 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
     __shared__ SelShared sh;
     extern __shared__ uint32_t part_keys[];  // [m] when m <= kPartLdsKeys
     const bool in_lds = m <= kPartLdsKeys;
+#ifdef POP_TRACE
+#define POP_PSTAMP(slot)                                                          \
+    do {                                                                          \
+        if (ex.trace && threadIdx.x == 0) ex.trace[slot] = wall_clock64();        \
+    } while (0)
+#else
+#define POP_PSTAMP(slot) \
+    do {                 \
+    } while (0)
+#endif
+    POP_PSTAMP(0);
     if (ex.sync && threadIdx.x < ex.n_sync) ex.sync[threadIdx.x] = 0;
     // while the keys pass through registers: the bits set in any key and the bits clear in any key (the radix select
     // starts below the leading bits that all keys share)
@@ -138,6 +149,7 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
         }
         __syncthreads();
     }
+    POP_PSTAMP(1);
     auto key = [&](int i) { return in_lds ? part_keys[i] : score_key(scores[i]); };
     // thresholds: retained (rank n_ret), retained + candidate (rank n_ret + n_cand) and, on request, the n_top best
     // channels.  An empty set is sought as a set of one and then closed (key above all keys, nothing taken).
@@ -158,10 +170,12 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
     if (n_ret == 0) kth[0] = 0xffffffffu, take[0] = 0;
     if (n_ret + n_cand == 0) kth[1] = 0xffffffffu, take[1] = 0;
     if (!top || ex.n_top == 0) kth[2] = 0xffffffffu, take[2] = 0;
+    POP_PSTAMP(2);
     if (top)
         partition_emit<3>(key, m, kth, take, region, ret_idx, cand_idx, ex, sh);
     else
         partition_emit<2>(key, m, kth, take, region, ret_idx, cand_idx, ex, sh);
+    POP_PSTAMP(3);
 }
 
 bool partition_takes_partials(int m) { return m <= kPartLdsKeys; }
