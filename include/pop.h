@@ -171,8 +171,11 @@ int pop_partition_top_from_scores(const float *scores, int m, int n_ret, int n_c
                                   unsigned char *region, int *ret_idx, int *cand_idx,
                                   unsigned char *top_mask, int *top_list, void *stream);
 
-/* Step selection from given candidate scores: cand_scores dev [n_cand] in cand_idx order, cand_idx dev [n_cand]
- * ascending, region dev [m].  Outputs (dev, may be NULL): mask [m] (retained + selected), sel_idx [k] ascending. */
+/* Step selection from given candidate scores (Sec. 3.3 "Decoding Stage": of the candidate region the k channels of
+ * highest step score stay active next to the retained region; equal scores by lower channel number):
+ * cand_scores dev [n_cand] in cand_idx order, cand_idx dev [n_cand] ascending, region dev [m], 0 <= k <= n_cand.
+ * Outputs (dev, may be NULL): mask [m] (retained + selected), sel_idx [k] ascending.
+ * Errors: NULL inputs -> POP_EINVAL; sizes out of range -> POP_ESHAPE. */
 int pop_topk_from_scores(const float *cand_scores, const int *cand_idx, int n_cand, int k,
                          const unsigned char *region, int m, unsigned char *mask, int *sel_idx, void *stream);
 
@@ -224,7 +227,7 @@ int pop_layer_set_wait_limit(pop_layer_t *layer, int looks);
  *       fused kernel, which forms a candidate's score from the same two rows it reads for h; a step with B > 1
  *       selects first and runs the forward pass over retained and selected channels only, as separate launches: h
  *       of an unselected candidate is then not computed, so pop_layer_get_hidden is defined on active channels
- *       only under this reading.  The shared batch mask is not available (POP_EUNSUPPORTED).
+ *       only under this reading.  With the shared batch mask s_k runs over the step's B rows.
  * Changing the reading discards the layer's partition (prefill again).  Errors: unknown value -> POP_EINVAL. */
 enum { POP_IMPORTANCE_OUTPUT_SIDE = 0, POP_IMPORTANCE_INPUT_SIDE = 1 };
 int pop_layer_set_importance(pop_layer_t *layer, int reading);

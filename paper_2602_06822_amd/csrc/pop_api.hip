@@ -577,9 +577,15 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
             // (a single sequence on a shape the fused kernel takes went there: it scores the candidates from the same
             // rows it reads for h.)  Here candidates are scored from their gate and up rows and |x_t| alone, so the
             // selection comes first and the forward pass runs over retained and selected channels only
-            if (B > 1 && L->shared_mask) return POP_EUNSUPPORTED;
+            const bool shared = B > 1 && L->shared_mask;
+            if (shared)
+                for (int b = 1; b < B; ++b)
+                    if (kk.k[b] != kk.k[0]) return POP_ESHAPE;
             POP_HIP(launch_input_squares(x_t, L->is_bf16, B, L->d, L->in_s2, s));
             POP_HIP(launch_input_side_scores(L->w, L->is_bf16, L->d, L->in_s2, B, L->cand_idx, n_cand, L->cscore, m, s));
+            // one mask for the batch: the root of the sum of the sequences' squared scores is this reading's importance
+            // over the step's B rows (Eq. 1-2 with s_k over tokens and samples); every row gets it
+            if (shared) POP_HIP(launch_aggregate_scores(L->cscore, m, B, n_cand, s));
             POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx,
                                 L->n_active, nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
                                 s));

@@ -521,10 +521,22 @@ def test_input_side_importance(pop, oracle, dtype):
         assert np.array_equal(mask, mask1)
         y_ref = oracle.pruned_ffn(x, L.w_gate, L.w_up, L.w_down, dtype, mask)
         assert max_abs_rel(y, y_ref) <= (FFN_MFMA_TOL_F32 if dtype == BF16 else tol)
+        # one mask for the batch: this reading's importance over the step's rows (s_k over tokens and samples)
         pop.pop_layer_set_shared_batch_mask(G.handle, True)
         with pytest.raises(pop.PopError) as e:
-            G.decode(xt, k)
-        assert e.value.status == pop.POP_EUNSUPPORTED
+            G.decode(xt, [k, 0, n_cand])
+        assert e.value.status == pop.POP_ESHAPE
+        out = G.decode(xt, [k] * 3)
+        c_ref = oracle.importance_input_side(xt, L.w_gate, L.w_up, dtype, chan=cand)[cand]
+        mask1, _, act1 = oracle.select(region, out["cscore"][0], cand, k)
+        for b in range(3):
+            assert score_rel_err(out["cscore"][b], c_ref, eps=1e-6) <= SCORE_TOL
+            assert np.array_equal(out["cscore"][b], out["cscore"][0])
+            assert np.array_equal(out["mask"][b], mask1)
+            assert np.array_equal(out["active_idx"][b][:n_ret + k], act1)
+            active = np.flatnonzero(mask1).astype(np.int32)
+            H = oracle.hidden(xt[b:b + 1], L.w_gate, L.w_up, dtype, chan=active)
+            assert max_abs_rel(out["y"][b], oracle.down(H, L.w_down, dtype, mask1)[0]) <= Y_TOL[dtype]
         pop.pop_layer_set_shared_batch_mask(G.handle, False)
         # back to the default reading
         pop.pop_layer_set_importance(G.handle, pop.POP_IMPORTANCE_OUTPUT_SIDE)
