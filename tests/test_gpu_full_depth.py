@@ -212,3 +212,24 @@ def test_decode_strategies_full_size(pop, oracle, strategy, gamma):
             out = _check_decode(oracle, G, L, region, cand, xt[t:t + 1], k)
             assert int(out["mask"].sum()) == n_ret + k
         _check_decode(oracle, G, L, region, cand, xt[1:3], [k, max(k - 5, 0)])
+
+
+def test_prefill_alternating_prompt_lengths_on_one_layer(pop, oracle):
+    """One layer of the benchmark shape, prefilled with a 512-token prompt (one contraction tile per compute unit: the
+    launch forms the scores itself, counting the tiles of each channel chunk in), a 2048-token prompt (several tiles
+    per compute unit: the partition launch sums the partial rows), a 130-token prompt (the small-tile form) and the
+    first prompt again: every call's scores against the oracle, and the last call bit for bit the first - the chunk
+    counters are back at rest after every launch, whatever ran before."""
+    cfg = synth.CFG2
+    L = synth.make_layer(cfg, 3)
+    n_ret, n_cand, _ = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, cfg.m, 0.35, 0.10)
+    xs = {T: synth.make_activations(L, T, "prompt_alt", T) for T in (512, 2048, 130)}
+    with GpuLayer(pop, L, max_tokens=2048, max_batch=1) as G:
+        first = None
+        for T in (512, 2048, 130, 512, 512):
+            got = _prefill_checked(oracle, G, L, xs[T], n_ret, n_cand, f"alt_T{T}", n_sample=8)
+            if T == 512:
+                if first is None:
+                    first = got
+                else:
+                    assert all(np.array_equal(a, b) for a, b in zip(first, got))
