@@ -209,16 +209,18 @@ __global__ __launch_bounds__(1024) void topk_kernel(const float *__restrict__ cs
                                                     int *__restrict__ active_idx, int *__restrict__ n_active,
                                                     int *__restrict__ sel_idx, unsigned char *selflag,
                                                     int *union_ctr, int *__restrict__ union_list,
-                                                    int *__restrict__ n_union)
+                                                    int *__restrict__ n_union, int keys_in_ext)
 {
     __shared__ SelShared sh;
     __shared__ int s_last;
+    extern __shared__ uint32_t topk_keys[];  // [n_cand] when the launch gave it: candidate sets beyond sh.keys
     const int b = blockIdx.x, B = gridDim.x, k = kk.k[b];
     unsigned char *mk = mask ? mask + (size_t)b * m : nullptr;
     int *act = active_idx ? active_idx + (size_t)b * act_stride + n_ret : (b == 0 ? sel_idx : nullptr);
     // selflag: [n_cand][POP_MAX_BATCH], one 8-byte word per candidate position
     block_select_candidates(cscore + (size_t)b * cs_stride, cand_idx, n_cand, k, mk, act, sh, SelectNoHook(),
-                            SelectNoHook(), nullptr, selflag ? selflag + b : nullptr, POP_MAX_BATCH);
+                            SelectNoHook(), nullptr, selflag ? selflag + b : nullptr, POP_MAX_BATCH, false,
+                            keys_in_ext ? topk_keys : nullptr, keys_in_ext ? n_cand : 0);
     if (n_active && threadIdx.x == 0) n_active[b] = n_ret + k;
     if (!union_list) return;
     // the flags of this sequence are written; the last workgroup to get here sees every sequence's flags
@@ -250,8 +252,17 @@ hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, 
                        unsigned char *selflag, int *union_ctr, int *union_list, int *n_union, hipStream_t s)
 {
     int threads = n_cand <= 2048 ? 256 : 1024;
-    hipLaunchKernelGGL(topk_kernel, dim3(B), dim3(threads), 0, s, cscore, cs_stride, cand_idx, n_cand, n_ret, m, k,
-                       act_stride, mask, active_idx, n_active, sel_idx, selflag, union_ctr, union_list, n_union);
+    // candidate sets beyond the select's own key buffer (re-scoring all channels of a layer) get theirs from the launch
+    const bool ext = n_cand > kSelLdsKeys && n_cand <= kPartLdsKeys;
+    const size_t lds = ext ? (size_t)n_cand * 4 : 0;
+    if (lds > 32 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(topk_kernel, dim3(B), dim3(threads), lds, s, cscore, cs_stride, cand_idx, n_cand, n_ret, m, k,
+                       act_stride, mask, active_idx, n_active, sel_idx, selflag, union_ctr, union_list, n_union,
+                       ext ? 1 : 0);
     return hipGetLastError();
 }
 

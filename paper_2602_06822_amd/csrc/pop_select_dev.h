@@ -355,7 +355,8 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
                                                         AfterSelected after_selected = AfterSelected(),
                                                         unsigned long long *tr = nullptr,
                                                         unsigned char *__restrict__ selpos = nullptr,
-                                                        int selpos_stride = 1, bool keys_ready = false)
+                                                        int selpos_stride = 1, bool keys_ready = false,
+                                                        uint32_t *keys_ext = nullptr, int keys_cap = 0)
 {
 #define SEL_STAMP(k) do { if (tr && threadIdx.x == 0) tr[k] = wall_clock64(); } while (0)
     SEL_STAMP(0);
@@ -363,30 +364,43 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
         return kCoherentScores ? __hip_atomic_load(&cs[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : cs[i];
     };
     // keys_ready: the caller has put score_key(score) of every candidate into sh.keys (n_cand <= kSelLdsKeys) and
-    // synchronised the block
-    const bool in_lds = n_cand <= kSelLdsKeys;
+    // synchronised the block.  keys_ext: LDS of the caller's for keys_cap keys, used instead of sh.keys (a large
+    // candidate set then stays out of global memory after the first sweep as well)
+    uint32_t *const keys = keys_ext ? keys_ext : sh.keys;
+    const bool in_lds = n_cand <= (keys_ext ? keys_cap : kSelLdsKeys);
     if (in_lds && !keys_ready) {
-        // eight independent loads in flight per thread: under a streaming load a trip to memory takes microseconds
-        for (int base = 0; base < n_cand; base += 8 * blockDim.x) {
-            float v[8];
+        // twelve independent loads in flight per thread: under a streaming load a trip to memory takes microseconds
+        constexpr int kLoads = 12;
+        for (int base = 0; base < n_cand; base += kLoads * blockDim.x) {
+            float v[kLoads];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kLoads; ++u) {
                 const int i = base + u * blockDim.x + threadIdx.x;
                 v[u] = score(i < n_cand ? i : 0);
             }
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < kLoads; ++u) {
                 const int i = base + u * blockDim.x + threadIdx.x;
-                if (i < n_cand) sh.keys[i] = score_key(v[u]);
+                if (i < n_cand) keys[i] = score_key(v[u]);
             }
         }
         __syncthreads();
     }
-    auto key = [&](int i) -> uint32_t { return in_lds ? sh.keys[i] : score_key(score(i)); };
+    auto key = [&](int i) -> uint32_t { return in_lds ? keys[i] : score_key(score(i)); };
     uint32_t kth;
     int take;
     SEL_STAMP(1);
-    radix_threshold(key, n_cand, k, sh, kth, take);
+    if (keys_ext && in_lds && k > 0) {
+        // a large key set in the caller's LDS: sh.keys is free for the short lists of the sweeps after the second
+        // digit (the two-threshold form, asked for the same rank twice)
+        const int cnt2[2] = {k, k};
+        uint32_t kth2[2];
+        int take2[2];
+        radix_thresholds_lists<2>(key, n_cand, cnt2, sh, kth2, take2);
+        kth = kth2[0], take = take2[0];
+    } else {
+        radix_threshold(key, n_cand, k, sh, kth, take);
+    }
     SEL_STAMP(2);
 
     const int E = (n_cand + blockDim.x - 1) / blockDim.x;
@@ -412,7 +426,7 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
     SEL_STAMP(5);
     // position of a selected element = (# greater before it) + (# admitted equal before it)
     // the channel numbers of this thread's range are requested together, not one trip to memory per element
-    constexpr int kPre = 8;
+    constexpr int kPre = 12;
     int jpre[kPre];
 #pragma unroll
     for (int u = 0; u < kPre; ++u) jpre[u] = lo + u < hi ? cand_idx[lo + u] : 0;
