@@ -587,7 +587,7 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
             // over the step's B rows (Eq. 1-2 with s_k over tokens and samples); every row gets it
             if (shared) POP_HIP(launch_aggregate_scores(L->cscore, m, B, n_cand, s));
             POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx,
-                                L->n_active, nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
+                                L->n_active, nullptr, B > 1 ? L->selflag : nullptr, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
                                 s));
             if (B == 1)
                 POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, 1, L->active_idx, n_ret + kk.k[0], nullptr, L->h,
@@ -620,7 +620,7 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
             if (shared) POP_HIP(launch_aggregate_scores(L->cscore, m, B, n_cand, s));
             // B > 1: the kernel also builds the union of the B selections for the batched down projection
             POP_HIP(launch_topk(L->cscore, m, L->cand_idx, n_cand, n_ret, m, B, kk, m, L->mask, L->active_idx,
-                                L->n_active, nullptr, L->selflag, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
+                                L->n_active, nullptr, B > 1 ? L->selflag : nullptr, L->sync + 8, B > 1 ? L->ulist : nullptr, L->n_ulist,
                                 s));
         }
         L->step_fused = false;
@@ -782,7 +782,11 @@ int pop_layer_get_norms(pop_layer_t *L, float *nrm, void *stream)
 }
 
 #ifdef POP_TRACE
-void pop_trace_set_buffer(void *dev_ptr) { g_trace = (unsigned long long *)dev_ptr; }
+void pop_trace_set_buffer(void *dev_ptr)
+{
+    g_trace = (unsigned long long *)dev_ptr;
+    set_select_trace(g_trace ? g_trace + 1010 * 8 : nullptr);
+}
 #endif
 
 int pop_layer_sync_status(pop_layer_t *L, void *stream)

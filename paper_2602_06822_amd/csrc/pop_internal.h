@@ -109,6 +109,7 @@ struct PartitionExtra {
     unsigned long long *trace = nullptr;  // profiling builds only: timestamps of the kernel's phases, else null
 };
 bool partition_takes_partials(int m);
+void set_select_trace(unsigned long long *p);  // profiling builds: phase stamps of topk_kernel (8 words), or null
 hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, unsigned char *region, int *ret_idx,
                             int *cand_idx, hipStream_t s, const PartitionExtra *extra = nullptr);
 // Per sequence b (grid = B): select k.k[b] of n_cand candidates by cscore[b*cs_stride + i]; writes the candidate

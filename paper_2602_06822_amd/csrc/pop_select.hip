@@ -197,6 +197,9 @@ hipError_t launch_partition(const float *scores, int m, int n_ret, int n_cand, u
 }
 
 // ---------------------------------------------------------------- per-step candidate top-k
+unsigned long long *g_select_trace = nullptr;  // profiling builds: where topk_kernel stamps its phases (else null)
+void set_select_trace(unsigned long long *p) { g_select_trace = p; }
+
 // One workgroup per sequence b.  Only candidate-dependent state is written: the candidate bytes of mask[b][:]
 // and the selected suffix of active_idx[b][:]; the retained / pruned bytes and the retained prefix are constant
 // for a partition (step_state_init_kernel).
@@ -209,18 +212,20 @@ __global__ __launch_bounds__(1024) void topk_kernel(const float *__restrict__ cs
                                                     int *__restrict__ active_idx, int *__restrict__ n_active,
                                                     int *__restrict__ sel_idx, unsigned char *selflag,
                                                     int *union_ctr, int *__restrict__ union_list,
-                                                    int *__restrict__ n_union, int keys_in_ext)
+                                                    int *__restrict__ n_union, int keys_in_ext,
+                                                    unsigned long long *tr)
 {
     __shared__ SelShared sh;
     __shared__ int s_last;
-    extern __shared__ uint32_t topk_keys[];  // [n_cand] when the launch gave it: candidate sets beyond sh.keys
+    extern __shared__ uint32_t topk_keys[];  // [2 n_cand] when the launch gave it: candidate sets beyond sh.keys
     const int b = blockIdx.x, B = gridDim.x, k = kk.k[b];
     unsigned char *mk = mask ? mask + (size_t)b * m : nullptr;
     int *act = active_idx ? active_idx + (size_t)b * act_stride + n_ret : (b == 0 ? sel_idx : nullptr);
     // selflag: [n_cand][POP_MAX_BATCH], one 8-byte word per candidate position
     block_select_candidates(cscore + (size_t)b * cs_stride, cand_idx, n_cand, k, mk, act, sh, SelectNoHook(),
-                            SelectNoHook(), nullptr, selflag ? selflag + b : nullptr, POP_MAX_BATCH, false,
+                            SelectNoHook(), b == 0 ? tr : nullptr, selflag ? selflag + b : nullptr, POP_MAX_BATCH, false,
                             keys_in_ext ? topk_keys : nullptr, keys_in_ext ? n_cand : 0);
+    if (tr && b == 0 && threadIdx.x == 0) tr[6] = wall_clock64();
     if (n_active && threadIdx.x == 0) n_active[b] = n_ret + k;
     if (!union_list) return;
     // the flags of this sequence are written; the last workgroup to get here sees every sequence's flags
@@ -253,8 +258,8 @@ hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, 
 {
     int threads = n_cand <= 2048 ? 256 : 1024;
     // candidate sets beyond the select's own key buffer (re-scoring all channels of a layer) get theirs from the launch
-    const bool ext = n_cand > kSelLdsKeys && n_cand <= kPartLdsKeys;
-    const size_t lds = ext ? (size_t)n_cand * 4 : 0;
+    const bool ext = n_cand > kSelLdsKeys && n_cand <= 16384;  // (keys and staged decisions: 8 bytes per candidate)
+    const size_t lds = ext ? (size_t)n_cand * 8 : 0;
     if (lds > 32 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -262,7 +267,7 @@ hipError_t launch_topk(const float *cscore, int cs_stride, const int *cand_idx, 
     }
     hipLaunchKernelGGL(topk_kernel, dim3(B), dim3(threads), lds, s, cscore, cs_stride, cand_idx, n_cand, n_ret, m, k,
                        act_stride, mask, active_idx, n_active, sel_idx, selflag, union_ctr, union_list, n_union,
-                       ext ? 1 : 0);
+                       ext ? 1 : 0, g_select_trace);
     return hipGetLastError();
 }
 

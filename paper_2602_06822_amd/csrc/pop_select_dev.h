@@ -364,10 +364,21 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
         return kCoherentScores ? __hip_atomic_load(&cs[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : cs[i];
     };
     // keys_ready: the caller has put score_key(score) of every candidate into sh.keys (n_cand <= kSelLdsKeys) and
-    // synchronised the block.  keys_ext: LDS of the caller's for keys_cap keys, used instead of sh.keys (a large
-    // candidate set then stays out of global memory after the first sweep as well)
+    // synchronised the block.  keys_ext: LDS of the caller's, 2 * keys_cap words, used instead of sh.keys (a large
+    // candidate set then stays out of global memory after the first sweep as well; the second half stages the
+    // decisions for the output pass)
     uint32_t *const keys = keys_ext ? keys_ext : sh.keys;
     const bool in_lds = n_cand <= (keys_ext ? keys_cap : kSelLdsKeys);
+    // (large sets: the channel numbers the output pass needs are requested now, so that they are there by then)
+    constexpr int kAhead = 12;
+    int jj[kAhead];
+    if (keys_ext && in_lds) {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int i = u * blockDim.x + threadIdx.x;
+            jj[u] = i < n_cand ? cand_idx[i] : 0;
+        }
+    }
     if (in_lds && !keys_ready) {
         // twelve independent loads in flight per thread: under a streaming load a trip to memory takes microseconds
         constexpr int kLoads = 12;
@@ -425,6 +436,46 @@ __device__ __forceinline__ void block_select_candidates(const float *__restrict_
     after_selected();
     SEL_STAMP(5);
     // position of a selected element = (# greater before it) + (# admitted equal before it)
+    if (keys_ext && in_lds) {
+        // Large sets (the caller's LDS holds n_cand more words behind the keys): every thread leaves the decisions of
+        // its contiguous range in LDS - the position among the selected, or -1 - and the outputs are then written
+        // by consecutive threads for consecutive candidates: whole cache lines instead of one byte per lane 11 apart.
+        int *code = reinterpret_cast<int *>(keys_ext + n_cand);
+        int eq = cnt[0], gt = cnt[1];
+        for (int i = lo; i < hi; ++i) {
+            const uint32_t kv = key(i);
+            const bool sel = (kv > kth) || (kv == kth && eq < take);
+            code[i] = sel ? gt + min(eq, take) : -1;
+            eq += (kv == kth);
+            gt += (kv > kth);
+        }
+        __syncthreads();
+        for (int base = 0; base < n_cand; base += kAhead * blockDim.x) {
+            if (base > 0) {  // (beyond what was requested at the start)
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int i = base + u * blockDim.x + threadIdx.x;
+                    jj[u] = i < n_cand ? cand_idx[i] : 0;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int i = base + u * blockDim.x + threadIdx.x;
+                if (i < n_cand) {
+                    const int c = code[i];
+                    if (mk) mk[jj[u]] = c >= 0 ? 1 : 0;
+                    if (selpos) {
+                        if (kCoherentFlags)
+                            coherent_store(&selpos[(size_t)i * selpos_stride], (unsigned char)(c >= 0 ? 1 : 0));
+                        else
+                            selpos[(size_t)i * selpos_stride] = c >= 0 ? 1 : 0;
+                    }
+                    if (c >= 0 && act_sel) act_sel[c] = jj[u];
+                }
+            }
+        }
+        return;
+    }
     // the channel numbers of this thread's range are requested together, not one trip to memory per element
     constexpr int kPre = 12;
     int jpre[kPre];
