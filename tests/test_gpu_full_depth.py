@@ -49,7 +49,7 @@ def test_config3_stack_32_layers_prompt_2048(pop, oracle):
     """The 32-layer stack of Llama-2-7B-shaped layers as the configuration states it: independent weights and inputs
     per layer, 2048-token prompts, one stream, four decode tokens through all 32 layers.  Every layer's step is
     checked against the oracle in the two-call form; then the same tokens run as one captured graph of 32
-    single-launch steps, replayed per token, and every layer's replayed mask, scores and output are checked again."""
+    one-call steps, replayed per token, and every layer's replayed mask, scores and output are checked again."""
     cfg, n_layers, T, steps, r = synth.CFG3, 32, 2048, 4, 0.35
     d, m = cfg.d, cfg.m
     n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r, 0.10)
@@ -70,7 +70,7 @@ def test_config3_stack_32_layers_prompt_2048(pop, oracle):
             for li, (L, G) in enumerate(zip(host_layers, stack)):
                 eager[t][li] = _check_decode(oracle, G, L, G.part[0], G.part[1], xts[li][t:t + 1], k)
             print(f"cfg3 token {t}: 32 layers ok (two calls)", flush=True)
-        # one graph of 32 single-launch steps
+        # one graph of 32 one-call steps
         side = torch.cuda.Stream()
         x_in = [torch.zeros(d, dtype=torch.int16, device="cuda") for _ in stack]
         y_g = [torch.zeros(d, dtype=torch.int16, device="cuda") for _ in stack]

@@ -633,9 +633,10 @@ def test_forward_pass_scratch_poisoned_and_side_stream(pop, oracle):
             side.synchronize()
 
 
-def test_single_launch_step_replays_from_a_graph(pop):
-    """The one-launch step keeps no per-launch state on the host: a captured launch is replayed several times,
-    with eager steps in between, and every replay must reproduce the eager result bit for bit."""
+def test_one_call_step_replays_from_a_graph(pop):
+    """The one-call step (fused kernel and tail kernel) keeps no per-launch state on the host: a captured step is
+    replayed several times, with eager steps in between, and every replay must reproduce the eager result bit for
+    bit."""
     d, m, T = 512, 1024, 32
     L = synth.make_layer(synth.small_config("graph_replay", d, m, BF16, n_outlier=2, heavy_tail=True))
     x = synth.make_activations(L, T, "prompt")
