@@ -224,6 +224,37 @@ def test_fused_step_many_rounds_per_workgroup(pop, oracle, monkeypatch, dtype, w
                 assert np.array_equal(first[key], again[key]), key
 
 
+@pytest.mark.parametrize("dtype,wgs", [(BF16, 4), (F32, 6)])
+def test_fused_step_input_side_many_candidate_slots(pop, oracle, monkeypatch, dtype, wgs):
+    """The input-side reading in the fused kernel with few workgroups: many candidate slots each, so rounds of
+    candidates only (four per round, two of them in the retained channels' buffers) and a last round of one to
+    three; candidate scores, selection, h of the active channels and y against the oracle."""
+    monkeypatch.setenv("POP_FUSED_WGS", str(wgs))
+    d, m, T = 512, 768, 40
+    L = synth.make_layer(synth.small_config(f"input_side_slots_{wgs}", d, m, dtype, n_outlier=2, heavy_tail=dtype == BF16))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 4, "decode")
+    for f_cand in (0.1, 0.123):  # 77 and 94 candidates: different remainders of four per workgroup
+        n_ret, n_cand, _ = pop.pop_region_counts(m, 0.3, f_cand)
+        with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+            pop.pop_layer_set_importance(G.handle, pop.POP_IMPORTANCE_INPUT_SIDE)
+            scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+            r1, _, cand1 = oracle.partition(scores, n_ret, n_cand)
+            assert np.array_equal(region, r1) and np.array_equal(cand, cand1)
+            for t, k in enumerate([n_cand // 2, 0, n_cand, 1]):
+                out = G.decode(xt[t:t + 1], k, one_call=bool(t % 2))
+                assert pop.pop_layer_step_kind(G.handle) == (1, wgs)
+                c_ref = oracle.importance_input_side(xt[t:t + 1], L.w_gate, L.w_up, dtype, chan=cand)[cand]
+                assert score_rel_err(out["cscore"][0], c_ref, eps=1e-6) <= SCORE_TOL
+                mask1, _, act1 = oracle.select(region, out["cscore"][0], cand, k)
+                assert np.array_equal(out["mask"][0], mask1)
+                assert np.array_equal(out["active_idx"][0][:n_ret + k], act1)
+                active = np.flatnonzero(mask1).astype(np.int32)
+                H = oracle.hidden(xt[t:t + 1], L.w_gate, L.w_up, dtype, chan=active)
+                assert score_rel_err(out["h"][0][active], H[0][active], eps=DECODE_FLOOR[dtype]) <= SCORE_TOL
+                assert max_abs_rel(out["y"][0], oracle.down(H, L.w_down, dtype, mask1)[0]) <= Y_TOL[dtype]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_degenerate_partitions(pop, oracle, dtype):
     d, m, T = 128, 90, 20
