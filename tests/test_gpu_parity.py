@@ -255,6 +255,35 @@ def test_fused_step_input_side_many_candidate_slots(pop, oracle, monkeypatch, dt
                 assert max_abs_rel(out["y"][0], oracle.down(H, L.w_down, dtype, mask1)[0]) <= Y_TOL[dtype]
 
 
+def test_large_candidate_sets(pop, oracle, monkeypatch):
+    """Candidate sets beyond the selection's own key buffer (4096 keys): a layer of many channels and a short hidden
+    size, most channels candidates.  One sequence and a batch of three with different k (the separate top-k launch with
+    its keys and decisions in launch-provided LDS; the batch also through the selection inside the gate/up launch),
+    and the input-side reading of the same layer."""
+    d, m, T = 128, 6000, 24
+    L = synth.make_layer(synth.small_config("large_cand", d, m, BF16, n_outlier=2, heavy_tail=True))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 4, "decode")
+    n_ret, n_cand = 700, 5000
+    with GpuLayer(pop, L, max_tokens=T, max_batch=3) as G:
+        scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        for k in (2500, 1, n_cand):
+            _check_decode(oracle, G, L, region, cand, xt[:1], k)
+        _check_decode(oracle, G, L, region, cand, xt[1:4], [2500, 0, 4999])
+        pop.pop_layer_set_importance(G.handle, pop.POP_IMPORTANCE_INPUT_SIDE)
+        scores, region, ret, cand = G.prefill(x, n_ret, n_cand)
+        out = G.decode(xt[1:4], [2500, 7, n_cand])
+        for b, k in enumerate([2500, 7, n_cand]):
+            c_ref = oracle.importance_input_side(xt[1 + b:2 + b], L.w_gate, L.w_up, BF16, chan=cand)[cand]
+            assert score_rel_err(out["cscore"][b], c_ref, eps=1e-6) <= SCORE_TOL
+            mask1, _, act1 = oracle.select(region, out["cscore"][b], cand, k)
+            assert np.array_equal(out["mask"][b], mask1)
+            assert np.array_equal(out["active_idx"][b][:n_ret + k], act1)
+            active = np.flatnonzero(mask1).astype(np.int32)
+            H = oracle.hidden(xt[1 + b:2 + b], L.w_gate, L.w_up, BF16, chan=active)
+            assert max_abs_rel(out["y"][b], oracle.down(H, L.w_down, BF16, mask1)[0]) <= Y_TOL[BF16]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 def test_degenerate_partitions(pop, oracle, dtype):
     d, m, T = 128, 90, 20
