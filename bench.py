@@ -181,6 +181,15 @@ def run(args):
     # the timed region proper: every step through the one-call entry point (pop_decode_step: the fused kernel and the
     # small kernel that sums its partial outputs), nothing between the calls.  A separate, shorter pass brackets every
     # n-th step's two calls with events (which costs that step its overlap with the next launch) for the percentiles.
+    if args.variant2_only:
+        # only the step that re-scores every channel (Variant 2: top-k over all m keys; batch-general kernels), for a
+        # kernel trace of its launches
+        cnt = pop.pop_strategy_counts(pop.POP_STRATEGY_RESCORE_ALL, m, r_main, 0.0)
+        t = timed(cnt, max(1, args.steps // 4), 1)["decode_us_per_token"]
+        print(json.dumps({"variant2_rescore_all": dict(n_ret=cnt[0], n_cand=cnt[1], k=cnt[2], us_per_token=round(t, 3))}))
+        for L in layers:
+            L.close()
+        return
     main = timed(r_main, args.steps, args.warmup, single=True)
     probed = timed(r_main, max(1, args.steps // 4), 1, probe_every=args.probe_every)
     for key in ("probe_mask_us", "probe_ffn_us", "probe_token_us_p10_p50_p90"):
@@ -665,6 +674,8 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true", help="also run three 256 MiB device copies")
     ap.add_argument("--other-shapes-only", action="store_true",
                     help="run only the 13B-shaped (B = 1, 4, 8) and Mixtral-expert timings")
+    ap.add_argument("--variant2-only", action="store_true",
+                    help="run only the decode step that re-scores all channels (ablation Variant 2)")
     ap.add_argument("--stack-only", action="store_true",
                     help="run only the 32-layer stack: eager two-call steps, eager one-call steps, captured graph")
     ap.add_argument("--forward", action="store_true", help="with --quick: keep the prefill-forward section")
