@@ -79,6 +79,9 @@ int pop_k_for_ratio(int m, double r, int n_ret, int n_cand, int *k);
  * Errors: a band that leaves [0, 1] or an unknown strategy -> POP_EINVAL. */
 enum { POP_STRATEGY_POP = 0, POP_STRATEGY_STATIC_MASK = 1, POP_STRATEGY_RESCORE_ALL = 2 };
 int pop_strategy_counts(int strategy, int m, double r, double gamma, int *n_ret, int *n_cand, int *k);
+/* Value for n_ret, n_cand (both), k0 and - as a NULL pointer - k in the calls below: "what the layer's strategy says"
+ * (pop_layer_set_strategy). */
+enum { POP_FROM_STRATEGY = -1 };
 
 /* Create a layer.  w_gate, w_up: dev [m][d]; w_down: dev [d][m]; all of dtype wdtype, read once, on `stream`,
  * and repacked channel-major (one contiguous gate+up row pair and one contiguous down column per channel).
@@ -211,6 +214,13 @@ int pop_layer_get_norms(pop_layer_t *layer, float *nrm, void *stream);
  * it).  The record is cleared by the report.  Every kernel exits either way; this call is how a caller finds out. */
 int pop_layer_sync_status(pop_layer_t *layer, void *stream);
 int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
+/* Host only.  Makes one of the ablation's decode strategies (Sec. 5, trade-off table; see pop_strategy_counts) the
+ * layer's mode at sparsity r (and band gamma for POP_STRATEGY_POP): pop_prefill_partition and pop_prefill_forward
+ * called with n_ret = n_cand = POP_FROM_STRATEGY (and k0 = POP_FROM_STRATEGY) then take the strategy's region sizes
+ * (and its k), and pop_decode_mask / pop_decode_step called with k == NULL select the strategy's k for every
+ * sequence.  Explicit counts keep working next to it.  Does not touch an existing partition.
+ * Errors: as pop_strategy_counts; without a strategy the sentinels give POP_ESTATE (prefill) / POP_EINVAL (k). */
+int pop_layer_set_strategy(pop_layer_t *layer, int strategy, double r, double gamma);
 /* Host only.  How many times a bounded in-kernel wait of the fused single-sequence decode step (Sec. 3.4: its
  * workgroups hand each other the candidates' h and the selection) looks for what it waits for before it gives
  * up (default 65536: a fraction of a second).  A wait that gives up flags the step (pop_layer_sync_status:

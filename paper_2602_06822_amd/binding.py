@@ -36,6 +36,7 @@ _SIGS = {
     "pop_region_counts": (_i, [_i, _dbl, _dbl, _ip, _ip, _ip]),
     "pop_k_for_ratio": (_i, [_i, _dbl, _i, _i, _ip]),
     "pop_strategy_counts": (_i, [_i, _i, _dbl, _dbl, _ip, _ip, _ip]),
+    "pop_layer_set_strategy": (_i, [_vp, _i, _dbl, _dbl]),
     "pop_layer_create": (_i, [C.POINTER(_vp), _i, _i, _i, _vp, _vp, _vp, _i, _i, _vp]),
     "pop_layer_destroy": (_i, [_vp]),
     "pop_prefill_partition": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
@@ -159,6 +160,8 @@ def pop_prefill_forward(layer, x, T, n_ret, n_cand, k0, y, ydtype, scores=None, 
 
 
 def _k_array(k, B):
+    if k is None:  # the layer's strategy decides (pop_layer_set_strategy)
+        return None
     if isinstance(k, int):
         k = [k] * B
     return (C.c_int * len(k))(*k)
@@ -229,6 +232,13 @@ def pop_layer_get_hidden(layer, h, B, stream=None):
 
 def pop_layer_sync_status(layer, stream=None):
     _check(_lib.pop_layer_sync_status(layer, _stream(stream)), "pop_layer_sync_status")
+
+
+POP_FROM_STRATEGY = -1
+
+
+def pop_layer_set_strategy(layer, strategy: int, r: float, gamma: float = 0.0):
+    _check(_lib.pop_layer_set_strategy(layer, strategy, r, gamma), "pop_layer_set_strategy")
 
 
 def pop_layer_set_wait_limit(layer, looks: int):

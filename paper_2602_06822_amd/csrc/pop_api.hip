@@ -63,6 +63,7 @@ struct pop_layer {
     int *rc_idx = nullptr;             // [m]: candidates then retained
     // decode step
     bool has_step = false, step_fused = false, ulist_prefix_ok = false;
+    int strat_n_ret = -1, strat_n_cand = -1, strat_k = -1;  // decode strategy of the layer (pop_layer_set_strategy)
     int step_B = 0;
     bool fused_ok = false;             // the fused kernel supports this partition
     FusedPlan plan = {};
@@ -468,6 +469,10 @@ int pop_prefill_partition(pop_layer_t *L, const void *x, int T, int n_ret, int n
     if (!L) return POP_EINVAL;
     if (T < 0 || T > L->max_tokens) return POP_ESHAPE;
     if (T > 0 && (!x || !aligned16(x))) return POP_EINVAL;
+    if (n_ret == POP_FROM_STRATEGY && n_cand == POP_FROM_STRATEGY) {
+        if (L->strat_n_ret < 0) return POP_ESTATE;
+        n_ret = L->strat_n_ret, n_cand = L->strat_n_cand;
+    }
     if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
     hipStream_t s = as_stream(stream);
     const int m = L->m;
@@ -495,6 +500,11 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
     if (T < 0 || T > L->max_tokens) return POP_ESHAPE;
     if (T > 0 && (!x || !y || !aligned16(x) || !aligned16(y))) return POP_EINVAL;
     if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
+    if (n_ret == POP_FROM_STRATEGY && n_cand == POP_FROM_STRATEGY) {
+        if (L->strat_n_ret < 0) return POP_ESTATE;
+        n_ret = L->strat_n_ret, n_cand = L->strat_n_cand;
+        if (k0 == POP_FROM_STRATEGY) k0 = L->strat_k;
+    }
     if (n_ret < 0 || n_cand < 0 || (long long)n_ret + n_cand > L->m) return POP_ESHAPE;
     if (k0 < 0 || k0 > n_cand) return POP_ESHAPE;
     hipStream_t s = as_stream(stream);
@@ -552,13 +562,15 @@ int pop_prefill_forward(pop_layer_t *L, const void *x, int T, int n_ret, int n_c
 int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float *cand_scores, unsigned char *mask,
                     int *active_idx, int *n_active, void *stream)
 {
-    if (!L || !x_t || !k || !aligned16(x_t)) return POP_EINVAL;
+    if (!L || !x_t || !aligned16(x_t)) return POP_EINVAL;
     if (!L->has_partition) return POP_ESTATE;
+    if (!k && L->strat_k < 0) return POP_EINVAL;  // no per-sequence counts and no strategy to take them from
     if (B < 1 || B > L->max_batch) return POP_ESHAPE;
     BatchK kk = {};
     for (int b = 0; b < B; ++b) {
-        if (k[b] < 0 || k[b] > L->n_cand) return POP_ESHAPE;
-        kk.k[b] = k[b];
+        const int kb = k ? k[b] : L->strat_k;
+        if (kb < 0 || kb > L->n_cand) return POP_ESHAPE;
+        kk.k[b] = kb;
     }
     hipStream_t s = as_stream(stream);
     const int m = L->m, n_ret = L->n_ret, n_cand = L->n_cand;
@@ -635,12 +647,15 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
 int pop_decode_step(pop_layer_t *L, const void *x_t, int B, const int *k, void *y, pop_dtype_t ydtype,
                     float *cand_scores, unsigned char *mask, int *active_idx, int *n_active, void *stream)
 {
-    if (!L || !x_t || !k || !y || !aligned16(x_t) || !aligned16(y)) return POP_EINVAL;
+    if (!L || !x_t || !y || !aligned16(x_t) || !aligned16(y)) return POP_EINVAL;
     if (ydtype != POP_F32 && ydtype != POP_BF16) return POP_EINVAL;
     if (!L->has_partition) return POP_ESTATE;
+    if (!k && L->strat_k < 0) return POP_EINVAL;
     if (B < 1 || B > L->max_batch) return POP_ESHAPE;
-    for (int b = 0; b < B; ++b)
-        if (k[b] < 0 || k[b] > L->n_cand) return POP_ESHAPE;
+    for (int b = 0; b < B; ++b) {
+        const int kb = k ? k[b] : L->strat_k;
+        if (kb < 0 || kb > L->n_cand) return POP_ESHAPE;
+    }
     // the launches of the two calls (a single-sequence step on a shape the fused kernel takes: that kernel, then the
     // small kernel that sums its workgroups' partial outputs)
     int rc = pop_decode_mask(L, x_t, B, k, cand_scores, mask, active_idx, n_active, stream);
@@ -823,6 +838,16 @@ int pop_layer_set_shared_batch_mask(pop_layer_t *L, int on)
     if (!L) return POP_EINVAL;
     L->shared_mask = on != 0;
     L->has_step = false;
+    return POP_OK;
+}
+
+int pop_layer_set_strategy(pop_layer_t *L, int strategy, double r, double gamma)
+{
+    if (!L) return POP_EINVAL;
+    int n_ret = 0, n_cand = 0, k = 0;
+    const int rc = pop_strategy_counts(strategy, L->m, r, gamma, &n_ret, &n_cand, &k);
+    if (rc != POP_OK) return rc;
+    L->strat_n_ret = n_ret, L->strat_n_cand = n_cand, L->strat_k = k;
     return POP_OK;
 }
 

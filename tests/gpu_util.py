@@ -83,7 +83,7 @@ class GpuLayer:
         """x_t: [B][d] storage.  Returns dict of host arrays (cscore, mask, active_idx, n_active, h, y).
         one_call: use pop_decode_step instead of pop_decode_mask + pop_pruned_ffn."""
         B = x_t.shape[0]
-        ks = [k] * B if isinstance(k, int) else list(k)
+        ks = None if k is None else ([k] * B if isinstance(k, int) else list(k))  # None: the layer's strategy decides
         n_ret, n_cand, m, d = self.n_ret, self.n_cand, self.m, self.d
         cs = torch.empty((B, max(n_cand, 1)), dtype=torch.float32, device="cuda")
         mask = torch.empty((B, m), dtype=torch.uint8, device="cuda")

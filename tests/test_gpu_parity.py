@@ -255,6 +255,46 @@ def test_fused_step_input_side_many_candidate_slots(pop, oracle, monkeypatch, dt
                 assert max_abs_rel(out["y"][0], oracle.down(H, L.w_down, dtype, mask1)[0]) <= Y_TOL[dtype]
 
 
+@pytest.mark.parametrize("strategy,gamma", [(0, 0.1), (0, 0.2), (1, 0.0), (2, 0.0)])
+def test_strategy_as_layer_mode(pop, oracle, strategy, gamma):
+    """The ablation's decode strategies as a mode of the layer: after pop_layer_set_strategy the sentinel counts give
+    the partition, the prompt's forward pass and the steps of the explicit counts of pop_strategy_counts, bit for
+    bit; without a strategy the sentinels are refused."""
+    d, m, T, r = 256, 640, 40, 0.4
+    L = synth.make_layer(synth.small_config(f"mode_{strategy}_{gamma}", d, m, BF16, n_outlier=2, heavy_tail=True))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 3, "decode")
+    n_ret, n_cand, k = pop.pop_strategy_counts(strategy, m, r, gamma)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=3) as G:
+        with pytest.raises(pop.PopError) as e:
+            pop.pop_prefill_partition(G.handle, dev(x), T, pop.POP_FROM_STRATEGY, pop.POP_FROM_STRATEGY)
+        assert e.value.status == pop.POP_ESTATE
+        explicit = G.prefill(x, n_ret, n_cand)
+        steps = [G.decode(xt[:1], k), G.decode(xt, k, one_call=True)]
+        fwd = G.prefill_forward(x, n_ret, n_cand, k, F32)
+        with pytest.raises(pop.PopError) as e:
+            G.decode(xt[:1], None)
+        assert e.value.status == pop.POP_EINVAL
+        with pytest.raises(pop.PopError):
+            pop.pop_layer_set_strategy(G.handle, 7, r, gamma)
+        pop.pop_layer_set_strategy(G.handle, strategy, r, gamma)
+        scores = torch.empty(m, dtype=torch.float32, device="cuda")
+        region = torch.empty(m, dtype=torch.uint8, device="cuda")
+        pop.pop_prefill_partition(G.handle, dev(x), T, pop.POP_FROM_STRATEGY, pop.POP_FROM_STRATEGY, scores, region)
+        assert np.array_equal(host(scores), explicit[0]) and np.array_equal(host(region), explicit[1])
+        for ref, (xb, one) in zip(steps, ((xt[:1], False), (xt, True))):
+            got = G.decode(xb, None, one_call=one)
+            for key in ("mask", "active_idx", "n_active", "cscore", "y"):
+                assert np.array_equal(got[key], ref[key]), key
+        y = torch.empty((T, d), dtype=torch.float32, device="cuda")
+        mask = torch.empty(m, dtype=torch.uint8, device="cuda")
+        pop.pop_prefill_forward(G.handle, dev(x), T, pop.POP_FROM_STRATEGY, pop.POP_FROM_STRATEGY, pop.POP_FROM_STRATEGY,
+                                y, F32, None, None, None, None, mask)
+        assert np.array_equal(host(mask), fwd[4]) and np.array_equal(host(y).astype(np.float64), fwd[5])
+        # and against the oracle: the mode's steps are the method's steps with those counts
+        _check_decode(oracle, G, L, explicit[1], explicit[3], xt[:1], k)
+
+
 def test_large_candidate_sets(pop, oracle, monkeypatch):
     """Candidate sets beyond the selection's own key buffer (4096 keys): a layer of many channels and a short hidden
     size, most channels candidates.  One sequence and a batch of three with different k (the separate top-k launch with
