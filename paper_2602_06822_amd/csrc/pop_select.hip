@@ -164,7 +164,11 @@ __global__ __launch_bounds__(1024) void partition_kernel(const float *__restrict
         const int cnt[2] = {max(n_ret, 1), max(n_ret + n_cand, 1)};
         uint32_t kth2[2];
         int take2[2];
+#ifdef POP_TRACE
+        radix_thresholds_lists<2>(key, m, cnt, sh, kth2, take2, in_lds, diff, ex.trace ? ex.trace + 4 : nullptr);
+#else
         radix_thresholds_lists<2>(key, m, cnt, sh, kth2, take2, in_lds, diff);
+#endif
         kth[0] = kth2[0], kth[1] = kth2[1], take[0] = take2[0], take[1] = take2[1];
     }
     if (n_ret == 0) kth[0] = 0xffffffffu, take[0] = 0;

@@ -200,7 +200,7 @@ __device__ __forceinline__ void radix_threshold(KeyFn key, int n, int n_top, Sel
 template <int NT, class KeyFn>
 __device__ __forceinline__ void radix_thresholds_lists(KeyFn key, int n, const int (&n_top)[NT], SelShared &sh,
                                                        uint32_t (&kth)[NT], int (&take)[NT], bool have_diff = false,
-                                                       uint32_t diff_in = 0)
+                                                       uint32_t diff_in = 0, unsigned long long *tr = nullptr)
 {
     static_assert(NT == 2 || NT == 3, "two or three thresholds");
     constexpr int kCap = kSelLdsKeys / NT;
@@ -300,6 +300,7 @@ __device__ __forceinline__ void radix_thresholds_lists(KeyFn key, int n, const i
             }
         }
         __syncthreads();
+        if (tr && threadIdx.x == 0 && pass < 4) tr[pass] = wall_clock64();  // (profiling builds: the sweep is done)
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             int c[4], lane_tot = 0;
