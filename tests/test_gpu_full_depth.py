@@ -233,3 +233,33 @@ def test_prefill_alternating_prompt_lengths_on_one_layer(pop, oracle):
                     first = got
                 else:
                     assert all(np.array_equal(a, b) for a, b in zip(first, got))
+
+
+@pytest.mark.timeout(600)
+def test_config2_every_step_of_the_benchmark_workload(pop, oracle):
+    """configs[1] as bench.py runs it: eight Llama-2-7B-shaped layers, a 512-token prompt each, then all 128 decode
+    tokens, alternating the two call forms.  Every step of every layer against the oracle: h and candidate scores,
+    the mask and active list byte for byte from the device's own float32 scores, y under that mask."""
+    cfg = synth.CFG2
+    n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, cfg.m, 0.35, 0.10)
+    worst = dict(h=0.0, cscore=0.0, y=0.0)
+    for li in range(8):
+        L = synth.make_layer(cfg, li)
+        x = synth.make_activations(L, 512, "prompt", li)
+        xd = synth.make_activations(L, 128, "decode", li)
+        with GpuLayer(pop, L, max_tokens=512, max_batch=1) as G:
+            scores, region, _, cand = _prefill_checked(oracle, G, L, x, n_ret, n_cand, f"cfg2_bench_layer{li}", n_sample=4)
+            rc = region != 2
+            for t in range(128):
+                out = G.decode(xd[t:t + 1], k, one_call=bool(t & 1))
+                ref = oracle.decode(xd[t], L.w_gate, L.w_up, L.w_down, BF16, region, cand, k, want_y=False)
+                worst["h"] = max(worst["h"], score_rel_err(out["h"][0][rc], ref["h"][rc], eps=DECODE_FLOOR[BF16]))
+                worst["cscore"] = max(worst["cscore"],
+                                      score_rel_err(out["cscore"][0], ref["cscore"], eps=DECODE_FLOOR[BF16]))
+                mask1, _, act1 = oracle.select(region, out["cscore"][0], cand, k)
+                assert np.array_equal(out["mask"][0], mask1), (li, t)
+                assert np.array_equal(out["active_idx"][0][:n_ret + k], act1), (li, t)
+                y_ref = oracle.down(ref["h"].reshape(1, -1), L.w_down, BF16, mask1)[0]
+                worst["y"] = max(worst["y"], max_abs_rel(out["y"][0], y_ref))
+        print(f"cfg2 layer {li}: 128 steps ok, worst so far {worst}", flush=True)
+    assert worst["h"] <= SCORE_TOL and worst["cscore"] <= SCORE_TOL and worst["y"] <= Y_TOL[BF16], worst
