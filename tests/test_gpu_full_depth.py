@@ -263,3 +263,11 @@ def test_config2_every_step_of_the_benchmark_workload(pop, oracle):
                 worst["y"] = max(worst["y"], max_abs_rel(out["y"][0], y_ref))
         print(f"cfg2 layer {li}: 128 steps ok, worst so far {worst}", flush=True)
     assert worst["h"] <= SCORE_TOL and worst["cscore"] <= SCORE_TOL and worst["y"] <= Y_TOL[BF16], worst
+
+
+@pytest.mark.timeout(900)
+def test_config5_moe_layer_all_decode_steps(pop, oracle):
+    """configs[4] at full depth: the 8-expert top-2 layer of Mixtral-shaped experts, prompt 1024, all 128 decode steps
+    (each token through its two experts, outputs combined with the router's weights) against the oracle."""
+    from test_gpu_parity import _moe_case
+    _moe_case(pop, oracle, synth.CFG5, 8, 1024, 128, 0.35, n_sample=8)
