@@ -108,13 +108,14 @@ def test_config3_stack_32_layers_prompt_2048(pop, oracle):
 
 @pytest.mark.timeout(900)
 def test_config4_stack_13b_batched(pop, oracle):
-    """Eight of the 40 Llama-2-13B-shaped layers (spread over the stack), 1024-token prompts, decode at B = 1, 4, 8
-    with a different k per sequence, two steps each on one stream; and the one-mask-per-batch mode at this size."""
+    """The stack of 40 Llama-2-13B-shaped layers (independent weights, inputs and partitions), 1024-token prompts,
+    decode at B = 1, 4, 8 with a different k per sequence on one stream - a step on every layer, a second one on every
+    fifth -; and the one-mask-per-batch mode at this size."""
     cfg, T, r = synth.CFG4, 1024, 0.50
     m = cfg.m
-    ids = [0, 5, 11, 17, 23, 29, 34, 39]
+    ids = list(range(40))
     n_ret, n_cand, k = pop.pop_strategy_counts(pop.POP_STRATEGY_POP, m, r, 0.10)
-    host_layers = synth.make_layers(cfg, ids, workers=8)
+    host_layers = synth.make_layers(cfg, ids, workers=16)
     stack = []
     try:
         for L, li in zip(host_layers, ids):
@@ -127,10 +128,12 @@ def test_config4_stack_13b_batched(pop, oracle):
         for step in range(2):
             for B in (1, 4, 8):
                 ks = [k] * B if B == 1 else [max(0, min(n_cand, k + 7 * b - 11)) for b in range(B)]
-                for L, li, G in zip(host_layers, ids, stack):
+                done = 0
+                for L, li, G in list(zip(host_layers, ids, stack))[::1 if step == 0 else 5]:
                     xt = synth.make_activations(L, 2 * B, f"decode_b{B}", li)[step * B:(step + 1) * B]
                     _check_decode(oracle, G, L, G.part[0], G.part[1], xt, ks)
-                print(f"cfg4 step {step} B={B}: {len(ids)} layers ok", flush=True)
+                    done += 1
+                print(f"cfg4 step {step} B={B}: {done} layers ok", flush=True)
         # one mask for the batch (Eq. 3's activation norm over the step's sequences) on two of the layers
         B = 8
         for L, li, G in list(zip(host_layers, ids, stack))[:2]:
