@@ -174,6 +174,21 @@ def test_input_side_importance_against_norms_and_loops(oracle, dtype):
     assert part[3] == I[3] and part[9] == I[9] and not part[[0, 1, 2, 4]].any()
 
 
+def test_input_side_importance_over_rows_is_the_root_of_the_rows_squared_scores(oracle):
+    """The input-side importance over several rows (a prompt, or the sequences of one batched step) equals the root
+    of the sum of the squared single-row importances: what the batch-wide mask of that reading is built from."""
+    d, m, T = 20, 26, 6
+    L = _tiny_layer(d, m, BF16, "inside_rows")
+    x = synth.make_activations(L, T, "inside_rows")
+    whole = oracle.importance_input_side(x, L.w_gate, L.w_up, BF16)
+    rows = np.stack([oracle.importance_input_side(x[t:t + 1], L.w_gate, L.w_up, BF16) for t in range(T)])
+    np.testing.assert_allclose(whole, np.sqrt((rows ** 2).sum(axis=0)), rtol=1e-12)
+    # and the output-side counterpart (Eq. 3 over the step's sequences): n_j * ||h_{:,j}|| from the per-row n_j |h_bj|
+    H = oracle.hidden(x, L.w_gate, L.w_up, BF16)
+    per_row = np.stack([oracle.importance(L.w_down, BF16, H[t:t + 1]) for t in range(T)])
+    np.testing.assert_allclose(oracle.importance(L.w_down, BF16, H), np.sqrt((per_row ** 2).sum(axis=0)), rtol=1e-12)
+
+
 def test_input_side_importance_closed_forms(oracle):
     """One-hot input: I_j = |c| * hypot(W_gate[j,k0], W_up[j,k0]).  All-ones input over T tokens with W_up = 0:
     I_j = sqrt(T) * ||W_gate[j,:]||.  Scaling x by a scales every score by |a|; scaling one channel's rows by b
