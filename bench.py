@@ -455,18 +455,21 @@ def time_layer_stack(pop, synth, lib, bench_layers, cnt, n_layers):
     d = cfg.d
     to_dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda()  # noqa: E731
     hs, xs = [], []
+    t_stack = 2048  # configs[2]'s prompt length (it shapes the partitions; the decode steps do not depend on it)
+    prompts = [to_dev(synth.make_activations(src.host_layer, t_stack, "prompt_stack", i))
+               for i, src in enumerate(bench_layers)]
     for i in range(n_layers):
         src = bench_layers[i % len(bench_layers)]
         L = src.host_layer
         h = pop.pop_layer_create(cfg.d, cfg.m, pop.POP_BF16, to_dev(L.w_gate), to_dev(L.w_up), to_dev(L.w_down),
-                                 PROMPT, 1)
-        pop.pop_prefill_partition(h, src.x_prompt, PROMPT, n_ret, n_cand)
+                                 t_stack, 1)
+        pop.pop_prefill_partition(h, prompts[i % len(bench_layers)], t_stack, n_ret, n_cand)
         hs.append(h)
         xs.append(src.x_decode[i // len(bench_layers)].clone())
     y = torch.empty(d, dtype=torch.int16, device="cuda")
     karr = (C.c_int * 1)(k)
     side = torch.cuda.Stream()
-    out = {"layers": n_layers}
+    out = {"layers": n_layers, "prompt_tokens": t_stack}
     torch.cuda.synchronize()
 
     def token(sp, single):
