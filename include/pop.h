@@ -152,7 +152,8 @@ int pop_pruned_ffn(pop_layer_t *layer, const void *x, int T, const unsigned char
  * It issues exactly those two calls' launches.  A B == 1 step on a shape the fused single-sequence kernel takes is
  * two launches: that kernel, whose workgroups hand each other the candidates' h and the selection inside the launch,
  * and a small kernel that sums their partial outputs.  Neither keeps host-side state per launch, so captured
- * launches can be replayed.  The waits inside the fused launch are bounded (pop_layer_set_wait_limit): if one gives
+ * launches can be replayed.  The waits inside the fused launch, and inside the first launch of a B > 1 step (its
+ * selecting workgroups wait for the candidates' scores), are bounded (pop_layer_set_wait_limit): if one gives
  * up, the step's results are invalid, pop_layer_sync_status reports POP_EDEVICE, every kernel still exits and the
  * next step is unaffected.
  * Errors: as pop_decode_mask; y == NULL or bad ydtype -> POP_EINVAL. */
@@ -221,11 +222,13 @@ int pop_layer_get_hidden(pop_layer_t *layer, float *h, int B, void *stream);
  * sequence.  Explicit counts keep working next to it.  Does not touch an existing partition.
  * Errors: as pop_strategy_counts; without a strategy the sentinels give POP_ESTATE (prefill) / POP_EINVAL (k). */
 int pop_layer_set_strategy(pop_layer_t *layer, int strategy, double r, double gamma);
-/* Host only.  How many times a bounded in-kernel wait of the fused single-sequence decode step (Sec. 3.4: its
- * workgroups hand each other the candidates' h and the selection) looks for what it waits for before it gives
- * up (default 65536: a fraction of a second).  A wait that gives up flags the step (pop_layer_sync_status:
- * POP_EDEVICE); every kernel still exits, and the next step is unaffected.  0 makes every wait give up at once unless
- * the data is already there: a testing knob.  Errors: NULL layer or looks < 0 -> POP_EINVAL. */
+/* Host only.  How many times a bounded in-kernel wait of a decode step looks for what it waits for before it gives
+ * up (default 65536: a fraction of a second).  Two kernels wait: the fused single-sequence step (Sec. 3.4: its
+ * workgroups hand each other the candidates' h and the selection) and the batched step's first launch, whose
+ * selecting workgroups wait for the candidates' scores.  A wait that gives up flags the step (pop_layer_sync_status:
+ * POP_EDEVICE) and leaves its results invalid; every kernel still exits, and the next step is unaffected.  0 makes
+ * every wait give up at once unless the data is already there: a testing knob.
+ * Errors: NULL layer or looks < 0 -> POP_EINVAL. */
 int pop_layer_set_wait_limit(pop_layer_t *layer, int looks);
 /* Host only.  Which reading of Sec. 3.1 defines channel importance on this layer (the paper's equations admit two):
  *   POP_IMPORTANCE_OUTPUT_SIDE (default)  the down projection and the intermediate activations, as at the top of

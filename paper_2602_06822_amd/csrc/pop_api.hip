@@ -67,7 +67,7 @@ struct pop_layer {
     int step_B = 0;
     bool fused_ok = false;             // the fused kernel supports this partition
     FusedPlan plan = {};
-    int *sync = nullptr;               // [8]
+    int *sync = nullptr;               // [16]: [2] error flag of the batched kernels, [8..9] and [10..12] their counters
     // what the fused kernel's workgroups hand to each other: 64-bit words {value, epoch}
     unsigned long long *hc = nullptr;     // [m] a candidate's h, by candidate position
     unsigned long long *selw = nullptr;   // per-workgroup selection words
@@ -622,8 +622,8 @@ int pop_decode_mask(pop_layer_t *L, const void *x_t, int B, const int *k, float 
         if (B > 1 && !shared)  // per-sequence top-k and their union inside the gate/up kernel, behind the retained channels
             POP_HIP(launch_gateup_select(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, L->h, L->nrm, L->cscore, m,
                                          L->cand_idx, n_cand, n_ret, kk, m, L->mask, L->active_idx, L->n_active,
-                                         L->selflag, L->ulist, L->n_ulist, L->sync + 10, L->sync + 2, L->n_cu,
-                                         &sel_inside, s));
+                                         L->selflag, L->ulist, L->n_ulist, L->sync + 10, L->sync + 2, L->spin_limit,
+                                         L->n_cu, &sel_inside, s));
         if (!sel_inside) {
             POP_HIP(launch_gateup(L->w, L->is_bf16, L->d, m, x_t, B, L->rc_idx, n_ret + n_cand, nullptr, L->h, L->nrm,
                                   L->cscore, m, n_cand, L->n_cu, s));

@@ -121,7 +121,11 @@ __global__ __launch_bounds__(1024) void gateup_kernel(const typename V::vec_t *_
 // acknowledged.  The last B workgroups wait, bounded, for all arrivals and run one sequence's top-k each, the last of
 // them also the union of the selections, while the others go on with the retained channels: the selection costs
 // no time of its own.  All workgroups are resident (at most one per compute unit is launched), so the wait ends;
-// if it ever expires the sticky error flag is raised.
+// if it ever expires the error flag is raised and the step's selection is not made.
+// The arrival counter is never rewound: a second word holds the arrivals expected before this launch, the selectors
+// wait for that plus this launch's workers, and the last selector moves the word on.  Every worker arrives exactly
+// once before the launch ends, whether or not a selector was still waiting for it, so the two words agree again
+// at the start of the next launch whatever happened in this one.
 struct GateupSelectArgs {
     const int *cand_idx;
     int n_cand, n_ret;
@@ -131,8 +135,9 @@ struct GateupSelectArgs {
     int *active_idx, *n_active;
     unsigned char *selflag;
     int *union_list, *n_union;
-    int *counters;  // [0] arrivals, [1] selectors done
+    int *counters;  // [0] arrivals (ever growing), [1] selectors done, [2] arrivals expected before this launch
     int *err_flag;
+    int spin_limit;  // looks a selector's wait takes before it gives up
 };
 
 template <class V, int B>
@@ -179,8 +184,9 @@ __global__ __launch_bounds__(1024) void gateup_select_kernel(const typename V::v
     }
 
     const int b = blockIdx.x - n_work;  // this workgroup selects for sequence b
+    const int target = sa.counters[2] + n_work;  // (written by the previous launch: an ordinary load)
     if (threadIdx.x == 0) {
-        const bool ok = spin_until(&sa.counters[0], n_work);
+        const bool ok = spin_until(&sa.counters[0], target, sa.spin_limit);
         if (!ok) *sa.err_flag = 1;
         s_flag = ok ? 1 : 0;
     }
@@ -226,8 +232,8 @@ __global__ __launch_bounds__(1024) void gateup_select_kernel(const typename V::v
         if ((coherent_load(&flags[i]) & live) != 0) sa.union_list[pos++] = sa.cand_idx[i];
     if (threadIdx.x == 0) {
         *sa.n_union = sa.n_ret + tot[0];
-        sa.counters[0] = 0;
         sa.counters[1] = 0;
+        sa.counters[2] = target;
     }
 }
 
@@ -313,10 +319,10 @@ hipError_t launch_gateup_select(const void *w, int is_bf16, int d, int m, const 
                                 float *h, const float *nrm, float *cscore, int cs_stride, const int *cand_idx,
                                 int n_cand, int n_ret, BatchK k, int act_stride, unsigned char *mask, int *active_idx,
                                 int *n_active, unsigned char *selflag, int *union_list, int *n_union, int *counters,
-                                int *err_flag, int n_cu, bool *fused, hipStream_t s)
+                                int *err_flag, int spin_limit, int n_cu, bool *fused, hipStream_t s)
 {
     GateupSelectArgs sa = {cand_idx, n_cand, n_ret, k, act_stride, mask, active_idx, n_active, selflag,
-                           union_list, n_union, counters, err_flag};
+                           union_list, n_union, counters, err_flag, spin_limit};
     if (is_bf16)
         return gateup_select_dispatch<VecBF16>(w, d / 8, x, B, rows, h, m, nrm, cscore, cs_stride, sa, n_cu, fused, s);
     return gateup_select_dispatch<VecF32>(w, d / 4, x, B, rows, h, m, nrm, cscore, cs_stride, sa, n_cu, fused, s);

@@ -71,15 +71,15 @@ __device__ __forceinline__ unsigned long long coherent_load(const unsigned long 
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Bounded wait until *addr >= target (a launch that waits is sized so that all its workgroups are resident).
-constexpr int kSpinLimit = 1 << 16;
-__device__ __forceinline__ bool spin_until(const int *addr, int target)
+// Bounded wait until the counter *addr, which only ever grows (and may wrap), has reached target: at most `limit`
+// looks, at least one (a launch that waits is sized so that all its workgroups are resident).
+__device__ __forceinline__ bool spin_until(const int *addr, int target, int limit)
 {
-    for (int it = 0; it < kSpinLimit; ++it) {
-        if (coherent_load(addr) >= target) return true;
+    for (int it = 0;; ++it) {
+        if (coherent_load(addr) - target >= 0) return true;
+        if (it >= limit) return false;
         __builtin_amdgcn_s_sleep(2);
     }
-    return false;
 }
 
 // ---- setup (pop_setup.hip) ----
@@ -191,7 +191,7 @@ hipError_t launch_gateup_select(const void *w, int is_bf16, int d, int m, const 
                                 float *h, const float *nrm, float *cscore, int cs_stride, const int *cand_idx,
                                 int n_cand, int n_ret, BatchK k, int act_stride, unsigned char *mask, int *active_idx,
                                 int *n_active, unsigned char *selflag, int *union_list, int *n_union, int *counters,
-                                int *err_flag, int n_cu, bool *fused, hipStream_t s);
+                                int *err_flag, int spin_limit, int n_cu, bool *fused, hipStream_t s);
 
 // ---- fused single-sequence decode step (pop_decode_fused.hip) ----
 struct FusedParams {

@@ -817,6 +817,47 @@ def test_expired_waits_flag_the_step_and_leave_the_next_one_alone(pop, oracle, d
         assert e.value.status == pop.POP_EINVAL
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_expired_wait_of_a_batched_step_leaves_the_next_one_alone(pop, oracle, dtype):
+    """B > 1: the selecting workgroups of the step's first launch wait for the candidates' scores.  With a wait limit
+    of 0 (set from the host) they give up at once: every kernel still exits, the step is reported as invalid
+    (POP_EDEVICE, once), and with the limit restored the following steps - same and other batch sizes - are
+    bit-identical to those of a fresh layer: the arrival counters agree again without anybody rewinding them."""
+    d, m, T, B = 512, 768, 40, 4
+    L = synth.make_layer(synth.small_config("expired_batch", d, m, dtype, n_outlier=2, heavy_tail=dtype == BF16))
+    x = synth.make_activations(L, T, "prompt")
+    xt = synth.make_activations(L, 4 * B, "decode")
+    n_ret, n_cand, _ = pop.pop_region_counts(m, 0.6, 0.1)
+    k = [n_cand // 2, n_cand // 3, n_cand, 0]
+    steps = [(0, B), (B, B), (2 * B, 3), (3 * B, B)]  # (first row of xt, sequences)
+    with GpuLayer(pop, L, max_tokens=T, max_batch=B) as G:
+        scores, region, ret, cand, _ = _check_prefill(oracle, G, L, x, n_ret, n_cand)
+        fresh = [G.decode(xt[t0:t0 + b], k[:b], one_call=True) for t0, b in steps]
+    with GpuLayer(pop, L, max_tokens=T, max_batch=B) as G:
+        G.prefill(x, n_ret, n_cand)
+        pop.pop_layer_set_wait_limit(G.handle, 0)
+        y = torch.zeros((B, d), dtype=torch.float32, device="cuda")
+        flagged = 0
+        for t in (1, 2):
+            pop.pop_decode_step(G.handle, dev(xt[t * B:(t + 1) * B]), B, k, y, F32)
+            torch.cuda.synchronize()  # the kernels came back
+            try:
+                pop.pop_layer_sync_status(G.handle)
+            except pop.PopError as e:
+                assert e.status == pop.POP_EDEVICE
+                flagged += 1
+                pop.pop_layer_sync_status(G.handle)  # reported once
+        assert flagged >= 1, "with no patience at all a selector cannot have found every score in place"
+        pop.pop_layer_set_wait_limit(G.handle, 1 << 16)
+        for (t0, b), ref in zip(steps, fresh):
+            again = G.decode(xt[t0:t0 + b], k[:b], one_call=True)  # (raises if the step was flagged)
+            for key in ("mask", "n_active", "cscore", "y"):
+                assert np.array_equal(again[key], ref[key]), (t0, key)
+            for q in range(b):
+                assert np.array_equal(again["active_idx"][q, :n_ret + k[q]], ref["active_idx"][q, :n_ret + k[q]])
+        _check_decode(oracle, G, L, region, cand, xt[:B], k)
+
+
 def test_determinism_and_poisoned_scratch(pop, oracle):
     """Two identical step sequences give bit-identical outputs, also after other work dirtied the scratch."""
     d, m, T = 512, 700, 64
