@@ -733,31 +733,33 @@ def test_forward_pass_scratch_poisoned_and_side_stream(pop, oracle):
             side.synchronize()
 
 
-def test_one_call_step_replays_from_a_graph(pop):
-    """The one-call step (fused kernel and tail kernel) keeps no per-launch state on the host: a captured step is
-    replayed several times, with eager steps in between, and every replay must reproduce the eager result bit for
-    bit."""
+@pytest.mark.parametrize("B", [1, 4])
+def test_one_call_step_replays_from_a_graph(pop, B):
+    """The one-call step keeps no per-launch state on the host (B = 1: fused kernel and tail kernel; B = 4: the
+    gate/up launch with the selection inside, whose counters are never rewound, the down projection and its
+    reduction): a captured step is replayed several times, with eager steps in between, and every replay must
+    reproduce the eager result bit for bit."""
     d, m, T = 512, 1024, 32
     L = synth.make_layer(synth.small_config("graph_replay", d, m, BF16, n_outlier=2, heavy_tail=True))
     x = synth.make_activations(L, T, "prompt")
-    xt = synth.make_activations(L, 3, "decode")
+    xt = synth.make_activations(L, 3 * B, "decode")
     n_ret, n_cand, _ = pop.pop_region_counts(m, 0.55, 0.1)
-    k = n_cand // 2
-    with GpuLayer(pop, L, max_tokens=T, max_batch=1) as G:
+    k = [n_cand // 2, n_cand // 3, n_cand // 2 + 1, n_cand // 4][:B]
+    with GpuLayer(pop, L, max_tokens=T, max_batch=B) as G:
         G.prefill(x, n_ret, n_cand)
         side = torch.cuda.Stream()
-        xs = [dev(xt[i:i + 1]) for i in range(3)]
-        y_eager = [torch.zeros(d, dtype=torch.int16, device="cuda") for _ in range(3)]
-        y_graph = torch.zeros(d, dtype=torch.int16, device="cuda")
+        xs = [dev(xt[i * B:(i + 1) * B]) for i in range(3)]
+        y_eager = [torch.zeros((B, d), dtype=torch.int16, device="cuda") for _ in range(3)]
+        y_graph = torch.zeros((B, d), dtype=torch.int16, device="cuda")
         with torch.cuda.stream(side):
             for i in range(3):
-                pop.pop_decode_step(G.handle, xs[i], 1, [k], y_eager[i], BF16, stream=side)
+                pop.pop_decode_step(G.handle, xs[i], B, k, y_eager[i], BF16, stream=side)
             side.synchronize()
-            assert pop.pop_layer_step_kind(G.handle)[0] == 1
+            assert pop.pop_layer_step_kind(G.handle)[0] == (1 if B == 1 else 2)
             x_in = xs[0].clone()
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                pop.pop_decode_step(G.handle, x_in, 1, [k], y_graph, BF16, stream=torch.cuda.current_stream())
+                pop.pop_decode_step(G.handle, x_in, B, k, y_graph, BF16, stream=torch.cuda.current_stream())
             for rep in range(6):
                 i = rep % 3
                 x_in.copy_(xs[i])
@@ -766,8 +768,8 @@ def test_one_call_step_replays_from_a_graph(pop):
                 torch.cuda.synchronize()
                 assert torch.equal(y_graph, y_eager[i]), f"replay {rep}"
                 # the program's own eager work between replays
-                y_tmp = torch.zeros(d, dtype=torch.int16, device="cuda")
-                pop.pop_decode_step(G.handle, xs[(i + 1) % 3], 1, [k], y_tmp, BF16, stream=torch.cuda.current_stream())
+                y_tmp = torch.zeros((B, d), dtype=torch.int16, device="cuda")
+                pop.pop_decode_step(G.handle, xs[(i + 1) % 3], B, k, y_tmp, BF16, stream=torch.cuda.current_stream())
                 torch.cuda.synchronize()
                 assert torch.equal(y_tmp, y_eager[(i + 1) % 3])
             pop.pop_layer_sync_status(G.handle)
